@@ -1,0 +1,221 @@
+/*
+ * libegeria: the plasticity-evaluation hot path of Egeria (arXiv 2201.06227)
+ * for AMD Instinct MI355X (gfx950).
+ *
+ * For one layer module the path is (Section 4.1-4.2 of the paper):
+ *   1. generate the reference model: quantise a snapshot of the training
+ *      model's weights to int8                                (egeria_quantize*)
+ *   2. run the reference model's forward on the same mini-batch and hook the
+ *      module's output activation A_R                         (egeria_ref_forward)
+ *   3. score the training model's activation A_T against A_R with the
+ *      training-plasticity metric of Eq. 1 (SP loss)          (egeria_plasticity)
+ * egeria_plasticity_eval chains 2 and 3 for a stack of modules.
+ *
+ * General rules of this interface
+ *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The
+ *     descriptor structs themselves are HOST memory holding device pointers.
+ *   - The caller owns every buffer.  The library never allocates or frees
+ *     device memory and never synchronises: all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and results
+ *     land in device memory when the stream reaches them.
+ *   - Device pointers must be 16-byte aligned.
+ *   - Argument errors are found on the host before anything is launched and
+ *     are reported through the return code; nothing is thrown.
+ *   - A NaN or infinity met by a quantiser sets a flag word inside the
+ *     workspace; egeria_check reads it back (that call does synchronise).
+ *   - Calls are re-entrant as long as they use distinct workspaces.  Two calls
+ *     that share a workspace must be ordered on one stream.
+ *
+ * Quantisation rule (the paper names int8 post-training quantisation and
+ * leaves the arithmetic to its framework; this library fixes it as):
+ *   absmax = max |x_i|;  scale = fp32(absmax / 127);  inv = fp32(127 / absmax)
+ *   (both divisions in fp64, rounded once); q_i = clamp(rne(x_i * inv), -127,
+ *   127) with one fp32 multiply; zero point 0.  absmax == 0, or so small that
+ *   inv overflows, quantises to all zeros with scale 1.  With a caller-supplied
+ *   static scale: inv = fp32(1 / scale) and values beyond the range saturate.
+ *
+ * int8 operand layout: a quantised matrix [rows, K] is stored row-major with
+ * each row padded with zero bytes to egeria_padded(K) = K rounded up to 16.
+ * A quantised NHWC image tensor [B, H, W, C] pads C the same way.
+ */
+#ifndef EGERIA_H
+#define EGERIA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EGERIA_OK = 0,
+    EGERIA_ERR_INVALID_ARG = 1,          /* null / misaligned pointer, non-positive size */
+    EGERIA_ERR_UNSUPPORTED = 2,          /* valid request outside what the kernels cover */
+    EGERIA_ERR_WORKSPACE_TOO_SMALL = 3,
+    EGERIA_ERR_NONFINITE = 4,            /* reported by egeria_check only */
+    EGERIA_ERR_HIP = 5                   /* a launch or runtime call failed */
+} egeria_status;
+
+typedef enum { EGERIA_F32 = 0, EGERIA_BF16 = 1 } egeria_dtype;
+
+/* Kinds of layer module the reference forward knows. */
+typedef enum {
+    EGERIA_FC_RELU = 0,      /* y = ReLU(x W^T + bias)                                   */
+    EGERIA_BASIC_BLOCK = 1,  /* conv3x3 - ReLU - conv3x3 (+ input) - ReLU                */
+    EGERIA_BOTTLENECK = 2,   /* conv1x1 - ReLU - conv3x3 - ReLU - conv1x1 (+ input) - ReLU */
+    EGERIA_BERT_LAYER = 3,   /* post-LN Transformer encoder layer                        */
+    EGERIA_BERT_STACK = 4    /* n_layers such layers chained                             */
+} egeria_block_kind;
+
+/* HOST struct.  Shape of one layer module.
+ *   FC_RELU     : batch, c_in (input features), c_out (output features)
+ *   BASIC_BLOCK : batch, c_in = c_mid = c_out, height, width, has_residual
+ *   BOTTLENECK  : batch, c_in, c_mid, c_out (= c_in when has_residual), height, width
+ *   BERT_*      : batch, seq, hidden, heads, ffn, n_layers (1 for BERT_LAYER), ln_eps
+ * Convolutions are stride 1; 3x3 ones use zero padding 1.  Batch-norm is taken
+ * as folded into the convolution's weight and per-channel bias. */
+typedef struct {
+    int32_t kind;
+    int32_t batch;
+    int32_t c_in, c_mid, c_out;
+    int32_t height, width;
+    int32_t has_residual;
+    int32_t seq, hidden, heads, ffn;
+    int32_t n_layers;
+    float ln_eps;
+} egeria_block_desc;
+
+/* HOST struct.  One quantised linear / convolution layer of the reference model.
+ *   w_q   : int8 [out, egeria_padded(K)]; K = in features for linear layers,
+ *           K = kh*kw*egeria_padded(c_in) ordered (kh, kw, c) for convolutions
+ *           (what egeria_quantize_nchw makes of an [out, in, kh, kw] tensor).
+ *   scale : 1 fp32, the tensor's scale.
+ *   bias  : fp32 [out] or NULL. */
+typedef struct {
+    const int8_t *w_q;
+    const float *scale;
+    const float *bias;
+} egeria_qlinear;
+
+/* HOST struct.  Affine parameters of one layer norm (each fp32 [hidden] or NULL
+ * for gamma = 1 / beta = 0). */
+typedef struct {
+    const float *gamma;
+    const float *beta;
+} egeria_norm;
+
+/* HOST struct.  The reference model of one layer module: `linear` in forward
+ * order (FC: 1; BASIC: 2; BOTTLENECK: 3; BERT: per layer qkv, attn_out, ffn1,
+ * ffn2), `norm` per BERT layer (post-attention, post-ffn); norm may be NULL. */
+typedef struct {
+    int32_t n_linear;
+    const egeria_qlinear *linear;   /* HOST array */
+    int32_t n_norm;
+    const egeria_norm *norm;        /* HOST array or NULL */
+} egeria_qweights;
+
+/* HOST struct.  Optional observation points of the reference forward, used by
+ * parity tests: for sub-layer i (same order as egeria_qweights.linear) the int8
+ * input in the layout the GEMM consumes ([M, egeria_padded(K)], NHWC for
+ * convolutions), its scale, the raw int32 accumulators [M, out] and the fp32
+ * output after the epilogue [M, out].  Any pointer may be NULL. */
+typedef struct {
+    int8_t *x_q;
+    float *x_scale;
+    int32_t *acc;
+    float *y;
+} egeria_tap;
+
+typedef struct {
+    int32_t n;
+    const egeria_tap *tap;          /* HOST array */
+} egeria_taps;
+
+/* K rounded up to a multiple of 16. */
+int64_t egeria_padded(int64_t k);
+
+/* Section 4.1: per-tensor int8 quantisation of n contiguous values (weights of
+ * a snapshot, or any activation).
+ *   x           n values of type dt.
+ *   fixed_scale NULL: dynamic (scale from absmax); else 1 fp32 static scale.
+ *   q           int8 [n] out.  scale_out: 1 fp32 out.
+ *   ws          at least egeria_quantize_workspace_bytes() bytes.
+ * n == 0 is valid and writes scale 1. */
+egeria_status egeria_quantize(const void *x, egeria_dtype dt, int64_t n, const float *fixed_scale,
+                              int8_t *q, float *scale_out, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/* Same rule, for a matrix [rows, cols] whose quantised rows are padded:
+ * q is int8 [rows, egeria_padded(cols)], pad bytes zero. */
+egeria_status egeria_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
+                                   const float *fixed_scale, int8_t *q, float *scale_out,
+                                   void *ws, size_t ws_bytes, void *stream);
+
+/* Same rule, for an [n, c, h, w] tensor (a mini-batch of images, or a
+ * convolution weight [out, in, kh, kw]) written channel-last:
+ * q is int8 [n, h, w, egeria_padded(c)], pad channels zero. */
+egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t h,
+                                   int64_t w, const float *fixed_scale, int8_t *q,
+                                   float *scale_out, void *ws, size_t ws_bytes, void *stream);
+
+/* x_i = q_i * scale. */
+egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x,
+                                void *stream);
+
+size_t egeria_quantize_workspace_bytes(void);
+
+/* Section 4.1 / 4.2: forward of the int8 reference model of one layer module on
+ * the mini-batch x, producing the hooked activation A_R.
+ *   x      fp32 mini-batch: [batch, c_in] (FC), NCHW [batch, c_in, h, w] (conv
+ *          kinds), [batch, seq, hidden] (BERT kinds).
+ *   a_ref  fp32 out, [n_layers][batch, D]: D = c_out (FC), h*w*c_out in NHWC
+ *          order (conv kinds; the metric does not depend on the feature order),
+ *          seq*hidden (BERT kinds).
+ *   taps   NULL or observation points.
+ *   ws     at least egeria_workspace_bytes(desc) bytes.
+ * Every linear / convolution input is quantised per tensor at run time
+ * (dynamic scale), the contraction is int8 x int8 -> int32 on the matrix
+ * cores, and the epilogue is, in fp32 and in this order: s = s_x * s_w;
+ * y = fma((float)acc, s, bias); [+ residual]; activation.  The residual of the
+ * conv kinds is the dequantised block input. */
+egeria_status egeria_ref_forward(const egeria_block_desc *desc, const egeria_qweights *qw,
+                                 const void *x, egeria_dtype x_dt, float *a_ref,
+                                 const egeria_taps *taps, void *ws, size_t ws_bytes, void *stream);
+
+/* Section 4.2, Eq. 1: training plasticity P = SP_loss(A_T, A_R) of two
+ * activations of the same mini-batch, both [b, D] row-major (sample-major):
+ *   Gt = Q Q^T (b x b), G = rows of Gt divided by max(their L2 norm, 1e-12),
+ *   P = sum_ij (G_T - G_R)_ij^2 / b^2.
+ * p_out: 1 fp32.  ws: at least egeria_plasticity_workspace_bytes(b, D).
+ * 1 <= b <= 128 (larger: EGERIA_ERR_UNSUPPORTED), D >= 1. */
+egeria_status egeria_plasticity(const void *a_train, egeria_dtype t_dt, const void *a_ref,
+                                egeria_dtype r_dt, int32_t b, int64_t D, float *p_out, void *ws,
+                                size_t ws_bytes, void *stream);
+
+size_t egeria_plasticity_workspace_bytes(int32_t b, int64_t D);
+
+/* Reference forward of a module (or stack) followed by one score per layer:
+ * a_train is a HOST array of desc->n_layers device pointers (each [batch, D] of
+ * type t_dt), p_out receives n_layers fp32 scores.  ws: at least
+ * egeria_workspace_bytes(desc) (which includes room for A_R and the metric). */
+egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria_qweights *qw,
+                                     const void *x, egeria_dtype x_dt,
+                                     const void *const *a_train, egeria_dtype t_dt, float *p_out,
+                                     void *ws, size_t ws_bytes, void *stream);
+
+/* Host-only and pure: bytes of workspace egeria_ref_forward and
+ * egeria_plasticity_eval need for this module; 0 if desc is invalid. */
+size_t egeria_workspace_bytes(const egeria_block_desc *desc);
+
+/* Reads the workspace's flag word back (synchronises `stream`): returns
+ * EGERIA_ERR_NONFINITE if a quantiser that used this workspace met a NaN or
+ * an infinity since the last check, and clears the flag. */
+egeria_status egeria_check(void *ws, void *stream);
+
+const char *egeria_status_string(egeria_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGERIA_H */

@@ -1,0 +1,329 @@
+"""ctypes binding of libegeria.so: same names as include/egeria.h, argument
+marshalling only.  Tensors are torch CUDA tensors (device memory + streams are
+all PyTorch is used for); every step of the path runs in the library's kernels.
+
+There is no fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import _build
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_NONFINITE, ERR_HIP = range(6)
+F32, BF16 = 0, 1
+FC_RELU, BASIC_BLOCK, BOTTLENECK, BERT_LAYER, BERT_STACK = range(5)
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+_i32 = ctypes.c_int32
+_sz = ctypes.c_size_t
+
+
+class BlockDesc(ctypes.Structure):
+    _fields_ = [("kind", _i32), ("batch", _i32), ("c_in", _i32), ("c_mid", _i32), ("c_out", _i32),
+                ("height", _i32), ("width", _i32), ("has_residual", _i32), ("seq", _i32),
+                ("hidden", _i32), ("heads", _i32), ("ffn", _i32), ("n_layers", _i32),
+                ("ln_eps", ctypes.c_float)]
+
+
+class QLinear(ctypes.Structure):
+    _fields_ = [("w_q", _vp), ("scale", _vp), ("bias", _vp)]
+
+
+class Norm(ctypes.Structure):
+    _fields_ = [("gamma", _vp), ("beta", _vp)]
+
+
+class QWeights(ctypes.Structure):
+    _fields_ = [("n_linear", _i32), ("linear", ctypes.POINTER(QLinear)), ("n_norm", _i32),
+                ("norm", ctypes.POINTER(Norm))]
+
+
+class Tap(ctypes.Structure):
+    _fields_ = [("x_q", _vp), ("x_scale", _vp), ("acc", _vp), ("y", _vp)]
+
+
+class Taps(ctypes.Structure):
+    _fields_ = [("n", _i32), ("tap", ctypes.POINTER(Tap))]
+
+
+class EgeriaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+_lib = None
+
+EXPORTS = [
+    "egeria_padded", "egeria_quantize", "egeria_quantize_rows", "egeria_quantize_nchw",
+    "egeria_dequantize", "egeria_quantize_workspace_bytes", "egeria_ref_forward",
+    "egeria_plasticity", "egeria_plasticity_workspace_bytes", "egeria_plasticity_eval",
+    "egeria_workspace_bytes", "egeria_check", "egeria_status_string",
+]
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first "
+                           "(python -c 'import __graft_entry__ as g; g.build()')")
+    L = ctypes.CDLL(path)
+    L.egeria_padded.restype = _i64
+    L.egeria_padded.argtypes = [_i64]
+    L.egeria_quantize.restype = ctypes.c_int
+    L.egeria_quantize.argtypes = [_vp, ctypes.c_int, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.egeria_quantize_rows.restype = ctypes.c_int
+    L.egeria_quantize_rows.argtypes = [_vp, ctypes.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.egeria_quantize_nchw.restype = ctypes.c_int
+    L.egeria_quantize_nchw.argtypes = [_vp, ctypes.c_int, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.egeria_dequantize.restype = ctypes.c_int
+    L.egeria_dequantize.argtypes = [_vp, _vp, _i64, _vp, _vp]
+    L.egeria_quantize_workspace_bytes.restype = _sz
+    L.egeria_quantize_workspace_bytes.argtypes = []
+    L.egeria_ref_forward.restype = ctypes.c_int
+    L.egeria_ref_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(QWeights), _vp, ctypes.c_int,
+                                     _vp, ctypes.POINTER(Taps), _vp, _sz, _vp]
+    L.egeria_plasticity.restype = ctypes.c_int
+    L.egeria_plasticity.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int, _i32, _i64, _vp, _vp, _sz, _vp]
+    L.egeria_plasticity_workspace_bytes.restype = _sz
+    L.egeria_plasticity_workspace_bytes.argtypes = [_i32, _i64]
+    L.egeria_plasticity_eval.restype = ctypes.c_int
+    L.egeria_plasticity_eval.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(QWeights), _vp, ctypes.c_int,
+                                         ctypes.POINTER(_vp), ctypes.c_int, _vp, _vp, _sz, _vp]
+    L.egeria_workspace_bytes.restype = _sz
+    L.egeria_workspace_bytes.argtypes = [ctypes.POINTER(BlockDesc)]
+    L.egeria_check.restype = ctypes.c_int
+    L.egeria_check.argtypes = [_vp, _vp]
+    L.egeria_status_string.restype = ctypes.c_char_p
+    L.egeria_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def status_string(code: int) -> str:
+    return lib().egeria_status_string(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise EgeriaError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t
+
+
+def padded(k: int) -> int:
+    return int(lib().egeria_padded(int(k)))
+
+
+def workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ---- quantise -----------------------------------------------------------------------------
+
+def quantize_workspace_bytes() -> int:
+    return int(lib().egeria_quantize_workspace_bytes())
+
+
+def quantize(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """egeria_quantize: int8 codes (same shape as x) and the 1-element fp32 scale."""
+    x = _dev(x)
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    ws = workspace(quantize_workspace_bytes(), x.device) if ws is None else ws
+    rc = lib().egeria_quantize(_ptr(x), _dt(x), x.numel(), _ptr(fixed_scale), _ptr(q), _ptr(scale), _ptr(ws),
+                               ws.numel(), _stream())
+    _check(rc, "egeria_quantize")
+    return q, scale
+
+
+def quantize_rows(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """egeria_quantize_rows: [rows, cols] -> int8 [rows, padded(cols)] and scale."""
+    x = _dev(x)
+    rows, cols = x.shape
+    q = torch.empty((rows, padded(cols)), dtype=torch.int8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    ws = workspace(quantize_workspace_bytes(), x.device) if ws is None else ws
+    rc = lib().egeria_quantize_rows(_ptr(x), _dt(x), rows, cols, _ptr(fixed_scale), _ptr(q), _ptr(scale),
+                                    _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_quantize_rows")
+    return q, scale
+
+
+def quantize_nchw(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """egeria_quantize_nchw: [n, c, h, w] -> int8 [n, h, w, padded(c)] and scale."""
+    x = _dev(x)
+    n, c, h, w = x.shape
+    q = torch.empty((n, h, w, padded(c)), dtype=torch.int8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    ws = workspace(quantize_workspace_bytes(), x.device) if ws is None else ws
+    rc = lib().egeria_quantize_nchw(_ptr(x), _dt(x), n, c, h, w, _ptr(fixed_scale), _ptr(q), _ptr(scale),
+                                    _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_quantize_nchw")
+    return q, scale
+
+
+def dequantize(q: torch.Tensor, scale: torch.Tensor) -> torch.Tensor:
+    q = _dev(q)
+    x = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(lib().egeria_dequantize(_ptr(q), _ptr(scale), q.numel(), _ptr(x), _stream()), "egeria_dequantize")
+    return x
+
+
+# ---- reference model ------------------------------------------------------------------------
+
+def make_desc(kind: int, dims: dict) -> BlockDesc:
+    d = BlockDesc()
+    d.kind = kind
+    d.batch = dims["batch"]
+    for k in ("c_in", "c_mid", "c_out", "height", "width", "has_residual", "seq", "hidden", "heads", "ffn"):
+        setattr(d, k, int(dims.get(k, 0)))
+    d.n_layers = int(dims.get("n_layers", 1))
+    d.ln_eps = float(dims.get("ln_eps", 0.0))
+    return d
+
+
+@dataclass
+class ReferenceModel:
+    """Device-resident int8 reference model of one layer module: the marshalled
+    egeria_qweights plus the tensors that keep its pointers alive."""
+    desc: BlockDesc
+    qweights: QWeights
+    w_q: List[torch.Tensor]
+    scales: List[torch.Tensor]
+    biases: List[Optional[torch.Tensor]]
+    _keep: tuple = ()
+
+
+def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
+                   biases: Sequence[Optional[torch.Tensor]]) -> ReferenceModel:
+    """Reference-model generation: quantise every weight tensor of the snapshot
+    with the library (egeria_quantize_rows for [out, in], egeria_quantize_nchw for
+    [out, in, kh, kw]) and marshal the result."""
+    w_q, scales = [], []
+    ws = workspace(quantize_workspace_bytes(), weights[0].device)
+    for w in weights:
+        q, s = quantize_nchw(w, ws=ws) if w.dim() == 4 else quantize_rows(w, ws=ws)
+        w_q.append(q)
+        scales.append(s)
+    arr = (QLinear * len(weights))()
+    for i in range(len(weights)):
+        arr[i].w_q = w_q[i].data_ptr()
+        arr[i].scale = scales[i].data_ptr()
+        arr[i].bias = 0 if biases[i] is None else biases[i].data_ptr()
+    qw = QWeights()
+    qw.n_linear = len(weights)
+    qw.linear = arr
+    qw.n_norm = 0
+    qw.norm = None
+    return ReferenceModel(make_desc(kind, dims), qw, w_q, scales, list(biases), (arr,))
+
+
+def workspace_bytes(desc: BlockDesc) -> int:
+    return int(lib().egeria_workspace_bytes(ctypes.byref(desc)))
+
+
+def plasticity_workspace_bytes(b: int, D: int) -> int:
+    return int(lib().egeria_plasticity_workspace_bytes(int(b), int(D)))
+
+
+def make_taps(ref: ReferenceModel, shapes: Sequence[dict], device="cuda"):
+    """Allocate observation buffers.  shapes[i] = dict(M=, kp=, N=)."""
+    arr = (Tap * len(shapes))()
+    bufs = []
+    for i, s in enumerate(shapes):
+        xq = torch.zeros((s["M"], s["kp"]), dtype=torch.int8, device=device)
+        sc = torch.zeros(1, dtype=torch.float32, device=device)
+        acc = torch.zeros((s["M"], s["N"]), dtype=torch.int32, device=device)
+        y = torch.zeros((s["M"], s["N"]), dtype=torch.float32, device=device)
+        arr[i].x_q, arr[i].x_scale, arr[i].acc, arr[i].y = xq.data_ptr(), sc.data_ptr(), acc.data_ptr(), y.data_ptr()
+        bufs.append(dict(x_q=xq, x_scale=sc, acc=acc, y=y))
+    taps = Taps()
+    taps.n = len(shapes)
+    taps.tap = arr
+    return taps, bufs, arr
+
+
+def ref_forward(ref: ReferenceModel, x: torch.Tensor, a_ref: torch.Tensor, ws: torch.Tensor,
+                taps: Optional[Taps] = None):
+    """egeria_ref_forward: enqueue the reference forward; a_ref is written in place."""
+    x, a_ref = _dev(x), _dev(a_ref)
+    rc = lib().egeria_ref_forward(ctypes.byref(ref.desc), ctypes.byref(ref.qweights), _ptr(x), _dt(x),
+                                  _ptr(a_ref), ctypes.byref(taps) if taps is not None else None, _ptr(ws),
+                                  ws.numel(), _stream())
+    _check(rc, "egeria_ref_forward")
+    return a_ref
+
+
+def plasticity(a_train: torch.Tensor, a_ref: torch.Tensor, p_out: Optional[torch.Tensor] = None,
+               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """egeria_plasticity on two [b, D] activations; returns the 1-element fp32 tensor."""
+    a_train, a_ref = _dev(a_train), _dev(a_ref)
+    b = a_train.shape[0]
+    D = a_train.numel() // b if b else 0
+    if a_ref.shape[0] != b or a_ref.numel() != a_train.numel():
+        raise ValueError("a_train and a_ref must both be [b, D]")
+    if p_out is None:
+        p_out = torch.empty(1, dtype=torch.float32, device=a_train.device)
+    if ws is None:
+        ws = workspace(plasticity_workspace_bytes(b, D), a_train.device)
+    rc = lib().egeria_plasticity(_ptr(a_train), _dt(a_train), _ptr(a_ref), _dt(a_ref), b, D, _ptr(p_out),
+                                 _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_plasticity")
+    return p_out
+
+
+def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torch.Tensor],
+                    p_out: torch.Tensor, ws: torch.Tensor) -> torch.Tensor:
+    """egeria_plasticity_eval: reference forward + one score per layer."""
+    x = _dev(x)
+    n = ref.desc.n_layers
+    if len(a_train) != n:
+        raise ValueError(f"{n} training activations expected")
+    ptrs = (_vp * n)(*[_dev(t).data_ptr() for t in a_train])
+    rc = lib().egeria_plasticity_eval(ctypes.byref(ref.desc), ctypes.byref(ref.qweights), _ptr(x), _dt(x), ptrs,
+                                      _dt(a_train[0]), _ptr(p_out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_plasticity_eval")
+    return p_out
+
+
+def check(ws: torch.Tensor) -> int:
+    """egeria_check: status code (OK or ERR_NONFINITE); synchronises the stream."""
+    return int(lib().egeria_check(_ptr(ws), _stream()))

@@ -1,0 +1,462 @@
+// C-ABI of libegeria (include/egeria.h): argument validation, workspace
+// planning and the per-module launch sequences of the reference forward.
+// Nothing here allocates device memory or synchronises, except egeria_check.
+#include "common.hpp"
+
+using namespace egeria;
+
+namespace {
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+inline int64_t pad16(int64_t k) { return (k + 15) / 16 * 16; }
+
+#define EG_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) return EGERIA_ERR_HIP;  \
+    } while (0)
+
+// Workspace plan of one layer module: byte offsets from the workspace base.
+struct Plan {
+    bool ok = false;
+    int slots = 0;          // quantise points
+    int n_linear = 0;
+    int n_layers = 1;
+    int64_t M = 0;          // rows of every GEMM (batch, batch*h*w, batch*seq)
+    int64_t D = 0;          // features per sample of the hooked activation
+    size_t off_q[3] = {0, 0, 0};      // int8 activation buffers
+    size_t off_f[5] = {0, 0, 0, 0, 0};  // fp32 intermediates
+    size_t off_aref[2] = {0, 0};      // A_R ping-pong (egeria_plasticity_eval)
+    size_t off_part = 0;              // metric partials
+    size_t fwd_bytes = 0;             // header + forward buffers
+    size_t total = 0;
+};
+
+bool valid_desc(const egeria_block_desc *d)
+{
+    if (!d || d->batch < 1) return false;
+    switch (d->kind) {
+    case EGERIA_FC_RELU:
+        return d->c_in >= 1 && d->c_out >= 1;
+    case EGERIA_BASIC_BLOCK:
+        return d->c_in >= 1 && d->c_mid == d->c_in && d->c_out == d->c_in && d->height >= 1 && d->width >= 1;
+    case EGERIA_BOTTLENECK:
+        return d->c_in >= 1 && d->c_mid >= 1 && d->c_out >= 1 && d->height >= 1 && d->width >= 1 &&
+               (!d->has_residual || d->c_out == d->c_in);
+    case EGERIA_BERT_LAYER:
+    case EGERIA_BERT_STACK:
+        return d->seq >= 1 && d->hidden >= 1 && d->heads >= 1 && d->hidden % d->heads == 0 && d->ffn >= 1 &&
+               d->n_layers >= 1 && (d->kind == EGERIA_BERT_STACK || d->n_layers == 1) && d->ln_eps >= 0.0f;
+    default:
+        return false;
+    }
+}
+
+Plan make_plan(const egeria_block_desc *d)
+{
+    Plan p;
+    if (!valid_desc(d)) return p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    const int64_t b = d->batch;
+    switch (d->kind) {
+    case EGERIA_FC_RELU:
+        p.slots = 1; p.n_linear = 1; p.M = b; p.D = d->c_out;
+        take(header_bytes(p.slots));
+        p.off_q[0] = take((size_t)(b * pad16(d->c_in)));
+        break;
+    case EGERIA_BASIC_BLOCK: {
+        p.slots = 2; p.n_linear = 2; p.M = b * d->height * d->width; p.D = (int64_t)d->height * d->width * d->c_out;
+        take(header_bytes(p.slots));
+        const int64_t cp = pad16(d->c_in);
+        p.off_q[0] = take((size_t)(p.M * cp));
+        p.off_q[1] = take((size_t)(p.M * cp));
+        p.off_f[0] = take((size_t)(p.M * d->c_in) * 4);
+        break;
+    }
+    case EGERIA_BOTTLENECK: {
+        p.slots = 3; p.n_linear = 3; p.M = b * d->height * d->width; p.D = (int64_t)d->height * d->width * d->c_out;
+        take(header_bytes(p.slots));
+        p.off_q[0] = take((size_t)(p.M * pad16(d->c_in)));
+        p.off_q[1] = take((size_t)(p.M * pad16(d->c_mid)));
+        p.off_q[2] = take((size_t)(p.M * pad16(d->c_mid)));
+        p.off_f[0] = take((size_t)(p.M * d->c_mid) * 4);
+        p.off_f[1] = take((size_t)(p.M * d->c_mid) * 4);
+        break;
+    }
+    default: {
+        p.n_layers = d->n_layers;
+        p.slots = 4 * p.n_layers; p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
+        take(header_bytes(p.slots));
+        const int64_t kmax = pad16(d->hidden > d->ffn ? d->hidden : d->ffn);
+        p.off_q[0] = take((size_t)(p.M * kmax));
+        p.off_f[0] = take((size_t)(p.M * 3 * d->hidden) * 4);   // qkv
+        p.off_f[1] = take((size_t)(p.M * d->hidden) * 4);       // ctx
+        p.off_f[2] = take((size_t)(p.M * d->hidden) * 4);       // attention / ffn projection
+        p.off_f[3] = take((size_t)(p.M * d->hidden) * 4);       // post-attention layer norm
+        p.off_f[4] = take((size_t)(p.M * d->ffn) * 4);          // ffn hidden
+        break;
+    }
+    }
+    p.fwd_bytes = off;
+    const size_t aref = (size_t)b * (size_t)p.D * 4;
+    p.off_aref[0] = take(aref);
+    p.off_aref[1] = p.n_layers > 1 ? take(aref) : p.off_aref[0];
+    p.off_part = take(b <= 128 ? plasticity_partial_bytes((int32_t)b, p.D) : 0);
+    p.total = off;
+    p.ok = true;
+    return p;
+}
+
+struct Fwd {
+    const egeria_block_desc *d;
+    const egeria_qweights *qw;
+    const egeria_taps *taps;
+    char *ws;
+    Plan p;
+    hipStream_t st;
+
+    uint32_t *slot(int i) const { return ws_absmax(ws, i); }
+    float *scale(int i) const { return ws_scale(ws, p.slots, i); }
+    int8_t *qbuf(int i) const { return (int8_t *)(ws + p.off_q[i]); }
+    float *fbuf(int i) const { return (float *)(ws + p.off_f[i]); }
+    const egeria_tap *tap(int i) const { return taps ? &taps->tap[i] : nullptr; }
+
+    egeria_status copy_tap_q(int i, const int8_t *src, size_t bytes, const float *sc) const
+    {
+        const egeria_tap *t = tap(i);
+        if (!t) return EGERIA_OK;
+        if (t->x_q) EG_HIP(hipMemcpyAsync(t->x_q, src, bytes, hipMemcpyDeviceToDevice, st));
+        if (t->x_scale) EG_HIP(hipMemcpyAsync(t->x_scale, sc, 4, hipMemcpyDeviceToDevice, st));
+        return EGERIA_OK;
+    }
+    egeria_status copy_tap_y(int i, const float *src, size_t bytes) const
+    {
+        const egeria_tap *t = tap(i);
+        if (t && t->y) EG_HIP(hipMemcpyAsync(t->y, src, bytes, hipMemcpyDeviceToDevice, st));
+        return EGERIA_OK;
+    }
+};
+
+#define EG_OK(expr)                              \
+    do {                                         \
+        egeria_status s__ = (expr);              \
+        if (s__ != EGERIA_OK) return s__;        \
+    } while (0)
+
+// One quantised linear layer on rows that are already int8.
+egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64_t M, int32_t N, int32_t kp,
+                       bool conv, int32_t H, int32_t W, int32_t cp, const float *sx, int act,
+                       const int8_t *res_q, const float *res_scale, int64_t res_ld, float *y,
+                       uint32_t *absmax_out)
+{
+    const egeria_qlinear &L = f.qw->linear[li];
+    GemmArgs g;
+    g.a = a; g.w = L.w_q; g.M = M; g.N = N; g.kp = kp; g.lda = lda;
+    g.conv3x3 = conv ? 1 : 0; g.H = H; g.W = W; g.cp = cp;
+    g.sx = sx; g.sw = L.scale; g.bias = L.bias; g.act = act;
+    g.res_q = res_q; g.res_scale = res_scale; g.res_ld = res_ld;
+    g.y = y; g.ldy = N;
+    const egeria_tap *t = f.tap(li);
+    g.acc_out = t ? t->acc : nullptr;
+    g.absmax_out = absmax_out;
+    EG_HIP(launch_gemm_i8(g, f.st));
+    return f.copy_tap_y(li, y, (size_t)M * N * 4);
+}
+
+egeria_status forward_fc(const Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
+{
+    const egeria_block_desc *d = f.d;
+    const int64_t kp = pad16(d->c_in);
+    EG_HIP(launch_absmax(x, dt, (int64_t)d->batch * d->c_in, f.slot(0), f.st));
+    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.slot(0), nullptr, f.qbuf(0), f.scale(0),
+                                nullptr, ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(d->batch * kp), f.scale(0)));
+    return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.scale(0), 1,
+                    nullptr, nullptr, 0, a_ref, nullptr);
+}
+
+egeria_status forward_conv_block(const Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
+{
+    const egeria_block_desc *d = f.d;
+    const int64_t M = f.p.M, hw = (int64_t)d->height * d->width;
+    const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
+    const int H = d->height, W = d->width;
+    EG_HIP(launch_absmax(x, dt, M * d->c_in, f.slot(0), f.st));
+    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.slot(0), nullptr, f.qbuf(0), f.scale(0),
+                                nullptr, ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));
+    const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
+    if (d->kind == EGERIA_BASIC_BLOCK) {
+        EG_OK(run_gemm(f, 0, f.qbuf(0), 0, M, d->c_mid, 9 * cin_p, true, H, W, cin_p, f.scale(0), 1, nullptr,
+                       nullptr, 0, f.fbuf(0), f.slot(1)));
+        EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.slot(1), nullptr, f.qbuf(1),
+                                    f.scale(1), nullptr, ws_flag(f.ws), f.st));
+        EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
+        return run_gemm(f, 1, f.qbuf(1), 0, M, d->c_out, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, res,
+                        f.scale(0), cin_p, a_ref, nullptr);
+    }
+    // bottleneck: 1x1 -> 3x3 -> 1x1
+    EG_OK(run_gemm(f, 0, f.qbuf(0), cin_p, M, d->c_mid, cin_p, false, 0, 0, 0, f.scale(0), 1, nullptr, nullptr,
+                   0, f.fbuf(0), f.slot(1)));
+    EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.slot(1), nullptr, f.qbuf(1),
+                                f.scale(1), nullptr, ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
+    EG_OK(run_gemm(f, 1, f.qbuf(1), 0, M, d->c_mid, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, nullptr,
+                   nullptr, 0, f.fbuf(1), f.slot(2)));
+    EG_HIP(launch_quantize_rows(f.fbuf(1), EGERIA_F32, M, d->c_mid, cmid_p, f.slot(2), nullptr, f.qbuf(2),
+                                f.scale(2), nullptr, ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(2, f.qbuf(2), (size_t)(M * cmid_p), f.scale(2)));
+    return run_gemm(f, 2, f.qbuf(2), cmid_p, M, d->c_out, cmid_p, false, 0, 0, 0, f.scale(2), 1, res, f.scale(0),
+                    cin_p, a_ref, nullptr);
+}
+
+// One encoder layer: `cur` -> `out`.  slot 4l must already hold absmax(cur).
+egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *out, bool last)
+{
+    const egeria_block_desc *d = f.d;
+    const int64_t M = f.p.M;
+    const int32_t Hd = d->hidden, F = d->ffn;
+    const int32_t hp = (int32_t)pad16(Hd), fp = (int32_t)pad16(F);
+    const int s0 = 4 * l;
+    const egeria_norm *nm = f.qw->norm ? &f.qw->norm[2 * l] : nullptr;
+    float *qkv = f.fbuf(0), *ctx = f.fbuf(1), *proj = f.fbuf(2), *y1 = f.fbuf(3), *ff = f.fbuf(4);
+    int8_t *xq = f.qbuf(0);
+
+    EG_HIP(launch_quantize_rows(cur, EGERIA_F32, M, Hd, hp, f.slot(s0), nullptr, xq, f.scale(s0), nullptr,
+                                ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
+    EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
+    EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
+
+    EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.slot(s0 + 1), nullptr, xq, f.scale(s0 + 1), nullptr,
+                                ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(s0 + 1, xq, (size_t)(M * hp), f.scale(s0 + 1)));
+    EG_OK(run_gemm(f, s0 + 1, xq, hp, M, Hd, hp, false, 0, 0, 0, f.scale(s0 + 1), 0, nullptr, nullptr, 0, proj,
+                   nullptr));
+    EG_HIP(launch_layernorm(cur, proj, M, Hd, nm ? nm[0].gamma : nullptr, nm ? nm[0].beta : nullptr, d->ln_eps,
+                            y1, f.slot(s0 + 2), f.st));
+
+    EG_HIP(launch_quantize_rows(y1, EGERIA_F32, M, Hd, hp, f.slot(s0 + 2), nullptr, xq, f.scale(s0 + 2), nullptr,
+                                ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(s0 + 2, xq, (size_t)(M * hp), f.scale(s0 + 2)));
+    EG_OK(run_gemm(f, s0 + 2, xq, hp, M, F, hp, false, 0, 0, 0, f.scale(s0 + 2), 2, nullptr, nullptr, 0, ff,
+                   f.slot(s0 + 3)));
+
+    EG_HIP(launch_quantize_rows(ff, EGERIA_F32, M, F, fp, f.slot(s0 + 3), nullptr, xq, f.scale(s0 + 3), nullptr,
+                                ws_flag(f.ws), f.st));
+    EG_OK(f.copy_tap_q(s0 + 3, xq, (size_t)(M * fp), f.scale(s0 + 3)));
+    EG_OK(run_gemm(f, s0 + 3, xq, fp, M, Hd, fp, false, 0, 0, 0, f.scale(s0 + 3), 0, nullptr, nullptr, 0, proj,
+                   nullptr));
+    EG_HIP(launch_layernorm(y1, proj, M, Hd, nm ? nm[1].gamma : nullptr, nm ? nm[1].beta : nullptr, d->ln_eps, out,
+                            last ? nullptr : f.slot(s0 + 4), f.st));
+    return EGERIA_OK;
+}
+
+egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
+                           egeria_dtype x_dt, const egeria_taps *taps, void *ws, size_t ws_bytes, Plan &p)
+{
+    if (!desc || !qw || !x || !ws) return EGERIA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
+    p = make_plan(desc);
+    if (!p.ok) return EGERIA_ERR_INVALID_ARG;
+    if (x_dt != EGERIA_F32 && x_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    if (desc->kind >= EGERIA_BERT_LAYER) {
+        if (x_dt != EGERIA_F32) return EGERIA_ERR_UNSUPPORTED;
+        if (desc->hidden / desc->heads > 64) return EGERIA_ERR_UNSUPPORTED;
+    }
+    if (qw->n_linear != p.n_linear || !qw->linear) return EGERIA_ERR_INVALID_ARG;
+    if (qw->norm && qw->n_norm != 2 * p.n_layers) return EGERIA_ERR_INVALID_ARG;
+    for (int i = 0; i < p.n_linear; ++i) {
+        const egeria_qlinear &L = qw->linear[i];
+        if (!L.w_q || !L.scale || !aligned16(L.w_q)) return EGERIA_ERR_INVALID_ARG;
+    }
+    if (taps && (taps->n != p.n_linear || !taps->tap)) return EGERIA_ERR_INVALID_ARG;
+    if (p.M * 16 > 0x7fffffffLL * 16) return EGERIA_ERR_UNSUPPORTED;
+    (void)ws_bytes;
+    return EGERIA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t egeria_padded(int64_t k) { return pad16(k); }
+
+size_t egeria_quantize_workspace_bytes(void) { return header_bytes(1); }
+
+static egeria_status quantize_common(const void *x, egeria_dtype dt, int64_t n_total, const float *fixed_scale,
+                                     int8_t *q, float *scale_out, void *ws, size_t ws_bytes)
+{
+    if (n_total < 0 || !scale_out || !ws) return EGERIA_ERR_INVALID_ARG;
+    if (n_total > 0 && (!x || !q)) return EGERIA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(q) || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
+    if (dt != EGERIA_F32 && dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    if (ws_bytes < header_bytes(1)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    return EGERIA_OK;
+}
+
+egeria_status egeria_quantize(const void *x, egeria_dtype dt, int64_t n, const float *fixed_scale, int8_t *q,
+                              float *scale_out, void *ws, size_t ws_bytes, void *stream)
+{
+    EG_OK(quantize_common(x, dt, n, fixed_scale, q, scale_out, ws, ws_bytes));
+    hipStream_t st = (hipStream_t)stream;
+    EG_HIP(launch_header_reset(ws, 1, st));
+    if (!fixed_scale) EG_HIP(launch_absmax(x, dt, n, ws_absmax(ws, 0), st));
+    EG_HIP(launch_quantize_rows(x, dt, 1, n, n, ws_absmax(ws, 0), fixed_scale, q, scale_out, nullptr, ws_flag(ws), st));
+    return EGERIA_OK;
+}
+
+egeria_status egeria_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
+                                   const float *fixed_scale, int8_t *q, float *scale_out, void *ws,
+                                   size_t ws_bytes, void *stream)
+{
+    if (rows < 0 || cols < 0) return EGERIA_ERR_INVALID_ARG;
+    EG_OK(quantize_common(x, dt, rows * cols, fixed_scale, q, scale_out, ws, ws_bytes));
+    hipStream_t st = (hipStream_t)stream;
+    EG_HIP(launch_header_reset(ws, 1, st));
+    if (!fixed_scale) EG_HIP(launch_absmax(x, dt, rows * cols, ws_absmax(ws, 0), st));
+    EG_HIP(launch_quantize_rows(x, dt, rows, cols, pad16(cols), ws_absmax(ws, 0), fixed_scale, q, scale_out, nullptr,
+                                ws_flag(ws), st));
+    return EGERIA_OK;
+}
+
+egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t h, int64_t w,
+                                   const float *fixed_scale, int8_t *q, float *scale_out, void *ws,
+                                   size_t ws_bytes, void *stream)
+{
+    if (n < 0 || c < 0 || h < 0 || w < 0) return EGERIA_ERR_INVALID_ARG;
+    EG_OK(quantize_common(x, dt, n * c * h * w, fixed_scale, q, scale_out, ws, ws_bytes));
+    if (n > 65535 || pad16(c) / 64 > 65535) return EGERIA_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    EG_HIP(launch_header_reset(ws, 1, st));
+    if (!fixed_scale) EG_HIP(launch_absmax(x, dt, n * c * h * w, ws_absmax(ws, 0), st));
+    if (n * c * h * w == 0) {
+        EG_HIP(launch_quantize_rows(x, dt, 0, 0, 0, ws_absmax(ws, 0), fixed_scale, q, scale_out, nullptr, ws_flag(ws), st));
+        return EGERIA_OK;
+    }
+    EG_HIP(launch_quantize_nchw(x, dt, n, c, h * w, pad16(c), ws_absmax(ws, 0), fixed_scale, q, scale_out, nullptr,
+                                ws_flag(ws), st));
+    return EGERIA_OK;
+}
+
+egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, void *stream)
+{
+    if (n < 0 || !scale) return EGERIA_ERR_INVALID_ARG;
+    if (n > 0 && (!q || !x)) return EGERIA_ERR_INVALID_ARG;
+    EG_HIP(launch_dequantize(q, scale, n, x, (hipStream_t)stream));
+    return EGERIA_OK;
+}
+
+size_t egeria_workspace_bytes(const egeria_block_desc *desc)
+{
+    Plan p = make_plan(desc);
+    return p.ok ? p.total : 0;
+}
+
+static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
+                                  egeria_dtype x_dt, float *a_ref, const egeria_taps *taps,
+                                  const void *const *a_train, egeria_dtype t_dt, float *p_out, void *ws,
+                                  const Plan &p, hipStream_t st)
+{
+    Fwd f{desc, qw, taps, (char *)ws, p, st};
+    const bool eval = p_out != nullptr;
+    const size_t aref_elems = (size_t)desc->batch * (size_t)p.D;
+    EG_HIP(launch_header_reset(ws, p.slots, st));
+    if (desc->kind < EGERIA_BERT_LAYER) {
+        float *out = a_ref ? a_ref : (float *)(f.ws + p.off_aref[0]);
+        if (desc->kind == EGERIA_FC_RELU) EG_OK(forward_fc(f, x, x_dt, out));
+        else EG_OK(forward_conv_block(f, x, x_dt, out));
+        if (eval)
+            EG_HIP(launch_plasticity(a_train[0], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out, f.ws + p.off_part, st));
+        return EGERIA_OK;
+    }
+    EG_HIP(launch_absmax(x, x_dt, p.M * desc->hidden, f.slot(0), st));
+    const float *cur = (const float *)x;
+    for (int l = 0; l < p.n_layers; ++l) {
+        float *out = a_ref ? a_ref + (size_t)l * aref_elems : (float *)(f.ws + p.off_aref[l & 1]);
+        EG_OK(forward_bert_layer(f, l, cur, out, l + 1 == p.n_layers));
+        if (eval)
+            EG_HIP(launch_plasticity(a_train[l], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out + l,
+                                     f.ws + p.off_part, st));
+        cur = out;
+    }
+    return EGERIA_OK;
+}
+
+egeria_status egeria_ref_forward(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
+                                 egeria_dtype x_dt, float *a_ref, const egeria_taps *taps, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    Plan p;
+    EG_OK(check_common(desc, qw, x, x_dt, taps, ws, ws_bytes, p));
+    if (!a_ref || !aligned16(a_ref)) return EGERIA_ERR_INVALID_ARG;
+    if (ws_bytes < p.fwd_bytes) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    return forward_impl(desc, qw, x, x_dt, a_ref, taps, nullptr, EGERIA_F32, nullptr, ws, p, (hipStream_t)stream);
+}
+
+size_t egeria_plasticity_workspace_bytes(int32_t b, int64_t D)
+{
+    if (b < 1 || b > 128 || D < 1) return 0;
+    return plasticity_partial_bytes(b, D);
+}
+
+egeria_status egeria_plasticity(const void *a_train, egeria_dtype t_dt, const void *a_ref, egeria_dtype r_dt,
+                                int32_t b, int64_t D, float *p_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!a_train || !a_ref || !p_out || !ws || b < 1 || D < 1) return EGERIA_ERR_INVALID_ARG;
+    if (!aligned16(a_train) || !aligned16(a_ref) || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
+    if ((t_dt != EGERIA_F32 && t_dt != EGERIA_BF16) || (r_dt != EGERIA_F32 && r_dt != EGERIA_BF16))
+        return EGERIA_ERR_INVALID_ARG;
+    if (b > 128) return EGERIA_ERR_UNSUPPORTED;
+    if (ws_bytes < plasticity_partial_bytes(b, D)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    EG_HIP(launch_plasticity(a_train, t_dt, a_ref, r_dt, b, D, p_out, ws, (hipStream_t)stream));
+    return EGERIA_OK;
+}
+
+egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
+                                     egeria_dtype x_dt, const void *const *a_train, egeria_dtype t_dt,
+                                     float *p_out, void *ws, size_t ws_bytes, void *stream)
+{
+    Plan p;
+    EG_OK(check_common(desc, qw, x, x_dt, nullptr, ws, ws_bytes, p));
+    if (!a_train || !p_out) return EGERIA_ERR_INVALID_ARG;
+    if (t_dt != EGERIA_F32 && t_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    for (int l = 0; l < p.n_layers; ++l)
+        if (!a_train[l] || !aligned16(a_train[l])) return EGERIA_ERR_INVALID_ARG;
+    if (desc->batch > 128) return EGERIA_ERR_UNSUPPORTED;
+    if (ws_bytes < p.total) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    return forward_impl(desc, qw, x, x_dt, nullptr, nullptr, a_train, t_dt, p_out, ws, p, (hipStream_t)stream);
+}
+
+egeria_status egeria_check(void *ws, void *stream)
+{
+    if (!ws) return EGERIA_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t flag = 0;
+    EG_HIP(hipMemcpyAsync(&flag, ws, 4, hipMemcpyDeviceToHost, st));
+    EG_HIP(hipStreamSynchronize(st));
+    if ((flag & 0xffffff00u) != kFlagMagic) return EGERIA_OK;     // workspace never used
+    if (flag & kFlagNonFinite) {
+        const uint32_t clean = kFlagMagic;
+        EG_HIP(hipMemcpyAsync(ws, &clean, 4, hipMemcpyHostToDevice, st));
+        EG_HIP(hipStreamSynchronize(st));
+        return EGERIA_ERR_NONFINITE;
+    }
+    return EGERIA_OK;
+}
+
+const char *egeria_status_string(egeria_status s)
+{
+    switch (s) {
+    case EGERIA_OK: return "ok";
+    case EGERIA_ERR_INVALID_ARG: return "invalid argument";
+    case EGERIA_ERR_UNSUPPORTED: return "unsupported shape or type";
+    case EGERIA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case EGERIA_ERR_NONFINITE: return "non-finite value met by a quantiser";
+    case EGERIA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

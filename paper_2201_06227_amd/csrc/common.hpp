@@ -1,0 +1,116 @@
+// Shared declarations of the gfx950 kernels behind include/egeria.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/egeria.h"
+
+namespace egeria {
+
+constexpr int kWave = 64;
+
+// ---- workspace header -------------------------------------------------------
+// word 0            : flag word, kFlagMagic | bits (bit 0: a quantiser met NaN/Inf)
+// words 16 .. 16+S  : one absmax slot per quantise point (bit pattern of a
+//                     non-negative fp32, combined with integer atomicMax)
+// then S fp32 scales, one per quantise point.
+constexpr uint32_t kFlagMagic = 0xE6E71A00u;
+constexpr uint32_t kFlagNonFinite = 1u;
+constexpr int kHeaderFixedWords = 16;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t header_bytes(int slots) { return align_up(4 * (size_t)(kHeaderFixedWords + 2 * slots), 256); }
+inline uint32_t *ws_flag(void *ws) { return (uint32_t *)ws; }
+inline uint32_t *ws_absmax(void *ws, int slot) { return (uint32_t *)ws + kHeaderFixedWords + slot; }
+inline float *ws_scale(void *ws, int slots, int slot) { return (float *)ws + kHeaderFixedWords + slots + slot; }
+
+// ---- launchers (each enqueues on `st` and returns hipGetLastError()) --------
+hipError_t launch_header_reset(void *ws, int slots, hipStream_t st);
+
+// max |x| over n values into *slot (atomicMax on the bit pattern; slot must have
+// been reset in stream order before).
+hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *slot, hipStream_t st);
+
+// Quantise a [rows, cols] matrix into int8 [rows, ldq] (ldq >= cols, multiple of
+// 16, pad bytes zero) with the scale derived from *slot (or *fixed_scale).
+// Writes the scale to scale_out and, if non-null, scale_out2.
+hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
+                                int64_t ldq, const uint32_t *slot, const float *fixed_scale,
+                                int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
+                                hipStream_t st);
+
+// Quantise [n, c, hw] (channel-major) into int8 [n, hw, cp] (channel-last, cp =
+// padded c, pad zero).
+hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
+                                int64_t cp, const uint32_t *slot, const float *fixed_scale,
+                                int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
+                                hipStream_t st);
+
+hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
+
+// int8 GEMM / implicit-GEMM convolution with fused dequantising epilogue.
+struct GemmArgs {
+    const int8_t *a;        // activations: [M, lda] (linear, 1x1 conv) or [B, H, W, cp] (3x3 conv)
+    const int8_t *w;        // weights [N, kp]
+    int64_t M;
+    int32_t N;
+    int32_t kp;             // padded reduction length in bytes (multiple of 16)
+    int64_t lda;            // row stride of `a` in bytes (linear mode)
+    int32_t conv3x3;        // 0: rows of `a` are contiguous; 1: 3x3 window gather, zero padding 1
+    int32_t H, W, cp;       // image height, width and padded channels (conv3x3 mode)
+    const float *sx;        // 1 fp32: scale of the activations
+    const float *sw;        // 1 fp32: scale of the weights
+    const float *bias;      // [N] or null
+    int32_t act;            // 0 none, 1 ReLU, 2 GELU (erf form)
+    const int8_t *res_q;    // optional residual as int8 [M, res_ld] with scale *res_scale
+    const float *res_scale;
+    int64_t res_ld;
+    float *y;               // fp32 out [M, ldy]
+    int64_t ldy;
+    int32_t *acc_out;       // optional raw accumulators [M, N]
+    uint32_t *absmax_out;   // optional: atomicMax of |y| (bit pattern)
+};
+hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
+
+// y = LN(x + res) over rows of length H, optional atomicMax of |y|.
+hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int32_t H,
+                            const float *gamma, const float *beta, float eps, float *y,
+                            uint32_t *absmax_out, hipStream_t st);
+
+// Multi-head self-attention on packed qkv [B, S, 3*Hd] -> ctx [B, S, Hd];
+// optional atomicMax of |ctx|.
+hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads,
+                            float *ctx, uint32_t *absmax_out, hipStream_t st);
+
+// Training plasticity.  ws_part must hold plasticity_partial_bytes(b, D).
+size_t plasticity_partial_bytes(int32_t b, int64_t D);
+hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r, egeria_dtype r_dt,
+                             int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st);
+
+// ---- device helpers ------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+// |v| as a bit pattern whose unsigned order is the order of |v|; NaN and Inf
+// compare above every finite value.
+__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+#endif
+
+}  // namespace egeria

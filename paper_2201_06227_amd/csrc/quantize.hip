@@ -1,0 +1,301 @@
+// Per-tensor symmetric int8 quantisation (Section 4.1 of the paper: the
+// reference model is an int8 post-training-quantised snapshot).  Two coalesced
+// HBM passes per tensor: an absolute-maximum reduction, then the map to codes.
+#include "common.hpp"
+
+namespace egeria {
+
+// ---- header reset ---------------------------------------------------------------
+__global__ void header_reset_kernel(uint32_t *ws, int slots)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) {
+        uint32_t f = ws[0];
+        if ((f & 0xffffff00u) != kFlagMagic) ws[0] = kFlagMagic;   // first use of this memory
+    }
+    if (t < slots) ws[kHeaderFixedWords + t] = 0u;
+}
+
+hipError_t launch_header_reset(void *ws, int slots, hipStream_t st)
+{
+    int threads = 256, blocks = (slots + threads) / threads;
+    hipLaunchKernelGGL(header_reset_kernel, dim3(blocks), dim3(threads), 0, st, (uint32_t *)ws, slots);
+    return hipGetLastError();
+}
+
+// ---- absolute maximum -------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv, int64_t n,
+                                                     uint32_t *__restrict__ slot)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
+    uint32_t m = 0;
+    if (!BF16) {
+        const float *x = (const float *)xv;
+        const int64_t n4 = n >> 2;
+        const float4 *x4 = (const float4 *)x;
+        for (int64_t i = tid; i < n4; i += nthreads) {
+            float4 v = x4[i];
+            uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
+            a = a > b ? a : b;
+            c = c > d ? c : d;
+            a = a > c ? a : c;
+            m = m > a ? m : a;
+        }
+        for (int64_t i = (n4 << 2) + tid; i < n; i += nthreads) {
+            uint32_t a = abs_bits(x[i]);
+            m = m > a ? m : a;
+        }
+    } else {
+        const uint16_t *x = (const uint16_t *)xv;
+        const int64_t n8 = n >> 3;
+        const uint4 *x8 = (const uint4 *)x;
+        for (int64_t i = tid; i < n8; i += nthreads) {
+            uint4 v = x8[i];
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t lo = (w[j] << 16) & 0x7fffffffu, hi = w[j] & 0x7fff0000u;
+                lo = lo > hi ? lo : hi;
+                m = m > lo ? m : lo;
+            }
+        }
+        for (int64_t i = (n8 << 3) + tid; i < n; i += nthreads) {
+            uint32_t a = ((uint32_t)x[i] << 16) & 0x7fffffffu;
+            m = m > a ? m : a;
+        }
+    }
+    m = wave_max_u32(m);
+    __shared__ uint32_t sm[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) sm[wv] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = sm[0] > sm[1] ? sm[0] : sm[1], b = sm[2] > sm[3] ? sm[2] : sm[3];
+        a = a > b ? a : b;
+        if (a) atomicMax(slot, a);
+    }
+}
+
+hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *slot, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const int threads = 256;
+    const int64_t per = dt == EGERIA_F32 ? 4 : 8;
+    int64_t blocks = (n / per + threads * 4 - 1) / (threads * 4);     // ~4 vectors per thread
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    if (dt == EGERIA_F32)
+        hipLaunchKernelGGL(absmax_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x, n, slot);
+    else
+        hipLaunchKernelGGL(absmax_kernel<true>, dim3((unsigned)blocks), dim3(threads), 0, st, x, n, slot);
+    return hipGetLastError();
+}
+
+// ---- scale from absmax --------------------------------------------------------------
+// Returns the multiplier inv and writes the scale; sets *bad when the tensor
+// holds a NaN or an infinity.
+__device__ __forceinline__ float scales_from(const uint32_t *slot, const float *fixed_scale,
+                                             float *scale, bool *bad)
+{
+    float inv, sc;
+    *bad = false;
+    if (fixed_scale) {
+        sc = *fixed_scale;
+        inv = (float)(1.0 / (double)sc);
+        if (slot && *slot >= 0x7f800000u) *bad = true;
+    } else {
+        uint32_t bits = *slot;
+        if (bits >= 0x7f800000u) { *bad = true; bits = 0; }
+        float absmax = __uint_as_float(bits);
+        sc = (float)((double)absmax / 127.0);
+        inv = (float)(127.0 / (double)absmax);
+    }
+    if (!(inv <= 3.402823466e+38f) || !(sc > 0.0f)) { sc = 1.0f; inv = 0.0f; }
+    *scale = sc;
+    return inv;
+}
+
+__device__ __forceinline__ uint32_t quant1(float x, float inv)
+{
+    float r = rintf(x * inv);                 // one fp32 multiply, round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (uint32_t)((int)r) & 0xffu;
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void *x, int64_t i)
+{
+    if (BF16) return bf16_to_f32(((const uint16_t *)x)[i]);
+    return ((const float *)x)[i];
+}
+
+// ---- quantise [rows, cols] -> int8 [rows, ldq] ---------------------------------------
+// One thread produces 16 consecutive codes of one row (one 16-byte store).
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(
+    const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
+    const uint32_t *__restrict__ slot, const float *__restrict__ fixed_scale,
+    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
+    uint32_t *__restrict__ flag)
+{
+    float scale;
+    bool bad;
+    const float inv = scales_from(slot, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *scale_out = scale;
+        if (scale_out2) *scale_out2 = scale;
+        if (bad && flag) atomicOr(flag, kFlagNonFinite);
+    }
+    const int64_t upr = (ldq + 15) >> 4;                     // 16-byte units per row
+    const int64_t units = rows * upr;
+    const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
+         u += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = u / upr;
+        const int64_t c0 = (u - row * upr) << 4;
+        const int64_t base = row * cols + c0;
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (vec_ok && c0 + 16 <= cols) {
+            if (!BF16) {
+                const float4 *p = (const float4 *)((const float *)x + base);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float4 v = p[j];
+                    w[j] = quant1(v.x, inv) | (quant1(v.y, inv) << 8) | (quant1(v.z, inv) << 16) |
+                           (quant1(v.w, inv) << 24);
+                }
+            } else {
+                const uint4 *p = (const uint4 *)((const uint16_t *)x + base);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    uint4 v = p[j];
+                    uint32_t s[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uint32_t lo = quant1(__uint_as_float(s[e] << 16), inv);
+                        uint32_t hi = quant1(__uint_as_float(s[e] & 0xffff0000u), inv);
+                        int o = j * 8 + e * 2;
+                        w[o >> 2] |= (lo << ((o & 3) * 8)) | (hi << (((o + 1) & 3) * 8));
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (c0 + e < cols) w[e >> 2] |= quant1(load_elem<BF16>(x, base + e), inv) << ((e & 3) * 8);
+        }
+        int8_t *dst = q + row * ldq + c0;
+        if (c0 + 16 <= ldq && (((row * ldq) & 15) == 0)) {
+            *(uint4 *)dst = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            for (int e = 0; e < 16 && c0 + e < ldq; ++e) dst[e] = (int8_t)((w[e >> 2] >> ((e & 3) * 8)) & 0xff);
+        }
+    }
+}
+
+hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
+                                int64_t ldq, const uint32_t *slot, const float *fixed_scale,
+                                int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
+                                hipStream_t st)
+{
+    const int threads = 256;
+    int64_t units = rows * ((ldq + 15) / 16);
+    int64_t blocks = (units + threads - 1) / threads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    if (dt == EGERIA_F32)
+        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x,
+                           rows, cols, ldq, slot, fixed_scale, q, scale_out, scale_out2, flag);
+    else
+        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3((unsigned)blocks), dim3(threads), 0, st, x,
+                           rows, cols, ldq, slot, fixed_scale, q, scale_out, scale_out2, flag);
+    return hipGetLastError();
+}
+
+// ---- quantise [n, c, hw] -> int8 [n, hw, cp] -------------------------------------------
+// A workgroup transposes a tile of 64 pixels x 64 channels through LDS: reads
+// are contiguous along the pixel axis, writes along the channel axis.
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_nchw_kernel(
+    const void *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
+    const uint32_t *__restrict__ slot, const float *__restrict__ fixed_scale,
+    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
+    uint32_t *__restrict__ flag)
+{
+    float scale;
+    bool bad;
+    const float inv = scales_from(slot, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+        *scale_out = scale;
+        if (scale_out2) *scale_out2 = scale;
+        if (bad && flag) atomicOr(flag, kFlagNonFinite);
+    }
+    __shared__ uint8_t tile[64][64 + 4];                  // [pixel][channel], padded rows
+    const int64_t img = blockIdx.z;
+    const int64_t p0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
+    const int tp = threadIdx.x & 63, tc = threadIdx.x >> 6;   // pixel lane, channel phase
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const int64_t ch = c0 + tc + 4 * i, p = p0 + tp;
+        uint32_t code = 0;
+        if (ch < c && p < hw) code = quant1(load_elem<BF16>(x, (img * c + ch) * hw + p), inv);
+        tile[tp][tc + 4 * i] = (uint8_t)code;
+    }
+    __syncthreads();
+    // 64 pixels x 4 units of 16 channels = 256 stores of 16 bytes
+    const int pix = threadIdx.x >> 2, un = threadIdx.x & 3;
+    const int64_t p = p0 + pix, ch0 = c0 + un * 16;
+    if (p < hw && ch0 < cp) {
+        const uint32_t *src = (const uint32_t *)&tile[pix][un * 16];
+        *(uint4 *)(q + (img * hw + p) * cp + ch0) = make_uint4(src[0], src[1], src[2], src[3]);
+    }
+}
+
+hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
+                                int64_t cp, const uint32_t *slot, const float *fixed_scale,
+                                int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
+                                hipStream_t st)
+{
+    dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n);
+    if (dt == EGERIA_F32)
+        hipLaunchKernelGGL(quantize_nchw_kernel<false>, grid, dim3(256), 0, st, x, n, c, hw, cp, slot,
+                           fixed_scale, q, scale_out, scale_out2, flag);
+    else
+        hipLaunchKernelGGL(quantize_nchw_kernel<true>, grid, dim3(256), 0, st, x, n, c, hw, cp, slot,
+                           fixed_scale, q, scale_out, scale_out2, flag);
+    return hipGetLastError();
+}
+
+// ---- dequantise ------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequantize_kernel(const int8_t *__restrict__ q,
+                                                         const float *__restrict__ scale, int64_t n,
+                                                         float *__restrict__ x)
+{
+    const float s = *scale;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        x[i] = (float)q[i] * s;
+}
+
+hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, q, scale, n, x);
+    return hipGetLastError();
+}
+
+}  // namespace egeria

@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI that need no GPU: the shared library loads,
+exports every function include/egeria.h declares, sizes workspaces sanely and
+rejects bad arguments before anything would be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def eg():
+    from paper_2201_06227_amd import _build, binding
+    if _build.is_stale():
+        _build.build_library()
+    binding.lib()
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "egeria.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(egeria_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(eg):
+    names = declared_functions()
+    assert len(names) >= 13
+    L = ctypes.CDLL(eg.library_path())
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(eg.EXPORTS) == names
+
+
+def test_status_strings_and_padding(eg):
+    assert eg.status_string(eg.OK) == "ok"
+    assert len({eg.status_string(c) for c in range(6)}) == 6
+    assert [eg.padded(k) for k in (0, 1, 16, 17, 144, 3072)] == [0, 16, 16, 32, 144, 3072]
+
+
+def test_workspace_sizes(eg):
+    d = eg.make_desc(eg.FC_RELU, dict(batch=32, c_in=512, c_out=512))
+    assert eg.workspace_bytes(d) >= 32 * 512 + 32 * 512 * 4
+    bad = eg.make_desc(eg.FC_RELU, dict(batch=0, c_in=512, c_out=512))
+    assert eg.workspace_bytes(bad) == 0
+    bad = eg.make_desc(eg.BOTTLENECK, dict(batch=2, c_in=32, c_mid=8, c_out=16, height=4, width=4, has_residual=1))
+    assert eg.workspace_bytes(bad) == 0          # the skip connection needs c_out == c_in
+    stack = eg.make_desc(eg.BERT_STACK, dict(batch=64, seq=256, hidden=768, heads=12, ffn=3072, n_layers=12,
+                                             ln_eps=1e-12))
+    one = eg.make_desc(eg.BERT_LAYER, dict(batch=64, seq=256, hidden=768, heads=12, ffn=3072, n_layers=1,
+                                           ln_eps=1e-12))
+    assert eg.workspace_bytes(stack) > eg.workspace_bytes(one) > 64 * 256 * 3072 * 4
+    assert eg.plasticity_workspace_bytes(128, 16384) >= 2 * 128 * 128 * 8
+    assert eg.plasticity_workspace_bytes(129, 16) == 0 and eg.plasticity_workspace_bytes(0, 16) == 0
+    assert eg.quantize_workspace_bytes() >= 64
+
+
+def test_bad_arguments_are_rejected_on_the_host(eg):
+    L = eg.lib()
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    assert L.egeria_quantize(null, eg.F32, 16, null, fake, fake, fake, 4096, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_quantize(fake, eg.F32, -1, null, fake, fake, fake, 4096, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_quantize(odd, eg.F32, 16, null, fake, fake, fake, 4096, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_quantize(fake, 7, 16, null, fake, fake, fake, 4096, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_quantize(fake, eg.F32, 16, null, fake, fake, fake, 8, null) == eg.ERR_WORKSPACE_TOO_SMALL
+    assert L.egeria_plasticity(fake, eg.F32, fake, eg.F32, 0, 10, fake, fake, 1 << 20, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_plasticity(fake, eg.F32, fake, eg.F32, 129, 10, fake, fake, 1 << 20, null) == eg.ERR_UNSUPPORTED
+    assert L.egeria_plasticity(fake, eg.F32, fake, eg.F32, 8, 10, fake, fake, 16, null) == eg.ERR_WORKSPACE_TOO_SMALL
+    assert L.egeria_plasticity(fake, eg.F32, null, eg.F32, 8, 10, fake, fake, 1 << 20, null) == eg.ERR_INVALID_ARG
+    d = eg.make_desc(eg.FC_RELU, dict(batch=4, c_in=8, c_out=8))
+    qw = eg.QWeights()
+    qw.n_linear = 2                        # an FC module has exactly one linear layer
+    arr = (eg.QLinear * 2)()
+    qw.linear = arr
+    assert L.egeria_ref_forward(ctypes.byref(d), ctypes.byref(qw), fake, eg.F32, fake, None, fake, 1 << 20,
+                                null) == eg.ERR_INVALID_ARG
+    qw.n_linear = 1
+    assert L.egeria_ref_forward(ctypes.byref(d), ctypes.byref(qw), fake, eg.F32, fake, None, fake, 1 << 20,
+                                null) == eg.ERR_INVALID_ARG      # null weight pointers
+    arr[0].w_q, arr[0].scale = 0x2000, 0x3000
+    assert L.egeria_ref_forward(ctypes.byref(d), ctypes.byref(qw), fake, eg.F32, fake, None, fake, 16,
+                                null) == eg.ERR_WORKSPACE_TOO_SMALL
+    big = eg.make_desc(eg.BERT_LAYER, dict(batch=2, seq=8, hidden=256, heads=2, ffn=64, n_layers=1))
+    qw4 = eg.QWeights()
+    arr4 = (eg.QLinear * 4)()
+    for i in range(4):
+        arr4[i].w_q, arr4[i].scale = 0x2000, 0x3000
+    qw4.n_linear, qw4.linear = 4, arr4
+    assert L.egeria_ref_forward(ctypes.byref(big), ctypes.byref(qw4), fake, eg.F32, fake, None, fake, 1 << 30,
+                                null) == eg.ERR_UNSUPPORTED      # head dimension 128 > 64
+
+
+def test_missing_library_fails_loudly(eg, monkeypatch, tmp_path):
+    from paper_2201_06227_amd import _build
+    monkeypatch.setattr(eg, "_lib", None)
+    monkeypatch.setattr(_build, "LIB", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        eg.lib()

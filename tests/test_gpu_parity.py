@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU
+oracle on the same seeded inputs.
+
+Bars: int8 codes, scales and int32 accumulators bit-exact; fp32 activations of
+the convolution / FC modules bit-exact too (their arithmetic is +, x, fma, max,
+rint in a fixed order); plasticity within 1e-4 relative of the fp64 oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eg():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2201_06227_amd import binding
+    binding.lib()                      # raises if the HIP library has not been built
+    return binding
+
+
+@pytest.fixture(scope="module")
+def gc():
+    import gpu_common
+    return gpu_common
+
+
+P_RTOL = 1e-4
+
+
+def p_close(got, want, b):
+    return abs(got - want) <= P_RTOL * abs(want) + 1e-12 * 4.0 / b
+
+
+# --------------------------------------------------------------------------- quantise
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 1000, 4099, (1 << 20) + 3])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_quantize_flat_bit_exact(eg, gc, orc, n, dtype):
+    rng = np.random.default_rng(100 + n)
+    x = (rng.standard_normal(n) * 3).astype(np.float32)
+    xt = gc.to_dev(x)
+    if dtype == "bf16":
+        xt = xt.to(torch.bfloat16)
+        x = xt.float().cpu().numpy()
+    q, s = eg.quantize(xt)
+    want_q, want_s = orc.quantize(x)
+    assert s.cpu().numpy()[0] == want_s
+    assert (q.cpu().numpy() == want_q).all()
+    xh = eg.dequantize(q, s).cpu().numpy()
+    assert (xh == orc.dequantize(want_q, want_s)).all()
+
+
+def test_quantize_special_tensors(eg, gc, orc):
+    ws = eg.workspace(eg.quantize_workspace_bytes())
+    for x in (np.zeros(100, np.float32), np.full(33, 1e-40, np.float32),
+              np.array([127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5], np.float32)):
+        q, s = eg.quantize(gc.to_dev(x), ws=ws)
+        wq, wsc = orc.quantize(x)
+        assert s.item() == wsc and (q.cpu().numpy() == wq).all()
+    assert eg.check(ws) == eg.OK
+    # static scale saturates
+    x = np.array([0.26, -3.0, 100.0, 0.24] * 5, np.float32)
+    q, s = eg.quantize(gc.to_dev(x), fixed_scale=gc.to_dev(np.array([0.5], np.float32)), ws=ws)
+    wq, wsc = orc.quantize(x, fixed_scale=0.5)
+    assert s.item() == wsc and (q.cpu().numpy() == wq).all()
+    # non-finite input raises the workspace flag, once
+    for bad in (np.nan, np.inf):
+        xb = np.ones(1000, np.float32)
+        xb[777] = bad
+        eg.quantize(gc.to_dev(xb), ws=ws)
+        assert eg.check(ws) == eg.ERR_NONFINITE
+        assert eg.check(ws) == eg.OK
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (3, 5), (7, 16), (33, 100), (64, 768), (130, 3072)])
+def test_quantize_rows_bit_exact(eg, gc, orc, shape):
+    rng = np.random.default_rng(sum(shape))
+    x = rng.standard_normal(shape).astype(np.float32)
+    q, s = eg.quantize_rows(gc.to_dev(x))
+    wq, wsc = orc.quantize(x)
+    assert s.item() == wsc
+    gc.assert_int8_rows(q.cpu().numpy(), wq)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 5, 7), (16, 16, 3, 3), (3, 70, 9, 9),
+                                   (2, 256, 14, 14), (4, 16, 32, 32)])
+def test_quantize_nchw_bit_exact(eg, gc, orc, shape):
+    rng = np.random.default_rng(sum(shape))
+    x = rng.standard_normal(shape).astype(np.float32)
+    q, s = eg.quantize_nchw(gc.to_dev(x))
+    wq, wsc = orc.quantize(x)
+    assert s.item() == wsc
+    gc.assert_conv_q(q.cpu().numpy().reshape(-1, q.shape[-1]), wq)
+
+
+# --------------------------------------------------------------------------- FC / conv modules
+
+def _check_linear_taps(gc, taps, ot, prefix, conv):
+    xq, acc, y = ot[prefix + "xq"], ot[prefix + "acc"], ot[prefix + "y"]
+    assert taps["x_scale"][0] == ot[prefix + "sx"]
+    if conv:
+        gc.assert_conv_q(taps["x_q"], xq)
+        assert (taps["acc"] == gc.nhwc(acc)).all()
+        assert (taps["y"] == gc.nhwc(y)).all()
+    else:
+        gc.assert_int8_rows(taps["x_q"], xq.reshape(-1, xq.shape[-1]))
+        assert (taps["acc"] == acc).all()
+        assert (taps["y"] == y).all()
+
+
+FC_CASES = [dict(b=1, k=1, n=1), dict(b=5, k=100, n=7), dict(b=130, k=200, n=257),
+            dict(b=64, k=3072, n=96), dict(b=32, k=512, n=512)]
+
+
+@pytest.mark.parametrize("kw", FC_CASES, ids=lambda k: "b{b}_k{k}_n{n}".format(**k))
+def test_fc_module_bit_exact(eg, gc, orc, kw):
+    wl = si.make_fc(seed=200 + kw["k"], **kw)
+    a_ref, taps, _ = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    _check_linear_taps(gc, taps[0], ot, "l0.", conv=False)
+    assert (a_ref[0] == ot["a_ref"]).all()
+
+
+BASIC_CASES = [dict(b=1, c=1, h=1, w=1), dict(b=3, c=8, h=7, w=6), dict(b=2, c=20, h=9, w=11),
+               dict(b=5, c=16, h=32, w=32), dict(b=2, c=64, h=13, w=13)]
+
+
+@pytest.mark.parametrize("kw", BASIC_CASES, ids=lambda k: "b{b}_c{c}_{h}x{w}".format(**k))
+def test_basic_block_bit_exact(eg, gc, orc, kw):
+    wl = si.make_basic_block(seed=300 + kw["c"], **kw)
+    a_ref, taps, _ = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    for i in range(2):
+        _check_linear_taps(gc, taps[i], ot, f"l{i}.", conv=True)
+    assert (a_ref[0].reshape(-1, kw["c"]) == gc.nhwc(ot["a_ref"])).all()
+
+
+BOTTLENECK_CASES = [dict(b=2, c_in=32, c_mid=16, h=5, w=5), dict(b=1, c_in=40, c_mid=24, h=7, w=3),
+                    dict(b=3, c_in=256, c_mid=64, h=14, w=14),
+                    dict(b=2, c_in=32, c_mid=16, h=5, w=5, has_residual=0)]
+
+
+@pytest.mark.parametrize("kw", BOTTLENECK_CASES,
+                         ids=lambda k: "b{b}_c{c_in}_{c_mid}_{h}x{w}_r{r}".format(r=k.get("has_residual", 1), **k))
+def test_bottleneck_bit_exact(eg, gc, orc, kw):
+    wl = si.make_bottleneck(seed=400 + kw["c_in"], **kw)
+    a_ref, taps, _ = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    for i in range(3):
+        _check_linear_taps(gc, taps[i], ot, f"l{i}.", conv=True)
+    assert (a_ref[0].reshape(-1, kw["c_in"]) == gc.nhwc(ot["a_ref"])).all()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_full_size_configs_bit_exact_and_scored(eg, gc, orc, cfg):
+    """Configs 1-3 at full size: every observation point bit-exact, and the
+    fused forward + score call within tolerance of the oracle's score."""
+    wl = si.make_config(cfg)
+    a_ref, taps, ref = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    conv = cfg != 1
+    for i in range(len(taps)):
+        _check_linear_taps(gc, taps[i], ot, f"l{i}.", conv=conv)
+    want = gc.nhwc(ot["a_ref"]).reshape(wl.batch, -1) if conv else ot["a_ref"]
+    assert (a_ref[0] == want).all()
+    a_t = si.train_forward(wl)[0]
+    p_want = orc.sp_loss(a_t.float().numpy(), want)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc))
+    p = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, gc.to_dev(wl.x), [a_t.to(gc.DEV)], p, ws)
+    torch.cuda.synchronize()
+    assert p_close(p.item(), p_want, wl.batch), (p.item(), p_want)
+
+
+# --------------------------------------------------------------------------- metric
+
+METRIC_CASES = [(1, 7), (2, 1), (2, 3), (4, 4), (5, 129), (8, 300), (31, 1000), (32, 512), (33, 515),
+                (64, 4096), (100, 2050), (128, 16384), (128, 777)]
+
+
+@pytest.mark.parametrize("b,D", METRIC_CASES)
+@pytest.mark.parametrize("rel", [0.3, 1e-3])
+def test_plasticity_matches_oracle(eg, gc, orc, b, D, rel):
+    a_t, a_r = si.noisy_pair(b, D, rel=rel, seed=500 + b + D)
+    p = eg.plasticity(gc.to_dev(a_t), gc.to_dev(a_r)).item()
+    want = orc.sp_loss(a_t, a_r)
+    assert p_close(p, want, b), (p, want)
+
+
+@pytest.mark.parametrize("b,D", [(8, 304), (32, 4096), (64, 1000)])
+def test_plasticity_bf16_training_activation(eg, gc, orc, b, D):
+    a_t, a_r = si.noisy_pair(b, D, rel=0.05, seed=600 + b)
+    t16 = gc.to_dev(a_t).to(torch.bfloat16)
+    want = orc.sp_loss(t16.float().cpu().numpy(), a_r)
+    assert p_close(eg.plasticity(t16, gc.to_dev(a_r)).item(), want, b)
+    r16 = gc.to_dev(a_r).to(torch.bfloat16)
+    want = orc.sp_loss(t16.float().cpu().numpy(), r16.float().cpu().numpy())
+    assert p_close(eg.plasticity(t16, r16).item(), want, b)
+
+
+def test_plasticity_golden_and_closed_forms(eg, gc, orc):
+    import os
+    from test_oracle_pins import _read_sp_cases
+    for c in _read_sp_cases():
+        p = eg.plasticity(gc.to_dev(c["T"]), gc.to_dev(c["R"])).item()
+        assert p_close(p, c["P"], c["b"]), (c["name"], p)
+    for b in (2, 32, 64, 128):
+        D = b + 5
+        q_t = np.zeros((b, D), np.float32)
+        q_t[np.arange(b), np.arange(b)] = 1 + np.arange(b) % 5
+        q_r = np.tile(np.linspace(0.5, 2, D, dtype=np.float32), (b, 1))
+        p = eg.plasticity(gc.to_dev(q_t), gc.to_dev(q_r)).item()
+        assert p_close(p, (2.0 / b) * (1 - 1 / math.sqrt(b)), b)
+
+
+def test_plasticity_invariants(eg, gc):
+    a_t, a_r = si.noisy_pair(16, 1000, rel=0.1, seed=700)
+    t, r = gc.to_dev(a_t), gc.to_dev(a_r)
+    assert eg.plasticity(t, t.clone()).item() == 0.0
+    p = eg.plasticity(t, r).item()
+    assert p > 0
+    assert eg.plasticity(t * 4, r * -0.125).item() == pytest.approx(p, rel=1e-5)
+    perm = torch.randperm(1000, device=gc.DEV)
+    assert eg.plasticity(t[:, perm].contiguous(), r).item() == pytest.approx(p, rel=1e-4)
+    # a zero row and a single sample stay finite
+    r0 = r.clone()
+    r0[3] = 0
+    assert math.isfinite(eg.plasticity(t, r0).item())
+    assert eg.plasticity(t[:1].contiguous(), r[:1].contiguous()).item() == 0.0
+    # same call twice: identical bits (partials are reduced in a fixed order)
+    assert eg.plasticity(t, r).item() == p
+
+
+@pytest.mark.parametrize("b,D,dt", [(128, 16384, "f32"), (64, 200704, "f32"), (32, 98304, "bf16"),
+                                    (64, 196608, "f32")])
+def test_plasticity_full_size_shapes(eg, gc, orc, b, D, dt):
+    a_t, a_r = si.noisy_pair(b, D, rel=0.01, seed=800 + b, nonneg=(D == 200704))
+    t = gc.to_dev(a_t)
+    if dt == "bf16":
+        t = t.to(torch.bfloat16)
+        a_t = t.float().cpu().numpy()
+    want = orc.sp_loss(a_t, a_r)
+    p = eg.plasticity(t, gc.to_dev(a_r)).item()
+    assert p_close(p, want, b), (p, want)
