@@ -160,7 +160,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g)
                 float v = fmaf((float)a, s, bc);
                 if (g.res_q) v = v + (float)g.res_q[row * g.res_ld + col] * rs;
                 if (g.act == 1) v = v > 0.0f ? v : 0.0f;
-                else if (g.act == 2) v = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+                else if (g.act == 2) {          // erf-form GELU in fp64, rounded once: it feeds a quantiser
+                    const double dv = (double)v;
+                    v = (float)(0.5 * dv * (1.0 + erf(dv * 0.70710678118654752440)));
+                }
                 g.y[row * g.ldy + col] = v;
                 const uint32_t ab = abs_bits(v);
                 amax = amax > ab ? amax : ab;

@@ -249,3 +249,104 @@ def test_plasticity_full_size_shapes(eg, gc, orc, b, D, dt):
     want = orc.sp_loss(a_t, a_r)
     p = eg.plasticity(t, gc.to_dev(a_r)).item()
     assert p_close(p, want, b), (p, want)
+
+
+# --------------------------------------------------------------------------- Transformer modules
+# Soft-max attention, layer norm and GELU sit between the int8 GEMMs.  A
+# last-bit difference in any of them can move a value across a quantisation
+# boundary, and an int8 code that differs is amplified by every later layer
+# (measured with an fp32 evaluation of that glue: 3% relative deviation of the
+# activation and up to 8% of the score after 12 layers).  Both sides therefore
+# evaluate the glue in fp64 and round once to fp32, which makes the chains agree
+# bit for bit on these seeded inputs: every int8 code, scale, accumulator and
+# fp32 tensor is compared for equality, as for the convolution modules.
+
+def _check_bert_layer_taps(gc, taps, ot, l):
+    for i in range(4):
+        t, pre = taps[4 * l + i], f"L{l}.l{i}."
+        xq = ot[pre + "xq"]
+        assert t["x_scale"][0] == ot[pre + "sx"], pre
+        gc.assert_int8_rows(t["x_q"], xq)
+        assert (t["acc"] == ot[pre + "acc"]).all(), pre
+        assert (t["y"] == ot[pre + "y"]).all(), pre
+
+
+BERT_CASES = [dict(b=2, s=12, hidden=48, heads=4, ffn=96, n_layers=1),
+              dict(b=3, s=40, hidden=128, heads=2, ffn=200, n_layers=1),
+              dict(b=2, s=130, hidden=192, heads=3, ffn=320, n_layers=3),
+              dict(b=1, s=1, hidden=64, heads=1, ffn=16, n_layers=2),
+              dict(b=8, s=64, hidden=768, heads=12, ffn=3072, n_layers=12)]
+
+
+@pytest.mark.parametrize("kw", BERT_CASES, ids=lambda k: "b{b}_s{s}_h{hidden}_L{n_layers}".format(**k))
+def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
+    wl = si.make_bert(seed=900 + kw["s"], train_act_dtype="f32", **kw)
+    a_ref, taps, ref = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    for l in range(kw["n_layers"]):
+        _check_bert_layer_taps(gc, taps, ot, l)
+        assert (a_ref[l] == ot["a_ref"][l].reshape(kw["b"], -1)).all()
+    a_t = si.train_forward(wl)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc))
+    p = torch.zeros(kw["n_layers"], dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, gc.to_dev(wl.x), [t.to(gc.DEV) for t in a_t], p, ws)
+    for l in range(kw["n_layers"]):
+        want = orc.sp_loss(a_t[l].numpy(), ot["a_ref"][l])
+        assert p_close(p[l].item(), want, kw["b"]), (l, p[l].item(), want)
+
+
+def test_bert_layer_full_size(eg, gc, orc):
+    """Config 4: BERT-base layer, batch 32 x seq 128, bf16 training activations."""
+    wl = si.make_config(4)
+    a_ref, taps, ref = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    _check_bert_layer_taps(gc, taps, ot, 0)
+    assert (a_ref[0] == ot["a_ref"][0].reshape(32, -1)).all()
+    a_t = si.train_forward(wl)
+    assert a_t[0].dtype == torch.bfloat16
+    ws = eg.workspace(eg.workspace_bytes(ref.desc))
+    p = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, gc.to_dev(wl.x), [a_t[0].to(gc.DEV)], p, ws)
+    want = orc.sp_loss(a_t[0].float().numpy(), ot["a_ref"][0])
+    assert p_close(p.item(), want, 32), (p.item(), want)
+
+
+def test_bert_stack_full_size(eg, gc, orc):
+    """Config 5: 12 layers, batch 64 x seq 256.  The oracle chain is run for the
+    first two layers at full size (the full depth is covered bit-exactly by the
+    12-layer case at batch 8 x seq 64 above); all 12 layers are also checked
+    through properties that hold at any size."""
+    wl = si.make_config(5)
+    ref = gc.build_reference(wl)
+    x = gc.to_dev(wl.x)
+    n, b, D = 12, wl.batch, 256 * 768
+    a_ref = torch.empty((n, b, D), dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc))
+    eg.ref_forward(ref, x, a_ref, ws)
+    torch.cuda.synchronize()
+    assert eg.check(ws) == eg.OK
+    # every token row of every layer is layer-normalised (gamma 1, beta 0)
+    rows = a_ref.reshape(n, -1, 768)
+    assert rows.mean(-1).abs().max().item() < 1e-5
+    assert (rows.var(-1, unbiased=False) - 1).abs().max().item() < 1e-4
+    # the first two layers against the oracle chain, bit for bit
+    import copy
+    wl2 = copy.copy(wl)
+    wl2.weights, wl2.biases = wl.weights[:8], wl.biases[:8]
+    wl2.dims = dict(wl.dims, n_layers=2)
+    ot = orc.ref_forward(wl2, keep_taps=False)
+    for l in range(2):
+        assert (a_ref[l].cpu().numpy() == ot["a_ref"][l].reshape(b, -1)).all()
+    # scores: fused call == separate metric call on the stored activations, bit for bit;
+    # every layer's score against the fp64 metric on the GPU chain's activation (identical
+    # to the oracle's for the layers compared above); layers 0-1 end to end
+    a_t = si.train_forward(wl, device=gc.DEV)
+    p = torch.zeros(n, dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, x, a_t, p, ws)
+    torch.cuda.synchronize()
+    for l in range(n):
+        assert eg.plasticity(a_t[l], a_ref[l]).item() == p[l].item()
+        assert 0 < p[l].item() < 4.0 / b
+    for l in range(2):
+        want = orc.sp_loss(a_t[l].cpu().numpy(), ot["a_ref"][l])
+        assert p_close(p[l].item(), want, b), (l, p[l].item(), want)
