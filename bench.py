@@ -1,0 +1,322 @@
+#!/usr/bin/env python3
+"""Benchmark of the plasticity-evaluation path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload N]
+
+A step is one whole evaluation of a layer module on one synthetic mini-batch:
+reference-model generation (int8 weight quantisation), the int8 reference
+forward, and the plasticity score of every layer of the module.  Inputs are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOAD_NAMES = {
+    1: "cfg1 FC 32x512x512 + ReLU",
+    2: "cfg2 ResNet-56 stage-1 basic block [128x16x32x32]",
+    3: "cfg3 ResNet-50 stage-3 bottleneck [64x1024x14x14]",
+    4: "cfg4 BERT-base encoder layer, batch 32 x seq 128, bf16 training activations",
+    5: "cfg5 BERT-base 12-layer encoder stack, batch 64 x seq 256",
+}
+
+PEAK_HBM_GBS = 8000.0
+PEAK_I8_TOPS = 5033.0        # dense int8 MFMA, 256 CUs x 8192 op/clk x 2.4 GHz
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_F64_MFMA_TFLOPS = 78.6
+
+
+def algorithmic_work(wl, cls, eg):
+    """Per step, for one kernel class: list of (ops, bytes) per launch, the
+    method's own arithmetic and the bytes it must move once (inputs read once,
+    outputs written once), independent of how the kernels are blocked."""
+    import synth_inputs as si
+    d = wl.dims
+    b = d["batch"]
+    out = []
+    if cls == eg.KERNEL_GRAM:
+        tsz = 2 if wl.train_act_dtype == "bf16" else 4
+        if wl.kind == si.KIND_FC_RELU:
+            D = d["c_out"]
+        elif wl.kind in (si.KIND_BASIC_BLOCK, si.KIND_BOTTLENECK):
+            D = d["height"] * d["width"] * d["c_out"]
+        else:
+            D = d["seq"] * d["hidden"]
+        for _ in range(d.get("n_layers", 1)):
+            out.append((2 * 2.0 * b * b * D, b * D * (tsz + 4.0)))       # two b x b x D Gram products
+    elif cls == eg.KERNEL_GEMM:
+        if wl.kind == si.KIND_FC_RELU:
+            shapes = [(b, d["c_out"], d["c_in"], d["c_in"], 0)]
+        elif wl.kind == si.KIND_BASIC_BLOCK:
+            M, c = b * d["height"] * d["width"], d["c_in"]
+            shapes = [(M, c, 9 * c, c, 0), (M, c, 9 * c, c, 1)]
+        elif wl.kind == si.KIND_BOTTLENECK:
+            M = b * d["height"] * d["width"]
+            shapes = [(M, d["c_mid"], d["c_in"], d["c_in"], 0), (M, d["c_mid"], 9 * d["c_mid"], d["c_mid"], 0),
+                      (M, d["c_out"], d["c_mid"], d["c_mid"], 1)]
+        else:
+            M, h, f = b * d["seq"], d["hidden"], d["ffn"]
+            shapes = [(M, 3 * h, h, h, 0), (M, h, h, h, 0), (M, f, h, h, 0), (M, h, f, f, 0)] * d["n_layers"]
+        for (M, N, K, kin, res) in shapes:
+            # int8 activations read once (not the im2col expansion), weights, fp32 output, int8 residual
+            out.append((2.0 * M * N * K, M * kin + N * K + 4.0 * M * N + (M * N if res else 0)))
+    elif cls == eg.KERNEL_ATTENTION:
+        M, h, S = b * d["seq"], d["hidden"], d["seq"]
+        for _ in range(d["n_layers"]):
+            out.append((4.0 * M * S * h, 4.0 * M * 3 * h + 4.0 * M * h))
+    return out
+
+
+def roofline_for(wl, cls, durations_ms, eg, steps):
+    """Achieved rate of one kernel class over the timed region against the
+    roofline that bounds it."""
+    work = algorithmic_work(wl, cls, eg)
+    names = {eg.KERNEL_GRAM: "gram_partial_kernel", eg.KERNEL_GEMM: "gemm_i8_kernel",
+             eg.KERNEL_ATTENTION: "attention_kernel"}
+    if not work or not durations_ms:
+        return None
+    per_step = len(work)
+    n_steps = len(durations_ms) // per_step
+    if n_steps == 0:
+        return None
+    total_s = sum(durations_ms[:n_steps * per_step]) * 1e-3
+    ops = sum(w[0] for w in work) * n_steps
+    byts = sum(w[1] for w in work) * n_steps
+    intensity = ops / byts
+    if cls == eg.KERNEL_GEMM:
+        peak_c, unit_c, scale = PEAK_I8_TOPS, "TOP/s", 1e12
+    elif cls == eg.KERNEL_ATTENTION:
+        peak_c, unit_c, scale = PEAK_F64_MFMA_TFLOPS, "TFLOP/s", 1e12
+    else:
+        peak_c, unit_c, scale = PEAK_F32_MFMA_TFLOPS, "TFLOP/s", 1e12
+    ridge = peak_c * scale / (PEAK_HBM_GBS * 1e9)
+    if intensity >= ridge:
+        achieved, peak, unit, bound = ops / total_s / scale, peak_c, unit_c, "mfma"
+    else:
+        achieved, peak, unit, bound = byts / total_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+    return {
+        "kernel": names[cls], "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+        "frac": round(achieved / peak, 4), "traffic": None,
+        "launches_per_step": per_step, "avg_launch_us": round(total_s / (n_steps * per_step) * 1e6, 3),
+        "algorithmic_ops_per_step": sum(w[0] for w in work), "algorithmic_bytes_per_step": sum(w[1] for w in work),
+        "intensity_op_per_byte": round(intensity, 2), "ridge_op_per_byte": round(ridge, 2),
+    }
+
+
+def setup(cfg, device):
+    import torch
+    import synth_inputs as si
+    from paper_2201_06227_amd import binding as eg
+    from paper_2201_06227_amd.evaluator import PlasticityEvaluator
+    wl = si.make_config(cfg)
+    dev = torch.device(device)
+    W = [torch.from_numpy(w).to(dev) for w in wl.weights]
+    B = [None if b is None else torch.from_numpy(b).to(dev) for b in wl.biases]
+    x = torch.from_numpy(wl.x).to(dev)
+    a_t = [t.contiguous() for t in si.train_forward(wl, device=device)]
+    ev = PlasticityEvaluator(wl.kind, wl.dims, W, B, device=device)
+    return wl, ev, x, a_t
+
+
+def time_steps(ev, x, a_t, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        ev.step(x, a_t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ev.step(x, a_t)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_breakdown(ev, x, a_t, eg, wl, steps=5):
+    """Average time per step of each kernel class (one class per pass)."""
+    import torch
+    names = {eg.KERNEL_ABSMAX: "absmax", eg.KERNEL_QUANTIZE: "quantize", eg.KERNEL_GEMM: "gemm_i8",
+             eg.KERNEL_GRAM: "gram_partial", eg.KERNEL_ATTENTION: "attention", eg.KERNEL_LAYERNORM: "layernorm"}
+    out = {}
+    cap = 4096
+    for cls, name in names.items():
+        eg.profile_begin(cls, cap)
+        for _ in range(steps):
+            ev.step(x, a_t)
+        torch.cuda.synchronize()
+        ms = eg.profile_end(cap)
+        if ms:
+            out[name] = {"us_per_step": round(sum(ms) / steps * 1e3, 2), "launches_per_step": len(ms) // steps}
+    return out
+
+
+def graph_replay(ev, x, a_t, steps, eager_p):
+    """Capture one step into a HIP graph and time its replays; every replay must
+    reproduce the eager scores bit for bit."""
+    import torch
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ev.step(x, a_t)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            ev.step(x, a_t)
+        ok = True
+        for _ in range(3):
+            ev.p_out.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            ok = ok and bool((ev.p_out == eager_p).all().item())
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        return {"ms_per_step": round(dt * 1e3, 4), "evals_per_s": round(ev.n_layers / dt, 2),
+                "replays_match_eager": ok}
+    except Exception as e:  # noqa: BLE001 - reported, never hidden
+        return {"error": f"{type(e).__name__}: {e}"}
+
+
+def cpu_baseline(cfg, budget_s=12.0):
+    """The CPU oracle as it stands, timed on this host on the same workload."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import oracle as orc
+    if cfg == 5:
+        # one full-size layer of the stack is ~1/12 of the workload and already takes seconds
+        wl = si.make_bert(b=64, s=256, n_layers=1, seed=si.SEED_BASE + 5, train_act_dtype="f32")
+        sample = "1 of the 12 layers at full batch (64 x 256 tokens), whole evaluation of that layer"
+    else:
+        wl = si.make_config(cfg)
+        sample = "whole workload, repeated"
+    a_t = [t.float().numpy() for t in si.train_forward(wl)]
+    n_layers = wl.dims.get("n_layers", 1)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        qw = orc.quantize_weights(wl.weights)
+        taps = orc.ref_forward(wl, qw, keep_taps=False)
+        a_ref = taps["a_ref"]
+        if wl.kind in (si.KIND_BASIC_BLOCK, si.KIND_BOTTLENECK):
+            a_ref = [np.ascontiguousarray(np.transpose(a_ref, (0, 2, 3, 1)))]
+        elif wl.kind == si.KIND_FC_RELU:
+            a_ref = [a_ref]
+        for l in range(n_layers):
+            orc.sp_loss(a_t[l], a_ref[l].reshape(a_t[l].shape))
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 200:
+            break
+    return {"value": round(reps * n_layers / el, 4), "unit": "evals/s", "cores": orc.num_threads(),
+            "kind": "oracle", "sample": f"{sample}; {reps} rep(s) in {el:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no multi-GPU leg (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    from paper_2201_06227_amd import _build, binding as eg
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    eg.lib()
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wl, ev, x, a_t = setup(args.workload, device)
+    # which kernel class dominates a step
+    for _ in range(3):
+        ev.step(x, a_t)
+    torch.cuda.synchronize()
+    breakdown = kernel_breakdown(ev, x, a_t, eg, wl)
+    timed_classes = {"gemm_i8": eg.KERNEL_GEMM, "gram_partial": eg.KERNEL_GRAM, "attention": eg.KERNEL_ATTENTION}
+    dominant = max((k for k in breakdown if k in timed_classes), key=lambda k: breakdown[k]["us_per_step"])
+    cls = timed_classes[dominant]
+    per_step = breakdown[dominant]["launches_per_step"]
+
+    # ---- the timed region: exactly K steps, the dominant kernel's launches bracketed by HIP events
+    for _ in range(args.warmup):
+        ev.step(x, a_t)
+    torch.cuda.synchronize()
+    eg.profile_begin(cls, args.steps * per_step)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev.step(x, a_t)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    durations = eg.profile_end(args.steps * per_step)
+    roof = roofline_for(wl, cls, durations, eg, args.steps)
+    eager_p = ev.p_out.clone()
+    if eg.check(ev.ws) != eg.OK or not bool(torch.isfinite(eager_p).all().item()):
+        print("non-finite values in the benchmark run", file=sys.stderr)
+        sys.exit(1)
+
+    result = {
+        "metric": "layer plasticity evals/s", "value": round(ev.n_layers / dt, 2), "unit": "evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.workload], "evals_per_step": ev.n_layers,
+                   "step": "weight quantise + int8 reference forward + plasticity score", "launch": "eager",
+                   "arithmetic": "int8 x int8 -> int32 contractions, fp32 epilogues and Gram products, fp64 finaliser"},
+        "roofline": roof,
+        "kernel_breakdown_us_per_step": breakdown,
+        "plasticity": [float(v) for v in eager_p.tolist()],
+    }
+    result["graph"] = graph_replay(ev, x, a_t, args.steps, eager_p)
+
+    if not args.no_others:
+        others = {}
+        del ev, x, a_t
+        torch.cuda.empty_cache()
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.workload:
+                continue
+            wl2, ev2, x2, a2 = setup(cfg, device)
+            k = 20 if cfg == 5 else 100
+            dt2 = time_steps(ev2, x2, a2, k, 5)
+            bd = kernel_breakdown(ev2, x2, a2, eg, wl2, steps=3)
+            dom = max((n for n in bd if n in timed_classes), key=lambda n: bd[n]["us_per_step"])
+            eg.profile_begin(timed_classes[dom], 4096)
+            for _ in range(3):
+                ev2.step(x2, a2)
+            torch.cuda.synchronize()
+            roof2 = roofline_for(wl2, timed_classes[dom], eg.profile_end(4096), eg, 3)
+            gr = graph_replay(ev2, x2, a2, k, ev2.p_out.clone())
+            others[f"cfg{cfg}"] = {"workload": WORKLOAD_NAMES[cfg], "evals_per_s": round(ev2.n_layers / dt2, 2),
+                                   "ms_per_step": round(dt2 * 1e3, 4), "steps": k, "graph": gr,
+                                   "roofline": roof2, "kernel_breakdown_us_per_step": bd}
+            del ev2, x2, a2, wl2
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

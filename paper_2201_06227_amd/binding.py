@@ -65,8 +65,11 @@ EXPORTS = [
     "egeria_padded", "egeria_quantize", "egeria_quantize_rows", "egeria_quantize_nchw",
     "egeria_dequantize", "egeria_quantize_workspace_bytes", "egeria_ref_forward",
     "egeria_plasticity", "egeria_plasticity_workspace_bytes", "egeria_plasticity_eval",
-    "egeria_workspace_bytes", "egeria_check", "egeria_status_string",
+    "egeria_workspace_bytes", "egeria_check", "egeria_status_string", "egeria_profile_begin",
+    "egeria_profile_end",
 ]
+
+KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM = range(7)
 
 
 def library_path() -> str:
@@ -109,6 +112,10 @@ def lib():
     L.egeria_workspace_bytes.argtypes = [ctypes.POINTER(BlockDesc)]
     L.egeria_check.restype = ctypes.c_int
     L.egeria_check.argtypes = [_vp, _vp]
+    L.egeria_profile_begin.restype = ctypes.c_int
+    L.egeria_profile_begin.argtypes = [_i32, _i32]
+    L.egeria_profile_end.restype = ctypes.c_int
+    L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
     L.egeria_status_string.restype = ctypes.c_char_p
     L.egeria_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -327,3 +334,15 @@ def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torc
 def check(ws: torch.Tensor) -> int:
     """egeria_check: status code (OK or ERR_NONFINITE); synchronises the stream."""
     return int(lib().egeria_check(_ptr(ws), _stream()))
+
+
+def profile_begin(kernel_class: int, max_launches: int) -> None:
+    _check(lib().egeria_profile_begin(int(kernel_class), int(max_launches)), "egeria_profile_begin")
+
+
+def profile_end(capacity: int):
+    """egeria_profile_end: list of per-launch durations in ms (waits for them)."""
+    buf = (ctypes.c_float * max(capacity, 1))()
+    n = _i32(0)
+    _check(lib().egeria_profile_end(buf, capacity, ctypes.byref(n)), "egeria_profile_end")
+    return [float(buf[i]) for i in range(min(n.value, capacity))]

@@ -2,8 +2,13 @@
 // planning and the per-module launch sequences of the reference forward.
 // Nothing here allocates device memory or synchronises, except egeria_check.
 #include "common.hpp"
+#include <vector>
 
 using namespace egeria;
+
+namespace egeria {
+ProfileState g_profile;
+}
 
 namespace {
 
@@ -442,6 +447,40 @@ egeria_status egeria_check(void *ws, void *stream)
         EG_HIP(hipMemcpyAsync(ws, &clean, 4, hipMemcpyHostToDevice, st));
         EG_HIP(hipStreamSynchronize(st));
         return EGERIA_ERR_NONFINITE;
+    }
+    return EGERIA_OK;
+}
+
+egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches)
+{
+    static std::vector<hipEvent_t> starts, stops;
+    if (kernel_class <= EGERIA_KERNEL_NONE || kernel_class > EGERIA_KERNEL_LAYERNORM || max_launches < 1)
+        return EGERIA_ERR_INVALID_ARG;
+    while ((int)starts.size() < max_launches) {
+        hipEvent_t a, b;
+        EG_HIP(hipEventCreate(&a));
+        EG_HIP(hipEventCreate(&b));
+        starts.push_back(a);
+        stops.push_back(b);
+    }
+    g_profile.start = starts.data();
+    g_profile.stop = stops.data();
+    g_profile.n = max_launches;
+    g_profile.count = 0;
+    g_profile.cls = kernel_class;
+    return EGERIA_OK;
+}
+
+egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out)
+{
+    if (!n_out || capacity < 0 || (capacity > 0 && !ms_out)) return EGERIA_ERR_INVALID_ARG;
+    const int n = g_profile.count;
+    g_profile.cls = 0;
+    g_profile.count = 0;
+    *n_out = n;
+    for (int i = 0; i < n && i < capacity; ++i) {
+        EG_HIP(hipEventSynchronize(g_profile.stop[i]));
+        EG_HIP(hipEventElapsedTime(&ms_out[i], g_profile.start[i], g_profile.stop[i]));
     }
     return EGERIA_OK;
 }

@@ -54,6 +54,7 @@ hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int3
                             uint32_t *absmax_out, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
+    ProfileScope prof(EGERIA_KERNEL_LAYERNORM, st);
     hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x, res, rows,
                        (int)H, gamma, beta, (double)eps, y, absmax_out);
     return hipGetLastError();
@@ -236,6 +237,7 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
     const int64_t grid = (int64_t)B * heads * qtiles;
     if (grid <= 0) return hipSuccess;
     if (dh > kDh || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProfileScope prof(EGERIA_KERNEL_ATTENTION, st);
     hipLaunchKernelGGL(attention_kernel, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B, (int)S, (int)Hd,
                        (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out);
     return hipGetLastError();

@@ -24,6 +24,32 @@ inline uint32_t *ws_flag(void *ws) { return (uint32_t *)ws; }
 inline uint32_t *ws_absmax(void *ws, int slot) { return (uint32_t *)ws + kHeaderFixedWords + slot; }
 inline float *ws_scale(void *ws, int slots, int slot) { return (float *)ws + kHeaderFixedWords + slots + slot; }
 
+// ---- optional event recording around one kernel class (egeria_profile_begin / egeria_profile_end) ----
+struct ProfileState {
+    int cls = 0;
+    hipEvent_t *start = nullptr;
+    hipEvent_t *stop = nullptr;
+    int n = 0;
+    int count = 0;
+};
+extern ProfileState g_profile;
+
+struct ProfileScope {
+    hipStream_t st;
+    int idx = -1;
+    ProfileScope(int cls, hipStream_t s) : st(s)
+    {
+        if (g_profile.cls == cls && g_profile.count < g_profile.n) {
+            idx = g_profile.count++;
+            (void)hipEventRecord(g_profile.start[idx], st);
+        }
+    }
+    ~ProfileScope()
+    {
+        if (idx >= 0) (void)hipEventRecord(g_profile.stop[idx], st);
+    }
+};
+
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) --------
 hipError_t launch_header_reset(void *ws, int slots, hipStream_t st);
 

@@ -186,6 +186,7 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     if (tiles <= 0) return hipSuccess;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProfileScope prof(EGERIA_KERNEL_GEMM, st);
     if (g.conv3x3)
         hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WM, WN, true>), dim3((unsigned)tiles), dim3(256), 0, st, g);
     else

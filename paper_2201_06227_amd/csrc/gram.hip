@@ -245,12 +245,16 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
 #define EGERIA_GRAM(T, R)                                                                         \
     hipLaunchKernelGGL((gram_partial_kernel<T, R>), dim3(grid), dim3(256), 0, st, a_t, a_r, (int)b, D, \
                        p, vec, part)
-    if (t_dt == EGERIA_F32 && r_dt == EGERIA_F32) EGERIA_GRAM(0, 0);
-    else if (t_dt == EGERIA_BF16 && r_dt == EGERIA_F32) EGERIA_GRAM(1, 0);
-    else if (t_dt == EGERIA_F32 && r_dt == EGERIA_BF16) EGERIA_GRAM(0, 1);
-    else EGERIA_GRAM(1, 1);
+    hipError_t e;
+    {
+        ProfileScope prof(EGERIA_KERNEL_GRAM, st);
+        if (t_dt == EGERIA_F32 && r_dt == EGERIA_F32) EGERIA_GRAM(0, 0);
+        else if (t_dt == EGERIA_BF16 && r_dt == EGERIA_F32) EGERIA_GRAM(1, 0);
+        else if (t_dt == EGERIA_F32 && r_dt == EGERIA_BF16) EGERIA_GRAM(0, 1);
+        else EGERIA_GRAM(1, 1);
+        e = hipGetLastError();
+    }
 #undef EGERIA_GRAM
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int nelem2 = (int)(2 * nelem);
     hipLaunchKernelGGL(gram_reduce_kernel, dim3((nelem2 + 255) / 256), dim3(256), 0, st, part, p.nsplit,

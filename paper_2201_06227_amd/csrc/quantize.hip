@@ -96,6 +96,7 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *sl
     int64_t blocks = (n / per + threads * 4 - 1) / (threads * 4);     // ~4 vectors per thread
     if (blocks < 1) blocks = 1;
     if (blocks > 2048) blocks = 2048;
+    ProfileScope prof(EGERIA_KERNEL_ABSMAX, st);
     if (dt == EGERIA_F32)
         hipLaunchKernelGGL(absmax_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x, n, slot);
     else
@@ -215,6 +216,7 @@ hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, in
     int64_t blocks = (units + threads - 1) / threads;
     if (blocks < 1) blocks = 1;
     if (blocks > 8192) blocks = 8192;
+    ProfileScope prof(EGERIA_KERNEL_QUANTIZE, st);
     if (dt == EGERIA_F32)
         hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x,
                            rows, cols, ldq, slot, fixed_scale, q, scale_out, scale_out2, flag);
@@ -269,6 +271,7 @@ hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64
                                 hipStream_t st)
 {
     dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n);
+    ProfileScope prof(EGERIA_KERNEL_QUANTIZE, st);
     if (dt == EGERIA_F32)
         hipLaunchKernelGGL(quantize_nchw_kernel<false>, grid, dim3(256), 0, st, x, n, c, hw, cp, slot,
                            fixed_scale, q, scale_out, scale_out2, flag);

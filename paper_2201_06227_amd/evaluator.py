@@ -1,0 +1,78 @@
+"""Pre-allocated driver of one plasticity evaluation: every buffer (quantised
+weights, scales, workspaces, scores) is allocated once, so that a step is a
+fixed sequence of C-ABI calls with no allocation and no host synchronisation.
+Argument marshalling only; all arithmetic is in libegeria's kernels."""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+import torch
+
+from . import binding as eg
+
+
+class PlasticityEvaluator:
+    """One layer module (or stack): snapshot weights -> int8 reference ->
+    reference forward on the mini-batch -> one score per layer.
+
+    step() = reference-model generation (weight quantisation, Section 4.1) +
+    reference forward + plasticity (Section 4.2, Eq. 1), all enqueued on the
+    current stream; scores land in `self.p_out`."""
+
+    def __init__(self, kind: int, dims: dict, weights: Sequence[torch.Tensor],
+                 biases: Sequence[Optional[torch.Tensor]], device="cuda"):
+        self.weights = [w.contiguous() for w in weights]
+        self.biases = list(biases)
+        self.desc = eg.make_desc(kind, dims)
+        self.n_layers = self.desc.n_layers
+        self.w_q, self.scales = [], []
+        for w in self.weights:
+            if w.dim() == 4:
+                o, i, kh, kw = w.shape
+                shape = (o, kh, kw, eg.padded(i))
+            else:
+                shape = (w.shape[0], eg.padded(w.shape[1]))
+            self.w_q.append(torch.empty(shape, dtype=torch.int8, device=device))
+            self.scales.append(torch.empty(1, dtype=torch.float32, device=device))
+        self._lin = (eg.QLinear * len(self.weights))()
+        for i in range(len(self.weights)):
+            self._lin[i].w_q = self.w_q[i].data_ptr()
+            self._lin[i].scale = self.scales[i].data_ptr()
+            self._lin[i].bias = 0 if self.biases[i] is None else self.biases[i].data_ptr()
+        self.qw = eg.QWeights()
+        self.qw.n_linear = len(self.weights)
+        self.qw.linear = self._lin
+        self.qw.n_norm = 0
+        self.qw.norm = None
+        self.qws = eg.workspace(eg.quantize_workspace_bytes(), device)
+        nbytes = eg.workspace_bytes(self.desc)
+        if nbytes == 0:
+            raise ValueError("invalid layer-module description")
+        self.ws = eg.workspace(nbytes, device)
+        self.p_out = torch.zeros(self.n_layers, dtype=torch.float32, device=device)
+        self._lib = eg.lib()
+
+    def quantize_weights(self):
+        L, st = self._lib, eg._stream()
+        for w, q, s in zip(self.weights, self.w_q, self.scales):
+            if w.dim() == 4:
+                o, i, kh, kw = w.shape
+                rc = L.egeria_quantize_nchw(w.data_ptr(), eg.F32, o, i, kh, kw, None, q.data_ptr(), s.data_ptr(),
+                                            self.qws.data_ptr(), self.qws.numel(), st)
+            else:
+                rc = L.egeria_quantize_rows(w.data_ptr(), eg.F32, w.shape[0], w.shape[1], None, q.data_ptr(),
+                                            s.data_ptr(), self.qws.data_ptr(), self.qws.numel(), st)
+            eg._check(rc, "egeria_quantize (weights)")
+
+    def evaluate(self, x: torch.Tensor, a_train: Sequence[torch.Tensor]) -> torch.Tensor:
+        ptrs = (ctypes.c_void_p * self.n_layers)(*[t.data_ptr() for t in a_train])
+        rc = self._lib.egeria_plasticity_eval(ctypes.byref(self.desc), ctypes.byref(self.qw), x.data_ptr(),
+                                              eg._dt(x), ptrs, eg._dt(a_train[0]), self.p_out.data_ptr(),
+                                              self.ws.data_ptr(), self.ws.numel(), eg._stream())
+        eg._check(rc, "egeria_plasticity_eval")
+        return self.p_out
+
+    def step(self, x: torch.Tensor, a_train: Sequence[torch.Tensor]) -> torch.Tensor:
+        self.quantize_weights()
+        return self.evaluate(x, a_train)
