@@ -40,12 +40,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict_
         }
     }
     if (absmax_out) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const uint32_t o = (uint32_t)__shfl_xor((int)amax, off, kWave);
-            amax = o > amax ? o : amax;
-        }
-        if (lane == 0 && amax) atomicMax(absmax_out, amax);
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, absmax_out, sm4);
     }
 }
 
@@ -54,10 +50,8 @@ hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int3
                             uint32_t *absmax_out, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
-    ProfileScope prof(EGERIA_KERNEL_LAYERNORM, st);
-    hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x, res, rows,
-                       (int)H, gamma, beta, (double)eps, y, absmax_out);
-    return hipGetLastError();
+    return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x,
+                    res, rows, (int)H, gamma, beta, (double)eps, y, absmax_out);
 }
 
 // ---- multi-head self-attention -----------------------------------------------------------
@@ -220,12 +214,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
             }
     }
     if (absmax_out) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const uint32_t ov = (uint32_t)__shfl_xor((int)amax, off, kWave);
-            amax = ov > amax ? ov : amax;
-        }
-        if (lane == 0 && amax) atomicMax(absmax_out, amax);
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, absmax_out, sm4);
     }
 }
 
@@ -237,10 +227,8 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
     const int64_t grid = (int64_t)B * heads * qtiles;
     if (grid <= 0) return hipSuccess;
     if (dh > kDh || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    ProfileScope prof(EGERIA_KERNEL_ATTENTION, st);
-    hipLaunchKernelGGL(attention_kernel, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B, (int)S, (int)Hd,
-                       (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out);
-    return hipGetLastError();
+    return launch_k(EGERIA_KERNEL_ATTENTION, attention_kernel, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B,
+                    (int)S, (int)Hd, (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out);
 }
 
 }  // namespace egeria

@@ -1,6 +1,7 @@
 // Shared declarations of the gfx950 kernels behind include/egeria.h.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include "../../include/egeria.h"
@@ -10,21 +11,31 @@ namespace egeria {
 constexpr int kWave = 64;
 
 // ---- workspace header -------------------------------------------------------
-// word 0            : flag word, kFlagMagic | bits (bit 0: a quantiser met NaN/Inf)
-// words 16 .. 16+S  : one absmax slot per quantise point (bit pattern of a
-//                     non-negative fp32, combined with integer atomicMax)
-// then S fp32 scales, one per quantise point.
+// word 0              : flag word, kFlagMagic | bits (bit 0: a quantiser met NaN/Inf);
+//                       only thread 0 of block 0 of a quantise kernel touches it
+// words 16 .. 16+S    : one absmax slot per quantise point whose tensor is produced
+//                       by a kernel of the chain (bit pattern of a non-negative
+//                       fp32, combined with integer atomicMax)
+// next S words        : fp32 scales, one per quantise point
+// next kAbsPartials   : per-workgroup maxima of the chain's input tensor (plain
+//                       stores by the absmax kernel, reduced by the consumer, so
+//                       no word of the header ever needs a separate reset launch)
 constexpr uint32_t kFlagMagic = 0xE6E71A00u;
 constexpr uint32_t kFlagNonFinite = 1u;
 constexpr int kHeaderFixedWords = 16;
+constexpr int kAbsPartials = 512;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-inline size_t header_bytes(int slots) { return align_up(4 * (size_t)(kHeaderFixedWords + 2 * slots), 256); }
+inline size_t header_bytes(int slots)
+{
+    return align_up(4 * (size_t)(kHeaderFixedWords + 2 * slots + kAbsPartials), 256);
+}
 inline uint32_t *ws_flag(void *ws) { return (uint32_t *)ws; }
 inline uint32_t *ws_absmax(void *ws, int slot) { return (uint32_t *)ws + kHeaderFixedWords + slot; }
 inline float *ws_scale(void *ws, int slots, int slot) { return (float *)ws + kHeaderFixedWords + slots + slot; }
+inline uint32_t *ws_partials(void *ws, int slots) { return (uint32_t *)ws + kHeaderFixedWords + 2 * slots; }
 
-// ---- optional event recording around one kernel class (egeria_profile_begin / egeria_profile_end) ----
+// ---- optional event timing of one kernel class (egeria_profile_begin / egeria_profile_end) ----
 struct ProfileState {
     int cls = 0;
     hipEvent_t *start = nullptr;
@@ -34,41 +45,41 @@ struct ProfileState {
 };
 extern ProfileState g_profile;
 
-struct ProfileScope {
-    hipStream_t st;
-    int idx = -1;
-    ProfileScope(int cls, hipStream_t s) : st(s)
-    {
-        if (g_profile.cls == cls && g_profile.count < g_profile.n) {
-            idx = g_profile.count++;
-            (void)hipEventRecord(g_profile.start[idx], st);
-        }
+// Every kernel of the library is launched through here.  When timing of class
+// `cls` is armed, the launch carries a start/stop event pair that receives the
+// dispatch's own begin and end timestamps.
+template <typename K, typename... Args>
+inline hipError_t launch_k(int cls, K kernel, dim3 grid, dim3 block, size_t smem, hipStream_t st, Args... args)
+{
+    if (cls != 0 && g_profile.cls == cls && g_profile.count < g_profile.n) {
+        const int i = g_profile.count++;
+        hipExtLaunchKernelGGL(kernel, grid, block, smem, st, g_profile.start[i], g_profile.stop[i], 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, smem, st, args...);
     }
-    ~ProfileScope()
-    {
-        if (idx >= 0) (void)hipEventRecord(g_profile.stop[idx], st);
-    }
-};
+    return hipGetLastError();
+}
 
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) --------
-hipError_t launch_header_reset(void *ws, int slots, hipStream_t st);
-
-// max |x| over n values into *slot (atomicMax on the bit pattern; slot must have
-// been reset in stream order before).
-hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *slot, hipStream_t st);
+// Per-workgroup maxima of |x| over n values into partials[0 .. absmax_blocks(n))
+// (plain stores).  Block 0 also clears `n_reset` words at `reset` (the atomic
+// slots of the chain that follows).
+int absmax_blocks(int64_t n, egeria_dtype dt);
+hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *partials, uint32_t *reset,
+                         int n_reset, hipStream_t st);
 
 // Quantise a [rows, cols] matrix into int8 [rows, ldq] (ldq >= cols, multiple of
-// 16, pad bytes zero) with the scale derived from *slot (or *fixed_scale).
-// Writes the scale to scale_out and, if non-null, scale_out2.
+// 16, pad bytes zero) with the scale derived from max(slot[0 .. n_slot)) (or
+// *fixed_scale).  Writes the scale to scale_out and, if non-null, scale_out2.
 hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
-                                int64_t ldq, const uint32_t *slot, const float *fixed_scale,
+                                int64_t ldq, const uint32_t *slot, int n_slot, const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st);
 
 // Quantise [n, c, hw] (channel-major) into int8 [n, hw, cp] (channel-last, cp =
 // padded c, pad zero).
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
-                                int64_t cp, const uint32_t *slot, const float *fixed_scale,
+                                int64_t cp, const uint32_t *slot, int n_slot, const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st);
 
@@ -136,6 +147,24 @@ __device__ __forceinline__ double wave_sum(double v)
 // |v| as a bit pattern whose unsigned order is the order of |v|; NaN and Inf
 // compare above every finite value.
 __device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+// Workgroup-wide maximum of a bit pattern, then at most one atomicMax per
+// workgroup, and none when the slot already holds a value at least as large.
+__device__ __forceinline__ void block_atomic_max(uint32_t v, uint32_t *slot, uint32_t *sm4)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) sm4[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = sm4[0] > sm4[1] ? sm4[0] : sm4[1], c = sm4[2] > sm4[3] ? sm4[2] : sm4[3];
+        a = a > c ? a : c;
+        if (a > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, a);
+    }
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 #endif
 

@@ -171,12 +171,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g)
         }
     }
     if (g.absmax_out) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const uint32_t o = (uint32_t)__shfl_xor((int)amax, off, kWave);
-            amax = o > amax ? o : amax;
-        }
-        if (lane == 0 && amax) atomicMax(g.absmax_out, amax);
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, g.absmax_out, sm4);
     }
 }
 
@@ -186,12 +182,11 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     if (tiles <= 0) return hipSuccess;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    ProfileScope prof(EGERIA_KERNEL_GEMM, st);
     if (g.conv3x3)
-        hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WM, WN, true>), dim3((unsigned)tiles), dim3(256), 0, st, g);
-    else
-        hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WM, WN, false>), dim3((unsigned)tiles), dim3(256), 0, st, g);
-    return hipGetLastError();
+        return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true>, dim3((unsigned)tiles), dim3(256), 0,
+                        st, g);
+    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false>, dim3((unsigned)tiles), dim3(256), 0, st,
+                    g);
 }
 
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)

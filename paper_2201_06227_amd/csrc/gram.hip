@@ -12,15 +12,19 @@
 // B + (M + M^T)/2 in fp64 in the finaliser.  Same bytes and the same number of
 // matrix-core operations as two plain Gram products.
 //
-// Kernel 1 (gram_partial): split-K over D.  A workgroup owns one 32x32 block
-//   (ib, jb) of both products and one chunk of D; its four waves interleave
-//   over the chunk, each lane reading 64 contiguous bytes of one sample row
-//   straight into v_mfma_f32_32x32x2f32 operand registers (the order of k
-//   inside the sum is free, so no transposition is needed).  The four waves'
-//   accumulators are summed through LDS and written as one partial.
-// Kernel 2 (gram_reduce): sums the partials over chunks in fp64.
-// Kernel 3 (sp_finalize): one workgroup: row norms, normalise, squared
-//   Frobenius difference, all in fp64; writes P as fp32.
+// Kernel 1 (gram_partial): split-K over D.  A workgroup owns one chunk of D and
+//   one macro tile of both products: 64x64 (four 32x32 blocks, one per wave) for
+//   b > 32, or the single 32x32 block for b <= 32 with the four waves splitting
+//   each K tile.  Sample rows are fetched with full-line coalesced loads into a
+//   double-buffered LDS stage (the next tile's loads are in flight while the
+//   current one is contracted) and read back as 128-bit v_mfma_f32_32x32x2f32
+//   operands: lane l takes row l % 32 and four consecutive k at 8s + 4(l / 32),
+//   A and B operand alike, so the order of k inside the sum never matters.
+// Kernel 2 (sp_finalize): one workgroup per row i of the b x b matrices: sums
+//   the partials over chunks in fp64 (four waves, fixed assignment, fixed
+//   order), forms row i of both Gram matrices, their norms and the row's share
+//   of the squared difference; the last workgroup to finish adds the b shares in
+//   index order and writes P.  Results are bit-reproducible from call to call.
 #include "common.hpp"
 
 namespace egeria {
@@ -28,241 +32,335 @@ namespace egeria {
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct GramPlan {
-    int side;        // ceil(b / 32)
-    int nblk;        // side * side
+    int mt;          // blocks of 32 per macro-tile side: 1 (b <= 32) or 2
+    int nm;          // macro tiles per side
+    int nmacro;      // nm * nm
+    int kt;          // K tile in floats: 128 (mt = 1) or 32 (mt = 2)
     int nsplit;      // chunks of D
-    int nsplit_pad;  // rounded up to a multiple of 8 (one chunk per XCD slot)
-    int64_t kc;      // chunk length, multiple of 128
+    int nsplit_pad;  // rounded up to a multiple of 8 (chunks are dealt to XCDs)
+    int64_t kc;      // chunk length, multiple of kt
 };
 
 static GramPlan plan_gram(int32_t b, int64_t D)
 {
     GramPlan p;
-    p.side = (b + 31) / 32;
-    p.nblk = p.side * p.side;
-    int64_t want = (512 + p.nblk - 1) / p.nblk;           // about two workgroups per CU
-    int64_t cap = D / (8 * (int64_t)b);                   // keep partials below ~1/8 of the input bytes
+    p.mt = b <= 32 ? 1 : 2;
+    p.nm = p.mt == 1 ? 1 : (b + 63) / 64;
+    p.nmacro = p.nm * p.nm;
+    p.kt = p.mt == 1 ? 128 : 32;
+    int64_t want = (512 + p.nmacro - 1) / p.nmacro;       // about two workgroups per CU
+    int64_t cap = D / ((p.mt == 1 ? 4 : 2) * (int64_t)b);  // bound the partials by a fraction of the input bytes
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
     int64_t kc = (D + want - 1) / want;
-    kc = (kc + 127) / 128 * 128;
+    kc = (kc + p.kt - 1) / p.kt * p.kt;
     p.kc = kc;
     p.nsplit = (int)((D + kc - 1) / kc);
     p.nsplit_pad = (p.nsplit + 7) / 8 * 8;
     return p;
 }
 
+// workspace of the metric: [counter | row shares (b doubles) | partials]
+static size_t off_rowsum() { return 256; }
+static size_t off_partials(int32_t b) { return 256 + align_up((size_t)b * sizeof(double), 256); }
+
 size_t plasticity_partial_bytes(int32_t b, int64_t D)
 {
     GramPlan p = plan_gram(b, D);
-    size_t nelem = 2 * (size_t)b * b;
-    return align_up((size_t)p.nsplit * nelem * sizeof(float), 256) + align_up(nelem * sizeof(double), 256);
+    return off_partials(b) + align_up((size_t)p.nsplit * 2 * (size_t)b * b * sizeof(float), 256);
 }
 
-// 16 consecutive values of one row, zero beyond the row / the chunk end.
+// ---- global -> register staging of one [rows x KT] tile -------------------------------
+// Thread `tid` owns float4 slots tid, tid + 256, ... of the tile (row-major
+// slots, KT/4 per row), so that a wave reads whole 128-byte lines.
 template <int DT>
-__device__ __forceinline__ void load16(const void *__restrict__ base, int64_t row, bool row_ok,
-                                       int64_t D, int64_t k, int64_t kend, bool vec, float (&v)[16])
+__device__ __forceinline__ float4 load4(const void *__restrict__ base, int64_t row, bool row_ok,
+                                        int64_t D, int64_t k, int64_t kend, bool vec)
 {
-    if (!row_ok || k >= kend) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = 0.0f;
-        return;
-    }
-    if (vec && k + 16 <= kend) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!row_ok || k >= kend) return v;
+    if (vec && k + 4 <= kend) {
         if (DT == 0) {
-            const float4 *p = (const float4 *)((const float *)base + row * D + k);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float4 q = p[j];
-                v[4 * j] = q.x; v[4 * j + 1] = q.y; v[4 * j + 2] = q.z; v[4 * j + 3] = q.w;
-            }
+            v = *(const float4 *)((const float *)base + row * D + k);
         } else {
-            const uint4 *p = (const uint4 *)((const uint16_t *)base + row * D + k);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                uint4 q = p[j];
-                uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[8 * j + 2 * e] = __uint_as_float(w[e] << 16);
-                    v[8 * j + 2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-                }
-            }
+            const uint2 q = *(const uint2 *)((const uint16_t *)base + row * D + k);
+            v.x = __uint_as_float(q.x << 16);
+            v.y = __uint_as_float(q.x & 0xffff0000u);
+            v.z = __uint_as_float(q.y << 16);
+            v.w = __uint_as_float(q.y & 0xffff0000u);
         }
     } else {
+        float e[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float x = 0.0f;
-            if (k + e < kend) {
-                if (DT == 0) x = ((const float *)base)[row * D + k + e];
-                else x = bf16_to_f32(((const uint16_t *)base)[row * D + k + e]);
-            }
-            v[e] = x;
-        }
+        for (int i = 0; i < 4; ++i)
+            if (k + i < kend)
+                e[i] = DT == 0 ? ((const float *)base)[row * D + k + i]
+                               : bf16_to_f32(((const uint16_t *)base)[row * D + k + i]);
+        v = make_float4(e[0], e[1], e[2], e[3]);
     }
+    return v;
 }
 
-template <int TDT, int RDT, bool DIAG>
-__device__ __forceinline__ void gram_block(const void *__restrict__ at, const void *__restrict__ ar,
-                                           int b, int64_t D, int64_t k0, int64_t k1, int ib, int jb,
-                                           bool vec, v16f &accM, v16f &accB)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 31, h = lane >> 5;
-    const int64_t row_i = (int64_t)ib * 32 + r, row_j = (int64_t)jb * 32 + r;
-    const bool ok_i = row_i < b, ok_j = row_j < b;
-    float ti[16], ri[16], tj[16], rj[16];
-    float nti[16], nri[16], ntj[16], nrj[16];
-    int64_t k = k0 + wave * 32 + h * 16;
-    load16<TDT>(at, row_i, ok_i, D, k, k1, vec, ti);
-    load16<RDT>(ar, row_i, ok_i, D, k, k1, vec, ri);
-    if (!DIAG) {
-        load16<TDT>(at, row_j, ok_j, D, k, k1, vec, tj);
-        load16<RDT>(ar, row_j, ok_j, D, k, k1, vec, rj);
-    }
-    for (; k - h * 16 < k1; k += 128) {
-        const int64_t kn = k + 128;
-        // next step's operands are requested before this step's products are issued
-        load16<TDT>(at, row_i, ok_i, D, kn, k1, vec, nti);
-        load16<RDT>(ar, row_i, ok_i, D, kn, k1, vec, nri);
-        if (!DIAG) {
-            load16<TDT>(at, row_j, ok_j, D, kn, k1, vec, ntj);
-            load16<RDT>(ar, row_j, ok_j, D, kn, k1, vec, nrj);
-        }
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const float a_t = ti[t], a_r = ri[t];
-            const float b_t = DIAG ? ti[t] : tj[t], b_r = DIAG ? ri[t] : rj[t];
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(a_t - a_r, b_t + b_r, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(a_r, b_r, accB, 0, 0, 0);
-        }
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            ti[t] = nti[t]; ri[t] = nri[t];
-            if (!DIAG) { tj[t] = ntj[t]; rj[t] = nrj[t]; }
-        }
-    }
-}
-
-template <int TDT, int RDT>
+template <int MT, int TDT, int RDT>
 __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restrict__ at,
                                                            const void *__restrict__ ar, int b,
                                                            int64_t D, GramPlan p, bool vec,
-                                                           float *__restrict__ part)
+                                                           float *__restrict__ part,
+                                                           uint32_t *__restrict__ counter)
 {
-    // consecutive workgroup ids land on different XCDs: give all blocks of one
-    // chunk to the same XCD so that its L2 serves the re-reads of that chunk
+    constexpr int ROWS = MT * 32;                 // rows per side of the macro tile
+    constexpr int KT = MT == 1 ? 128 : 32;        // floats per K tile
+    constexpr int LD = KT + 4;                    // padded LDS row
+    constexpr int SLOTS = ROWS * KT / 4;          // float4 slots of one tensor tile
+    constexpr int NIT = SLOTS / 256;              // slots per thread
+    constexpr int NTEN = MT == 1 ? 2 : 4;         // tensors staged: T_i, R_i (, T_j, R_j)
+    static_assert(SLOTS % 256 == 0, "tile must divide over the workgroup");
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // [2 stages][NTEN][ROWS][LD]
+
+    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0u;      // ticket of the finaliser
+
+    // consecutive workgroup ids land on different XCDs: all macro tiles of one
+    // chunk go to the same XCD so that its L2 serves the re-reads of that chunk
     const int id = blockIdx.x;
     const int xcd = id & 7, slot = id >> 3;
-    const int chunk = (slot / p.nblk) * 8 + xcd;
-    const int blk = slot % p.nblk;
+    const int chunk = (slot / p.nmacro) * 8 + xcd;
+    const int mtile = slot % p.nmacro;
     if (chunk >= p.nsplit) return;
-    const int ib = blk / p.side, jb = blk % p.side;
+    const int mi = mtile / p.nm, mj = mtile % p.nm;
+    const bool diag = MT == 1 || mi == mj;
     const int64_t k0 = (int64_t)chunk * p.kc;
     const int64_t k1 = k0 + p.kc < D ? k0 + p.kc : D;
+    const int ntiles = (int)((k1 - k0 + KT - 1) / KT);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+
+    // rows / columns this thread stages
+    int srow[NIT], scol[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int s = tid + it * 256;
+        srow[it] = s / (KT / 4);
+        scol[it] = (s % (KT / 4)) * 4;
+    }
+    float4 st[NTEN][NIT];
+    auto fetch = [&](int t) {
+        const int64_t kb = k0 + (int64_t)t * KT;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int64_t ri = (int64_t)mi * ROWS + srow[it];
+            st[0][it] = load4<TDT>(at, ri, ri < b, D, kb + scol[it], k1, vec);
+            st[1][it] = load4<RDT>(ar, ri, ri < b, D, kb + scol[it], k1, vec);
+            if (NTEN == 4 && !diag) {
+                const int64_t rj = (int64_t)mj * ROWS + srow[it];
+                st[2][it] = load4<TDT>(at, rj, rj < b, D, kb + scol[it], k1, vec);
+                st[3][it] = load4<RDT>(ar, rj, rj < b, D, kb + scol[it], k1, vec);
+            }
+        }
+    };
+    auto stash = [&](int stage) {
+        float *base = lds + (size_t)stage * NTEN * ROWS * LD;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int o = srow[it] * LD + scol[it];
+            *(float4 *)&base[0 * ROWS * LD + o] = st[0][it];
+            *(float4 *)&base[1 * ROWS * LD + o] = st[1][it];
+            if (NTEN == 4 && !diag) {
+                *(float4 *)&base[2 * ROWS * LD + o] = st[2][it];
+                *(float4 *)&base[3 * ROWS * LD + o] = st[3][it];
+            }
+        }
+    };
 
     v16f accM, accB;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { accM[r] = 0.0f; accB[r] = 0.0f; }
-    if (ib == jb) gram_block<TDT, RDT, true>(at, ar, b, D, k0, k1, ib, jb, vec, accM, accB);
-    else gram_block<TDT, RDT, false>(at, ar, b, D, k0, k1, ib, jb, vec, accM, accB);
+    for (int i = 0; i < 16; ++i) { accM[i] = 0.0f; accB[i] = 0.0f; }
 
-    __shared__ float red[4][2][1024];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        red[wave][0][r * 64 + lane] = accM[r];
-        red[wave][1][r * 64 + lane] = accB[r];
-    }
+    // operand rows of this wave inside the macro tile
+    const int bi = MT == 1 ? 0 : (wave >> 1), bj = MT == 1 ? 0 : (wave & 1);
+    const int rowA = bi * 32 + r, rowB = bj * 32 + r;
+    const int kw0 = MT == 1 ? wave * 32 : 0;      // this wave's 32-float slice of the K tile
+
+    fetch(0);
+    stash(0);
     __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) fetch(t + 1);
+        const float *base = lds + (size_t)(t & 1) * NTEN * ROWS * LD;
+        const float *pTi = base + 0 * ROWS * LD + rowA * LD + kw0 + 4 * h;
+        const float *pRi = base + 1 * ROWS * LD + rowA * LD + kw0 + 4 * h;
+        const float *pTj = base + (diag ? 0 : 2) * ROWS * LD + rowB * LD + kw0 + 4 * h;
+        const float *pRj = base + (diag ? 1 : 3) * ROWS * LD + rowB * LD + kw0 + 4 * h;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const float4 ti = *(const float4 *)(pTi + 8 * s), ri = *(const float4 *)(pRi + 8 * s);
+            const float4 tj = *(const float4 *)(pTj + 8 * s), rj = *(const float4 *)(pRj + 8 * s);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.x - ri.x, tj.x + rj.x, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.x, rj.x, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.y - ri.y, tj.y + rj.y, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.y, rj.y, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.z - ri.z, tj.z + rj.z, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.z, rj.z, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.w - ri.w, tj.w + rj.w, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.w, rj.w, accB, 0, 0, 0);
+        }
+        if (t + 1 < ntiles) stash((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // lane l of a 32x32 block holds column l % 32, rows 8 * (i / 4) + 4 * (l / 32) + i % 4
     const size_t nelem = (size_t)b * b;
     float *dst = part + (size_t)chunk * 2 * nelem;
-    for (int e = threadIdx.x; e < 2048; e += 256) {
-        const int prod = e >> 10, w = e & 1023;
-        const int r = w >> 6, l = w & 63;
-        const float s = (red[0][prod][w] + red[1][prod][w]) + (red[2][prod][w] + red[3][prod][w]);
-        const int row = ib * 32 + (r >> 2) * 8 + (l >> 5) * 4 + (r & 3);
-        const int col = jb * 32 + (l & 31);
-        if (row < b && col < b) dst[prod * nelem + (size_t)row * b + col] = s;
+    if (MT == 1) {
+        // the four waves hold partial sums over disjoint k: add them through LDS
+        float *red = lds;                         // [4][2][1024], the stage memory is free now
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            red[(wave * 2 + 0) * 1024 + i * 64 + lane] = accM[i];
+            red[(wave * 2 + 1) * 1024 + i * 64 + lane] = accB[i];
+        }
+        __syncthreads();
+        for (int e = tid; e < 2048; e += 256) {
+            const int prod = e >> 10, w = e & 1023;
+            const int i = w >> 6, l = w & 63;
+            const float s = (red[(0 * 2 + prod) * 1024 + w] + red[(1 * 2 + prod) * 1024 + w]) +
+                            (red[(2 * 2 + prod) * 1024 + w] + red[(3 * 2 + prod) * 1024 + w]);
+            const int row = (i >> 2) * 8 + (l >> 5) * 4 + (i & 3), col = l & 31;
+            if (row < b && col < b) dst[prod * nelem + (size_t)row * b + col] = s;
+        }
+    } else {
+        const int col = mj * ROWS + bj * 32 + r;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = mi * ROWS + bi * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
+            if (row < b && col < b) {
+                dst[(size_t)row * b + col] = accM[i];
+                dst[nelem + (size_t)row * b + col] = accB[i];
+            }
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int nsplit,
-                                                          int nelem2, double *__restrict__ out)
-{
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= nelem2) return;
-    double s = 0.0;
-    for (int c = 0; c < nsplit; ++c) s += (double)part[(size_t)c * nelem2 + e];
-    out[e] = s;
-}
-
-// red = [M | B], each b x b doubles.
-__global__ __launch_bounds__(256) void sp_finalize_kernel(const double *__restrict__ red, int b,
+// One workgroup per row i.  part = [nsplit][2][b][b] (M then B).
+__global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restrict__ part, int nsplit,
+                                                          int b, double *__restrict__ rowsum,
+                                                          uint32_t *__restrict__ counter,
                                                           float *__restrict__ p_out)
 {
-    const double *M = red, *B = red + (size_t)b * b;
+    __shared__ double sm[3][4][128];              // [m_ij | m_ji | b_ij][wave][column]
+    __shared__ double fin[4];
+    __shared__ bool last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    double acc = 0.0;
-    for (int i = wave; i < b; i += 4) {
-        double nt2 = 0.0, nr2 = 0.0;
-        for (int j = lane; j < b; j += 64) {
-            const double gr = B[(size_t)i * b + j];
-            const double gt = gr + 0.5 * (M[(size_t)i * b + j] + M[(size_t)j * b + i]);
-            nt2 += gt * gt;
-            nr2 += gr * gr;
+    const int i = blockIdx.x;
+    const size_t nelem = (size_t)b * b;
+    // each wave sums the chunks c = wave, wave + 4, ... for up to two columns per lane
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int j = lane + 64 * half;
+        double mij = 0.0, mji = 0.0, bij = 0.0;
+        if (j < b) {
+            const float *pm = part + (size_t)i * b + j, *pmt = part + (size_t)j * b + i;
+            const float *pb = part + nelem + (size_t)i * b + j;
+            for (int c = wave; c < nsplit; c += 4) {
+                const size_t o = (size_t)c * 2 * nelem;
+                mij += (double)pm[o];
+                mji += (double)pmt[o];
+                bij += (double)pb[o];
+            }
+        }
+        sm[0][wave][j] = mij;
+        sm[1][wave][j] = mji;
+        sm[2][wave][j] = bij;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        double gt[2], gr[2], nt2 = 0.0, nr2 = 0.0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int j = lane + 64 * half;
+            gt[half] = gr[half] = 0.0;
+            if (j < b) {
+                const double mij = (sm[0][0][j] + sm[0][1][j]) + (sm[0][2][j] + sm[0][3][j]);
+                const double mji = (sm[1][0][j] + sm[1][1][j]) + (sm[1][2][j] + sm[1][3][j]);
+                gr[half] = (sm[2][0][j] + sm[2][1][j]) + (sm[2][2][j] + sm[2][3][j]);
+                gt[half] = gr[half] + 0.5 * (mij + mji);
+            }
+            nt2 += gt[half] * gt[half];
+            nr2 += gr[half] * gr[half];
         }
         nt2 = wave_sum(nt2);
         nr2 = wave_sum(nr2);
         double nt = sqrt(nt2), nr = sqrt(nr2);
         nt = nt < 1e-12 ? 1e-12 : nt;
         nr = nr < 1e-12 ? 1e-12 : nr;
-        for (int j = lane; j < b; j += 64) {
-            const double gr = B[(size_t)i * b + j];
-            const double gt = gr + 0.5 * (M[(size_t)i * b + j] + M[(size_t)j * b + i]);
-            const double d = gt / nt - gr / nr;
+        double acc = 0.0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const double d = gt[half] / nt - gr[half] / nr;
             acc += d * d;
         }
+        acc = wave_sum(acc);
+        if (lane == 0) {
+            rowsum[i] = acc;
+            __threadfence();                                   // publish the share, then take a ticket
+            const uint32_t ticket = atomicAdd(counter, 1u);
+            last = ticket == (uint32_t)(b - 1);
+        }
     }
-    acc = wave_sum(acc);
-    __shared__ double sm[4];
-    if (lane == 0) sm[wave] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) *p_out = (float)(((sm[0] + sm[1]) + (sm[2] + sm[3])) / ((double)b * (double)b));
+    if (!last) return;
+    __threadfence();                                           // see every other workgroup's share
+    if (wave == 0) {
+        // b <= 128 shares, added in index order by a fixed tree
+        double v0 = lane < b ? __hip_atomic_load(&rowsum[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+        double v1 = lane + 64 < b ? __hip_atomic_load(&rowsum[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+        const double tot = wave_sum(v0 + v1);
+        if (lane == 0) *p_out = (float)(tot / ((double)b * (double)b));
+    }
+    (void)fin;
 }
 
 hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r, egeria_dtype r_dt,
                              int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st)
 {
     const GramPlan p = plan_gram(b, D);
-    const size_t nelem = (size_t)b * b;
-    float *part = (float *)ws_part;
-    double *red = (double *)((char *)ws_part + align_up((size_t)p.nsplit * 2 * nelem * sizeof(float), 256));
+    uint32_t *counter = (uint32_t *)ws_part;
+    double *rowsum = (double *)((char *)ws_part + off_rowsum());
+    float *part = (float *)((char *)ws_part + off_partials(b));
     const bool vec = (t_dt == EGERIA_F32 ? (D % 4 == 0) : (D % 8 == 0)) &&
                      (r_dt == EGERIA_F32 ? (D % 4 == 0) : (D % 8 == 0));
-    const unsigned grid = (unsigned)(p.nsplit_pad * p.nblk);
-#define EGERIA_GRAM(T, R)                                                                         \
-    hipLaunchKernelGGL((gram_partial_kernel<T, R>), dim3(grid), dim3(256), 0, st, a_t, a_r, (int)b, D, \
-                       p, vec, part)
-    hipError_t e;
-    {
-        ProfileScope prof(EGERIA_KERNEL_GRAM, st);
-        if (t_dt == EGERIA_F32 && r_dt == EGERIA_F32) EGERIA_GRAM(0, 0);
-        else if (t_dt == EGERIA_BF16 && r_dt == EGERIA_F32) EGERIA_GRAM(1, 0);
-        else if (t_dt == EGERIA_F32 && r_dt == EGERIA_BF16) EGERIA_GRAM(0, 1);
-        else EGERIA_GRAM(1, 1);
-        e = hipGetLastError();
+    const dim3 grid((unsigned)(p.nsplit_pad * p.nmacro)), block(256);
+    const int tcode = t_dt == EGERIA_BF16 ? 1 : 0, rcode = r_dt == EGERIA_BF16 ? 1 : 0;
+    hipError_t e = hipSuccess;
+#define EGERIA_GRAM(MTV, T, R)                                                                         \
+    do {                                                                                               \
+        constexpr int rows = MTV * 32, kt = MTV == 1 ? 128 : 32, nten = MTV == 1 ? 2 : 4;              \
+        constexpr size_t smem = (size_t)2 * nten * rows * (kt + 4) * sizeof(float);                    \
+        static bool attr_set = false;                                                                  \
+        if (!attr_set) {                                                                               \
+            e = hipFuncSetAttribute((const void *)gram_partial_kernel<MTV, T, R>,                      \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);            \
+            if (e != hipSuccess) return e;                                                             \
+            attr_set = true;                                                                           \
+        }                                                                                              \
+        e = launch_k(EGERIA_KERNEL_GRAM, gram_partial_kernel<MTV, T, R>, grid, block, smem, st, a_t,   \
+                     a_r, (int)b, D, p, vec, part, counter);                                           \
+    } while (0)
+    if (p.mt == 1) {
+        if (!tcode && !rcode) EGERIA_GRAM(1, 0, 0);
+        else if (tcode && !rcode) EGERIA_GRAM(1, 1, 0);
+        else if (!tcode && rcode) EGERIA_GRAM(1, 0, 1);
+        else EGERIA_GRAM(1, 1, 1);
+    } else {
+        if (!tcode && !rcode) EGERIA_GRAM(2, 0, 0);
+        else if (tcode && !rcode) EGERIA_GRAM(2, 1, 0);
+        else if (!tcode && rcode) EGERIA_GRAM(2, 0, 1);
+        else EGERIA_GRAM(2, 1, 1);
     }
 #undef EGERIA_GRAM
     if (e != hipSuccess) return e;
-    const int nelem2 = (int)(2 * nelem);
-    hipLaunchKernelGGL(gram_reduce_kernel, dim3((nelem2 + 255) / 256), dim3(256), 0, st, part, p.nsplit,
-                       nelem2, red);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sp_finalize_kernel, dim3(1), dim3(256), 0, st, red, (int)b, p_out);
-    return hipGetLastError();
+    return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(256), 0, st,
+                    (const float *)part, p.nsplit, (int)b, rowsum, counter, p_out);
 }
 
 }  // namespace egeria

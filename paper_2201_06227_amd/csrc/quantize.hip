@@ -5,24 +5,6 @@
 
 namespace egeria {
 
-// ---- header reset ---------------------------------------------------------------
-__global__ void header_reset_kernel(uint32_t *ws, int slots)
-{
-    int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t == 0) {
-        uint32_t f = ws[0];
-        if ((f & 0xffffff00u) != kFlagMagic) ws[0] = kFlagMagic;   // first use of this memory
-    }
-    if (t < slots) ws[kHeaderFixedWords + t] = 0u;
-}
-
-hipError_t launch_header_reset(void *ws, int slots, hipStream_t st)
-{
-    int threads = 256, blocks = (slots + threads) / threads;
-    hipLaunchKernelGGL(header_reset_kernel, dim3(blocks), dim3(threads), 0, st, (uint32_t *)ws, slots);
-    return hipGetLastError();
-}
-
 // ---- absolute maximum -------------------------------------------------------------
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
@@ -34,10 +16,22 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return v;
 }
 
+__device__ __forceinline__ uint32_t max4_bits(float4 v)
+{
+    uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
+    a = a > b ? a : b;
+    c = c > d ? c : d;
+    return a > c ? a : c;
+}
+
+// Each workgroup writes the maximum of its grid-stride share to partials[blockIdx.x]
+// (bit pattern of |x|, so NaN and Inf order above every finite value).
 template <bool BF16>
 __global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv, int64_t n,
-                                                     uint32_t *__restrict__ slot)
+                                                     uint32_t *__restrict__ partials,
+                                                     uint32_t *__restrict__ reset, int n_reset)
 {
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_reset) reset[threadIdx.x] = 0u;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
     uint32_t m = 0;
@@ -45,16 +39,21 @@ __global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv
         const float *x = (const float *)xv;
         const int64_t n4 = n >> 2;
         const float4 *x4 = (const float4 *)x;
-        for (int64_t i = tid; i < n4; i += nthreads) {
-            float4 v = x4[i];
-            uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
+        int64_t i = tid;
+        for (; i + 3 * nthreads < n4; i += 4 * nthreads) {           // four independent loads in flight
+            const float4 v0 = x4[i], v1 = x4[i + nthreads], v2 = x4[i + 2 * nthreads], v3 = x4[i + 3 * nthreads];
+            uint32_t a = max4_bits(v0), b = max4_bits(v1), c = max4_bits(v2), d = max4_bits(v3);
             a = a > b ? a : b;
             c = c > d ? c : d;
             a = a > c ? a : c;
             m = m > a ? m : a;
         }
-        for (int64_t i = (n4 << 2) + tid; i < n; i += nthreads) {
-            uint32_t a = abs_bits(x[i]);
+        for (; i < n4; i += nthreads) {
+            const uint32_t a = max4_bits(x4[i]);
+            m = m > a ? m : a;
+        }
+        for (int64_t k = (n4 << 2) + tid; k < n; k += nthreads) {
+            const uint32_t a = abs_bits(x[k]);
             m = m > a ? m : a;
         }
     } else {
@@ -83,49 +82,72 @@ __global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t a = sm[0] > sm[1] ? sm[0] : sm[1], b = sm[2] > sm[3] ? sm[2] : sm[3];
-        a = a > b ? a : b;
-        if (a) atomicMax(slot, a);
+        partials[blockIdx.x] = a > b ? a : b;
     }
 }
 
-hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *slot, hipStream_t st)
+int absmax_blocks(int64_t n, egeria_dtype dt)
 {
-    if (n <= 0) return hipSuccess;
-    const int threads = 256;
     const int64_t per = dt == EGERIA_F32 ? 4 : 8;
-    int64_t blocks = (n / per + threads * 4 - 1) / (threads * 4);     // ~4 vectors per thread
+    int64_t blocks = (n / per + 256 * 4 - 1) / (256 * 4);            // about four vectors per thread
     if (blocks < 1) blocks = 1;
-    if (blocks > 2048) blocks = 2048;
-    ProfileScope prof(EGERIA_KERNEL_ABSMAX, st);
+    if (blocks > kAbsPartials) blocks = kAbsPartials;
+    return (int)blocks;
+}
+
+hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *partials, uint32_t *reset,
+                         int n_reset, hipStream_t st)
+{
+    const dim3 grid((unsigned)absmax_blocks(n, dt)), block(256);
+    if (n_reset > 256) return hipErrorInvalidValue;
     if (dt == EGERIA_F32)
-        hipLaunchKernelGGL(absmax_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x, n, slot);
-    else
-        hipLaunchKernelGGL(absmax_kernel<true>, dim3((unsigned)blocks), dim3(threads), 0, st, x, n, slot);
-    return hipGetLastError();
+        return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<false>, grid, block, 0, st, x, n, partials, reset, n_reset);
+    return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<true>, grid, block, 0, st, x, n, partials, reset, n_reset);
 }
 
 // ---- scale from absmax --------------------------------------------------------------
-// Returns the multiplier inv and writes the scale; sets *bad when the tensor
-// holds a NaN or an infinity.
-__device__ __forceinline__ float scales_from(const uint32_t *slot, const float *fixed_scale,
-                                             float *scale, bool *bad)
+// Called by every thread at the top of a quantise kernel.  Reduces the n_slot
+// candidate maxima, returns the multiplier inv and the scale; *bad is set when
+// the tensor holds a NaN or an infinity.
+__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot,
+                                             const float *__restrict__ fixed_scale, float *scale, bool *bad)
 {
+    uint32_t bits = 0;
+    const int lane = threadIdx.x & 63;
+    for (int i = lane; i < n_slot; i += 64) {
+        const uint32_t v = slot[i];
+        bits = bits > v ? bits : v;
+    }
+    bits = wave_max_u32(bits);
     float inv, sc;
-    *bad = false;
+    *bad = bits >= 0x7f800000u;
     if (fixed_scale) {
         sc = *fixed_scale;
         inv = (float)(1.0 / (double)sc);
-        if (slot && *slot >= 0x7f800000u) *bad = true;
     } else {
-        uint32_t bits = *slot;
-        if (bits >= 0x7f800000u) { *bad = true; bits = 0; }
-        float absmax = __uint_as_float(bits);
+        if (*bad) bits = 0;
+        const float absmax = __uint_as_float(bits);
         sc = (float)((double)absmax / 127.0);
         inv = (float)(127.0 / (double)absmax);
     }
     if (!(inv <= 3.402823466e+38f) || !(sc > 0.0f)) { sc = 1.0f; inv = 0.0f; }
     *scale = sc;
     return inv;
+}
+
+// Only thread 0 of block 0 of a quantise kernel reads or writes the flag word,
+// and kernels that share a workspace are ordered on one stream, so plain
+// accesses are enough.  Memory that does not yet carry the magic is initialised.
+__device__ __forceinline__ void publish(float scale, bool bad, float *scale_out, float *scale_out2, uint32_t *flag)
+{
+    *scale_out = scale;
+    if (scale_out2) *scale_out2 = scale;
+    if (flag) {
+        uint32_t f = *flag;
+        if ((f & 0xffffff00u) != kFlagMagic) f = kFlagMagic;
+        if (bad) f |= kFlagNonFinite;
+        *flag = f;
+    }
 }
 
 __device__ __forceinline__ uint32_t quant1(float x, float inv)
@@ -147,18 +169,14 @@ __device__ __forceinline__ float load_elem(const void *x, int64_t i)
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(
     const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
-    const uint32_t *__restrict__ slot, const float *__restrict__ fixed_scale,
+    const uint32_t *__restrict__ slot, int n_slot, const float *__restrict__ fixed_scale,
     int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
     uint32_t *__restrict__ flag)
 {
     float scale;
     bool bad;
-    const float inv = scales_from(slot, fixed_scale, &scale, &bad);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *scale_out = scale;
-        if (scale_out2) *scale_out2 = scale;
-        if (bad && flag) atomicOr(flag, kFlagNonFinite);
-    }
+    const float inv = scales_from(slot, n_slot, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t upr = (ldq + 15) >> 4;                     // 16-byte units per row
     const int64_t units = rows * upr;
     const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
@@ -207,23 +225,20 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(
 }
 
 hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
-                                int64_t ldq, const uint32_t *slot, const float *fixed_scale,
+                                int64_t ldq, const uint32_t *slot, int n_slot, const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st)
 {
-    const int threads = 256;
-    int64_t units = rows * ((ldq + 15) / 16);
-    int64_t blocks = (units + threads - 1) / threads;
+    const int64_t units = rows * ((ldq + 15) / 16);
+    int64_t blocks = (units + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 8192) blocks = 8192;
-    ProfileScope prof(EGERIA_KERNEL_QUANTIZE, st);
+    const dim3 grid((unsigned)blocks), block(256);
     if (dt == EGERIA_F32)
-        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3((unsigned)blocks), dim3(threads), 0, st, x,
-                           rows, cols, ldq, slot, fixed_scale, q, scale_out, scale_out2, flag);
-    else
-        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3((unsigned)blocks), dim3(threads), 0, st, x,
-                           rows, cols, ldq, slot, fixed_scale, q, scale_out, scale_out2, flag);
-    return hipGetLastError();
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_rows_kernel<false>, grid, block, 0, st, x, rows, cols, ldq,
+                        slot, n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_rows_kernel<true>, grid, block, 0, st, x, rows, cols, ldq, slot,
+                    n_slot, fixed_scale, q, scale_out, scale_out2, flag);
 }
 
 // ---- quantise [n, c, hw] -> int8 [n, hw, cp] -------------------------------------------
@@ -232,18 +247,15 @@ hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, in
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_nchw_kernel(
     const void *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
-    const uint32_t *__restrict__ slot, const float *__restrict__ fixed_scale,
+    const uint32_t *__restrict__ slot, int n_slot, const float *__restrict__ fixed_scale,
     int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
     uint32_t *__restrict__ flag)
 {
     float scale;
     bool bad;
-    const float inv = scales_from(slot, fixed_scale, &scale, &bad);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
-        *scale_out = scale;
-        if (scale_out2) *scale_out2 = scale;
-        if (bad && flag) atomicOr(flag, kFlagNonFinite);
-    }
+    const float inv = scales_from(slot, n_slot, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+        publish(scale, bad, scale_out, scale_out2, flag);
     __shared__ uint8_t tile[64][64 + 4];                  // [pixel][channel], padded rows
     const int64_t img = blockIdx.z;
     const int64_t p0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
@@ -266,19 +278,16 @@ __global__ __launch_bounds__(256) void quantize_nchw_kernel(
 }
 
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
-                                int64_t cp, const uint32_t *slot, const float *fixed_scale,
+                                int64_t cp, const uint32_t *slot, int n_slot, const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st)
 {
-    dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n);
-    ProfileScope prof(EGERIA_KERNEL_QUANTIZE, st);
+    const dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n), block(256);
     if (dt == EGERIA_F32)
-        hipLaunchKernelGGL(quantize_nchw_kernel<false>, grid, dim3(256), 0, st, x, n, c, hw, cp, slot,
-                           fixed_scale, q, scale_out, scale_out2, flag);
-    else
-        hipLaunchKernelGGL(quantize_nchw_kernel<true>, grid, dim3(256), 0, st, x, n, c, hw, cp, slot,
-                           fixed_scale, q, scale_out, scale_out2, flag);
-    return hipGetLastError();
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_kernel<false>, grid, block, 0, st, x, n, c, hw, cp, slot,
+                        n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_kernel<true>, grid, block, 0, st, x, n, c, hw, cp, slot,
+                    n_slot, fixed_scale, q, scale_out, scale_out2, flag);
 }
 
 // ---- dequantise ------------------------------------------------------------------------
@@ -297,8 +306,7 @@ hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, flo
     if (n <= 0) return hipSuccess;
     int64_t blocks = (n + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, q, scale, n, x);
-    return hipGetLastError();
+    return launch_k(EGERIA_KERNEL_NONE, dequantize_kernel, dim3((unsigned)blocks), dim3(256), 0, st, q, scale, n, x);
 }
 
 }  // namespace egeria
