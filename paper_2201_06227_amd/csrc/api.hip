@@ -173,6 +173,9 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     const egeria_qlinear &L = f.qw->linear[li];
     GemmArgs g;
     g.a = a; g.w = L.w_q; g.M = M; g.N = N; g.kp = kp; g.lda = lda;
+    g.a_bytes = conv ? M * (int64_t)cp : M * lda;
+    g.w_bytes = (int64_t)N * kp;
+    if (g.a_bytes >= (1LL << 31) || g.w_bytes >= (1LL << 31)) return EGERIA_ERR_UNSUPPORTED;
     g.conv3x3 = conv ? 1 : 0; g.H = H; g.W = W; g.cp = cp;
     g.sx = sx; g.sw = L.scale; g.bias = L.bias; g.act = act;
     g.res_q = res_q; g.res_scale = res_scale; g.res_ld = res_ld;

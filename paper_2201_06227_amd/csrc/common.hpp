@@ -93,6 +93,8 @@ struct GemmArgs {
     int32_t N;
     int32_t kp;             // padded reduction length in bytes (multiple of 16)
     int64_t lda;            // row stride of `a` in bytes (linear mode)
+    int64_t a_bytes;        // extent of `a` in bytes (< 2^31)
+    int64_t w_bytes;        // extent of `w` in bytes (< 2^31)
     int32_t conv3x3;        // 0: rows of `a` are contiguous; 1: 3x3 window gather, zero padding 1
     int32_t H, W, cp;       // image height, width and padded channels (conv3x3 mode)
     const float *sx;        // 1 fp32: scale of the activations
