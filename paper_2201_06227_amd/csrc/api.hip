@@ -91,7 +91,8 @@ Plan make_plan(const egeria_block_desc *d)
     }
     default: {
         p.n_layers = d->n_layers;
-        p.slots = 4 * p.n_layers; p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
+        p.slots = 5 * p.n_layers;      // four quantise points per layer + one exact-absmax word for the GELU
+        p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
         take(header_bytes(p.slots));
         const int64_t kmax = pad16(d->hidden > d->ffn ? d->hidden : d->ffn);
         p.off_q[0] = take((size_t)(p.M * kmax));
@@ -168,7 +169,7 @@ struct Fwd {
 egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64_t M, int32_t N, int32_t kp,
                        bool conv, int32_t H, int32_t W, int32_t cp, const float *sx, int act,
                        const int8_t *res_q, const float *res_scale, int64_t res_ld, float *y,
-                       uint32_t *absmax_out)
+                       uint32_t *absmax_out, bool amax_pos = false, bool tap_y = true)
 {
     const egeria_qlinear &L = f.qw->linear[li];
     GemmArgs g;
@@ -183,8 +184,9 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     const egeria_tap *t = f.tap(li);
     g.acc_out = t ? t->acc : nullptr;
     g.absmax_out = absmax_out;
+    g.amax_pos = amax_pos ? 1 : 0;
     EG_HIP(launch_gemm_i8(g, f.st));
-    return f.copy_tap_y(li, y, (size_t)M * N * 4);
+    return tap_y ? f.copy_tap_y(li, y, (size_t)M * N * 4) : EGERIA_OK;
 }
 
 egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
@@ -263,11 +265,16 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     EG_HIP(launch_quantize_rows(y1, EGERIA_F32, M, Hd, hp, f.amax(s0 + 2), f.n_amax(s0 + 2), nullptr, xq, f.scale(s0 + 2), nullptr,
                                 ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0 + 2, xq, (size_t)(M * hp), f.scale(s0 + 2)));
-    EG_OK(run_gemm(f, s0 + 2, xq, hp, M, F, hp, false, 0, 0, 0, f.scale(s0 + 2), 2, nullptr, nullptr, 0, ff,
-                   f.slot(s0 + 3)));
-
-    EG_HIP(launch_quantize_rows(ff, EGERIA_F32, M, F, fp, f.amax(s0 + 3), f.n_amax(s0 + 3), nullptr, xq, f.scale(s0 + 3), nullptr,
-                                ws_flag(f.ws), f.st));
+    // first feed-forward GEMM: pre-activations only, tracking their positive maximum;
+    // GELU is applied inside the next quantiser
+    uint32_t *exact_word = f.slot(4 * f.p.n_layers + l);
+    EG_OK(run_gemm(f, s0 + 2, xq, hp, M, F, hp, false, 0, 0, 0, f.scale(s0 + 2), 0, nullptr, nullptr, 0, ff,
+                   f.slot(s0 + 3), true, false));
+    if (const egeria_tap *t = f.tap(s0 + 2))
+        if (t->y) EG_HIP(launch_gelu_exact(ff, M * (int64_t)F, t->y, f.st));
+    EG_HIP(launch_gelu_absmax_exact(ff, M * (int64_t)F, f.slot(s0 + 3), exact_word, f.st));
+    EG_HIP(launch_quantize_gelu_rows(ff, M, F, fp, f.slot(s0 + 3), exact_word, xq, f.scale(s0 + 3), ws_flag(f.ws),
+                                     f.st));
     EG_OK(f.copy_tap_q(s0 + 3, xq, (size_t)(M * fp), f.scale(s0 + 3)));
     EG_OK(run_gemm(f, s0 + 3, xq, fp, M, Hd, fp, false, 0, 0, 0, f.scale(s0 + 3), 0, nullptr, nullptr, 0, proj,
                    nullptr));

@@ -83,6 +83,19 @@ hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st);
 
+// Fused GELU + quantise of a linear layer's pre-activations v [rows, cols]:
+// codes of gelu(v) under the per-tensor scale of gelu(v), without storing
+// gelu(v).  vmax holds max(v, 0) over the tensor (bit pattern); exact_absmax is
+// a second word that launch_gelu_absmax_exact fills when vmax is too small for
+// the shortcut absmax = gelu(vmax).
+hipError_t launch_gelu_absmax_exact(const float *v, int64_t n, const uint32_t *vmax, uint32_t *exact_absmax,
+                                    hipStream_t st);
+hipError_t launch_quantize_gelu_rows(const float *v, int64_t rows, int64_t cols, int64_t ldq,
+                                     const uint32_t *vmax, const uint32_t *exact_absmax, int8_t *q,
+                                     float *scale_out, uint32_t *flag, hipStream_t st);
+// y = gelu(v) evaluated in fp64, rounded once (observation points only).
+hipError_t launch_gelu_exact(const float *v, int64_t n, float *y, hipStream_t st);
+
 hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
 
 // int8 GEMM / implicit-GEMM convolution with fused dequantising epilogue.
@@ -108,6 +121,7 @@ struct GemmArgs {
     int64_t ldy;
     int32_t *acc_out;       // optional raw accumulators [M, N]
     uint32_t *absmax_out;   // optional: atomicMax of |y| (bit pattern)
+    int32_t amax_pos;       // 1: track max(y, 0) instead of |y| (input of the fused GELU quantiser)
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 

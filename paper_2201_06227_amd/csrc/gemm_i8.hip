@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                 }
                 out[e] = v;
                 if (col + e < g.N) {
-                    const uint32_t ab = abs_bits(v);
+                    const uint32_t ab = g.amax_pos ? (v > 0.0f ? __float_as_uint(v) : 0u) : abs_bits(v);
                     amax = amax > ab ? amax : ab;
                 }
             }

@@ -290,6 +290,123 @@ hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64
                     n_slot, fixed_scale, q, scale_out, scale_out2, flag);
 }
 
+// ---- fused GELU + quantise ---------------------------------------------------------------
+// The GELU output of a Transformer layer's first feed-forward GEMM is consumed
+// only by the next quantiser, and its codes must equal those of the fp64
+// evaluation rounded to fp32.  GELU is evaluated in fp32 first; a lane falls
+// back to the fp64 form only when its value times inv lies closer to a rounding
+// boundary than the fp32 evaluation's error bound (a few elements per 100 000).
+__device__ __forceinline__ float gelu_exact(float v)
+{
+    const double d = (double)v;
+    return (float)(0.5 * d * (1.0 + erf(d * 0.70710678118654752440)));
+}
+
+constexpr float kGeluShortcutMin = 0.5f;   // gelu(0.5) = 0.346 exceeds max |gelu| over v < 0 (0.17)
+
+__global__ __launch_bounds__(256) void gelu_absmax_exact_kernel(const float *__restrict__ v, int64_t n,
+                                                                const uint32_t *__restrict__ vmax,
+                                                                uint32_t *__restrict__ exact_absmax)
+{
+    if (__uint_as_float(*vmax) >= kGeluShortcutMin) return;       // the shortcut applies: nothing to do
+    uint32_t m = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t a = abs_bits(gelu_exact(v[i]));
+        m = m > a ? m : a;
+    }
+    __shared__ uint32_t sm4[4];
+    block_atomic_max(m, exact_absmax, sm4);
+}
+
+hipError_t launch_gelu_absmax_exact(const float *v, int64_t n, const uint32_t *vmax, uint32_t *exact_absmax,
+                                    hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 1023) / 1024;
+    if (blocks > 1024) blocks = 1024;
+    return launch_k(EGERIA_KERNEL_NONE, gelu_absmax_exact_kernel, dim3((unsigned)blocks), dim3(256), 0, st, v, n, vmax,
+                    exact_absmax);
+}
+
+__device__ __forceinline__ uint32_t quant_gelu1(float v, float inv)
+{
+    const float g32 = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    float t = g32 * inv;
+    // |fp32 gelu - exact| <= 1e-6 * max(1, |v|); times inv, plus the product's own rounding
+    const float bound = inv * 1.0e-6f * fmaxf(1.0f, fabsf(v)) + 2.0e-5f;
+    const float frac = t - floorf(t);
+    if (!(fabsf(frac - 0.5f) > bound)) t = gelu_exact(v) * inv;
+    float r = rintf(t);
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (uint32_t)((int)r) & 0xffu;
+}
+
+__global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
+    const float *__restrict__ v, int64_t rows, int64_t cols, int64_t ldq, const uint32_t *__restrict__ vmax,
+    const uint32_t *__restrict__ exact_absmax, int8_t *__restrict__ q, float *__restrict__ scale_out,
+    uint32_t *__restrict__ flag)
+{
+    // absolute maximum of gelu(v): gelu is increasing for v >= 0 and bounded by 0.17 for v < 0
+    const float vm = __uint_as_float(*vmax);
+    const bool bad = !(vm <= 3.402823466e+38f);
+    float absmax = vm >= kGeluShortcutMin ? gelu_exact(vm) : __uint_as_float(*exact_absmax);
+    if (bad) absmax = 0.0f;
+    float scale = (float)((double)absmax / 127.0);
+    float inv = (float)(127.0 / (double)absmax);
+    if (!(inv <= 3.402823466e+38f) || !(scale > 0.0f)) { scale = 1.0f; inv = 0.0f; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, nullptr, flag);
+    const int64_t upr = ldq >> 4;
+    const int64_t units = rows * upr;
+    const bool vec_ok = (cols & 3) == 0;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
+         u += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = u / upr;
+        const int64_t c0 = (u - row * upr) << 4;
+        const int64_t base = row * cols + c0;
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (vec_ok && c0 + 16 <= cols) {
+            const float4 *p = (const float4 *)(v + base);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4 x = p[j];
+                w[j] = quant_gelu1(x.x, inv) | (quant_gelu1(x.y, inv) << 8) | (quant_gelu1(x.z, inv) << 16) |
+                       (quant_gelu1(x.w, inv) << 24);
+            }
+        } else {
+#pragma unroll 1
+            for (int e = 0; e < 16; ++e)
+                if (c0 + e < cols) w[e >> 2] |= quant_gelu1(v[base + e], inv) << ((e & 3) * 8);
+        }
+        *(uint4 *)(q + row * ldq + c0) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+hipError_t launch_quantize_gelu_rows(const float *v, int64_t rows, int64_t cols, int64_t ldq,
+                                     const uint32_t *vmax, const uint32_t *exact_absmax, int8_t *q,
+                                     float *scale_out, uint32_t *flag, hipStream_t st)
+{
+    const int64_t units = rows * (ldq / 16);
+    int64_t blocks = (units + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_gelu_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, v,
+                    rows, cols, ldq, vmax, exact_absmax, q, scale_out, flag);
+}
+
+__global__ __launch_bounds__(256) void gelu_exact_kernel(const float *__restrict__ v, int64_t n, float *__restrict__ y)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        y[i] = gelu_exact(v[i]);
+}
+
+hipError_t launch_gelu_exact(const float *v, int64_t n, float *y, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    return launch_k(EGERIA_KERNEL_NONE, gelu_exact_kernel, dim3((unsigned)blocks), dim3(256), 0, st, v, n, y);
+}
+
 // ---- dequantise ------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dequantize_kernel(const int8_t *__restrict__ q,
                                                          const float *__restrict__ scale, int64_t n,

@@ -295,6 +295,21 @@ def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
         assert p_close(p[l].item(), want, kw["b"]), (l, p[l].item(), want)
 
 
+def test_bert_small_preactivations(eg, gc, orc):
+    """The fused GELU quantiser takes absmax = gelu(max v) as a shortcut when
+    max v >= 0.5; with tiny feed-forward weights it must fall back to the exact
+    absolute maximum of gelu(v) (which may then sit at a negative v)."""
+    wl = si.make_bert(b=2, s=24, hidden=64, heads=2, ffn=160, n_layers=2, seed=977, train_act_dtype="f32")
+    for l in range(2):
+        wl.weights[4 * l + 2] = (wl.weights[4 * l + 2] * np.float32(0.02)).astype(np.float32)
+    a_ref, taps, ref = gc.run_forward(wl)
+    ot = orc.ref_forward(wl)
+    assert float(np.abs(ot["L0.l2.acc"]).max()) > 0 and float(ot["L0.l2.y"].max()) < 0.3
+    for l in range(2):
+        _check_bert_layer_taps(gc, taps, ot, l)
+        assert (a_ref[l] == ot["a_ref"][l].reshape(2, -1)).all()
+
+
 def test_bert_layer_full_size(eg, gc, orc):
     """Config 4: BERT-base layer, batch 32 x seq 128, bf16 training activations."""
     wl = si.make_config(4)
