@@ -304,6 +304,62 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
                     tpx);
 }
 
+// ---- 3x3 convolution with at most 16 input channels and at most 32 outputs ----------------
+// (the first stages of CIFAR-style ResNets).  The problem is bandwidth bound and
+// each output pixel needs only 9 x 16 bytes of input, so there is no LDS stage
+// and no barrier: a wave owns 32 consecutive output pixels; lane l reads, for
+// K step s, the 16 channel bytes of pixel l % 32 displaced by tap 2s + l / 32
+// (half-waves read contiguous 512-byte runs) and the matching 16 weight bytes of
+// output channel l % 32; five MFMAs cover the nine taps (the tenth is zero).
+__global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 31, h = lane >> 5;
+    const int64_t m = ((int64_t)blockIdx.x * 4 + wave) * 32 + p;
+    const bool m_ok = m < g.M;
+    const int ow = (int)(m % g.W), oh = (int)((m / g.W) % g.H);
+    const float s = (*g.sx) * (*g.sw);
+    const float rs = g.res_q ? *g.res_scale : 0.0f;
+    v4i fa[5], fb[5];
+#pragma unroll
+    for (int st = 0; st < 5; ++st) {
+        const int tap = 2 * st + h;
+        const int kh = tap / 3, dh = kh - 1, dw = tap - kh * 3 - 1;
+        const bool ok = m_ok && tap < 9 && (unsigned)(oh + dh) < (unsigned)g.H && (unsigned)(ow + dw) < (unsigned)g.W;
+        fa[st] = ok ? *(const v4i *)(g.a + (m + (int64_t)dh * g.W + dw) * 16) : v4i{0, 0, 0, 0};
+        fb[st] = (p < g.N && tap < 9) ? *(const v4i *)(g.w + (int64_t)p * g.kp + tap * 16) : v4i{0, 0, 0, 0};
+    }
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+#pragma unroll
+    for (int st = 0; st < 5; ++st) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[st], fb[st], acc, 0, 0, 0);
+
+    // lane holds output channel p and pixels 8 * (r / 4) + 4 * h + r % 4 of the wave's 32
+    const int col = p;
+    const bool col_ok = col < g.N;
+    const float bc = (g.bias && col_ok) ? g.bias[col] : 0.0f;
+    const int64_t mw = ((int64_t)blockIdx.x * 4 + wave) * 32;
+    uint32_t amax = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int64_t row = mw + (r >> 2) * 8 + h * 4 + (r & 3);
+        if (!col_ok || row >= g.M) continue;
+        const int a = acc[r];
+        if (g.acc_out) g.acc_out[row * g.N + col] = a;
+        float v = fmaf((float)a, s, bc);
+        if (g.res_q) v = v + (float)g.res_q[row * g.res_ld + col] * rs;
+        if (g.act == 1) v = v > 0.0f ? v : 0.0f;
+        g.y[row * g.ldy + col] = v;
+        const uint32_t ab = g.amax_pos ? (v > 0.0f ? __float_as_uint(v) : 0u) : abs_bits(v);
+        amax = amax > ab ? amax : ab;
+    }
+    if (g.absmax_out) {
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, g.absmax_out, sm4);
+    }
+}
+
 // Tile choice.  With fp32 outputs the epilogue (convert, scale, store) costs as
 // much as the K loop unless K is long, so two 128x128 workgroups per CU, one in
 // its K loop while the other stores, beat one 256-wide workgroup; the wide
@@ -311,6 +367,12 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
     auto ntiles = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * (int64_t)((g.N + bn - 1) / bn); };
+    if (g.conv3x3 && g.cp == 16 && g.N <= 32 && g.act != 2) {
+        const int64_t blocks = (g.M + 127) / 128;
+        if (blocks <= 0) return hipSuccess;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        return launch_k(EGERIA_KERNEL_GEMM, conv3x3_c16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g);
+    }
     if (g.N <= 32) return launch_variant<128, 32, 4, 1>(g, st);
     if (g.kp >= 2048) {
         if (ntiles(256, 256) >= 448) return launch_variant<256, 256, 2, 2>(g, st);
