@@ -126,7 +126,8 @@ struct Fwd {
     // where the absolute maximum of quantise point i is found: the input tensor's
     // per-workgroup maxima for point 0, an atomically combined word otherwise
     const uint32_t *amax(int i) const { return i == 0 ? ws_partials(ws, p.slots) : ws_absmax(ws, i); }
-    int n_amax(int i) const { return i == 0 ? n_in : 1; }
+    int n_amax(int i) const { return i == 0 ? n_in : kAmaxWays; }
+    int stride_amax(int i) const { return i == 0 ? 1 : kAmaxStride; }
     uint32_t *slot(int i) const { return ws_absmax(ws, i); }
     float *scale(int i) const { return ws_scale(ws, p.slots, i); }
     int8_t *qbuf(int i) const { return (int8_t *)(ws + p.off_q[i]); }
@@ -194,7 +195,7 @@ egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
     const egeria_block_desc *d = f.d;
     const int64_t kp = pad16(d->c_in);
     EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
-    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.n_amax(0), nullptr, f.qbuf(0), f.scale(0),
+    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.n_amax(0), f.stride_amax(0), nullptr, f.qbuf(0), f.scale(0),
                                 nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(d->batch * kp), f.scale(0)));
     return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.scale(0), 1,
@@ -208,14 +209,14 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
     const int H = d->height, W = d->width;
     EG_OK(f.input_absmax(x, dt, M * d->c_in));
-    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.n_amax(0), nullptr, f.qbuf(0), f.scale(0),
+    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.n_amax(0), f.stride_amax(0), nullptr, f.qbuf(0), f.scale(0),
                                 nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));
     const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
     if (d->kind == EGERIA_BASIC_BLOCK) {
         EG_OK(run_gemm(f, 0, f.qbuf(0), 0, M, d->c_mid, 9 * cin_p, true, H, W, cin_p, f.scale(0), 1, nullptr,
                        nullptr, 0, f.fbuf(0), f.slot(1)));
-        EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), nullptr, f.qbuf(1),
+        EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), f.stride_amax(1), nullptr, f.qbuf(1),
                                     f.scale(1), nullptr, ws_flag(f.ws), f.st));
         EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
         return run_gemm(f, 1, f.qbuf(1), 0, M, d->c_out, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, res,
@@ -224,12 +225,12 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     // bottleneck: 1x1 -> 3x3 -> 1x1
     EG_OK(run_gemm(f, 0, f.qbuf(0), cin_p, M, d->c_mid, cin_p, false, 0, 0, 0, f.scale(0), 1, nullptr, nullptr,
                    0, f.fbuf(0), f.slot(1)));
-    EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), nullptr, f.qbuf(1),
+    EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), f.stride_amax(1), nullptr, f.qbuf(1),
                                 f.scale(1), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
     EG_OK(run_gemm(f, 1, f.qbuf(1), 0, M, d->c_mid, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, nullptr,
                    nullptr, 0, f.fbuf(1), f.slot(2)));
-    EG_HIP(launch_quantize_rows(f.fbuf(1), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(2), f.n_amax(2), nullptr, f.qbuf(2),
+    EG_HIP(launch_quantize_rows(f.fbuf(1), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(2), f.n_amax(2), f.stride_amax(2), nullptr, f.qbuf(2),
                                 f.scale(2), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(2, f.qbuf(2), (size_t)(M * cmid_p), f.scale(2)));
     return run_gemm(f, 2, f.qbuf(2), cmid_p, M, d->c_out, cmid_p, false, 0, 0, 0, f.scale(2), 1, res, f.scale(0),
@@ -248,13 +249,13 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     float *qkv = f.fbuf(0), *ctx = f.fbuf(1), *proj = f.fbuf(2), *y1 = f.fbuf(3), *ff = f.fbuf(4);
     int8_t *xq = f.qbuf(0);
 
-    EG_HIP(launch_quantize_rows(cur, EGERIA_F32, M, Hd, hp, f.amax(s0), f.n_amax(s0), nullptr, xq, f.scale(s0), nullptr,
+    EG_HIP(launch_quantize_rows(cur, EGERIA_F32, M, Hd, hp, f.amax(s0), f.n_amax(s0), f.stride_amax(s0), nullptr, xq, f.scale(s0), nullptr,
                                 ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
     EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
     EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
 
-    EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.amax(s0 + 1), f.n_amax(s0 + 1), nullptr, xq, f.scale(s0 + 1), nullptr,
+    EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.amax(s0 + 1), f.n_amax(s0 + 1), f.stride_amax(s0 + 1), nullptr, xq, f.scale(s0 + 1), nullptr,
                                 ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0 + 1, xq, (size_t)(M * hp), f.scale(s0 + 1)));
     EG_OK(run_gemm(f, s0 + 1, xq, hp, M, Hd, hp, false, 0, 0, 0, f.scale(s0 + 1), 0, nullptr, nullptr, 0, proj,
@@ -262,7 +263,7 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     EG_HIP(launch_layernorm(cur, proj, M, Hd, nm ? nm[0].gamma : nullptr, nm ? nm[0].beta : nullptr, d->ln_eps,
                             y1, f.slot(s0 + 2), f.st));
 
-    EG_HIP(launch_quantize_rows(y1, EGERIA_F32, M, Hd, hp, f.amax(s0 + 2), f.n_amax(s0 + 2), nullptr, xq, f.scale(s0 + 2), nullptr,
+    EG_HIP(launch_quantize_rows(y1, EGERIA_F32, M, Hd, hp, f.amax(s0 + 2), f.n_amax(s0 + 2), f.stride_amax(s0 + 2), nullptr, xq, f.scale(s0 + 2), nullptr,
                                 ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0 + 2, xq, (size_t)(M * hp), f.scale(s0 + 2)));
     // first feed-forward GEMM: pre-activations only, tracking their positive maximum;
@@ -331,9 +332,13 @@ egeria_status egeria_quantize(const void *x, egeria_dtype dt, int64_t n, const f
 {
     EG_OK(quantize_common(x, dt, n, fixed_scale, q, scale_out, ws, ws_bytes));
     hipStream_t st = (hipStream_t)stream;
+    if (!fixed_scale && n > 0 && n <= kSmallTensor) {
+        EG_HIP(launch_quantize_small(x, dt, 1, (int)n, 1, (int)n, q, scale_out, ws_flag(ws), st));
+        return EGERIA_OK;
+    }
     const int nb = fixed_scale ? 0 : absmax_blocks(n, dt);
     if (!fixed_scale) EG_HIP(launch_absmax(x, dt, n, ws_partials(ws, 1), nullptr, 0, st));
-    EG_HIP(launch_quantize_rows(x, dt, 1, n, n, ws_partials(ws, 1), nb, fixed_scale, q, scale_out, nullptr, ws_flag(ws),
+    EG_HIP(launch_quantize_rows(x, dt, 1, n, n, ws_partials(ws, 1), nb, 1, fixed_scale, q, scale_out, nullptr, ws_flag(ws),
                                 st));
     return EGERIA_OK;
 }
@@ -345,9 +350,13 @@ egeria_status egeria_quantize_rows(const void *x, egeria_dtype dt, int64_t rows,
     if (rows < 0 || cols < 0) return EGERIA_ERR_INVALID_ARG;
     EG_OK(quantize_common(x, dt, rows * cols, fixed_scale, q, scale_out, ws, ws_bytes));
     hipStream_t st = (hipStream_t)stream;
+    if (!fixed_scale && rows * cols > 0 && rows * pad16(cols) <= kSmallTensor) {
+        EG_HIP(launch_quantize_small(x, dt, (int)rows, (int)cols, 1, (int)pad16(cols), q, scale_out, ws_flag(ws), st));
+        return EGERIA_OK;
+    }
     const int nb = fixed_scale ? 0 : absmax_blocks(rows * cols, dt);
     if (!fixed_scale) EG_HIP(launch_absmax(x, dt, rows * cols, ws_partials(ws, 1), nullptr, 0, st));
-    EG_HIP(launch_quantize_rows(x, dt, rows, cols, pad16(cols), ws_partials(ws, 1), nb, fixed_scale, q, scale_out,
+    EG_HIP(launch_quantize_rows(x, dt, rows, cols, pad16(cols), ws_partials(ws, 1), nb, 1, fixed_scale, q, scale_out,
                                 nullptr, ws_flag(ws), st));
     return EGERIA_OK;
 }
@@ -360,14 +369,18 @@ egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, in
     EG_OK(quantize_common(x, dt, n * c * h * w, fixed_scale, q, scale_out, ws, ws_bytes));
     if (n > 65535 || pad16(c) / 64 > 65535) return EGERIA_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
+    if (!fixed_scale && n * c * h * w > 0 && n * h * w * pad16(c) <= kSmallTensor) {
+        EG_HIP(launch_quantize_small(x, dt, (int)n, (int)c, (int)(h * w), (int)pad16(c), q, scale_out, ws_flag(ws), st));
+        return EGERIA_OK;
+    }
     const int nb = fixed_scale ? 0 : absmax_blocks(n * c * h * w, dt);
     if (!fixed_scale) EG_HIP(launch_absmax(x, dt, n * c * h * w, ws_partials(ws, 1), nullptr, 0, st));
     if (n * c * h * w == 0) {
-        EG_HIP(launch_quantize_rows(x, dt, 0, 0, 0, ws_partials(ws, 1), nb, fixed_scale, q, scale_out, nullptr,
+        EG_HIP(launch_quantize_rows(x, dt, 0, 0, 0, ws_partials(ws, 1), nb, 1, fixed_scale, q, scale_out, nullptr,
                                     ws_flag(ws), st));
         return EGERIA_OK;
     }
-    EG_HIP(launch_quantize_nchw(x, dt, n, c, h * w, pad16(c), ws_partials(ws, 1), nb, fixed_scale, q, scale_out,
+    EG_HIP(launch_quantize_nchw(x, dt, n, c, h * w, pad16(c), ws_partials(ws, 1), nb, 1, fixed_scale, q, scale_out,
                                 nullptr, ws_flag(ws), st));
     return EGERIA_OK;
 }

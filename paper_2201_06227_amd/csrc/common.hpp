@@ -24,16 +24,30 @@ constexpr uint32_t kFlagMagic = 0xE6E71A00u;
 constexpr uint32_t kFlagNonFinite = 1u;
 constexpr int kHeaderFixedWords = 16;
 constexpr int kAbsPartials = 512;
+// An atomically combined maximum is spread over kAmaxWays words, kAmaxStride
+// words apart (workgroup id modulo the ways picks the word): thousands of
+// workgroups finishing together would otherwise serialise on one address.
+constexpr int kAmaxWays = 64;
+constexpr int kAmaxStride = 64;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t header_bytes(int slots)
 {
-    return align_up(4 * (size_t)(kHeaderFixedWords + 2 * slots + kAbsPartials), 256);
+    return align_up(4 * (size_t)(kHeaderFixedWords + slots * (kAmaxWays * kAmaxStride + 1) + kAbsPartials), 256);
 }
 inline uint32_t *ws_flag(void *ws) { return (uint32_t *)ws; }
-inline uint32_t *ws_absmax(void *ws, int slot) { return (uint32_t *)ws + kHeaderFixedWords + slot; }
-inline float *ws_scale(void *ws, int slots, int slot) { return (float *)ws + kHeaderFixedWords + slots + slot; }
-inline uint32_t *ws_partials(void *ws, int slots) { return (uint32_t *)ws + kHeaderFixedWords + 2 * slots; }
+inline uint32_t *ws_absmax(void *ws, int slot)
+{
+    return (uint32_t *)ws + kHeaderFixedWords + (size_t)slot * kAmaxWays * kAmaxStride;
+}
+inline float *ws_scale(void *ws, int slots, int slot)
+{
+    return (float *)ws + kHeaderFixedWords + (size_t)slots * kAmaxWays * kAmaxStride + slot;
+}
+inline uint32_t *ws_partials(void *ws, int slots)
+{
+    return (uint32_t *)ws + kHeaderFixedWords + (size_t)slots * (kAmaxWays * kAmaxStride + 1);
+}
 
 // ---- optional event timing of one kernel class (egeria_profile_begin / egeria_profile_end) ----
 struct ProfileState {
@@ -62,8 +76,8 @@ inline hipError_t launch_k(int cls, K kernel, dim3 grid, dim3 block, size_t smem
 
 // ---- launchers (each enqueues on `st` and returns hipGetLastError()) --------
 // Per-workgroup maxima of |x| over n values into partials[0 .. absmax_blocks(n))
-// (plain stores).  Block 0 also clears `n_reset` words at `reset` (the atomic
-// slots of the chain that follows).
+// (plain stores).  Block 0 also clears the ways of `n_reset` atomic slots that
+// start at `reset` (the quantise points of the chain that follows).
 int absmax_blocks(int64_t n, egeria_dtype dt);
 hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *partials, uint32_t *reset,
                          int n_reset, hipStream_t st);
@@ -72,14 +86,16 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *pa
 // 16, pad bytes zero) with the scale derived from max(slot[0 .. n_slot)) (or
 // *fixed_scale).  Writes the scale to scale_out and, if non-null, scale_out2.
 hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
-                                int64_t ldq, const uint32_t *slot, int n_slot, const float *fixed_scale,
+                                int64_t ldq, const uint32_t *slot, int n_slot, int slot_stride,
+                                const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st);
 
 // Quantise [n, c, hw] (channel-major) into int8 [n, hw, cp] (channel-last, cp =
 // padded c, pad zero).
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
-                                int64_t cp, const uint32_t *slot, int n_slot, const float *fixed_scale,
+                                int64_t cp, const uint32_t *slot, int n_slot, int slot_stride,
+                                const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st);
 
@@ -95,6 +111,12 @@ hipError_t launch_quantize_gelu_rows(const float *v, int64_t rows, int64_t cols,
                                      float *scale_out, uint32_t *flag, hipStream_t st);
 // y = gelu(v) evaluated in fp64, rounded once (observation points only).
 hipError_t launch_gelu_exact(const float *v, int64_t n, float *y, hipStream_t st);
+
+// One-launch quantisation of a small tensor [nimg, c, hw] -> int8 [nimg, hw, cp]
+// (at most kSmallTensor values, dynamic scale only).
+constexpr int64_t kSmallTensor = 16384;
+hipError_t launch_quantize_small(const void *x, egeria_dtype dt, int nimg, int c, int hw, int cp, int8_t *q,
+                                 float *scale_out, uint32_t *flag, hipStream_t st);
 
 hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
 
@@ -178,8 +200,21 @@ __device__ __forceinline__ void block_atomic_max(uint32_t v, uint32_t *slot, uin
     if (threadIdx.x == 0) {
         uint32_t a = sm4[0] > sm4[1] ? sm4[0] : sm4[1], c = sm4[2] > sm4[3] ? sm4[2] : sm4[3];
         a = a > c ? a : c;
-        if (a > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, a);
+        uint32_t *way = slot + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride;
+        if (a > __hip_atomic_load(way, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(way, a);
     }
+}
+// Maximum over the ways of an atomically combined word; every lane of the wave
+// must call it.
+__device__ __forceinline__ uint32_t reduce_ways(const uint32_t *slot)
+{
+    uint32_t v = slot[(threadIdx.x & (kAmaxWays - 1)) * kAmaxStride];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 #endif

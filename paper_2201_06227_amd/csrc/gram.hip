@@ -20,11 +20,12 @@
 //   current one is contracted) and read back as 128-bit v_mfma_f32_32x32x2f32
 //   operands: lane l takes row l % 32 and four consecutive k at 8s + 4(l / 32),
 //   A and B operand alike, so the order of k inside the sum never matters.
-// Kernel 2 (sp_finalize): one workgroup per row i of the b x b matrices: sums
-//   the partials over chunks in fp64 (four waves, fixed assignment, fixed
-//   order), forms row i of both Gram matrices, their norms and the row's share
-//   of the squared difference; the last workgroup to finish adds the b shares in
-//   index order and writes P.  Results are bit-reproducible from call to call.
+// Kernel 2 (gram_reduce): sums the partials over chunks in fp64, element-wise,
+//   coalesced, in a fixed order.
+// Kernel 3 (sp_finalize): one wave per row i of the b x b matrices: row i of
+//   both Gram matrices, their norms and the row's share of the squared
+//   difference; the last wave to finish adds the b shares in index order and
+//   writes P.  Results are bit-reproducible from call to call.
 #include "common.hpp"
 
 namespace egeria {
@@ -60,9 +61,10 @@ static GramPlan plan_gram(int32_t b, int64_t D)
     return p;
 }
 
-// workspace of the metric: [counter | row shares (b doubles) | partials]
+// workspace of the metric: [counter | row shares (b doubles) | reduced M, B (2 b^2 doubles) | partials]
 static size_t off_rowsum() { return 256; }
-static size_t off_partials(int32_t b) { return 256 + align_up((size_t)b * sizeof(double), 256); }
+static size_t off_red(int32_t b) { return 256 + align_up((size_t)b * sizeof(double), 256); }
+static size_t off_partials(int32_t b) { return off_red(b) + align_up(2 * (size_t)b * b * sizeof(double), 256); }
 
 size_t plasticity_partial_bytes(int32_t b, int64_t D)
 {
@@ -116,8 +118,6 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     constexpr int NTEN = MT == 1 ? 2 : 4;         // tensors staged: T_i, R_i (, T_j, R_j)
     static_assert(SLOTS % 256 == 0, "tile must divide over the workgroup");
     extern __shared__ __attribute__((aligned(16))) float lds[];   // [2 stages][NTEN][ROWS][LD]
-
-    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0u;      // ticket of the finaliser
 
     // consecutive workgroup ids land on different XCDs: all macro tiles of one
     // chunk go to the same XCD so that its L2 serves the re-reads of that chunk
@@ -241,83 +241,74 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     }
 }
 
-// One workgroup per row i.  part = [nsplit][2][b][b] (M then B).
-__global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restrict__ part, int nsplit,
-                                                          int b, double *__restrict__ rowsum,
-                                                          uint32_t *__restrict__ counter,
-                                                          float *__restrict__ p_out)
+// Sum of the partials over chunks in fp64, element-wise (coalesced, fixed order):
+// part = [nsplit][2][b][b] (M then B) -> red = [2][b][b] doubles.
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int nsplit,
+                                                          int nelem2, double *__restrict__ red,
+                                                          uint32_t *__restrict__ counter)
 {
-    __shared__ double sm[3][4][128];              // [m_ij | m_ji | b_ij][wave][column]
-    __shared__ double fin[4];
-    __shared__ bool last;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = blockIdx.x;
-    const size_t nelem = (size_t)b * b;
-    // each wave sums the chunks c = wave, wave + 4, ... for up to two columns per lane
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e == 0) *counter = 0u;                    // ticket of the finaliser
+    if (e >= nelem2) return;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int c = 0;
+    for (; c + 3 < nsplit; c += 4) {              // four independent loads in flight
+        s0 += (double)part[(size_t)c * nelem2 + e];
+        s1 += (double)part[(size_t)(c + 1) * nelem2 + e];
+        s2 += (double)part[(size_t)(c + 2) * nelem2 + e];
+        s3 += (double)part[(size_t)(c + 3) * nelem2 + e];
+    }
+    for (; c < nsplit; ++c) s0 += (double)part[(size_t)c * nelem2 + e];
+    red[e] = (s0 + s1) + (s2 + s3);
+}
+
+// One wave per row i of the b x b matrices: row i of both Gram matrices, their
+// norms, the row's share of the squared difference; the last wave to finish adds
+// the b shares in index order and writes P.
+__global__ __launch_bounds__(64) void sp_finalize_kernel(const double *__restrict__ red, int b,
+                                                         double *__restrict__ rowsum,
+                                                         uint32_t *__restrict__ counter,
+                                                         float *__restrict__ p_out)
+{
+    const int lane = threadIdx.x, i = blockIdx.x;
+    const double *M = red, *B = red + (size_t)b * b;
+    double gt[2], gr[2], nt2 = 0.0, nr2 = 0.0;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int j = lane + 64 * half;
-        double mij = 0.0, mji = 0.0, bij = 0.0;
+        gt[half] = gr[half] = 0.0;
         if (j < b) {
-            const float *pm = part + (size_t)i * b + j, *pmt = part + (size_t)j * b + i;
-            const float *pb = part + nelem + (size_t)i * b + j;
-            for (int c = wave; c < nsplit; c += 4) {
-                const size_t o = (size_t)c * 2 * nelem;
-                mij += (double)pm[o];
-                mji += (double)pmt[o];
-                bij += (double)pb[o];
-            }
+            gr[half] = B[(size_t)i * b + j];
+            gt[half] = gr[half] + 0.5 * (M[(size_t)i * b + j] + M[(size_t)j * b + i]);
         }
-        sm[0][wave][j] = mij;
-        sm[1][wave][j] = mji;
-        sm[2][wave][j] = bij;
+        nt2 += gt[half] * gt[half];
+        nr2 += gr[half] * gr[half];
     }
-    __syncthreads();
-    if (wave == 0) {
-        double gt[2], gr[2], nt2 = 0.0, nr2 = 0.0;
+    nt2 = wave_sum(nt2);
+    nr2 = wave_sum(nr2);
+    double nt = sqrt(nt2), nr = sqrt(nr2);
+    nt = nt < 1e-12 ? 1e-12 : nt;
+    nr = nr < 1e-12 ? 1e-12 : nr;
+    double acc = 0.0;
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int j = lane + 64 * half;
-            gt[half] = gr[half] = 0.0;
-            if (j < b) {
-                const double mij = (sm[0][0][j] + sm[0][1][j]) + (sm[0][2][j] + sm[0][3][j]);
-                const double mji = (sm[1][0][j] + sm[1][1][j]) + (sm[1][2][j] + sm[1][3][j]);
-                gr[half] = (sm[2][0][j] + sm[2][1][j]) + (sm[2][2][j] + sm[2][3][j]);
-                gt[half] = gr[half] + 0.5 * (mij + mji);
-            }
-            nt2 += gt[half] * gt[half];
-            nr2 += gr[half] * gr[half];
-        }
-        nt2 = wave_sum(nt2);
-        nr2 = wave_sum(nr2);
-        double nt = sqrt(nt2), nr = sqrt(nr2);
-        nt = nt < 1e-12 ? 1e-12 : nt;
-        nr = nr < 1e-12 ? 1e-12 : nr;
-        double acc = 0.0;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const double d = gt[half] / nt - gr[half] / nr;
-            acc += d * d;
-        }
-        acc = wave_sum(acc);
-        if (lane == 0) {
-            rowsum[i] = acc;
-            __threadfence();                                   // publish the share, then take a ticket
-            const uint32_t ticket = atomicAdd(counter, 1u);
-            last = ticket == (uint32_t)(b - 1);
-        }
+    for (int half = 0; half < 2; ++half) {
+        const double d = gt[half] / nt - gr[half] / nr;
+        acc += d * d;
     }
-    __syncthreads();
-    if (!last) return;
-    __threadfence();                                           // see every other workgroup's share
-    if (wave == 0) {
-        // b <= 128 shares, added in index order by a fixed tree
-        double v0 = lane < b ? __hip_atomic_load(&rowsum[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-        double v1 = lane + 64 < b ? __hip_atomic_load(&rowsum[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-        const double tot = wave_sum(v0 + v1);
-        if (lane == 0) *p_out = (float)(tot / ((double)b * (double)b));
+    acc = wave_sum(acc);
+    uint32_t ticket = 0;
+    if (lane == 0) {
+        rowsum[i] = acc;
+        __threadfence();                                   // publish the share, then take a ticket
+        ticket = atomicAdd(counter, 1u);
     }
-    (void)fin;
+    ticket = (uint32_t)__shfl((int)ticket, 0, kWave);
+    if (ticket != (uint32_t)(b - 1)) return;
+    __threadfence();                                       // see every other wave's share
+    const double v0 = lane < b ? __hip_atomic_load(&rowsum[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    const double v1 = lane + 64 < b ? __hip_atomic_load(&rowsum[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    const double tot = wave_sum(v0 + v1);
+    if (lane == 0) *p_out = (float)(tot / ((double)b * (double)b));
 }
 
 hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r, egeria_dtype r_dt,
@@ -359,8 +350,13 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     }
 #undef EGERIA_GRAM
     if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(256), 0, st,
-                    (const float *)part, p.nsplit, (int)b, rowsum, counter, p_out);
+    double *red = (double *)((char *)ws_part + off_red(b));
+    const int nelem2 = 2 * b * b;
+    e = launch_k(EGERIA_KERNEL_NONE, gram_reduce_kernel, dim3((unsigned)((nelem2 + 255) / 256)), dim3(256), 0, st,
+                 (const float *)part, p.nsplit, nelem2, red, counter);
+    if (e != hipSuccess) return e;
+    return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(64), 0, st, (const double *)red,
+                    (int)b, rowsum, counter, p_out);
 }
 
 }  // namespace egeria

@@ -31,7 +31,9 @@ __global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv
                                                      uint32_t *__restrict__ partials,
                                                      uint32_t *__restrict__ reset, int n_reset)
 {
-    if (blockIdx.x == 0 && (int)threadIdx.x < n_reset) reset[threadIdx.x] = 0u;
+    if (blockIdx.x == 0)
+        for (int t = threadIdx.x; t < n_reset * kAmaxWays; t += blockDim.x)
+            reset[(size_t)(t / kAmaxWays) * kAmaxWays * kAmaxStride + (t % kAmaxWays) * kAmaxStride] = 0u;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
     uint32_t m = 0;
@@ -99,7 +101,6 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *pa
                          int n_reset, hipStream_t st)
 {
     const dim3 grid((unsigned)absmax_blocks(n, dt)), block(256);
-    if (n_reset > 256) return hipErrorInvalidValue;
     if (dt == EGERIA_F32)
         return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<false>, grid, block, 0, st, x, n, partials, reset, n_reset);
     return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<true>, grid, block, 0, st, x, n, partials, reset, n_reset);
@@ -109,13 +110,13 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *pa
 // Called by every thread at the top of a quantise kernel.  Reduces the n_slot
 // candidate maxima, returns the multiplier inv and the scale; *bad is set when
 // the tensor holds a NaN or an infinity.
-__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot,
+__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
                                              const float *__restrict__ fixed_scale, float *scale, bool *bad)
 {
     uint32_t bits = 0;
     const int lane = threadIdx.x & 63;
     for (int i = lane; i < n_slot; i += 64) {
-        const uint32_t v = slot[i];
+        const uint32_t v = slot[(size_t)i * slot_stride];
         bits = bits > v ? bits : v;
     }
     bits = wave_max_u32(bits);
@@ -169,13 +170,14 @@ __device__ __forceinline__ float load_elem(const void *x, int64_t i)
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(
     const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
-    const uint32_t *__restrict__ slot, int n_slot, const float *__restrict__ fixed_scale,
+    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+    const float *__restrict__ fixed_scale,
     int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
     uint32_t *__restrict__ flag)
 {
     float scale;
     bool bad;
-    const float inv = scales_from(slot, n_slot, fixed_scale, &scale, &bad);
+    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t upr = (ldq + 15) >> 4;                     // 16-byte units per row
     const int64_t units = rows * upr;
@@ -225,7 +227,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(
 }
 
 hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
-                                int64_t ldq, const uint32_t *slot, int n_slot, const float *fixed_scale,
+                                int64_t ldq, const uint32_t *slot, int n_slot, int slot_stride,
+                                const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st)
 {
@@ -236,9 +239,9 @@ hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, in
     const dim3 grid((unsigned)blocks), block(256);
     if (dt == EGERIA_F32)
         return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_rows_kernel<false>, grid, block, 0, st, x, rows, cols, ldq,
-                        slot, n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+                        slot, n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2, flag);
     return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_rows_kernel<true>, grid, block, 0, st, x, rows, cols, ldq, slot,
-                    n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+                    n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2, flag);
 }
 
 // ---- quantise [n, c, hw] -> int8 [n, hw, cp] -------------------------------------------
@@ -247,13 +250,14 @@ hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, in
 template <bool BF16>
 __global__ __launch_bounds__(256) void quantize_nchw_kernel(
     const void *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
-    const uint32_t *__restrict__ slot, int n_slot, const float *__restrict__ fixed_scale,
+    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+    const float *__restrict__ fixed_scale,
     int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
     uint32_t *__restrict__ flag)
 {
     float scale;
     bool bad;
-    const float inv = scales_from(slot, n_slot, fixed_scale, &scale, &bad);
+    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
         publish(scale, bad, scale_out, scale_out2, flag);
     __shared__ uint8_t tile[64][64 + 4];                  // [pixel][channel], padded rows
@@ -278,16 +282,62 @@ __global__ __launch_bounds__(256) void quantize_nchw_kernel(
 }
 
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
-                                int64_t cp, const uint32_t *slot, int n_slot, const float *fixed_scale,
+                                int64_t cp, const uint32_t *slot, int n_slot, int slot_stride,
+                                const float *fixed_scale,
                                 int8_t *q, float *scale_out, float *scale_out2, uint32_t *flag,
                                 hipStream_t st)
 {
     const dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n), block(256);
     if (dt == EGERIA_F32)
         return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_kernel<false>, grid, block, 0, st, x, n, c, hw, cp, slot,
-                        n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+                        n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2, flag);
     return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_kernel<true>, grid, block, 0, st, x, n, c, hw, cp, slot,
-                    n_slot, fixed_scale, q, scale_out, scale_out2, flag);
+                    n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2, flag);
+}
+
+// ---- small tensors: one workgroup, one launch -----------------------------------------------
+// Absolute maximum, scale and codes of a tensor of a few thousand values
+// (convolution weights of a narrow layer, a small mini-batch): both passes in
+// one workgroup, so the tensor costs one kernel launch instead of two.
+// General form [nimg, c, hw] -> int8 [nimg, hw, cp]; a row-major matrix is the
+// case hw = 1.
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restrict__ x, int nimg, int c, int hw,
+                                                             int cp, int8_t *__restrict__ q,
+                                                             float *__restrict__ scale_out,
+                                                             uint32_t *__restrict__ flag)
+{
+    const int total = nimg * c * hw;
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < total; i += 256) {
+        const uint32_t a = abs_bits(load_elem<BF16>(x, i));
+        m = m > a ? m : a;
+    }
+    m = wave_max_u32(m);
+    __shared__ uint32_t sm[4];
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    float scale;
+    bool bad;
+    const float inv = scales_from(sm, 4, 1, nullptr, &scale, &bad);
+    if (threadIdx.x == 0) publish(scale, bad, scale_out, nullptr, flag);
+    const int nout = nimg * hw * cp;
+    for (int o = threadIdx.x; o < nout; o += 256) {
+        const int ch = o % cp, pp = (o / cp) % hw, img = o / (cp * hw);
+        uint32_t code = 0;
+        if (ch < c) code = quant1(load_elem<BF16>(x, ((int64_t)img * c + ch) * hw + pp), inv);
+        q[o] = (int8_t)code;
+    }
+}
+
+hipError_t launch_quantize_small(const void *x, egeria_dtype dt, int nimg, int c, int hw, int cp, int8_t *q,
+                                 float *scale_out, uint32_t *flag, hipStream_t st)
+{
+    if (dt == EGERIA_F32)
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_small_kernel<false>, dim3(1), dim3(256), 0, st, x, nimg, c, hw,
+                        cp, q, scale_out, flag);
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_small_kernel<true>, dim3(1), dim3(256), 0, st, x, nimg, c, hw, cp,
+                    q, scale_out, flag);
 }
 
 // ---- fused GELU + quantise ---------------------------------------------------------------
@@ -308,7 +358,7 @@ __global__ __launch_bounds__(256) void gelu_absmax_exact_kernel(const float *__r
                                                                 const uint32_t *__restrict__ vmax,
                                                                 uint32_t *__restrict__ exact_absmax)
 {
-    if (__uint_as_float(*vmax) >= kGeluShortcutMin) return;       // the shortcut applies: nothing to do
+    if (__uint_as_float(reduce_ways(vmax)) >= kGeluShortcutMin) return;   // the shortcut applies: nothing to do
     uint32_t m = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const uint32_t a = abs_bits(gelu_exact(v[i]));
@@ -347,9 +397,10 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
     uint32_t *__restrict__ flag)
 {
     // absolute maximum of gelu(v): gelu is increasing for v >= 0 and bounded by 0.17 for v < 0
-    const float vm = __uint_as_float(*vmax);
+    const float vm = __uint_as_float(reduce_ways(vmax));
     const bool bad = !(vm <= 3.402823466e+38f);
-    float absmax = vm >= kGeluShortcutMin ? gelu_exact(vm) : __uint_as_float(*exact_absmax);
+    const float exact = __uint_as_float(reduce_ways(exact_absmax));
+    float absmax = vm >= kGeluShortcutMin ? gelu_exact(vm) : exact;
     if (bad) absmax = 0.0f;
     float scale = (float)((double)absmax / 127.0);
     float inv = (float)(127.0 / (double)absmax);
