@@ -143,9 +143,10 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
         srow[it] = s / (KT / 4);
         scol[it] = (s % (KT / 4)) * 4;
     }
-    float4 st[NTEN][NIT];
-    auto fetch = [&](int t) {
-        const int64_t kb = k0 + (int64_t)t * KT;
+    // Two register sets: global loads run two K tiles ahead of the MFMAs (one
+    // tile of MFMAs is shorter than an HBM round trip), LDS holds two stages.
+    auto fetch = [&](int t, float4 (&st)[NTEN][NIT]) {
+        const int64_t kb = k0 + (int64_t)t * KT;       // past the chunk's end load4 returns zeros
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int64_t ri = (int64_t)mi * ROWS + srow[it];
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
             }
         }
     };
-    auto stash = [&](int stage) {
+    auto stash = [&](int stage, const float4 (&st)[NTEN][NIT]) {
         float *base = lds + (size_t)stage * NTEN * ROWS * LD;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
@@ -181,31 +182,48 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     const int rowA = bi * 32 + r, rowB = bj * 32 + r;
     const int kw0 = MT == 1 ? wave * 32 : 0;      // this wave's 32-float slice of the K tile
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles) fetch(t + 1);
-        const float *base = lds + (size_t)(t & 1) * NTEN * ROWS * LD;
+    auto contract = [&](int stage) {
+        const float *base = lds + (size_t)stage * NTEN * ROWS * LD;
         const float *pTi = base + 0 * ROWS * LD + rowA * LD + kw0 + 4 * h;
         const float *pRi = base + 1 * ROWS * LD + rowA * LD + kw0 + 4 * h;
         const float *pTj = base + (diag ? 0 : 2) * ROWS * LD + rowB * LD + kw0 + 4 * h;
         const float *pRj = base + (diag ? 1 : 3) * ROWS * LD + rowB * LD + kw0 + 4 * h;
+        float4 ti[4], ri[4], tj[4], rj[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const float4 ti = *(const float4 *)(pTi + 8 * s), ri = *(const float4 *)(pRi + 8 * s);
-            const float4 tj = *(const float4 *)(pTj + 8 * s), rj = *(const float4 *)(pRj + 8 * s);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.x - ri.x, tj.x + rj.x, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.x, rj.x, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.y - ri.y, tj.y + rj.y, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.y, rj.y, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.z - ri.z, tj.z + rj.z, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.z, rj.z, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti.w - ri.w, tj.w + rj.w, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri.w, rj.w, accB, 0, 0, 0);
+            ti[s] = *(const float4 *)(pTi + 8 * s);
+            ri[s] = *(const float4 *)(pRi + 8 * s);
+            tj[s] = *(const float4 *)(pTj + 8 * s);
+            rj[s] = *(const float4 *)(pRj + 8 * s);
         }
-        if (t + 1 < ntiles) stash((t + 1) & 1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].x - ri[s].x, tj[s].x + rj[s].x, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].x, rj[s].x, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].y - ri[s].y, tj[s].y + rj[s].y, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].y, rj[s].y, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].z - ri[s].z, tj[s].z + rj[s].z, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].z, rj[s].z, accB, 0, 0, 0);
+            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].w - ri[s].w, tj[s].w + rj[s].w, accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].w, rj[s].w, accB, 0, 0, 0);
+        }
+    };
+
+    float4 st0[NTEN][NIT], st1[NTEN][NIT];
+    fetch(0, st0);
+    fetch(1, st1);
+    stash(0, st0);
+    __syncthreads();
+    // step t: tile t is in LDS stage t & 1, tile t + 1 in the set `rs`, tile t + 2 is requested into `rl`
+    auto step = [&](int t, float4 (&rs)[NTEN][NIT], float4 (&rl)[NTEN][NIT]) {
+        fetch(t + 2, rl);
+        contract(t & 1);
+        stash((t + 1) & 1, rs);
         __syncthreads();
+    };
+    for (int t = 0; t < ntiles; t += 2) {         // an odd count runs one extra step on zeros
+        step(t, st1, st0);
+        step(t + 1, st0, st1);
     }
 
     // lane l of a 32x32 block holds column l % 32, rows 8 * (i / 4) + 4 * (l / 32) + i % 4
