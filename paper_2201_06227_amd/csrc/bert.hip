@@ -59,7 +59,7 @@ hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int3
 // context feeds a quantiser, where a last-bit difference can flip an int8 code
 // and the flip is then amplified by every later layer.
 //
-// A workgroup owns one (batch, head) pair and 128 queries, 32 per wave (two
+// A workgroup owns one (batch, head) pair and 64 * QB queries, 16 * QB per wave (QB
 // blocks of 16); key / value tiles of 32 rows pass through LDS as fp32 and are
 // widened when read.  The products run on v_mfma_f64_16x16x4f64 in the
 // transposed form
@@ -73,16 +73,18 @@ constexpr int kDh = 64;             // head dimension covered (smaller heads are
 constexpr int kKeyTile = 32;
 constexpr int kKVPad = kDh + 4;
 
+template <int QB>
 __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict__ qkv, int B, int S,
                                                         int Hd, int heads, int dh, double scale,
                                                         float *__restrict__ ctx,
                                                         uint32_t *__restrict__ absmax_out)
 {
-    __shared__ __attribute__((aligned(16))) float sK[kKeyTile][kKVPad];
-    __shared__ __attribute__((aligned(16))) float sV[kKeyTile][kKVPad];
+    __shared__ __attribute__((aligned(16))) float sKb[2][kKeyTile][kKVPad];   // two stages
+    __shared__ __attribute__((aligned(16))) float sVb[2][kKeyTile][kKVPad];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int qtiles = (S + 127) / 128;
+    constexpr int QT = 64 * QB;          // queries per workgroup
+    const int qtiles = (S + QT - 1) / QT;
     const int bh = blockIdx.x / qtiles, qt = blockIdx.x % qtiles;
     const int bi = bh / heads, hd = bh % heads;
     const int64_t tok0 = (int64_t)bi * S;
@@ -90,11 +92,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
     const float *qbase = qkv + hd * dh, *kbase = qbase + Hd, *vbase = qbase + 2 * Hd;
 
     // query rows as the B operand of S^T = K Q^T: d = 16u + 4g + e (u, e = 0..3)
-    double qr[2][16];
-    int qidx[2];
+    double qr[QB][16];
+    int qidx[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int q = qt * 128 + wave * 32 + qb * 16 + c;
+    for (int qb = 0; qb < QB; ++qb) {
+        const int q = qt * QT + wave * (16 * QB) + qb * 16 + c;
         qidx[qb] = q;
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -105,31 +107,68 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
             }
     }
 
-    v4d o[2][4];                       // O^T: [query block][16-row block of the head dim]
+    v4d o[QB][4];                       // O^T: [query block][16-row block of the head dim]
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 4; ++r) o[qb][db][r] = 0.0;
-    double mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.0, 0.0};
+    double mrun[QB], lrun[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { mrun[qb] = -INFINITY; lrun[qb] = 0.0; }
 
-    for (int j0 = 0; j0 < S; j0 += kKeyTile) {
-        __syncthreads();
-        for (int i = tid; i < kKeyTile * kDh; i += 256) {
-            const int kr = i >> 6, d = i & 63;
-            const bool ok = (j0 + kr) < S && d < dh;
+    // Key / value tiles: thread t stages float4 slots t and t + 256 of the
+    // 32 x 64 tile (row = slot / 16); the next tile's global loads are issued
+    // before the current tile is contracted and land in the other LDS stage.
+    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
+    float4 pk[2], pv[2];
+    auto fetch = [&](int j0) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + it * 256, kr = sl >> 4, d = (sl & 15) * 4;
             const int64_t off = (tok0 + j0 + kr) * ld + d;
-            sK[kr][d] = ok ? kbase[off] : 0.0f;
-            sV[kr][d] = ok ? vbase[off] : 0.0f;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b4 = a;
+            if (j0 + kr < S) {
+                if (vec4 && d + 4 <= dh) {
+                    a = *(const float4 *)(kbase + off);
+                    b4 = *(const float4 *)(vbase + off);
+                } else {
+                    float ea[4] = {0.f, 0.f, 0.f, 0.f}, eb[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (d + e < dh) { ea[e] = kbase[off + e]; eb[e] = vbase[off + e]; }
+                    a = make_float4(ea[0], ea[1], ea[2], ea[3]);
+                    b4 = make_float4(eb[0], eb[1], eb[2], eb[3]);
+                }
+            }
+            pk[it] = a;
+            pv[it] = b4;
         }
-        __syncthreads();
+    };
+    auto stash = [&](int stage) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + it * 256, kr = sl >> 4, d = (sl & 15) * 4;
+            *(float4 *)&sKb[stage][kr][d] = pk[it];
+            *(float4 *)&sVb[stage][kr][d] = pv[it];
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    int stage = 0;
+    for (int j0 = 0; j0 < S; j0 += kKeyTile, stage ^= 1) {
+        const bool more = j0 + kKeyTile < S;
+        if (more) fetch(j0 + kKeyTile);
+        float (*sK)[kKVPad] = sKb[stage];
+        float (*sV)[kKVPad] = sVb[stage];
 
-        v4d st[2][2];                  // [key block][query block]
+        v4d st[2][QB];                  // [key block][query block]
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) st[kb][qb][r] = 0.0;
 #pragma unroll
@@ -141,13 +180,13 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
                         st[kb][qb] = __builtin_amdgcn_mfma_f64_16x16x4f64(k4[e], qr[qb][4 * u + e], st[kb][qb], 0, 0, 0);
             }
         }
         // register r of st[kb][qb] is key j0 + 16*kb + 4*r + g for this lane's query
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             double mx = -INFINITY;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -188,15 +227,17 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
                 for (int db = 0; db < 4; ++db) {
                     const double vv = (double)sV[kr][db * 16 + c];
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
                         o[qb][db] = __builtin_amdgcn_mfma_f64_16x16x4f64(vv, st[kb][qb][r], o[qb][db], 0, 0, 0);
                 }
             }
+        if (more) stash(stage ^ 1);
+        __syncthreads();
     }
 
     uint32_t amax = 0;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int q = qidx[qb];
         if (q >= S) continue;
         float *dst = ctx + (tok0 + q) * Hd + hd * dh;
@@ -223,11 +264,12 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
                             float *ctx, uint32_t *absmax_out, hipStream_t st)
 {
     const int dh = Hd / heads;
-    const int qtiles = (S + 127) / 128;
+    constexpr int QB = 1;               // one 16-query block per wave: ~120 VGPRs, several waves per SIMD
+    const int qtiles = (S + 64 * QB - 1) / (64 * QB);
     const int64_t grid = (int64_t)B * heads * qtiles;
     if (grid <= 0) return hipSuccess;
     if (dh > kDh || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    return launch_k(EGERIA_KERNEL_ATTENTION, attention_kernel, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B,
+    return launch_k(EGERIA_KERNEL_ATTENTION, attention_kernel<QB>, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B,
                     (int)S, (int)Hd, (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out);
 }
 
