@@ -135,7 +135,7 @@ struct GemmArgs {
     const float *sx;        // 1 fp32: scale of the activations
     const float *sw;        // 1 fp32: scale of the weights
     const float *bias;      // [N] or null
-    int32_t act;            // 0 none, 1 ReLU, 2 GELU (erf form)
+    int32_t act;            // 0 none, 1 ReLU
     const int8_t *res_q;    // optional residual as int8 [M, res_ld] with scale *res_scale
     const float *res_scale;
     int64_t res_ld;

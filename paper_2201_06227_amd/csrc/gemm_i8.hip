@@ -49,6 +49,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     const int64_t m0 = tile_m * BM;
     const int n0 = tile_n * BN;
     const int unit = tid & 3;                    // which 16-byte unit of the 64-byte K step
+    // epilogue scalars, requested now so that their latency hides behind the K loop
+    const float s = (*g.sx) * (*g.sw);
+    const float rs = g.res_q ? *g.res_scale : 0.0f;
 
     // Operands are fetched with raw buffer loads: a lane whose row or K offset is
     // out of range is given an offset beyond the buffer and reads zeros, so the
@@ -192,10 +195,20 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     // up with four consecutive columns of one row: 16-byte loads of bias and
     // residual, 16-byte stores of the output.
     constexpr int EW = TN * 32, ELD = EW + 4;
+    constexpr int QPR = EW / 4;                  // 4-column groups per row; divides 64
+    constexpr int RPI = 64 / QPR;                // rows a wave covers per pass
     int *ebuf = (int *)lds + wave * 32 * ELD;
-    const float s = (*g.sx) * (*g.sw);
-    const float rs = g.res_q ? *g.res_scale : 0.0f;
     const bool vec4 = (g.N & 3) == 0 && (g.ldy & 3) == 0;
+    // a lane keeps the same four columns through the whole epilogue
+    const int c4 = (lane % QPR) * 4;
+    const int col = n0 + wn * EW + c4;
+    const bool full = vec4 && col + 4 <= g.N;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (g.bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < g.N) bv[e] = g.bias[col + e];
+    }
     uint32_t amax = 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -206,26 +219,14 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
             for (int r = 0; r < 16; ++r)
                 ebuf[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
         __syncthreads();
-#pragma unroll 1
-        for (int q = lane; q < 32 * EW / 4; q += 64) {
-            const int rr = q / (EW / 4), c4 = (q % (EW / 4)) * 4;
+#pragma unroll 4
+        for (int pass = 0; pass < 32 / RPI; ++pass) {
+            const int rr = pass * RPI + lane / QPR;
             const int64_t row = m0 + (wm * TM + i) * 32 + rr;
-            const int col = n0 + wn * EW + c4;
             if (row >= g.M || col >= g.N) continue;
             const int4 a4 = *(const int4 *)&ebuf[rr * ELD + c4];
             const int av[4] = {a4.x, a4.y, a4.z, a4.w};
-            float bv[4] = {0.f, 0.f, 0.f, 0.f}, rv[4] = {0.f, 0.f, 0.f, 0.f}, out[4];
-            const bool full = vec4 && col + 4 <= g.N;
-            if (g.bias) {
-                if (full) {
-                    const float4 b4 = *(const float4 *)(g.bias + col);
-                    bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < g.N) bv[e] = g.bias[col + e];
-                }
-            }
+            float rv[4] = {0.f, 0.f, 0.f, 0.f}, out[4];
             if (g.res_q) {
                 const int8_t *rp = g.res_q + row * g.res_ld + col;
                 if (full) {
@@ -243,10 +244,6 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                 float v = fmaf((float)av[e], s, bv[e]);
                 if (g.res_q) v = v + rv[e];
                 if (g.act == 1) v = v > 0.0f ? v : 0.0f;
-                else if (g.act == 2) {          // erf-form GELU in fp64, rounded once: it feeds a quantiser
-                    const double dv = (double)v;
-                    v = (float)(0.5 * dv * (1.0 + erf(dv * 0.70710678118654752440)));
-                }
                 out[e] = v;
                 if (col + e < g.N) {
                     const uint32_t ab = g.amax_pos ? (v > 0.0f ? __float_as_uint(v) : 0u) : abs_bits(v);
@@ -367,7 +364,7 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
     auto ntiles = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * (int64_t)((g.N + bn - 1) / bn); };
-    if (g.conv3x3 && g.cp == 16 && g.N <= 32 && g.act != 2) {
+    if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
         const int64_t blocks = (g.M + 127) / 128;
         if (blocks <= 0) return hipSuccess;
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;

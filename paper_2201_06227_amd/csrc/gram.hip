@@ -259,25 +259,31 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     }
 }
 
-// Sum of the partials over chunks in fp64, element-wise (coalesced, fixed order):
-// part = [nsplit][2][b][b] (M then B) -> red = [2][b][b] doubles.
+// Sum of the partials over chunks in fp64 (fixed assignment, fixed order):
+// part = [nsplit][2][b][b] (M then B) -> red = [2][b][b] doubles.  A workgroup
+// owns 32 consecutive elements; its 8 groups of 32 lanes each take every 8th
+// chunk (128-byte coalesced reads) and the 8 sums are added through LDS.
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int nsplit,
                                                           int nelem2, double *__restrict__ red,
                                                           uint32_t *__restrict__ counter)
 {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e == 0) *counter = 0u;                    // ticket of the finaliser
-    if (e >= nelem2) return;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int c = 0;
-    for (; c + 3 < nsplit; c += 4) {              // four independent loads in flight
-        s0 += (double)part[(size_t)c * nelem2 + e];
-        s1 += (double)part[(size_t)(c + 1) * nelem2 + e];
-        s2 += (double)part[(size_t)(c + 2) * nelem2 + e];
-        s3 += (double)part[(size_t)(c + 3) * nelem2 + e];
+    __shared__ double sm[8][32];
+    const int el = threadIdx.x & 31, cg = threadIdx.x >> 5;
+    const int e = blockIdx.x * 32 + el;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0u;       // ticket of the finaliser
+    double s0 = 0.0, s1 = 0.0;
+    if (e < nelem2) {
+        int c = cg;
+        for (; c + 8 < nsplit; c += 16) {                         // two independent loads in flight
+            s0 += (double)part[(size_t)c * nelem2 + e];
+            s1 += (double)part[(size_t)(c + 8) * nelem2 + e];
+        }
+        if (c < nsplit) s0 += (double)part[(size_t)c * nelem2 + e];
     }
-    for (; c < nsplit; ++c) s0 += (double)part[(size_t)c * nelem2 + e];
-    red[e] = (s0 + s1) + (s2 + s3);
+    sm[cg][el] = s0 + s1;
+    __syncthreads();
+    if (cg == 0 && e < nelem2)
+        red[e] = ((sm[0][el] + sm[1][el]) + (sm[2][el] + sm[3][el])) + ((sm[4][el] + sm[5][el]) + (sm[6][el] + sm[7][el]));
 }
 
 // One wave per row i of the b x b matrices: row i of both Gram matrices, their
@@ -370,7 +376,7 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     if (e != hipSuccess) return e;
     double *red = (double *)((char *)ws_part + off_red(b));
     const int nelem2 = 2 * b * b;
-    e = launch_k(EGERIA_KERNEL_NONE, gram_reduce_kernel, dim3((unsigned)((nelem2 + 255) / 256)), dim3(256), 0, st,
+    e = launch_k(EGERIA_KERNEL_NONE, gram_reduce_kernel, dim3((unsigned)((nelem2 + 31) / 32)), dim3(256), 0, st,
                  (const float *)part, p.nsplit, nelem2, red, counter);
     if (e != hipSuccess) return e;
     return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(64), 0, st, (const double *)red,
