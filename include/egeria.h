@@ -159,6 +159,28 @@ egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, in
                                    int64_t w, const float *fixed_scale, int8_t *q,
                                    float *scale_out, void *ws, size_t ws_bytes, void *stream);
 
+/* HOST struct.  One weight tensor of a snapshot: a linear layer's [out, in]
+ * matrix (kh = kw = 1) or a convolution's [out, in, kh, kw] kernel, contiguous. */
+typedef struct {
+    const void *w;
+    int32_t dtype;                  /* egeria_dtype */
+    int32_t out, in, kh, kw;
+    int8_t *w_q;                    /* out: int8 [out, kh, kw, egeria_padded(in)], pad zero */
+    float *scale;                   /* out: 1 fp32 */
+} egeria_weight;
+
+/* Section 4.1, reference-model generation: quantises all n weight tensors of
+ * a snapshot, each with its own dynamic per-tensor scale, with the same codes
+ * and scales egeria_quantize_rows / egeria_quantize_nchw give tensor by tensor,
+ * in one or two kernel launches per 32 tensors.
+ *   w   HOST array of n descriptors (device pointers inside).
+ *   ws  at least egeria_quantize_weights_workspace_bytes(n) bytes.
+ * Empty tensors are valid (scale 1).  Tensors of 2^31 or more padded bytes
+ * are EGERIA_ERR_UNSUPPORTED. */
+egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes,
+                                      void *stream);
+size_t egeria_quantize_weights_workspace_bytes(int32_t n);
+
 /* x_i = q_i * scale. */
 egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x,
                                 void *stream);

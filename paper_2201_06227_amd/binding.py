@@ -53,6 +53,11 @@ class Taps(ctypes.Structure):
     _fields_ = [("n", _i32), ("tap", ctypes.POINTER(Tap))]
 
 
+class Weight(ctypes.Structure):
+    _fields_ = [("w", _vp), ("dtype", _i32), ("out", _i32), ("in_", _i32), ("kh", _i32), ("kw", _i32),
+                ("w_q", _vp), ("scale", _vp)]
+
+
 class EgeriaError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -66,7 +71,7 @@ EXPORTS = [
     "egeria_dequantize", "egeria_quantize_workspace_bytes", "egeria_ref_forward",
     "egeria_plasticity", "egeria_plasticity_workspace_bytes", "egeria_plasticity_eval",
     "egeria_workspace_bytes", "egeria_check", "egeria_status_string", "egeria_profile_begin",
-    "egeria_profile_end",
+    "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
 ]
 
 KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM = range(7)
@@ -94,6 +99,10 @@ def lib():
     L.egeria_quantize_rows.argtypes = [_vp, ctypes.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
     L.egeria_quantize_nchw.restype = ctypes.c_int
     L.egeria_quantize_nchw.argtypes = [_vp, ctypes.c_int, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.egeria_quantize_weights.restype = ctypes.c_int
+    L.egeria_quantize_weights.argtypes = [ctypes.POINTER(Weight), _i32, _vp, _sz, _vp]
+    L.egeria_quantize_weights_workspace_bytes.restype = _sz
+    L.egeria_quantize_weights_workspace_bytes.argtypes = [_i32]
     L.egeria_dequantize.restype = ctypes.c_int
     L.egeria_dequantize.argtypes = [_vp, _vp, _i64, _vp, _vp]
     L.egeria_quantize_workspace_bytes.restype = _sz
@@ -205,6 +214,41 @@ def quantize_nchw(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, w
                                     _ptr(ws), ws.numel(), _stream())
     _check(rc, "egeria_quantize_nchw")
     return q, scale
+
+
+def weight_table(weights: Sequence[torch.Tensor], w_q: Sequence[torch.Tensor], scales: Sequence[torch.Tensor]):
+    """HOST array of egeria_weight descriptors for egeria_quantize_weights."""
+    tab = (Weight * len(weights))()
+    for t, w, q, s in zip(tab, weights, w_q, scales):
+        _dev(w)
+        if w.dim() == 4:
+            t.out, t.in_, t.kh, t.kw = w.shape
+        else:
+            t.out, t.in_ = w.shape
+            t.kh = t.kw = 1
+        t.w, t.dtype, t.w_q, t.scale = w.data_ptr(), _dt(w), q.data_ptr(), s.data_ptr()
+    return tab
+
+
+def quantize_weights_workspace_bytes(n: int) -> int:
+    return int(lib().egeria_quantize_weights_workspace_bytes(int(n)))
+
+
+def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor] = None):
+    """egeria_quantize_weights: every tensor of a snapshot in one call.  Returns
+    the int8 tensors ([out, padded(in)] or [out, kh, kw, padded(in)]) and scales."""
+    dev = weights[0].device if weights else "cuda"
+    w_q, scales = [], []
+    for w in weights:
+        shape = (w.shape[0], w.shape[2], w.shape[3], padded(w.shape[1])) if w.dim() == 4 else \
+            (w.shape[0], padded(w.shape[1]))
+        w_q.append(torch.empty(shape, dtype=torch.int8, device=dev))
+        scales.append(torch.empty(1, dtype=torch.float32, device=dev))
+    ws = workspace(quantize_weights_workspace_bytes(len(weights)), dev) if ws is None else ws
+    tab = weight_table(weights, w_q, scales)
+    rc = lib().egeria_quantize_weights(tab, len(weights), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_quantize_weights")
+    return w_q, scales
 
 
 def dequantize(q: torch.Tensor, scale: torch.Tensor) -> torch.Tensor:

@@ -385,6 +385,62 @@ egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, in
     return EGERIA_OK;
 }
 
+size_t egeria_quantize_weights_workspace_bytes(int32_t n)
+{
+    if (n < 0) return 0;
+    return align_up(4 * ((size_t)kHeaderFixedWords + (size_t)kWeightBatch * kAbsPartials), 256);
+}
+
+egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0 || (n > 0 && !w) || !ws || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
+    if (ws_bytes < egeria_quantize_weights_workspace_bytes(n)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    for (int i = 0; i < n; ++i) {
+        const egeria_weight &t = w[i];
+        if (t.out < 0 || t.in < 0 || t.kh < 1 || t.kw < 1 || !t.scale) return EGERIA_ERR_INVALID_ARG;
+        if (t.dtype != EGERIA_F32 && t.dtype != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+        const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
+        if (total > 0 && (!t.w || !t.w_q)) return EGERIA_ERR_INVALID_ARG;
+        if (!aligned16(t.w) || !aligned16(t.w_q)) return EGERIA_ERR_INVALID_ARG;
+        if ((int64_t)t.out * t.kh * t.kw * pad16(t.in) >= ((int64_t)1 << 31)) return EGERIA_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t *partials = (uint32_t *)ws + kHeaderFixedWords;
+    int i = 0;
+    while (i < n) {
+        WeightBatch b;
+        b.n = 0;
+        int blocks = 0;
+        bool one = true;
+        for (; i < n && b.n < kWeightBatch; ++i) {
+            const egeria_weight &t = w[i];
+            const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
+            WeightJob &jb = b.job[b.n++];
+            jb.x = t.w;
+            jb.q = t.w_q;
+            jb.scale = t.scale;
+            jb.o = t.out;
+            jb.c = t.in;
+            jb.hw = t.kh * t.kw;
+            jb.cp = (int32_t)pad16(t.in);
+            jb.bf16 = t.dtype == EGERIA_BF16;
+            // one workgroup for a small tensor, else about four 16-byte loads per thread
+            int64_t nblk = total <= kSmallTensor ? 1 : (total + 4095) / 4096;
+            if (nblk > kAbsPartials) nblk = kAbsPartials;
+            const int64_t units = (int64_t)t.out * jb.hw * (jb.cp / 16);
+            jb.first_block = blocks;
+            jb.nblk = (int32_t)nblk;
+            jb.epb = (int32_t)(((total + nblk - 1) / nblk + 7) / 8 * 8);
+            jb.upb = (int32_t)((units + nblk - 1) / nblk);
+            jb.pad_ = 0;
+            blocks += (int)nblk;
+            one = one && nblk == 1;
+        }
+        EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st));
+    }
+    return EGERIA_OK;
+}
+
 egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, void *stream)
 {
     if (n < 0 || !scale) return EGERIA_ERR_INVALID_ARG;

@@ -45,13 +45,100 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict_
     }
 }
 
+// Same, for rows of at most 256*NV floats with H a multiple of 4: the row is
+// read once with 16-byte loads and stays in registers (as the exact fp64 sums
+// x + res) for the three passes.
+template <int NV>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restrict__ x,
+                                                            const float *__restrict__ res, int64_t rows,
+                                                            int H, const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, double eps,
+                                                            float *__restrict__ y,
+                                                            uint32_t *__restrict__ absmax_out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    const int nv = H >> 2;
+    uint32_t amax = 0;
+    if (row < rows) {
+        const float4 *xr = reinterpret_cast<const float4 *>(x + row * H);
+        const float4 *rr = res ? reinterpret_cast<const float4 *>(res + row * H) : nullptr;
+        float4 xv[NV], rv[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            xv[i] = c < nv ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            rv[i] = (rr && c < nv) ? rr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        double v[NV][4];
+        double s = 0.0;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            v[i][0] = (double)xv[i].x + (double)rv[i].x;
+            v[i][1] = (double)xv[i].y + (double)rv[i].y;
+            v[i][2] = (double)xv[i].z + (double)rv[i].z;
+            v[i][3] = (double)xv[i].w + (double)rv[i].w;
+            s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+        }
+        const double mean = wave_sum(s) / (double)H;
+        double q = 0.0;
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (lane + 64 * i < nv) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[i][e] -= mean;
+                    q += v[i][e] * v[i][e];
+                }
+            }
+        const double var = wave_sum(q) / (double)H;
+        const double rstd = 1.0 / sqrt(var + eps);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nv) {
+                const float4 gm = gamma ? reinterpret_cast<const float4 *>(gamma)[c] : make_float4(1.f, 1.f, 1.f, 1.f);
+                const float4 bt = beta ? reinterpret_cast<const float4 *>(beta)[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                float4 o;
+                o.x = (float)(v[i][0] * rstd * (double)gm.x + (double)bt.x);
+                o.y = (float)(v[i][1] * rstd * (double)gm.y + (double)bt.y);
+                o.z = (float)(v[i][2] * rstd * (double)gm.z + (double)bt.z);
+                o.w = (float)(v[i][3] * rstd * (double)gm.w + (double)bt.w);
+                reinterpret_cast<float4 *>(y + row * H)[c] = o;
+                const uint32_t a0 = abs_bits(o.x), a1 = abs_bits(o.y), a2 = abs_bits(o.z), a3 = abs_bits(o.w);
+                const uint32_t m01 = a0 > a1 ? a0 : a1, m23 = a2 > a3 ? a2 : a3;
+                const uint32_t m = m01 > m23 ? m01 : m23;
+                amax = amax > m ? amax : m;
+            }
+        }
+    }
+    if (absmax_out) {
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, absmax_out, sm4);
+    }
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
 hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int32_t H,
                             const float *gamma, const float *beta, float eps, float *y,
                             uint32_t *absmax_out, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
-    return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x,
-                    res, rows, (int)H, gamma, beta, (double)eps, y, absmax_out);
+    const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+    const bool vec = (H % 4) == 0 && H <= 1024 && aligned16(x) && aligned16(res) && aligned16(gamma) &&
+                     aligned16(beta) && aligned16(y);
+    if (vec && H <= 256)
+        return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_vec_kernel<1>, grid, block, 0, st, x, res, rows, (int)H,
+                        gamma, beta, (double)eps, y, absmax_out);
+    if (vec && H <= 768)
+        return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_vec_kernel<3>, grid, block, 0, st, x, res, rows, (int)H,
+                        gamma, beta, (double)eps, y, absmax_out);
+    if (vec)
+        return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_vec_kernel<4>, grid, block, 0, st, x, res, rows, (int)H,
+                        gamma, beta, (double)eps, y, absmax_out);
+    return launch_k(EGERIA_KERNEL_LAYERNORM, layernorm_kernel, grid, block, 0, st, x, res, rows, (int)H, gamma, beta,
+                    (double)eps, y, absmax_out);
 }
 
 // ---- multi-head self-attention -----------------------------------------------------------

@@ -118,6 +118,29 @@ constexpr int64_t kSmallTensor = 16384;
 hipError_t launch_quantize_small(const void *x, egeria_dtype dt, int nimg, int c, int hw, int cp, int8_t *q,
                                  float *scale_out, uint32_t *flag, hipStream_t st);
 
+// A batch of weight tensors [o, c, hw] -> int8 [o, hw, cp] quantised together
+// (dynamic per-tensor scales).  The table travels as a kernel argument.
+struct WeightJob {
+    const void *x;
+    int8_t *q;
+    float *scale;
+    int32_t o, c, hw, cp;
+    int32_t bf16;
+    int32_t first_block;    // first workgroup of this tensor within the launch
+    int32_t nblk;           // workgroups of this tensor (<= kAbsPartials)
+    int32_t epb;            // input values per workgroup (multiple of 8)
+    int32_t upb;            // 16-byte output units per workgroup
+    int32_t pad_;
+};
+constexpr int kWeightBatch = 32;
+struct WeightBatch {
+    WeightJob job[kWeightBatch];
+    int32_t n;
+};
+// one_launch: every job has nblk == 1.  partials: total_blocks words.
+hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
+                                   uint32_t *flag, hipStream_t st);
+
 hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
 
 // int8 GEMM / implicit-GEMM convolution with fused dequantising epilogue.

@@ -340,6 +340,147 @@ hipError_t launch_quantize_small(const void *x, egeria_dtype dt, int nimg, int c
                     q, scale_out, flag);
 }
 
+// ---- a whole snapshot of weight tensors in one or two launches ------------------------------
+// Every workgroup finds its tensor in the launch's table (kernel argument) and
+// works on a fixed share of it: first the maximum of its share of the values,
+// then its share of the 16-byte output units [o][hw][cp / 16].
+__device__ __forceinline__ int find_job(const WeightBatch &b, int blk)
+{
+    int j = 0;
+    while (j + 1 < b.n && blk >= b.job[j + 1].first_block) ++j;
+    return j;
+}
+
+__device__ __forceinline__ uint32_t job_share_absmax(const WeightJob &jb, int lb, uint32_t *sm)
+{
+    const int64_t n_in = (int64_t)jb.o * jb.c * jb.hw;
+    const int64_t beg = (int64_t)lb * jb.epb;
+    int64_t end = beg + jb.epb;
+    if (end > n_in) end = n_in;
+    uint32_t m = 0;
+    if (!jb.bf16) {
+        const float *x = (const float *)jb.x;
+        const int64_t n4 = end > beg ? (end - beg) >> 2 : 0;
+        const float4 *x4 = (const float4 *)(x + beg);                // epb is a multiple of 8
+        int64_t i = threadIdx.x;
+        for (; i + 768 < n4; i += 1024) {                            // four independent loads in flight
+            const float4 v0 = x4[i], v1 = x4[i + 256], v2 = x4[i + 512], v3 = x4[i + 768];
+            uint32_t a = max4_bits(v0), b = max4_bits(v1), c = max4_bits(v2), d = max4_bits(v3);
+            a = a > b ? a : b;
+            c = c > d ? c : d;
+            a = a > c ? a : c;
+            m = m > a ? m : a;
+        }
+        for (; i < n4; i += 256) {
+            const uint32_t a = max4_bits(x4[i]);
+            m = m > a ? m : a;
+        }
+        for (int64_t k = beg + (n4 << 2) + threadIdx.x; k < end; k += 256) {
+            const uint32_t a = abs_bits(x[k]);
+            m = m > a ? m : a;
+        }
+    } else {
+        const uint16_t *x = (const uint16_t *)jb.x;
+        for (int64_t k = beg + threadIdx.x; k < end; k += 256) {
+            const uint32_t a = ((uint32_t)x[k] << 16) & 0x7fffffffu;
+            m = m > a ? m : a;
+        }
+    }
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    const uint32_t a = sm[0] > sm[1] ? sm[0] : sm[1], b = sm[2] > sm[3] ? sm[2] : sm[3];
+    return a > b ? a : b;
+}
+
+// Tensors of one launch report to the same flag word at the same time.
+__device__ __forceinline__ void publish_shared(float scale, bool bad, float *scale_out, uint32_t *flag)
+{
+    *scale_out = scale;
+    uint32_t old = *flag;
+    for (;;) {
+        uint32_t want = (old & 0xffffff00u) == kFlagMagic ? old : kFlagMagic;
+        if (bad) want |= kFlagNonFinite;
+        if (want == old) break;
+        const uint32_t seen = atomicCAS(flag, old, want);
+        if (seen == old) break;
+        old = seen;
+    }
+}
+
+__device__ __forceinline__ void job_share_quantize(const WeightJob &jb, int lb, float inv)
+{
+    const int cpu = jb.cp >> 4;
+    const int64_t units = (int64_t)jb.o * jb.hw * cpu;
+    const int64_t beg = (int64_t)lb * jb.upb;
+    int64_t end = beg + jb.upb;
+    if (end > units) end = units;
+    const bool rows_vec = jb.hw == 1 && !jb.bf16 && (jb.c & 3) == 0;
+    for (int64_t u = beg + threadIdx.x; u < end; u += 256) {
+        const int c0 = (int)(u % cpu) << 4;
+        const int64_t op = u / cpu;                       // o * hw + pixel
+        const int pix = (int)(op % jb.hw);
+        const int64_t oc = op / jb.hw;
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (rows_vec && c0 + 16 <= jb.c) {
+            const float4 *p = (const float4 *)((const float *)jb.x + oc * jb.c + c0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4 v = p[j];
+                w[j] = quant1(v.x, inv) | (quant1(v.y, inv) << 8) | (quant1(v.z, inv) << 16) | (quant1(v.w, inv) << 24);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (c0 + e < jb.c) {
+                    const int64_t idx = (oc * jb.c + c0 + e) * jb.hw + pix;
+                    const float v = jb.bf16 ? bf16_to_f32(((const uint16_t *)jb.x)[idx]) : ((const float *)jb.x)[idx];
+                    w[e >> 2] |= quant1(v, inv) << ((e & 3) * 8);
+                }
+        }
+        *(uint4 *)(jb.q + (u << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// PHASE 0: every tensor of the launch fits one workgroup; maximum, scale and codes in one go.
+// PHASE 1: per-workgroup maxima -> partials[blockIdx.x].   PHASE 2: scale from the partials, codes.
+template <int PHASE>
+__global__ __launch_bounds__(256) void quantize_weights_kernel(const WeightBatch b, uint32_t *__restrict__ partials,
+                                                               uint32_t *__restrict__ flag)
+{
+    __shared__ uint32_t sm[4];
+    const int j = find_job(b, (int)blockIdx.x);
+    const WeightJob &jb = b.job[j];
+    const int lb = (int)blockIdx.x - jb.first_block;
+    if (PHASE == 1) {
+        const uint32_t m = job_share_absmax(jb, lb, sm);
+        if (threadIdx.x == 0) partials[blockIdx.x] = m;
+        return;
+    }
+    float scale;
+    bool bad;
+    float inv;
+    if (PHASE == 0) {
+        (void)job_share_absmax(jb, lb, sm);
+        inv = scales_from(sm, 4, 1, nullptr, &scale, &bad);
+    } else {
+        inv = scales_from(partials + jb.first_block, jb.nblk, 1, nullptr, &scale, &bad);
+    }
+    if (lb == 0 && threadIdx.x == 0) publish_shared(scale, bad, jb.scale, flag);
+    job_share_quantize(jb, lb, inv);
+}
+
+hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
+                                   uint32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)total_blocks), block(256);
+    if (one_launch)
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<0>, grid, block, 0, st, b, partials, flag);
+    hipError_t e = launch_k(EGERIA_KERNEL_ABSMAX, quantize_weights_kernel<1>, grid, block, 0, st, b, partials, flag);
+    if (e != hipSuccess) return e;
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<2>, grid, block, 0, st, b, partials, flag);
+}
+
 // ---- fused GELU + quantise ---------------------------------------------------------------
 // The GELU output of a Transformer layer's first feed-forward GEMM is consumed
 // only by the next quantiser, and its codes must equal those of the fp64

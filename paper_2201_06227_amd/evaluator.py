@@ -45,7 +45,8 @@ class PlasticityEvaluator:
         self.qw.linear = self._lin
         self.qw.n_norm = 0
         self.qw.norm = None
-        self.qws = eg.workspace(eg.quantize_workspace_bytes(), device)
+        self.qws = eg.workspace(eg.quantize_weights_workspace_bytes(len(self.weights)), device)
+        self._wtab = eg.weight_table(self.weights, self.w_q, self.scales)
         nbytes = eg.workspace_bytes(self.desc)
         if nbytes == 0:
             raise ValueError("invalid layer-module description")
@@ -54,16 +55,9 @@ class PlasticityEvaluator:
         self._lib = eg.lib()
 
     def quantize_weights(self):
-        L, st = self._lib, eg._stream()
-        for w, q, s in zip(self.weights, self.w_q, self.scales):
-            if w.dim() == 4:
-                o, i, kh, kw = w.shape
-                rc = L.egeria_quantize_nchw(w.data_ptr(), eg.F32, o, i, kh, kw, None, q.data_ptr(), s.data_ptr(),
-                                            self.qws.data_ptr(), self.qws.numel(), st)
-            else:
-                rc = L.egeria_quantize_rows(w.data_ptr(), eg.F32, w.shape[0], w.shape[1], None, q.data_ptr(),
-                                            s.data_ptr(), self.qws.data_ptr(), self.qws.numel(), st)
-            eg._check(rc, "egeria_quantize (weights)")
+        rc = self._lib.egeria_quantize_weights(self._wtab, len(self.weights), self.qws.data_ptr(), self.qws.numel(),
+                                               eg._stream())
+        eg._check(rc, "egeria_quantize_weights")
 
     def evaluate(self, x: torch.Tensor, a_train: Sequence[torch.Tensor]) -> torch.Tensor:
         ptrs = (ctypes.c_void_p * self.n_layers)(*[t.data_ptr() for t in a_train])

@@ -100,6 +100,44 @@ def test_quantize_nchw_bit_exact(eg, gc, orc, shape):
     gc.assert_conv_q(q.cpu().numpy().reshape(-1, q.shape[-1]), wq)
 
 
+WEIGHT_SETS = {
+    "small_convs": [(16, 16, 3, 3), (16, 16, 3, 3)],
+    "bottleneck": [(64, 256, 1, 1), (64, 64, 3, 3), (256, 64, 1, 1)],
+    "mixed_ragged": [(7, 100), (1, 1), (33, 70, 3, 3), (130, 3072), (5, 3), (2304, 768)],
+    "many": [(48 + i, 17 + 3 * i) for i in range(40)],
+}
+
+
+@pytest.mark.parametrize("name", sorted(WEIGHT_SETS))
+def test_quantize_weights_batch_bit_exact(eg, gc, orc, name):
+    """One call for a whole snapshot gives the codes and scales of the per-tensor rule."""
+    rng = np.random.default_rng(len(name))
+    ws_np = [(rng.standard_normal(sh) * (0.02 + 0.3 * i)).astype(np.float32) for i, sh in enumerate(WEIGHT_SETS[name])]
+    w_q, scales = eg.quantize_weights([gc.to_dev(w) for w in ws_np])
+    for w, q, s in zip(ws_np, w_q, scales):
+        wq, wsc = orc.quantize(w)
+        assert s.item() == wsc
+        if w.ndim == 4:
+            gc.assert_conv_q(q.cpu().numpy().reshape(-1, q.shape[-1]), wq)
+        else:
+            gc.assert_int8_rows(q.cpu().numpy(), wq)
+
+
+def test_quantize_weights_batch_flags_and_empty(eg, gc, orc):
+    ws = eg.workspace(eg.quantize_weights_workspace_bytes(3))
+    good = np.ones((4, 20), np.float32)
+    bad = np.ones((200, 300), np.float32)
+    bad[150, 7] = np.inf
+    w_q, scales = eg.quantize_weights([gc.to_dev(good), gc.to_dev(np.zeros((8, 8), np.float32))], ws=ws)
+    assert eg.check(ws) == eg.OK
+    assert scales[1].item() == 1.0 and not w_q[1].any().item()
+    eg.quantize_weights([gc.to_dev(good), gc.to_dev(bad), gc.to_dev(good)], ws=ws)
+    assert eg.check(ws) == eg.ERR_NONFINITE
+    assert eg.check(ws) == eg.OK
+    w_q, scales = eg.quantize_weights([], ws=ws)
+    assert w_q == []
+
+
 # --------------------------------------------------------------------------- FC / conv modules
 
 def _check_linear_taps(gc, taps, ot, prefix, conv):
