@@ -18,6 +18,7 @@
 // works on a contiguous range of tiles (N fastest) and its L2 serves the
 // re-reads of A rows and of the weights.
 #include "common.hpp"
+#include <type_traits>
 
 namespace egeria {
 
@@ -26,47 +27,81 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;          // K bytes per step
-constexpr int kLdsRow = 80;      // padded LDS row in bytes
+constexpr int kStages = 3;       // LDS stages: one being read, two being filled
+
+typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes
+// LDS bytes [lds_base + 16 l, lds_base + 16 l + 16) with what it reads at byte
+// offset voff of the buffer (zeros if voff is out of range).  Written as an
+// assembly statement so that the request stays outstanding across later LDS
+// reads of other stages: completion is awaited with an explicit vmcnt wait,
+// and ordering against other waves' reads with workgroup barriers.
+__device__ __forceinline__ void load_to_lds_b128(v4i rsrc, uint32_t lds_base, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
 
 template <int BM, int BN, int WM, int WN, bool CONV>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tiles, int tiles_per_xcd)
 {
     static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(BM % 16 == 0 && BN % 16 == 0, "tiles are made of 16-row chunks");
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_IT = (BM * 4 + 255) / 256, B_IT = (BN * 4 + 255) / 256;
-    constexpr int STAGE = (BM + BN) * kLdsRow;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [2][BM + BN][80]
+    constexpr int A_CH = BM / 16, B_CH = BN / 16;                       // 1-KiB chunks (16 rows x 64 bytes) per K step
+    constexpr int A_IT = (A_CH + 3) / 4, B_IT = (B_CH + 3) / 4;         // chunks per wave
+    constexpr int STAGE = (BM + BN) * kBK;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [kStages][BM + BN][64]
 
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile = xcd * tiles_per_xcd + local;
     if (local >= tiles_per_xcd || tile >= tiles) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave / WN, wn = wave % WN;
     const int tiles_n = (g.N + BN - 1) / BN;
     const int64_t tile_m = tile / tiles_n;
     const int tile_n = tile % tiles_n;
     const int64_t m0 = tile_m * BM;
     const int n0 = tile_n * BN;
-    const int unit = tid & 3;                    // which 16-byte unit of the 64-byte K step
     // epilogue scalars, requested now so that their latency hides behind the K loop
     const float s = (*g.sx) * (*g.sw);
     const float rs = g.res_q ? *g.res_scale : 0.0f;
 
-    // Operands are fetched with raw buffer loads: a lane whose row or K offset is
-    // out of range is given an offset beyond the buffer and reads zeros, so the
-    // main loop is straight-line code that the scheduler hints below can order.
+    // Operands go from global memory straight into LDS (buffer loads with the
+    // LDS modifier): one such instruction of a wave fills 1 KiB, lane l writing
+    // bytes [16 l, 16 l + 16) of it, i.e. unit l % 4 of row l / 4 of a 16-row
+    // chunk with 64-byte rows.  Which 16 bytes of K a lane fetches for that
+    // slot is free, so the K units of row r are stored rotated by
+    // (r / 4) % 4 (exclusive-or): the 128-bit operand reads of 16 consecutive
+    // rows then fall on 16 distinct bank groups.  A lane whose row or K offset
+    // is out of range is given an offset beyond the buffer and writes zeros.
     constexpr uint32_t kOob = 0x80000000u;
-    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void *)g.a, 0, (int)g.a_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)g.w, 0, (int)g.w_bytes, 0x00020000);
+    auto descriptor = [](const void *p, int64_t bytes) {             // raw buffer: base, no stride, extent, dword format
+        const uint64_t a = (uint64_t)p;
+        v4i d;
+        d[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+        d[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32) & 0xffff);
+        d[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+        d[3] = 0x00020000;
+        return d;
+    };
+    const v4i rsrc_a = descriptor(g.a, g.a_bytes), rsrc_w = descriptor(g.w, g.w_bytes);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte *)lds;      // LDS address of the stage array
+    const int rloc = lane >> 2;                                  // row within the chunk
+    const int unit = (lane & 3) ^ ((lane >> 4) & 3);             // K unit this lane fetches
     uint32_t a_base[A_IT];               // byte offset of the row (linear) or of the centre pixel (conv)
     bool a_ok[A_IT];
     int a_oh[A_IT], a_ow[A_IT];
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-        const int r = (tid + it * 256) >> 2;
+        const int r = ((wave_u + it * 4) % A_CH) * 16 + rloc;
         const int64_t m = m0 + r;
-        a_ok[it] = r < BM && m < g.M;
+        a_ok[it] = m < g.M;
         a_base[it] = a_ok[it] ? (uint32_t)(m * (CONV ? (int64_t)g.cp : g.lda)) : 0u;
         if (CONV) {
             a_ow[it] = (int)(m % g.W);
@@ -77,12 +112,15 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     bool b_ok[B_IT];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
-        const int r = (tid + it * 256) >> 2;
-        b_ok[it] = r < BN && n0 + r < g.N;
+        const int r = ((wave_u + it * 4) % B_CH) * 16 + rloc;
+        b_ok[it] = n0 + r < g.N;
         b_base[it] = b_ok[it] ? (uint32_t)(n0 + r) * (uint32_t)g.kp : 0u;
     }
 
-    auto load_tiles = [&](int kt, v4u (&ra)[A_IT], v4u (&rb)[B_IT]) {
+    // requests K step kt into LDS stage `stage`.  Every wave issues exactly
+    // A_IT + B_IT loads (the waits below count them): where a tile has fewer
+    // chunks than that, waves fetch a chunk twice, writing the same bytes.
+    auto fetch = [&](int kt, int stage) {
         const int k0 = kt * kBK + unit * 16;
         const bool k_ok = k0 < g.kp;
         int dh = 0, dw = 0, delta = k0;
@@ -93,39 +131,32 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
             dw = tap - kh * 3 - 1;
             delta = (dh * g.W + dw) * g.cp + (k0 - tap * g.cp);
         }
+        const uint32_t sA = lds0 + stage * STAGE, sB = sA + BM * kBK;
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
+            const int chunk = (wave_u + it * 4) % A_CH;
             bool ok = a_ok[it] && k_ok;
             if (CONV) ok = ok && (unsigned)(a_oh[it] + dh) < (unsigned)g.H && (unsigned)(a_ow[it] + dw) < (unsigned)g.W;
-            ra[it] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? a_base[it] + (uint32_t)delta : kOob, 0, 0);
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it)
-            rb[it] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (b_ok[it] && k_ok) ? b_base[it] + (uint32_t)k0 : kOob, 0, 0);
-    };
-    auto store_tiles = [&](int stage, const v4u (&ra)[A_IT], const v4u (&rb)[B_IT]) {
-        uint8_t *sA = lds + stage * STAGE, *sB = sA + BM * kLdsRow;
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-            const int r = (tid + it * 256) >> 2;
-            if ((BM * 4) % 256 == 0 || r < BM) *(v4u *)&sA[r * kLdsRow + unit * 16] = ra[it];
+            load_to_lds_b128(rsrc_a, sA + chunk * 1024, ok ? a_base[it] + (uint32_t)delta : kOob);
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-            const int r = (tid + it * 256) >> 2;
-            if ((BN * 4) % 256 == 0 || r < BN) *(v4u *)&sB[r * kLdsRow + unit * 16] = rb[it];
+            const int chunk = (wave_u + it * 4) % B_CH;
+            load_to_lds_b128(rsrc_w, sB + chunk * 1024, (b_ok[it] && k_ok) ? b_base[it] + (uint32_t)k0 : kOob);
         }
     };
-    // operand fragments of one 32-byte K half-step
+    // operand fragments of one 32-byte K half-step: lane l supplies row l % 32, K unit 2 ks + l / 32
+    const int frow = lane & 31;
+    const int fsw = (frow >> 2) & 3;
     auto read_frags = [&](int stage, int ks, v4i (&fa)[TM], v4i (&fb)[TN]) {
-        const uint8_t *sA = lds + stage * STAGE, *sB = sA + BM * kLdsRow;
-        const int koff = (ks * 2 + (lane >> 5)) * 16;
+        const uint8_t *sA = lds + stage * STAGE, *sB = sA + BM * kBK;
+        const int koff = ((ks * 2 + (lane >> 5)) ^ fsw) * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fa[i] = *(const v4i *)&sA[((wm * TM + i) * 32 + (lane & 31)) * kLdsRow + koff];
+            fa[i] = *(const v4i *)&sA[((wm * TM + i) * 32 + frow) * kBK + koff];
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            fb[j] = *(const v4i *)&sB[((wn * TN + j) * 32 + (lane & 31)) * kLdsRow + koff];
+            fb[j] = *(const v4i *)&sB[((wn * TN + j) * 32 + frow) * kBK + koff];
     };
 
     v16i acc[TM][TN];
@@ -143,129 +174,110 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
 
-    // Software pipeline.  Global loads run two K steps ahead in two register
-    // sets; LDS holds two stages; operand fragments are double buffered.  The
-    // scheduler hints spread the step's memory instructions between its MFMAs:
-    // an MFMA occupies the matrix pipe for 32 cycles during which the wave may
-    // issue loads, LDS reads and LDS writes, and the LDS write port (a quarter
-    // of the read rate) is the scarce resource.
+    // Software pipeline over three LDS stages.  During step kt the matrix cores
+    // work on stage kt % 3, K step kt + 1 is landing in the next stage and K
+    // step kt + 2 is requested into the third (the one step kt - 1 read: every
+    // wave has passed the barrier that ended that step).  One barrier per step.
     constexpr int NMF = TM * TN;                 // MFMAs per half step
-    constexpr int NLD = A_IT + B_IT;             // global loads / LDS writes per step
     constexpr int NRD = TM + TN;                 // LDS operand reads per half step
     const int nk = (g.kp + kBK - 1) / kBK;
-    v4u ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
     v4i fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    load_tiles(0, ra0, rb0);
-    load_tiles(1, ra1, rb1);
-    store_tiles(0, ra0, rb0);
+    fetch(0, 0);
+    fetch(1, 1);
+    __builtin_amdgcn_s_waitcnt(0x0f70 | ((A_IT + B_IT) & 0xf) | (((A_IT + B_IT) >> 4) << 14));   // vmcnt: K step 0 landed
     __syncthreads();
     read_frags(0, 0, fa0, fb0);
-    // step kt: tile kt is in LDS stage kt & 1, tile kt + 1 is in (or on its way to)
-    // the register set `rs`, tile kt + 2 is requested into the set `rl`
-    auto step = [&](int kt, v4u (&rsa)[A_IT], v4u (&rsb)[B_IT], v4u (&rla)[A_IT], v4u (&rlb)[B_IT]) {
-        load_tiles(kt + 2, rla, rlb);            // past the end of K the loader returns zeros
-        read_frags(kt & 1, 1, fa1, fb1);
-        store_tiles((kt + 1) & 1, rsa, rsb);
+    int st = 0;                                  // stage of K step kt
+    for (int kt = 0; kt < nk; ++kt) {            // past the end of K the loads return zeros
+        const int st1 = st == kStages - 1 ? 0 : st + 1, st2 = st1 == kStages - 1 ? 0 : st1 + 1;
+        read_frags(st, 1, fa1, fb1);
+        fetch(kt + 2, st2);
         mfma_all(fa0, fb0);
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
-            if (i < NLD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);          // one global load
             if (i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one LDS read
-            if (i >= NMF - NLD) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            if (i < A_IT + B_IT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one load
         }
+        __builtin_amdgcn_s_waitcnt(0x0f70 | ((A_IT + B_IT) & 0xf) | (((A_IT + B_IT) >> 4) << 14));  // K step kt + 1 landed
         __syncthreads();
-        read_frags((kt + 1) & 1, 0, fa0, fb0);
+        read_frags(st1, 0, fa0, fb0);
         mfma_all(fa1, fb1);
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-    };
-    for (int kt = 0; kt < nk; kt += 2) {        // an odd count runs one extra step on zeros
-        step(kt, ra1, rb1, ra0, rb0);
-        step(kt + 1, ra0, rb0, ra1, rb1);
+        st = st1;
     }
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the zero-filled K steps past the end
 
-    // ---- epilogue.  Lane l of a 32x32 accumulator block holds column l % 32 and
-    // rows 8 * (r / 4) + 4 * (l / 32) + r % 4 (r = 0..15).  One block row of the
-    // wave tile at a time is passed through LDS (free now) so that each lane ends
-    // up with four consecutive columns of one row: 16-byte loads of bias and
-    // residual, 16-byte stores of the output.
-    constexpr int EW = TN * 32, ELD = EW + 4;
-    constexpr int QPR = EW / 4;                  // 4-column groups per row; divides 64
-    constexpr int RPI = 64 / QPR;                // rows a wave covers per pass
-    int *ebuf = (int *)lds + wave * 32 * ELD;
-    const bool vec4 = (g.N & 3) == 0 && (g.ldy & 3) == 0;
-    // a lane keeps the same four columns through the whole epilogue
-    const int c4 = (lane % QPR) * 4;
-    const int col = n0 + wn * EW + c4;
-    const bool full = vec4 && col + 4 <= g.N;
-    float bv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (g.bias) {
+    // ---- epilogue, straight from the accumulators.  Lane l of a 32x32 block
+    // holds column l % 32 and rows 8 * (r / 4) + 4 * (l / 32) + r % 4 (r = 0..15),
+    // so for a fixed r each half of the wave owns 32 consecutive columns of one
+    // row: every store instruction writes two full 128-byte row segments, and the
+    // row part of the address is uniform (scalar arithmetic only).
+    const int lcol = lane & 31, lrow = (lane >> 5) * 4;
+    const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
+    // Running maximum for the next quantiser, kept as a bit pattern so that a
+    // NaN or an infinity stays visible.  Non-negative values (after ReLU, or
+    // when only positive values are wanted) order like signed integers.
+    const bool pos = g.amax_pos != 0;
+    int32_t amax = 0;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && g.y && !g.acc_out;
+    const uint32_t yoff = (uint32_t)(lrow * g.ldy + lcol);
+    const uint32_t roff = g.res_q ? (uint32_t)(lrow * g.res_ld + lcol) : 0u;
+    const uint32_t aoff = (uint32_t)(lrow * g.N + lcol);
+    // EDGE false: interior tile, no bounds tests, no observation outputs.
+    // EDGE true : edge tiles and observed runs, every element tested.
+    auto emit = [&](auto edge_c, auto res_c, auto relu_c, auto pos_c) {
+        constexpr bool EDGE = decltype(edge_c)::value, RES = decltype(res_c)::value, RELU = decltype(relu_c)::value;
+        constexpr bool POS = decltype(pos_c)::value;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (col + e < g.N) bv[e] = g.bias[col + e];
-    }
-    uint32_t amax = 0;
+        for (int j = 0; j < TN; ++j) {
+            const int col0 = n0 + (wn_u * TN + j) * 32;
+            const bool col_ok = !EDGE || col0 + lcol < g.N;
+            const float bj = (g.bias && col_ok) ? g.bias[col0 + lcol] : 0.0f;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        __syncthreads();
+            for (int i = 0; i < TM; ++i) {
+                const int64_t row0 = m0 + (wm_u * TM + i) * 32;
+                float *yb = g.y + row0 * g.ldy + col0;
+                const int8_t *rb = g.res_q + row0 * g.res_ld + col0;
+                int32_t *ab = g.acc_out + row0 * g.N + col0;
+                const int rows_left = EDGE ? (int)(g.M - row0 < 32 ? g.M - row0 : 32) - lrow : 32;
+                // the block stays in the accumulation registers until its turn
+                asm volatile("" : "+a"(acc[i][j]));
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                ebuf[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
-        __syncthreads();
-#pragma unroll 4
-        for (int pass = 0; pass < 32 / RPI; ++pass) {
-            const int rr = pass * RPI + lane / QPR;
-            const int64_t row = m0 + (wm * TM + i) * 32 + rr;
-            if (row >= g.M || col >= g.N) continue;
-            const int4 a4 = *(const int4 *)&ebuf[rr * ELD + c4];
-            const int av[4] = {a4.x, a4.y, a4.z, a4.w};
-            float rv[4] = {0.f, 0.f, 0.f, 0.f}, out[4];
-            if (g.res_q) {
-                const int8_t *rp = g.res_q + row * g.res_ld + col;
-                if (full) {
-                    const uint32_t w = *(const uint32_t *)rp;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) rv[e] = (float)(int8_t)((w >> (8 * e)) & 0xff) * rs;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < g.N) rv[e] = (float)rp[e] * rs;
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = 8 * (r >> 2) + (r & 3);
+                    if (EDGE && !(col_ok && rr < rows_left)) continue;
+                    const int a = acc[i][j][r];
+                    float v = fmaf((float)a, s, bj);
+                    if (EDGE ? g.res_q != nullptr : RES) v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
+                    if (EDGE ? g.act == 1 : RELU) v = v > 0.0f ? v : 0.0f;
+                    if (!EDGE || g.y) yb[(size_t)rr * g.ldy + yoff] = v;
+                    if (EDGE && g.acc_out) ab[(size_t)rr * g.N + aoff] = a;
+                    int32_t bits = (int32_t)__float_as_uint(v);
+                    if (EDGE ? !(g.act == 1 || pos) : !(RELU || POS)) bits &= 0x7fffffff;
+                    amax = amax > bits ? amax : bits;
                 }
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float v = fmaf((float)av[e], s, bv[e]);
-                if (g.res_q) v = v + rv[e];
-                if (g.act == 1) v = v > 0.0f ? v : 0.0f;
-                out[e] = v;
-                if (col + e < g.N) {
-                    const uint32_t ab = g.amax_pos ? (v > 0.0f ? __float_as_uint(v) : 0u) : abs_bits(v);
-                    amax = amax > ab ? amax : ab;
-                }
-            }
-            if (full) {
-                *(float4 *)(g.y + row * g.ldy + col) = make_float4(out[0], out[1], out[2], out[3]);
-                if (g.acc_out) *(int4 *)(g.acc_out + row * g.N + col) = a4;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < g.N) {
-                        g.y[row * g.ldy + col + e] = out[e];
-                        if (g.acc_out) g.acc_out[row * g.N + col + e] = av[e];
-                    }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    if (!interior) emit(T{}, F{}, F{}, F{});
+    else if (g.res_q) {
+        if (g.act == 1) emit(F{}, T{}, T{}, F{}); else emit(F{}, T{}, F{}, F{});
+    } else {
+        if (g.act == 1) emit(F{}, F{}, T{}, F{});
+        else if (pos) emit(F{}, F{}, F{}, T{});
+        else emit(F{}, F{}, F{}, F{});
     }
     if (g.absmax_out) {
         __shared__ uint32_t sm4[4];
-        block_atomic_max(amax, g.absmax_out, sm4);
+        block_atomic_max((uint32_t)amax, g.absmax_out, sm4);
     }
 }
 
@@ -277,7 +289,7 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     if (tiles > 0x3fffffffLL) return hipErrorInvalidValue;
     const int tpx = (int)((tiles + 7) / 8);
     const dim3 grid((unsigned)(tpx * 8)), block(256);
-    constexpr size_t smem = (size_t)2 * (BM + BN) * kLdsRow;
+    constexpr size_t smem = (size_t)kStages * (BM + BN) * kBK;
     hipError_t e;
     if (g.conv3x3) {
         static bool set = false;
@@ -357,13 +369,15 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     }
 }
 
-// Tile choice.  With fp32 outputs the epilogue (convert, scale, store) costs as
-// much as the K loop unless K is long, so two 128x128 workgroups per CU, one in
-// its K loop while the other stores, beat one 256-wide workgroup; the wide
-// tiles pay off for long K, where the LDS and L1 traffic per MFMA matters.
+// Tile choice.  A tile shape is priced by the work the chip does for it,
+// padding included: workgroups run in rounds of 256 CUs x (workgroups resident
+// per CU), a partly filled last round costs as much as a full one, and the
+// smaller shapes pay more LDS and L1 traffic per MFMA.  With fp32 outputs the
+// epilogue (convert, scale, store) costs as much as the K loop unless K is
+// long, so for short K only shapes with two workgroups per CU are considered:
+// one is in its K loop while the other stores.
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
-    auto ntiles = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * (int64_t)((g.N + bn - 1) / bn); };
     if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
         const int64_t blocks = (g.M + 127) / 128;
         if (blocks <= 0) return hipSuccess;
@@ -371,11 +385,28 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
         return launch_k(EGERIA_KERNEL_GEMM, conv3x3_c16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g);
     }
     if (g.N <= 32) return launch_variant<128, 32, 4, 1>(g, st);
-    if (g.kp >= 2048) {
-        if (ntiles(256, 256) >= 448) return launch_variant<256, 256, 2, 2>(g, st);
-        if (ntiles(256, 128) >= 224) return launch_variant<256, 128, 2, 2>(g, st);
+    struct Shape { int bm, bn, resident; double penalty; };
+    static const Shape shapes[4] = {{256, 256, 1, 1.00}, {256, 128, 2, 1.06}, {128, 192, 2, 1.10}, {128, 128, 3, 1.20}};
+    int best = 3;
+    double best_cost = 0.0;
+    for (int i = 0; i < 4; ++i) {
+        const Shape &sh = shapes[i];
+        if (sh.resident == 1 && g.kp < 2048) continue;
+        const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
+        const int64_t slots = 256 * (int64_t)sh.resident;
+        const int64_t rounds = (tiles + slots - 1) / slots;
+        const double cost = (double)rounds * sh.resident * sh.bm * sh.bn * sh.penalty;
+        if (best_cost == 0.0 || cost < best_cost) {
+            best_cost = cost;
+            best = i;
+        }
     }
-    return launch_variant<128, 128, 2, 2>(g, st);
+    switch (best) {
+    case 0: return launch_variant<256, 256, 2, 2>(g, st);
+    case 1: return launch_variant<256, 128, 2, 2>(g, st);
+    case 2: return launch_variant<128, 192, 2, 2>(g, st);
+    default: return launch_variant<128, 128, 2, 2>(g, st);
+    }
 }
 
 }  // namespace egeria
