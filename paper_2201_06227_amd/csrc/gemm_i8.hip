@@ -27,7 +27,15 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;          // K bytes per step
-constexpr int kStages = 3;       // LDS stages: one being read, two being filled
+// LDS stages of a tile shape: one being read, the others being filled.  Shapes
+// that leave room for a single workgroup per CU get as deep a ring as fits.
+constexpr int stages_for(int bm, int bn)
+{
+    const int stage = (bm + bn) * kBK;
+    if (bm * bn < 256 * 192) return 3;
+    const int fit = 150 * 1024 / stage;
+    return fit > 6 ? 6 : fit;
+}
 
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
@@ -54,7 +62,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     constexpr int A_CH = BM / 16, B_CH = BN / 16;                       // 1-KiB chunks (16 rows x 64 bytes) per K step
     constexpr int A_IT = (A_CH + 3) / 4, B_IT = (B_CH + 3) / 4;         // chunks per wave
     constexpr int STAGE = (BM + BN) * kBK;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [kStages][BM + BN][64]
+    constexpr int NST = stages_for(BM, BN);
+    constexpr int NLD = A_IT + B_IT;                                    // loads per wave and K step
+    static_assert((NST - 2) * NLD < 64, "outstanding loads must fit the wait counter");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [NST][BM + BN][64]
 
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile = xcd * tiles_per_xcd + local;
@@ -117,33 +128,49 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
         b_base[it] = b_ok[it] ? (uint32_t)(n0 + r) * (uint32_t)g.kp : 0u;
     }
 
-    // requests K step kt into LDS stage `stage`.  Every wave issues exactly
-    // A_IT + B_IT loads (the waits below count them): where a tile has fewer
-    // chunks than that, waves fetch a chunk twice, writing the same bytes.
-    auto fetch = [&](int kt, int stage) {
-        const int k0 = kt * kBK + unit * 16;
-        const bool k_ok = k0 < g.kp;
-        int dh = 0, dw = 0, delta = k0;
+    // Requests for K step kt into LDS stage `stage`, one 1-KiB chunk per call
+    // (idx < A_IT: a chunk of A, else of W).  Every wave issues exactly NLD loads
+    // per K step (the waits below count them): where a tile has fewer chunks
+    // than that, waves fetch a chunk twice, writing the same bytes.
+    struct StepAddr {
+        int k0, dh, dw, delta;
+        bool k_ok;
+    };
+    auto step_addr = [&](int kt) {
+        StepAddr sa;
+        sa.k0 = kt * kBK + unit * 16;
+        sa.k_ok = sa.k0 < g.kp;
+        sa.dh = 0;
+        sa.dw = 0;
+        sa.delta = sa.k0;
         if (CONV) {
-            const int tap = k0 / g.cp;
+            const int tap = sa.k0 / g.cp;
             const int kh = tap / 3;
-            dh = kh - 1;
-            dw = tap - kh * 3 - 1;
-            delta = (dh * g.W + dw) * g.cp + (k0 - tap * g.cp);
+            sa.dh = kh - 1;
+            sa.dw = tap - kh * 3 - 1;
+            sa.delta = (sa.dh * g.W + sa.dw) * g.cp + (sa.k0 - tap * g.cp);
         }
+        return sa;
+    };
+    auto fetch_one = [&](const StepAddr &sa, int stage, int idx) {
         const uint32_t sA = lds0 + stage * STAGE, sB = sA + BM * kBK;
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
+        if (idx < A_IT) {
+            const int it = idx;
             const int chunk = (wave_u + it * 4) % A_CH;
-            bool ok = a_ok[it] && k_ok;
-            if (CONV) ok = ok && (unsigned)(a_oh[it] + dh) < (unsigned)g.H && (unsigned)(a_ow[it] + dw) < (unsigned)g.W;
-            load_to_lds_b128(rsrc_a, sA + chunk * 1024, ok ? a_base[it] + (uint32_t)delta : kOob);
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
+            bool ok = a_ok[it] && sa.k_ok;
+            if (CONV)
+                ok = ok && (unsigned)(a_oh[it] + sa.dh) < (unsigned)g.H && (unsigned)(a_ow[it] + sa.dw) < (unsigned)g.W;
+            load_to_lds_b128(rsrc_a, sA + chunk * 1024, ok ? a_base[it] + (uint32_t)sa.delta : kOob);
+        } else {
+            const int it = idx - A_IT;
             const int chunk = (wave_u + it * 4) % B_CH;
-            load_to_lds_b128(rsrc_w, sB + chunk * 1024, (b_ok[it] && k_ok) ? b_base[it] + (uint32_t)k0 : kOob);
+            load_to_lds_b128(rsrc_w, sB + chunk * 1024, (b_ok[it] && sa.k_ok) ? b_base[it] + (uint32_t)sa.k0 : kOob);
         }
+    };
+    auto fetch = [&](int kt, int stage) {
+        const StepAddr sa = step_addr(kt);
+#pragma unroll
+        for (int idx = 0; idx < A_IT + B_IT; ++idx) fetch_one(sa, stage, idx);
     };
     // operand fragments of one 32-byte K half-step: lane l supplies row l % 32, K unit 2 ks + l / 32
     const int frow = lane & 31;
@@ -174,32 +201,40 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
 
-    // Software pipeline over three LDS stages.  During step kt the matrix cores
-    // work on stage kt % 3, K step kt + 1 is landing in the next stage and K
-    // step kt + 2 is requested into the third (the one step kt - 1 read: every
-    // wave has passed the barrier that ended that step).  One barrier per step.
+    // Software pipeline over a ring of NST LDS stages.  During step kt the
+    // matrix cores work on stage kt % NST, K steps kt + 1 .. kt + NST - 2 are
+    // landing in the following stages and K step kt + NST - 1 is requested into
+    // the stage that step kt - 1 read (every wave has passed the barrier that
+    // ended that step).  One barrier per step.
     constexpr int NMF = TM * TN;                 // MFMAs per half step
     constexpr int NRD = TM + TN;                 // LDS operand reads per half step
+    constexpr int kWaitNext = 0x0f70 | (((NST - 2) * NLD) & 0xf) | ((((NST - 2) * NLD) >> 4) << 14);   // vmcnt only
     const int nk = (g.kp + kBK - 1) / kBK;
     v4i fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    fetch(0, 0);
-    fetch(1, 1);
-    __builtin_amdgcn_s_waitcnt(0x0f70 | ((A_IT + B_IT) & 0xf) | (((A_IT + B_IT) >> 4) << 14));   // vmcnt: K step 0 landed
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) fetch(p, p);
+    __builtin_amdgcn_s_waitcnt(kWaitNext);       // K step 0 landed
     __syncthreads();
     read_frags(0, 0, fa0, fb0);
     int st = 0;                                  // stage of K step kt
     for (int kt = 0; kt < nk; ++kt) {            // past the end of K the loads return zeros
-        const int st1 = st == kStages - 1 ? 0 : st + 1, st2 = st1 == kStages - 1 ? 0 : st1 + 1;
+        const int st1 = st == NST - 1 ? 0 : st + 1, stl = st == 0 ? NST - 1 : st - 1;
         read_frags(st, 1, fa1, fb1);
-        fetch(kt + 2, st2);
-        mfma_all(fa0, fb0);
+        const StepAddr sa = step_addr(kt + NST - 1);
+        // the step's requests are spread between its first MFMAs: a burst of them
+        // would fill the memory pipeline's queue and stall the wave's MFMA issue
 #pragma unroll
-        for (int i = 0; i < NMF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
-            if (i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);          // one LDS read
-            if (i < A_IT + B_IT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one load
-        }
-        __builtin_amdgcn_s_waitcnt(0x0f70 | ((A_IT + B_IT) & 0xf) | (((A_IT + B_IT) >> 4) << 14));  // K step kt + 1 landed
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+                constexpr int per = (NLD + NMF - 1) / NMF;               // requests after each MFMA
+#pragma unroll
+                for (int q = 0; q < per; ++q)
+                    if ((i * TN + j) * per + q < NLD) fetch_one(sa, stl, (i * TN + j) * per + q);
+                if ((i * TN + j) * per < NLD) __builtin_amdgcn_sched_barrier(0);   // keep the MFMA before its requests
+            }
+        __builtin_amdgcn_s_waitcnt(kWaitNext);   // K step kt + 1 landed
         __syncthreads();
         read_frags(st1, 0, fa0, fb0);
         mfma_all(fa1, fb1);
@@ -289,7 +324,7 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     if (tiles > 0x3fffffffLL) return hipErrorInvalidValue;
     const int tpx = (int)((tiles + 7) / 8);
     const dim3 grid((unsigned)(tpx * 8)), block(256);
-    constexpr size_t smem = (size_t)kStages * (BM + BN) * kBK;
+    constexpr size_t smem = (size_t)stages_for(BM, BN) * (BM + BN) * kBK;
     hipError_t e;
     if (g.conv3x3) {
         static bool set = false;
@@ -386,10 +421,11 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     }
     if (g.N <= 32) return launch_variant<128, 32, 4, 1>(g, st);
     struct Shape { int bm, bn, resident; double penalty; };
-    static const Shape shapes[4] = {{256, 256, 1, 1.00}, {256, 128, 2, 1.06}, {128, 192, 2, 1.10}, {128, 128, 3, 1.20}};
-    int best = 3;
+    static const Shape shapes[5] = {{256, 256, 1, 1.00}, {256, 192, 1, 1.03}, {256, 128, 2, 1.06},
+                                    {128, 192, 2, 1.10}, {128, 128, 3, 1.20}};
+    int best = 4;
     double best_cost = 0.0;
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 5; ++i) {
         const Shape &sh = shapes[i];
         if (sh.resident == 1 && g.kp < 2048) continue;
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
@@ -403,8 +439,9 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     }
     switch (best) {
     case 0: return launch_variant<256, 256, 2, 2>(g, st);
-    case 1: return launch_variant<256, 128, 2, 2>(g, st);
-    case 2: return launch_variant<128, 192, 2, 2>(g, st);
+    case 1: return launch_variant<256, 192, 2, 2>(g, st);
+    case 2: return launch_variant<256, 128, 2, 2>(g, st);
+    case 3: return launch_variant<128, 192, 2, 2>(g, st);
     default: return launch_variant<128, 128, 2, 2>(g, st);
     }
 }
