@@ -421,11 +421,11 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     }
     if (g.N <= 32) return launch_variant<128, 32, 4, 1>(g, st);
     struct Shape { int bm, bn, resident; double penalty; };
-    static const Shape shapes[5] = {{256, 256, 1, 1.00}, {256, 192, 1, 1.03}, {256, 128, 2, 1.06},
-                                    {128, 192, 2, 1.10}, {128, 128, 3, 1.20}};
+    static const Shape shapes[6] = {{256, 256, 1, 1.00}, {256, 192, 1, 1.03}, {256, 128, 2, 1.06},
+                                    {128, 192, 2, 1.10}, {128, 128, 3, 1.20}, {128, 64, 4, 1.40}};
     int best = 4;
     double best_cost = 0.0;
-    for (int i = 0; i < 5; ++i) {
+    for (int i = 0; i < 6; ++i) {
         const Shape &sh = shapes[i];
         if (sh.resident == 1 && g.kp < 2048) continue;
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
@@ -442,6 +442,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     case 1: return launch_variant<256, 192, 2, 2>(g, st);
     case 2: return launch_variant<256, 128, 2, 2>(g, st);
     case 3: return launch_variant<128, 192, 2, 2>(g, st);
+    case 5: return launch_variant<128, 64, 2, 2>(g, st);
     default: return launch_variant<128, 128, 2, 2>(g, st);
     }
 }
