@@ -409,8 +409,9 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
 // per CU), a partly filled last round costs as much as a full one, and the
 // smaller shapes pay more LDS and L1 traffic per MFMA.  With fp32 outputs the
 // epilogue (convert, scale, store) costs as much as the K loop unless K is
-// long, so for short K only shapes with two workgroups per CU are considered:
-// one is in its K loop while the other stores.
+// long, so for short K only shapes with two workgroups per CU are considered
+// (one is in its K loop while the other stores), and for very short K, where
+// the kernel is a stream of stores, only the small shapes.
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
     if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
@@ -428,6 +429,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     for (int i = 0; i < 6; ++i) {
         const Shape &sh = shapes[i];
         if (sh.resident == 1 && g.kp < 2048) continue;
+        if (sh.bm * sh.bn > 128 * 128 && g.kp < 512) continue;     // store bound: many small workgroups in flight
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
         const int64_t slots = 256 * (int64_t)sh.resident;
         const int64_t rounds = (tiles + slots - 1) / slots;

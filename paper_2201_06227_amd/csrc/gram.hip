@@ -20,12 +20,14 @@
 //   current one is contracted) and read back as 128-bit v_mfma_f32_32x32x2f32
 //   operands: lane l takes row l % 32 and four consecutive k at 8s + 4(l / 32),
 //   A and B operand alike, so the order of k inside the sum never matters.
-// Kernel 2 (gram_reduce): sums the partials over chunks in fp64, element-wise,
-//   coalesced, in a fixed order.
-// Kernel 3 (sp_finalize): one wave per row i of the b x b matrices: row i of
-//   both Gram matrices, their norms and the row's share of the squared
-//   difference; the last wave to finish adds the b shares in index order and
-//   writes P.  Results are bit-reproducible from call to call.
+//   Each workgroup stores its M block twice, as is and transposed, so that
+//   the next kernel reads rows only.
+// Kernel 2 (sp_finalize): one workgroup per row i of the b x b matrices.  It
+//   sums row i of M, M^T and B over the chunks in fp64 (fixed assignment of
+//   chunks to thread groups, fixed order), forms row i of both Gram matrices,
+//   their norms and the row's share of the squared difference; the last
+//   workgroup to finish adds the b shares in index order and writes P.
+//   Results are bit-reproducible from call to call.
 #include "common.hpp"
 
 namespace egeria {
@@ -61,15 +63,14 @@ static GramPlan plan_gram(int32_t b, int64_t D)
     return p;
 }
 
-// workspace of the metric: [counter | row shares (b doubles) | reduced M, B (2 b^2 doubles) | partials]
+// workspace of the metric: [counter | row shares (b doubles) | partials [nsplit][3][b][b] (M, M^T, B)]
 static size_t off_rowsum() { return 256; }
-static size_t off_red(int32_t b) { return 256 + align_up((size_t)b * sizeof(double), 256); }
-static size_t off_partials(int32_t b) { return off_red(b) + align_up(2 * (size_t)b * b * sizeof(double), 256); }
+static size_t off_partials(int32_t b) { return 256 + align_up((size_t)b * sizeof(double), 256); }
 
 size_t plasticity_partial_bytes(int32_t b, int64_t D)
 {
     GramPlan p = plan_gram(b, D);
-    return off_partials(b) + align_up((size_t)p.nsplit * 2 * (size_t)b * b * sizeof(float), 256);
+    return off_partials(b) + align_up((size_t)p.nsplit * 3 * (size_t)b * b * sizeof(float), 256);
 }
 
 // ---- global -> register staging of one [rows x KT] tile -------------------------------
@@ -228,7 +229,8 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
 
     // lane l of a 32x32 block holds column l % 32, rows 8 * (i / 4) + 4 * (l / 32) + i % 4
     const size_t nelem = (size_t)b * b;
-    float *dst = part + (size_t)chunk * 2 * nelem;
+    float *dst = part + (size_t)chunk * 3 * nelem;               // M | M^T | B of this chunk
+    if (id == 0 && tid == 0) *counter = 0u;                       // ticket of the finaliser
     if (MT == 1) {
         // the four waves hold partial sums over disjoint k: add them through LDS
         float *red = lds;                         // [4][2][1024], the stage memory is free now
@@ -244,91 +246,119 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
             const float s = (red[(0 * 2 + prod) * 1024 + w] + red[(1 * 2 + prod) * 1024 + w]) +
                             (red[(2 * 2 + prod) * 1024 + w] + red[(3 * 2 + prod) * 1024 + w]);
             const int row = (i >> 2) * 8 + (l >> 5) * 4 + (i & 3), col = l & 31;
-            if (row < b && col < b) dst[prod * nelem + (size_t)row * b + col] = s;
+            if (row < b && col < b) {
+                if (prod == 0) {
+                    dst[(size_t)row * b + col] = s;
+                    dst[nelem + (size_t)col * b + row] = s;
+                } else {
+                    dst[2 * nelem + (size_t)row * b + col] = s;
+                }
+            }
         }
     } else {
         const int col = mj * ROWS + bj * 32 + r;
+        const bool quad_ok = (b & 3) == 0;        // four consecutive rows of a column: one 16-byte store of M^T
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = mi * ROWS + bi * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
             if (row < b && col < b) {
                 dst[(size_t)row * b + col] = accM[i];
-                dst[nelem + (size_t)row * b + col] = accB[i];
+                dst[2 * nelem + (size_t)row * b + col] = accB[i];
+                if (!quad_ok) dst[nelem + (size_t)col * b + row] = accM[i];
+            }
+        }
+        if (quad_ok && col < b) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = mi * ROWS + bi * 32 + q * 8 + h * 4;
+                if (row < b)
+                    *(float4 *)&dst[nelem + (size_t)col * b + row] =
+                        make_float4(accM[4 * q], accM[4 * q + 1], accM[4 * q + 2], accM[4 * q + 3]);
             }
         }
     }
 }
 
-// Sum of the partials over chunks in fp64 (fixed assignment, fixed order):
-// part = [nsplit][2][b][b] (M then B) -> red = [2][b][b] doubles.  A workgroup
-// owns 32 consecutive elements; its 8 groups of 32 lanes each take every 8th
-// chunk (128-byte coalesced reads) and the 8 sums are added through LDS.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const float *__restrict__ part, int nsplit,
-                                                          int nelem2, double *__restrict__ red,
-                                                          uint32_t *__restrict__ counter)
+// One workgroup per row i (b <= 128).  The 256 threads form G = 256 / W groups of
+// W >= b lanes (W = 32, 64 or 128); group g adds chunks g, g + G, ... of row i
+// of M, M^T and B in fp64, lane j taking column j (coalesced 4 W-byte reads),
+// and the G sums are added in group order.
+__global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restrict__ part, int nsplit, int b,
+                                                          double *__restrict__ rowsum,
+                                                          uint32_t *__restrict__ counter,
+                                                          float *__restrict__ p_out)
 {
-    __shared__ double sm[8][32];
-    const int el = threadIdx.x & 31, cg = threadIdx.x >> 5;
-    const int e = blockIdx.x * 32 + el;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *counter = 0u;       // ticket of the finaliser
-    double s0 = 0.0, s1 = 0.0;
-    if (e < nelem2) {
-        int c = cg;
-        for (; c + 8 < nsplit; c += 16) {                         // two independent loads in flight
-            s0 += (double)part[(size_t)c * nelem2 + e];
-            s1 += (double)part[(size_t)(c + 8) * nelem2 + e];
-        }
-        if (c < nsplit) s0 += (double)part[(size_t)c * nelem2 + e];
-    }
-    sm[cg][el] = s0 + s1;
-    __syncthreads();
-    if (cg == 0 && e < nelem2)
-        red[e] = ((sm[0][el] + sm[1][el]) + (sm[2][el] + sm[3][el])) + ((sm[4][el] + sm[5][el]) + (sm[6][el] + sm[7][el]));
-}
-
-// One wave per row i of the b x b matrices: row i of both Gram matrices, their
-// norms, the row's share of the squared difference; the last wave to finish adds
-// the b shares in index order and writes P.
-__global__ __launch_bounds__(64) void sp_finalize_kernel(const double *__restrict__ red, int b,
-                                                         double *__restrict__ rowsum,
-                                                         uint32_t *__restrict__ counter,
-                                                         float *__restrict__ p_out)
-{
-    const int lane = threadIdx.x, i = blockIdx.x;
-    const double *M = red, *B = red + (size_t)b * b;
-    double gt[2], gr[2], nt2 = 0.0, nr2 = 0.0;
+    __shared__ double sm[3][256];
+    __shared__ double wsum[4];
+    const int i = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int W = b <= 32 ? 32 : (b <= 64 ? 64 : 128), G = 256 / W;
+    const int j = t & (W - 1), grp = t / W;
+    const size_t nelem = (size_t)b * b, cstride = 3 * nelem;
+    constexpr int U = 8;                                          // chunks in flight per thread (3 loads each)
+    double am = 0.0, at = 0.0, ab = 0.0;
+    if (j < b) {
+        const float *p = part + (size_t)i * b + j;
+        int c = grp;
+        for (; c + (U - 1) * G < nsplit; c += U * G) {
+            float vm[U], vt[U], vb[U];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int j = lane + 64 * half;
-        gt[half] = gr[half] = 0.0;
-        if (j < b) {
-            gr[half] = B[(size_t)i * b + j];
-            gt[half] = gr[half] + 0.5 * (M[(size_t)i * b + j] + M[(size_t)j * b + i]);
+            for (int u = 0; u < U; ++u) {
+                const float *pc = p + (size_t)(c + u * G) * cstride;
+                vm[u] = pc[0];
+                vt[u] = pc[nelem];
+                vb[u] = pc[2 * nelem];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                am += (double)vm[u];
+                at += (double)vt[u];
+                ab += (double)vb[u];
+            }
         }
-        nt2 += gt[half] * gt[half];
-        nr2 += gr[half] * gr[half];
+        for (; c < nsplit; c += G) {
+            const float *pc = p + (size_t)c * cstride;
+            am += (double)pc[0];
+            at += (double)pc[nelem];
+            ab += (double)pc[2 * nelem];
+        }
     }
-    nt2 = wave_sum(nt2);
-    nr2 = wave_sum(nr2);
-    double nt = sqrt(nt2), nr = sqrt(nr2);
+    sm[0][t] = am;
+    sm[1][t] = at;
+    sm[2][t] = ab;
+    __syncthreads();
+    double gt = 0.0, gr = 0.0;
+    if (t < W && t < b) {
+        double m = 0.0, mt = 0.0, bb = 0.0;
+        for (int g = 0; g < G; ++g) {
+            m += sm[0][g * W + t];
+            mt += sm[1][g * W + t];
+            bb += sm[2][g * W + t];
+        }
+        gr = bb;                                   // row i of R R^T
+        gt = bb + 0.5 * (m + mt);                  // row i of T T^T
+    }
+    // sums over the row: waves 0 and 1 hold the (at most 128) columns
+    auto row_sum = [&](double v) {
+        v = wave_sum(v);
+        __syncthreads();
+        if (lane == 0) wsum[wave] = v;
+        __syncthreads();
+        return wsum[0] + wsum[1];
+    };
+    double nt = sqrt(row_sum(gt * gt)), nr = sqrt(row_sum(gr * gr));
     nt = nt < 1e-12 ? 1e-12 : nt;
     nr = nr < 1e-12 ? 1e-12 : nr;
-    double acc = 0.0;
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const double d = gt[half] / nt - gr[half] / nr;
-        acc += d * d;
-    }
-    acc = wave_sum(acc);
-    uint32_t ticket = 0;
-    if (lane == 0) {
-        rowsum[i] = acc;
+    const double d = (t < W && t < b) ? gt / nt - gr / nr : 0.0;
+    const double share = row_sum(d * d);
+    __shared__ uint32_t ticket_s;
+    if (t == 0) {
+        rowsum[i] = share;
         __threadfence();                                   // publish the share, then take a ticket
-        ticket = atomicAdd(counter, 1u);
+        ticket_s = atomicAdd(counter, 1u);
     }
-    ticket = (uint32_t)__shfl((int)ticket, 0, kWave);
-    if (ticket != (uint32_t)(b - 1)) return;
-    __threadfence();                                       // see every other wave's share
+    __syncthreads();
+    if (ticket_s != (uint32_t)(b - 1) || wave != 0) return;
+    __threadfence();                                       // see every other workgroup's share
     const double v0 = lane < b ? __hip_atomic_load(&rowsum[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
     const double v1 = lane + 64 < b ? __hip_atomic_load(&rowsum[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
     const double tot = wave_sum(v0 + v1);
@@ -374,13 +404,8 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     }
 #undef EGERIA_GRAM
     if (e != hipSuccess) return e;
-    double *red = (double *)((char *)ws_part + off_red(b));
-    const int nelem2 = 2 * b * b;
-    e = launch_k(EGERIA_KERNEL_NONE, gram_reduce_kernel, dim3((unsigned)((nelem2 + 31) / 32)), dim3(256), 0, st,
-                 (const float *)part, p.nsplit, nelem2, red, counter);
-    if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(64), 0, st, (const double *)red,
-                    (int)b, rowsum, counter, p_out);
+    return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(256), 0, st, (const float *)part,
+                    p.nsplit, (int)b, rowsum, counter, p_out);
 }
 
 }  // namespace egeria

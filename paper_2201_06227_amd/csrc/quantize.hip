@@ -281,6 +281,53 @@ __global__ __launch_bounds__(256) void quantize_nchw_kernel(
     }
 }
 
+// Same map without the LDS stage, for fp32 input whose pixel count is a
+// multiple of 4: a thread owns 4 consecutive pixels x 16 channels (sixteen
+// 16-byte loads, lanes along the pixel axis, all in flight together) and
+// writes four 16-byte channel groups.
+__global__ __launch_bounds__(256) void quantize_nchw_vec_kernel(
+    const float *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
+    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+    const float *__restrict__ fixed_scale,
+    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
+    uint32_t *__restrict__ flag)
+{
+    float scale;
+    bool bad;
+    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
+    const int64_t pq = hw >> 2, cg = cp >> 4;
+    const int64_t units = n * cg * pq;
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = (u % pq) << 2;
+        const int64_t ig = u / pq;
+        const int64_t g = ig % cg, img = ig / cg;
+        const int64_t ch0 = g << 4;
+        float4 v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            v[e] = ch0 + e < c ? *(const float4 *)(x + (img * c + ch0 + e) * hw + p) : make_float4(0.f, 0.f, 0.f, 0.f);
+        uint32_t w[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[k][j] = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const uint32_t sh = (e & 3) * 8;
+            uint32_t c0 = quant1(v[e].x, inv), c1 = quant1(v[e].y, inv), c2 = quant1(v[e].z, inv), c3 = quant1(v[e].w, inv);
+            if (ch0 + e >= c) c0 = c1 = c2 = c3 = 0;                  // pad channels are zero even when inv is not finite
+            w[0][e >> 2] |= c0 << sh;
+            w[1][e >> 2] |= c1 << sh;
+            w[2][e >> 2] |= c2 << sh;
+            w[3][e >> 2] |= c3 << sh;
+        }
+        int8_t *dst = q + (img * hw + p) * cp + ch0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) *(uint4 *)(dst + k * cp) = make_uint4(w[k][0], w[k][1], w[k][2], w[k][3]);
+    }
+}
+
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
                                 int64_t cp, const uint32_t *slot, int n_slot, int slot_stride,
                                 const float *fixed_scale,
@@ -288,6 +335,14 @@ hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64
                                 hipStream_t st)
 {
     const dim3 grid((unsigned)((hw + 63) / 64), (unsigned)((cp + 63) / 64), (unsigned)n), block(256);
+    if (dt == EGERIA_F32 && (hw & 3) == 0 && hw >= 4 && n > 0 && c > 0) {
+        const int64_t units = n * (cp >> 4) * (hw >> 2);
+        int64_t blocks = (units + 255) / 256;
+        if (blocks > 16384) blocks = 16384;
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_vec_kernel, dim3((unsigned)blocks), block, 0, st,
+                        (const float *)x, n, c, hw, cp, slot, n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2,
+                        flag);
+    }
     if (dt == EGERIA_F32)
         return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_nchw_kernel<false>, grid, block, 0, st, x, n, c, hw, cp, slot,
                         n_slot, slot_stride, fixed_scale, q, scale_out, scale_out2, flag);
