@@ -78,7 +78,10 @@ def roofline_for(wl, cls, durations_ms, eg, steps):
     """Achieved rate of one kernel class over the timed region against the
     roofline that bounds it."""
     work = algorithmic_work(wl, cls, eg)
-    names = {eg.KERNEL_GRAM: "gram_partial_kernel", eg.KERNEL_GEMM: "gemm_i8_kernel",
+    import synth_inputs as si
+    small_conv = wl.kind == si.KIND_BASIC_BLOCK and wl.dims["c_in"] <= 16 and wl.dims["c_out"] <= 32
+    names = {eg.KERNEL_GRAM: "gram_partial_kernel",
+             eg.KERNEL_GEMM: "conv3x3_c16_kernel" if small_conv else "gemm_i8_kernel",
              eg.KERNEL_ATTENTION: "attention_kernel"}
     if not work or not durations_ms:
         return None
@@ -286,6 +289,18 @@ def main():
         "kernel_breakdown_us_per_step": breakdown,
         "plasticity": [float(v) for v in eager_p.tolist()],
     }
+    # the other MFMA kernel classes of the step, each timed in a short pass of its own
+    others_roof = {}
+    for name, c in timed_classes.items():
+        if name == dominant or name not in breakdown:
+            continue
+        n = breakdown[name]["launches_per_step"] * 20
+        eg.profile_begin(c, n)
+        for _ in range(20):
+            ev.step(x, a_t)
+        torch.cuda.synchronize()
+        others_roof[name] = roofline_for(wl, c, eg.profile_end(n), eg, 20)
+    result["roofline_other_kernels"] = others_roof
     result["graph"] = graph_replay(ev, x, a_t, args.steps, eager_p)
 
     if not args.no_others:
