@@ -574,17 +574,46 @@ hipError_t launch_gelu_absmax_exact(const float *v, int64_t n, const uint32_t *v
                     exact_absmax);
 }
 
-__device__ __forceinline__ uint32_t quant_gelu1(float v, float inv)
+// fp32 GELU through the rational-times-Gaussian form of the complementary error
+// function (Abramowitz & Stegun 7.1.26: erfc(x) = (a1 t + ... + a5 t^5) exp(-x^2),
+// t = 1 / (1 + p x), |error| <= 1.5e-7 for x >= 0).  For v < 0 the factor
+// 1 + erf(v / sqrt 2) = erfc(|v| / sqrt 2) is used as it comes, without
+// cancellation.  With the hardware reciprocal and exponential (1 ulp each) and
+// fp32 Horner steps the absolute error of the factor stays below 6e-7, that of
+// gelu below 1e-6 * max(1, |v|): the bound the quantiser below relies on.
+__device__ __forceinline__ float gelu_fast(float v)
 {
-    const float g32 = 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
-    float t = g32 * inv;
-    // |fp32 gelu - exact| <= 1e-6 * max(1, |v|); times inv, plus the product's own rounding
-    const float bound = inv * 1.0e-6f * fmaxf(1.0f, fabsf(v)) + 2.0e-5f;
-    const float frac = t - floorf(t);
-    if (!(fabsf(frac - 0.5f) > bound)) t = gelu_exact(v) * inv;
+    const float ax = fabsf(v) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    p = p * t;
+    const float e = __builtin_amdgcn_exp2f(ax * ax * -1.44269504088896340736f);
+    const float c = p * e;                         // erfc(|v| / sqrt 2)
+    const float w = v < 0.0f ? c : 2.0f - c;       // 1 + erf(v / sqrt 2)
+    return 0.5f * v * w;
+}
+
+// Code of gelu(v) from the fp32 evaluation; *unsure is set when the value
+// times inv lies within the evaluation's error bound of a rounding boundary
+// (a few elements per 100 000): the caller then takes the fp64 form.
+__device__ __forceinline__ uint32_t code_of(float t)
+{
     float r = rintf(t);
     r = fminf(fmaxf(r, -127.0f), 127.0f);
     return (uint32_t)((int)r) & 0xffu;
+}
+
+__device__ __forceinline__ uint32_t quant_gelu_fast(float v, float inv, bool *unsure)
+{
+    const float t = gelu_fast(v) * inv;
+    // |fp32 gelu - exact| <= 1e-6 * max(1, |v|); times inv, plus the product's own rounding
+    const float bound = inv * 1.0e-6f * fmaxf(1.0f, fabsf(v)) + 2.0e-5f;
+    const float frac = t - floorf(t);
+    *unsure = !(fabsf(frac - 0.5f) > bound);
+    return code_of(t);
 }
 
 __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
@@ -611,18 +640,34 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
         const int64_t c0 = (u - row * upr) << 4;
         const int64_t base = row * cols + c0;
         uint32_t w[4] = {0, 0, 0, 0};
+        uint32_t redo = 0;                         // elements that need the fp64 form
         if (vec_ok && c0 + 16 <= cols) {
             const float4 *p = (const float4 *)(v + base);
+            float4 x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = p[j];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float4 x = p[j];
-                w[j] = quant_gelu1(x.x, inv) | (quant_gelu1(x.y, inv) << 8) | (quant_gelu1(x.z, inv) << 16) |
-                       (quant_gelu1(x.w, inv) << 24);
+                bool u0, u1, u2, u3;
+                w[j] = quant_gelu_fast(x[j].x, inv, &u0) | (quant_gelu_fast(x[j].y, inv, &u1) << 8) |
+                       (quant_gelu_fast(x[j].z, inv, &u2) << 16) | (quant_gelu_fast(x[j].w, inv, &u3) << 24);
+                redo |= ((u0 ? 1u : 0u) | (u1 ? 2u : 0u) | (u2 ? 4u : 0u) | (u3 ? 8u : 0u)) << (4 * j);
             }
         } else {
+            redo = 0xffffu;                        // ragged tail of a row: every element through the loop below
+        }
+        // one copy of the fp64 code, rolled: the values are re-read (they are in cache)
 #pragma unroll 1
-            for (int e = 0; e < 16; ++e)
-                if (c0 + e < cols) w[e >> 2] |= quant_gelu1(v[base + e], inv) << ((e & 3) * 8);
+        while (redo) {
+            const int e = __ffs((int)redo) - 1;
+            redo &= redo - 1;
+            if (c0 + e >= cols) continue;
+            const uint32_t code = code_of(gelu_exact(v[base + e]) * inv);
+            const uint32_t sh = (e & 3) * 8, keep = ~(0xffu << sh);
+            if ((e >> 2) == 0) w[0] = (w[0] & keep) | (code << sh);
+            if ((e >> 2) == 1) w[1] = (w[1] & keep) | (code << sh);
+            if ((e >> 2) == 2) w[2] = (w[2] & keep) | (code << sh);
+            if ((e >> 2) == 3) w[3] = (w[3] & keep) | (code << sh);
         }
         *(uint4 *)(q + row * ldq + c0) = make_uint4(w[0], w[1], w[2], w[3]);
     }
