@@ -26,15 +26,20 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-constexpr int kBK = 64;          // K bytes per step
-// LDS stages of a tile shape: one being read, the others being filled.  Shapes
-// that leave room for a single workgroup per CU get as deep a ring as fits.
-constexpr int stages_for(int bm, int bn)
+// K bytes per step, BK: 128 (one 128-byte cache line of every row per request)
+// or 64.  With 64-byte steps each line is fetched half now and half one step
+// later; the stage is half as large, so more workgroups or stages fit a CU.
+// LDS stages of a tile shape: one being read, the others being filled.
+constexpr int stages_for(int bm, int bn, int bk)
 {
-    const int stage = (bm + bn) * kBK;
-    if (bm * bn < 256 * 192) return 3;
-    const int fit = 150 * 1024 / stage;
-    return fit > 6 ? 6 : fit;
+    const int stage = (bm + bn) * bk;
+    if (bk == 64) {
+        if (bm * bn < 256 * 192) return 3;
+        const int fit = 150 * 1024 / stage;
+        return fit > 6 ? 6 : fit;
+    }
+    if (3 * stage > 150 * 1024) return 2;
+    return 2 * stage <= 80 * 1024 ? 2 : 3;
 }
 
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
@@ -53,19 +58,25 @@ __device__ __forceinline__ void load_to_lds_b128(v4i rsrc, uint32_t lds_base, ui
                  : "memory", "m0");
 }
 
-template <int BM, int BN, int WM, int WN, bool CONV>
+template <int BM, int BN, int WM, int WN, bool CONV, int BK>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tiles, int tiles_per_xcd)
 {
+    static_assert(BK == 64 || BK == 128, "K step of 64 or 128 bytes");
+    constexpr int kBK = BK;
+    constexpr int UPR = BK / 16;                 // 16-byte K units per row of a stage
+    constexpr int kRowsPerChunk = 64 / UPR;      // rows one load instruction of a wave covers
+    constexpr int SWR = 16 / UPR;                // rows that share a rotation of the K units
+    constexpr int NSUB = BK / 32;                // 32-byte sub-steps (one MFMA deep) per step
     static_assert(WM * WN == 4, "four waves per workgroup");
-    static_assert(BM % 16 == 0 && BN % 16 == 0, "tiles are made of 16-row chunks");
+    static_assert(BM % kRowsPerChunk == 0 && BN % kRowsPerChunk == 0, "tiles are made of whole chunks");
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_CH = BM / 16, B_CH = BN / 16;                       // 1-KiB chunks (16 rows x 64 bytes) per K step
+    constexpr int A_CH = BM / kRowsPerChunk, B_CH = BN / kRowsPerChunk; // 1-KiB chunks per K step
     constexpr int A_IT = (A_CH + 3) / 4, B_IT = (B_CH + 3) / 4;         // chunks per wave
     constexpr int STAGE = (BM + BN) * kBK;
-    constexpr int NST = stages_for(BM, BN);
+    constexpr int NST = stages_for(BM, BN, BK);
     constexpr int NLD = A_IT + B_IT;                                    // loads per wave and K step
     static_assert((NST - 2) * NLD < 64, "outstanding loads must fit the wait counter");
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [NST][BM + BN][64]
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];       // [NST][BM + BN][BK]
 
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int tile = xcd * tiles_per_xcd + local;
@@ -85,11 +96,11 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
 
     // Operands go from global memory straight into LDS (buffer loads with the
     // LDS modifier): one such instruction of a wave fills 1 KiB, lane l writing
-    // bytes [16 l, 16 l + 16) of it, i.e. unit l % 4 of row l / 4 of a 16-row
-    // chunk with 64-byte rows.  Which 16 bytes of K a lane fetches for that
-    // slot is free, so the K units of row r are stored rotated by
-    // (r / 4) % 4 (exclusive-or): the 128-bit operand reads of 16 consecutive
-    // rows then fall on 16 distinct bank groups.  A lane whose row or K offset
+    // bytes [16 l, 16 l + 16) of it, i.e. unit l % UPR of row l / UPR of a chunk
+    // of 64 / UPR rows (UPR = BK / 16 units per row).  Which 16 bytes of K a
+    // lane fetches for that slot is free, so the K units of row r are stored
+    // rotated by (r / (16 / UPR)) % UPR (exclusive-or): the 128-bit operand
+    // reads of 16 consecutive rows then fall on 16 distinct bank groups.  A lane whose row or K offset
     // is out of range is given an offset beyond the buffer and writes zeros.
     constexpr uint32_t kOob = 0x80000000u;
     auto descriptor = [](const void *p, int64_t bytes) {             // raw buffer: base, no stride, extent, dword format
@@ -103,14 +114,17 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     };
     const v4i rsrc_a = descriptor(g.a, g.a_bytes), rsrc_w = descriptor(g.w, g.w_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte *)lds;      // LDS address of the stage array
-    const int rloc = lane >> 2;                                  // row within the chunk
-    const int unit = (lane & 3) ^ ((lane >> 4) & 3);             // K unit this lane fetches
+    const int rloc = lane / UPR;                                 // row within the chunk
+    // K unit this lane fetches: slot ^ ((row / SWR) % UPR) with row = chunk * (64 / UPR) + rloc and
+    // chunk = wave + 4 * it; the chunk's share of that is (chunk * 4) % UPR = (wave % 2) * 4 % UPR
+    const int unit = (lane % UPR) ^ (((wave_u & 1) * 4 + rloc / SWR) % UPR);
+    static_assert(A_CH % 2 == 0 && B_CH % 2 == 0, "a wave's chunks must keep their parity");
     uint32_t a_base[A_IT];               // byte offset of the row (linear) or of the centre pixel (conv)
     bool a_ok[A_IT];
     int a_oh[A_IT], a_ow[A_IT];
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-        const int r = ((wave_u + it * 4) % A_CH) * 16 + rloc;
+        const int r = ((wave_u + it * 4) % A_CH) * kRowsPerChunk + rloc;
         const int64_t m = m0 + r;
         a_ok[it] = m < g.M;
         a_base[it] = a_ok[it] ? (uint32_t)(m * (CONV ? (int64_t)g.cp : g.lda)) : 0u;
@@ -123,7 +137,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     bool b_ok[B_IT];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
-        const int r = ((wave_u + it * 4) % B_CH) * 16 + rloc;
+        const int r = ((wave_u + it * 4) % B_CH) * kRowsPerChunk + rloc;
         b_ok[it] = n0 + r < g.N;
         b_base[it] = b_ok[it] ? (uint32_t)(n0 + r) * (uint32_t)g.kp : 0u;
     }
@@ -172,9 +186,9 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
 #pragma unroll
         for (int idx = 0; idx < A_IT + B_IT; ++idx) fetch_one(sa, stage, idx);
     };
-    // operand fragments of one 32-byte K half-step: lane l supplies row l % 32, K unit 2 ks + l / 32
+    // operand fragments of one 32-byte K sub-step ks: lane l supplies row l % 32, K unit 2 ks + l / 32
     const int frow = lane & 31;
-    const int fsw = (frow >> 2) & 3;
+    const int fsw = (frow / SWR) % UPR;
     auto read_frags = [&](int stage, int ks, v4i (&fa)[TM], v4i (&fb)[TN]) {
         const uint8_t *sA = lds + stage * STAGE, *sB = sA + BM * kBK;
         const int koff = ((ks * 2 + (lane >> 5)) ^ fsw) * 16;
@@ -205,9 +219,10 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     // matrix cores work on stage kt % NST, K steps kt + 1 .. kt + NST - 2 are
     // landing in the following stages and K step kt + NST - 1 is requested into
     // the stage that step kt - 1 read (every wave has passed the barrier that
-    // ended that step).  One barrier per step.
-    constexpr int NMF = TM * TN;                 // MFMAs per half step
-    constexpr int NRD = TM + TN;                 // LDS operand reads per half step
+    // ended that step).  One barrier per step; a step is two or four 32-byte
+    // sub-steps whose operand fragments are double-buffered in registers.
+    constexpr int NMF = TM * TN;                 // MFMAs per sub-step
+    constexpr int NRD = TM + TN;                 // LDS operand reads per sub-step
     constexpr int kWaitNext = 0x0f70 | (((NST - 2) * NLD) & 0xf) | ((((NST - 2) * NLD) >> 4) << 14);   // vmcnt only
     const int nk = (g.kp + kBK - 1) / kBK;
     v4i fa0[TM], fb0[TN], fa1[TM], fb1[TN];
@@ -216,6 +231,13 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     __builtin_amdgcn_s_waitcnt(kWaitNext);       // K step 0 landed
     __syncthreads();
     read_frags(0, 0, fa0, fb0);
+    auto hint = [&]() {                           // one LDS read after each of the first MFMAs
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
     int st = 0;                                  // stage of K step kt
     for (int kt = 0; kt < nk; ++kt) {            // past the end of K the loads return zeros
         const int st1 = st == NST - 1 ? 0 : st + 1, stl = st == 0 ? NST - 1 : st - 1;
@@ -234,15 +256,19 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                     if ((i * TN + j) * per + q < NLD) fetch_one(sa, stl, (i * TN + j) * per + q);
                 if ((i * TN + j) * per < NLD) __builtin_amdgcn_sched_barrier(0);   // keep the MFMA before its requests
             }
+        if (NSUB == 4) {
+            read_frags(st, 2, fa0, fb0);
+            mfma_all(fa1, fb1);
+            hint();
+            read_frags(st, 3, fa1, fb1);
+            mfma_all(fa0, fb0);
+            hint();
+        }
         __builtin_amdgcn_s_waitcnt(kWaitNext);   // K step kt + 1 landed
         __syncthreads();
         read_frags(st1, 0, fa0, fb0);
         mfma_all(fa1, fb1);
-#pragma unroll
-        for (int i = 0; i < NMF; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < NRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
+        hint();
         st = st1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the zero-filled K steps past the end
@@ -316,7 +342,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK>
 static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
 {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
@@ -324,27 +350,27 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     if (tiles > 0x3fffffffLL) return hipErrorInvalidValue;
     const int tpx = (int)((tiles + 7) / 8);
     const dim3 grid((unsigned)(tpx * 8)), block(256);
-    constexpr size_t smem = (size_t)stages_for(BM, BN) * (BM + BN) * kBK;
+    constexpr size_t smem = (size_t)stages_for(BM, BN, BK) * (BM + BN) * BK;
     hipError_t e;
     if (g.conv3x3) {
         static bool set = false;
         if (!set) {
-            e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, true>,
+            e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, true, BK>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
             set = true;
         }
-        return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true>, grid, block, smem, st, g, (int)tiles,
+        return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true, BK>, grid, block, smem, st, g, (int)tiles,
                         tpx);
     }
     static bool set = false;
     if (!set) {
-        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false>,
+        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         set = true;
     }
-    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false>, grid, block, smem, st, g, (int)tiles,
+    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK>, grid, block, smem, st, g, (int)tiles,
                     tpx);
 }
 
@@ -404,6 +430,37 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     }
 }
 
+// The tile shapes on offer: rows x columns of the output tile, K bytes per
+// step, workgroups of that shape that fit a CU together (registers and LDS),
+// and the relative cost of a unit of tile area (smaller tiles move more LDS
+// and L1 bytes per MFMA).
+struct TileShape {
+    int bm, bn, bk, resident;
+    double penalty;
+};
+constexpr int kNumShapes = 9;
+static const TileShape kShapes[kNumShapes] = {
+    {256, 256, 128, 1, 1.00}, {256, 192, 128, 1, 1.03}, {256, 128, 64, 2, 1.06}, {128, 192, 64, 2, 1.10},
+    {128, 128, 64, 3, 1.20},  {128, 128, 128, 2, 1.22}, {128, 64, 64, 4, 1.40},  {128, 64, 128, 3, 1.38},
+    {256, 128, 128, 1, 1.05},
+};
+
+static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
+{
+    switch (i) {
+    case 0: return launch_variant<256, 256, 2, 2, 128>(g, st);
+    case 1: return launch_variant<256, 192, 2, 2, 128>(g, st);
+    case 2: return launch_variant<256, 128, 2, 2, 64>(g, st);
+    case 3: return launch_variant<128, 192, 2, 2, 64>(g, st);
+    case 4: return launch_variant<128, 128, 2, 2, 64>(g, st);
+    case 5: return launch_variant<128, 128, 2, 2, 128>(g, st);
+    case 6: return launch_variant<128, 64, 2, 2, 64>(g, st);
+    case 7: return launch_variant<128, 64, 2, 2, 128>(g, st);
+    case 8: return launch_variant<256, 128, 2, 2, 128>(g, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 // Tile choice.  A tile shape is priced by the work the chip does for it,
 // padding included: workgroups run in rounds of 256 CUs x (workgroups resident
 // per CU), a partly filled last round costs as much as a full one, and the
@@ -420,14 +477,11 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         return launch_k(EGERIA_KERNEL_GEMM, conv3x3_c16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g);
     }
-    if (g.N <= 32) return launch_variant<128, 32, 4, 1>(g, st);
-    struct Shape { int bm, bn, resident; double penalty; };
-    static const Shape shapes[6] = {{256, 256, 1, 1.00}, {256, 192, 1, 1.03}, {256, 128, 2, 1.06},
-                                    {128, 192, 2, 1.10}, {128, 128, 3, 1.20}, {128, 64, 4, 1.40}};
-    int best = 4;
+    if (g.N <= 32) return launch_variant<128, 32, 4, 1, 64>(g, st);
+    int best = 0;
     double best_cost = 0.0;
-    for (int i = 0; i < 6; ++i) {
-        const Shape &sh = shapes[i];
+    for (int i = 0; i < kNumShapes; ++i) {
+        const TileShape &sh = kShapes[i];
         if (sh.resident == 1 && g.kp < 2048) continue;
         if (sh.bm * sh.bn > 128 * 128 && g.kp < 512) continue;     // store bound: many small workgroups in flight
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
@@ -439,14 +493,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
             best = i;
         }
     }
-    switch (best) {
-    case 0: return launch_variant<256, 256, 2, 2>(g, st);
-    case 1: return launch_variant<256, 192, 2, 2>(g, st);
-    case 2: return launch_variant<256, 128, 2, 2>(g, st);
-    case 3: return launch_variant<128, 192, 2, 2>(g, st);
-    case 5: return launch_variant<128, 64, 2, 2>(g, st);
-    default: return launch_variant<128, 128, 2, 2>(g, st);
-    }
+    return launch_shape(best, g, st);
 }
 
 }  // namespace egeria
