@@ -74,7 +74,36 @@ def algorithmic_work(wl, cls, eg):
     return out
 
 
-def roofline_for(wl, cls, durations_ms, eg, steps):
+KERNEL_SOURCES = {"gram_partial_kernel": "gram.hip", "gemm_i8_kernel": "gemm_i8.hip", "conv3x3_c16_kernel": "gemm_i8.hip",
+                  "attention_kernel": "bert.hip"}
+
+
+def source_digest(kernel):
+    """Digest of the sources a kernel is built from: counters taken before a change do not describe it."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2201_06227_amd", "csrc")
+    for name in (KERNEL_SOURCES[kernel], "common.hpp"):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(cfg, kernel):
+    """HBM bytes per launch from profiles/hbm_traffic.txt (written by bench_traffic.py from two
+    rocprofv3 --pmc runs), or None if there is no entry or the kernel has changed since."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 6 and f[0] == f"cfg{cfg}" and f[1] == kernel and f[5] == source_digest(kernel):
+            return {"fetch_bytes": float(f[2]), "write_bytes": float(f[3]), "bytes": float(f[2]) + float(f[3]),
+                    "launches_averaged": int(f[4])}
+    return None
+
+
+def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None):
     """Achieved rate of one kernel class over the timed region against the
     roofline that bounds it."""
     work = algorithmic_work(wl, cls, eg)
@@ -106,7 +135,7 @@ def roofline_for(wl, cls, durations_ms, eg, steps):
         achieved, peak, unit, bound = byts / total_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
     return {
         "kernel": names[cls], "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-        "frac": round(achieved / peak, 4), "traffic": None,
+        "frac": round(achieved / peak, 4), "traffic": measured_traffic(cfg, names[cls]) if cfg else None,
         "launches_per_step": per_step, "avg_launch_us": round(total_s / (n_steps * per_step) * 1e6, 3),
         "algorithmic_ops_per_step": sum(w[0] for w in work), "algorithmic_bytes_per_step": sum(w[1] for w in work),
         "intensity_op_per_byte": round(intensity, 2), "ridge_op_per_byte": round(ridge, 2),
@@ -231,6 +260,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="after the run, launch a scaled copy of known size (64 MiB int8 -> 256 MiB fp32) three times: "
+                         "the reference that bench_traffic.py scales the HBM counters of a rocprofv3 --pmc run by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU leg (run with --gpus 1)", file=sys.stderr)
@@ -270,7 +302,7 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
     durations = eg.profile_end(args.steps * per_step)
-    roof = roofline_for(wl, cls, durations, eg, args.steps)
+    roof = roofline_for(wl, cls, durations, eg, args.steps, args.workload)
     eager_p = ev.p_out.clone()
     if eg.check(ev.ws) != eg.OK or not bool(torch.isfinite(eager_p).all().item()):
         print("non-finite values in the benchmark run", file=sys.stderr)
@@ -299,7 +331,7 @@ def main():
         for _ in range(20):
             ev.step(x, a_t)
         torch.cuda.synchronize()
-        others_roof[name] = roofline_for(wl, c, eg.profile_end(n), eg, 20)
+        others_roof[name] = roofline_for(wl, c, eg.profile_end(n), eg, 20, args.workload)
     result["roofline_other_kernels"] = others_roof
     result["graph"] = graph_replay(ev, x, a_t, args.steps, eager_p)
 
@@ -319,7 +351,7 @@ def main():
             for _ in range(3):
                 ev2.step(x2, a2)
             torch.cuda.synchronize()
-            roof2 = roofline_for(wl2, timed_classes[dom], eg.profile_end(4096), eg, 3)
+            roof2 = roofline_for(wl2, timed_classes[dom], eg.profile_end(4096), eg, 3, cfg)
             gr = graph_replay(ev2, x2, a2, k, ev2.p_out.clone())
             others[f"cfg{cfg}"] = {"workload": WORKLOAD_NAMES[cfg], "evals_per_s": round(ev2.n_layers / dt2, 2),
                                    "ms_per_step": round(dt2 * 1e3, 4), "steps": k, "graph": gr,
@@ -328,6 +360,14 @@ def main():
             torch.cuda.empty_cache()
         result["other_workloads"] = others
 
+    if args.calibrate:
+        n = 64 << 20
+        q = torch.zeros(n, dtype=torch.int8, device=device)
+        sc = torch.ones(1, dtype=torch.float32, device=device)
+        for _ in range(3):
+            out = eg.dequantize(q, sc)
+        torch.cuda.synchronize()
+        del q, out
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(result))

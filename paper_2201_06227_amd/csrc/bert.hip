@@ -164,7 +164,8 @@ template <int QB>
 __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict__ qkv, int B, int S,
                                                         int Hd, int heads, int dh, double scale,
                                                         float *__restrict__ ctx,
-                                                        uint32_t *__restrict__ absmax_out)
+                                                        uint32_t *__restrict__ absmax_out, int total,
+                                                        int per_xcd)
 {
     __shared__ __attribute__((aligned(16))) float sKb[2][kKeyTile][kKVPad];   // two stages
     __shared__ __attribute__((aligned(16))) float sVb[2][kKeyTile][kKVPad];
@@ -172,7 +173,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
     const int c = lane & 15, g = lane >> 4;
     constexpr int QT = 64 * QB;          // queries per workgroup
     const int qtiles = (S + QT - 1) / QT;
-    const int bh = blockIdx.x / qtiles, qt = blockIdx.x % qtiles;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; each XCD is given a
+    // contiguous range of (batch, head, query tile) so that the query tiles of
+    // one head, which re-read the same K and V, share an L2.
+    const int vid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || vid >= total) return;
+    const int bh = vid / qtiles, qt = vid % qtiles;
     const int bi = bh / heads, hd = bh % heads;
     const int64_t tok0 = (int64_t)bi * S;
     const int64_t ld = 3 * (int64_t)Hd;
@@ -355,9 +361,10 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
     const int qtiles = (S + 64 * QB - 1) / (64 * QB);
     const int64_t grid = (int64_t)B * heads * qtiles;
     if (grid <= 0) return hipSuccess;
-    if (dh > kDh || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    return launch_k(EGERIA_KERNEL_ATTENTION, attention_kernel<QB>, dim3((unsigned)grid), dim3(256), 0, st, qkv, (int)B,
-                    (int)S, (int)Hd, (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out);
+    if (dh > kDh || grid > 0x7ffffff0LL) return hipErrorInvalidValue;
+    const int per_xcd = (int)((grid + 7) / 8);
+    return launch_k(EGERIA_KERNEL_ATTENTION, attention_kernel<QB>, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, qkv,
+                    (int)B, (int)S, (int)Hd, (int)heads, dh, 1.0 / sqrt((double)dh), ctx, absmax_out, (int)grid, per_xcd);
 }
 
 }  // namespace egeria
