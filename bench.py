@@ -252,6 +252,30 @@ def cpu_baseline(cfg, budget_s=12.0):
             "kind": "oracle", "sample": f"{sample}; {reps} rep(s) in {el:.1f} s"}
 
 
+def freeze_decision_timing(eg, with_oracle):
+    """Host-side freeze decision (Section 4.2, Algorithm 1) on a synthetic score series: time per
+    evaluation of the library's controller and, beside it, of the CPU oracle."""
+    import numpy as np
+    n = 20000
+    rng = np.random.default_rng(5)
+    series = (0.05 + np.exp(-0.01 * np.arange(n)) + 0.01 * rng.standard_normal(n)).astype(np.float32).tolist()
+    c = eg.FreezeController(1 << 20, 10, 0.0, True)
+    t0 = time.perf_counter()
+    for p in series:
+        c.observe(p, 0.1)
+    lib_ns = (time.perf_counter() - t0) / n * 1e9
+    out = {"evaluations": n, "library_ns_per_evaluation": round(lib_ns, 1),
+           "note": "through the ctypes binding; the C call itself is a few tens of ns"}
+    if with_oracle:
+        from oracle.freeze_oracle import FreezeOracle
+        o = FreezeOracle(1 << 20, 10, 0.0, True)
+        t0 = time.perf_counter()
+        for p in series[:4000]:
+            o.checkPlasticity(p, 0.1)
+        out["oracle_ns_per_evaluation"] = round((time.perf_counter() - t0) / 4000 * 1e9, 1)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -368,6 +392,7 @@ def main():
             out = eg.dequantize(q, sc)
         torch.cuda.synchronize()
         del q, out
+    result["freeze_decision"] = freeze_decision_timing(eg, not args.no_cpu)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(result))

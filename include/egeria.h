@@ -237,6 +237,56 @@ egeria_status egeria_check(void *ws, void *stream);
 
 const char *egeria_status_string(egeria_status s);
 
+/* ---- Freeze decision (Section 4.2 "How to Decide Layer Freezing", Eq. 2, Algorithm 1) ----
+ * Host-only: consumes the stream of plasticity scores of the frontmost active
+ * layer module and says when to freeze it and when to unfreeze everything.
+ * Nothing here touches the GPU.
+ *
+ * Per evaluation (egeria_freeze_observe), in the algorithm's order:
+ *   1. If the front module is the last one, nothing is decided.
+ *   2. If fewer than W consecutive stale evaluations have been counted: the score
+ *      is smoothed (Eq. 2, read as the mean of the last min(W, count) scores),
+ *      appended to the module's history, the least-squares slope s of the last
+ *      min(max(W, 2), length) smoothed values against 0, 1, 2, ... is taken (no
+ *      slope from a single value: the counter is reset), and the counter is incremented if
+ *      |s| < T, else reset.  With T <= 0 at init, T is 20 % of the largest |s|
+ *      among the module's first three slopes and nothing is counted before.
+ *      Otherwise the module is frozen: action FREEZE, the next module becomes
+ *      the front with empty history (the score passed in is ignored).
+ *   3. With lr_annealing set: once lr <= 0.1 * lr_ref * (1 + 1e-12), lr_ref being
+ *      the rate passed in when the first module was frozen, every module is
+ *      unfrozen, the first becomes the front again and W is halved (integer
+ *      division, at least 1): action UNFREEZE_ALL.
+ * All arithmetic is fp64.  W must be in [1, EGERIA_FREEZE_MAX_W]. */
+#define EGERIA_FREEZE_MAX_W 256
+
+typedef enum { EGERIA_FREEZE_NONE = 0, EGERIA_FREEZE_FREEZE = 1, EGERIA_FREEZE_UNFREEZE_ALL = 2 } egeria_freeze_action;
+
+/* HOST struct, owned by the caller, initialised by egeria_freeze_init; its
+ * fields are the controller's whole state (no hidden allocation). */
+typedef struct {
+    int32_t n_modules, front, W, stale, lr_annealing, has_lr_ref, n_first_slopes, has_T;
+    int64_t n_raw, n_smooth;                 /* values seen for the front module */
+    double T_user, T, max_first_slope, lr_ref;
+    double raw[EGERIA_FREEZE_MAX_W];         /* ring: last W scores */
+    double smooth[EGERIA_FREEZE_MAX_W];      /* ring: last W smoothed scores */
+} egeria_freeze_state;
+
+/* HOST struct.  What one evaluation decided.  smoothed / slope are NaN when the
+ * evaluation produced none (freeze call, last module, first value). */
+typedef struct {
+    int32_t action;                          /* egeria_freeze_action */
+    int32_t front;                           /* frontmost active module after this evaluation */
+    int32_t stale;                           /* consecutive stale evaluations counted so far */
+    int32_t W;                               /* current window / counter length */
+    double smoothed, slope, T;               /* T is NaN until known */
+} egeria_freeze_decision;
+
+egeria_status egeria_freeze_init(egeria_freeze_state *st, int32_t n_modules, int32_t W, double T,
+                                 int32_t lr_annealing);
+egeria_status egeria_freeze_observe(egeria_freeze_state *st, double p, double lr,
+                                    egeria_freeze_decision *out);
+
 /* Instrumentation for benchmarks (not part of the method): time every launch
  * of one kernel class with a pair of HIP events recorded on the launch's own
  * stream, so that a caller can time that kernel inside a larger timed region.

@@ -58,6 +58,23 @@ class Weight(ctypes.Structure):
                 ("w_q", _vp), ("scale", _vp)]
 
 
+FREEZE_MAX_W = 256
+FREEZE_NONE, FREEZE_FREEZE, FREEZE_UNFREEZE_ALL = range(3)
+
+
+class FreezeState(ctypes.Structure):
+    _fields_ = [("n_modules", _i32), ("front", _i32), ("W", _i32), ("stale", _i32), ("lr_annealing", _i32),
+                ("has_lr_ref", _i32), ("n_first_slopes", _i32), ("has_T", _i32), ("n_raw", _i64), ("n_smooth", _i64),
+                ("T_user", ctypes.c_double), ("T", ctypes.c_double), ("max_first_slope", ctypes.c_double),
+                ("lr_ref", ctypes.c_double), ("raw", ctypes.c_double * FREEZE_MAX_W),
+                ("smooth", ctypes.c_double * FREEZE_MAX_W)]
+
+
+class FreezeDecision(ctypes.Structure):
+    _fields_ = [("action", _i32), ("front", _i32), ("stale", _i32), ("W", _i32), ("smoothed", ctypes.c_double),
+                ("slope", ctypes.c_double), ("T", ctypes.c_double)]
+
+
 class EgeriaError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -72,6 +89,7 @@ EXPORTS = [
     "egeria_plasticity", "egeria_plasticity_workspace_bytes", "egeria_plasticity_eval",
     "egeria_workspace_bytes", "egeria_check", "egeria_status_string", "egeria_profile_begin",
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
+    "egeria_freeze_init", "egeria_freeze_observe",
 ]
 
 KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM = range(7)
@@ -125,6 +143,11 @@ def lib():
     L.egeria_profile_begin.argtypes = [_i32, _i32]
     L.egeria_profile_end.restype = ctypes.c_int
     L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
+    L.egeria_freeze_init.restype = ctypes.c_int
+    L.egeria_freeze_init.argtypes = [ctypes.POINTER(FreezeState), _i32, _i32, ctypes.c_double, _i32]
+    L.egeria_freeze_observe.restype = ctypes.c_int
+    L.egeria_freeze_observe.argtypes = [ctypes.POINTER(FreezeState), ctypes.c_double, ctypes.c_double,
+                                        ctypes.POINTER(FreezeDecision)]
     L.egeria_status_string.restype = ctypes.c_char_p
     L.egeria_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -378,6 +401,21 @@ def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torc
 def check(ws: torch.Tensor) -> int:
     """egeria_check: status code (OK or ERR_NONFINITE); synchronises the stream."""
     return int(lib().egeria_check(_ptr(ws), _stream()))
+
+
+class FreezeController:
+    """egeria_freeze_init / egeria_freeze_observe on a state struct owned here."""
+
+    def __init__(self, n_modules: int, W: int, T: float = 0.0, lr_annealing: bool = True):
+        self.state = FreezeState()
+        _check(lib().egeria_freeze_init(ctypes.byref(self.state), n_modules, W, float(T), 1 if lr_annealing else 0),
+               "egeria_freeze_init")
+
+    def observe(self, p: float, lr: float) -> FreezeDecision:
+        d = FreezeDecision()
+        _check(lib().egeria_freeze_observe(ctypes.byref(self.state), float(p), float(lr), ctypes.byref(d)),
+               "egeria_freeze_observe")
+        return d
 
 
 def profile_begin(kernel_class: int, max_launches: int) -> None:
