@@ -2,12 +2,12 @@
 """Turns two `rocprofv3 --pmc` runs of bench.py into HBM bytes per kernel launch.
 
     cd /tmp && export TMPDIR=/tmp && cd <repo>
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o f -- \\
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d out/pmc_fetch -o f -- \\
         python3 bench.py --workload N --no-others --no-cpu --steps 20 --warmup 3 --calibrate
-    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o w -- \\
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d out/pmc_write -o w -- \\
         python3 bench.py --workload N --no-others --no-cpu --steps 20 --warmup 3 --calibrate
-    python3 bench_traffic.py --workload N --fetch gpurun_out/pmc_fetch/f_counter_collection.csv \\
-        --write gpurun_out/pmc_write/w_counter_collection.csv
+    python3 bench_traffic.py --workload N --fetch out/pmc_fetch/f_counter_collection.csv \\
+        --write out/pmc_write/w_counter_collection.csv
 
 FETCH_SIZE and WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by
 what the same counter reads for bench.py's calibration launches, a scaled
