@@ -157,6 +157,49 @@ def setup(cfg, device):
     return wl, ev, x, a_t
 
 
+def calibration_scales(wl, device):
+    """Static activation scales for the FC / convolution workloads: absmax / 127 of every layer input of
+    the fp32 model on this mini-batch (stock framework operators; an input of the path, not part of it)."""
+    import torch
+    import torch.nn.functional as F
+    import synth_inputs as si
+    dev = torch.device(device)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    x = t(wl.x)
+    W = [t(w) for w in wl.weights]
+    B = [None if b is None else t(b) for b in wl.biases]
+    pts = [x]
+    with torch.no_grad():
+        if wl.kind == si.KIND_BASIC_BLOCK:
+            pts.append(torch.relu(F.conv2d(x, W[0], B[0], padding=1)))
+        elif wl.kind == si.KIND_BOTTLENECK:
+            h = torch.relu(F.conv2d(x, W[0], B[0]))
+            pts.append(h)
+            pts.append(torch.relu(F.conv2d(h, W[1], B[1], padding=1)))
+    return torch.stack([p.abs().max() / 127.0 for p in pts]).to(torch.float32).contiguous()
+
+
+def static_mode(cfg, device, steps):
+    """The same workload with static activation scales (Section 5 of the paper: static quantisation
+    for convolutional networks): no maximum passes, intermediate layers write int8 directly."""
+    import torch
+    import synth_inputs as si
+    from paper_2201_06227_amd.evaluator import PlasticityEvaluator
+    wl = si.make_config(cfg)
+    if wl.kind not in (si.KIND_FC_RELU, si.KIND_BASIC_BLOCK, si.KIND_BOTTLENECK):
+        return None
+    dev = torch.device(device)
+    W = [torch.from_numpy(w).to(dev) for w in wl.weights]
+    B = [None if b is None else torch.from_numpy(b).to(dev) for b in wl.biases]
+    x = torch.from_numpy(wl.x).to(dev)
+    a_t = [t.contiguous() for t in si.train_forward(wl, device=device)]
+    ev = PlasticityEvaluator(wl.kind, wl.dims, W, B, device=device, act_scales=calibration_scales(wl, device))
+    dt = time_steps(ev, x, a_t, steps, 10)
+    return {"evals_per_s": round(ev.n_layers / dt, 2), "ms_per_step": round(dt * 1e3, 4), "steps": steps,
+            "plasticity": [float(v) for v in ev.p_out.tolist()],
+            "scales": "absmax / 127 of each layer input of the fp32 model on the same mini-batch"}
+
+
 def time_steps(ev, x, a_t, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -392,6 +435,7 @@ def main():
             out = eg.dequantize(q, sc)
         torch.cuda.synchronize()
         del q, out
+    result["static_scale_mode"] = static_mode(args.workload, device, args.steps)
     result["freeze_decision"] = freeze_decision_timing(eg, not args.no_cpu)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.workload)

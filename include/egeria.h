@@ -113,6 +113,16 @@ typedef struct {
     const egeria_qlinear *linear;   /* HOST array */
     int32_t n_norm;
     const egeria_norm *norm;        /* HOST array or NULL */
+    /* NULL: every activation is quantised with a dynamic scale (absolute maximum
+     * of the tensor at run time).  Else a DEVICE array of n_linear fp32: the
+     * static scale of the input of linear[i] (Section 5: static quantisation for
+     * convolutional networks; values beyond 127 * scale saturate).  Scales must
+     * be positive and finite.  FC and convolution kinds only; with the BERT kinds
+     * (dynamic quantisation, Section 5) it is EGERIA_ERR_UNSUPPORTED.  In this
+     * mode a layer that feeds another one writes that layer's int8 input
+     * directly, without a fp32 round trip, and non-finite values are not
+     * detected. */
+    const float *act_scale;
 } egeria_qweights;
 
 /* HOST struct.  Optional observation points of the reference forward, used by

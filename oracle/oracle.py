@@ -185,12 +185,12 @@ def quantize_weights(weights):
     return [quantize(w) for w in weights]
 
 
-def linear_int8(x, wq, sw, bias, act=ACT_NONE, taps=None, tag=""):
-    """Dynamically quantised linear layer: quantise the fp32 input per tensor,
-    integer GEMM, dequantising epilogue."""
+def linear_int8(x, wq, sw, bias, act=ACT_NONE, taps=None, tag="", act_scale=None):
+    """Quantised linear layer: quantise the fp32 input per tensor (dynamic scale,
+    or the static scale `act_scale`), integer GEMM, dequantising epilogue."""
     shp = x.shape
     x2 = x.reshape(-1, shp[-1])
-    xq, sx = quantize(x2)
+    xq, sx = quantize(x2, act_scale)
     acc = gemm_i8(xq, wq)
     y = dequant_bias_act(acc, sx, sw, bias, act)
     if taps is not None:
@@ -198,10 +198,10 @@ def linear_int8(x, wq, sw, bias, act=ACT_NONE, taps=None, tag=""):
     return y.reshape(shp[:-1] + (wq.shape[0],))
 
 
-def fc_relu(x, qw, biases):
+def fc_relu(x, qw, biases, act_scales=None):
     taps = {}
     (wq, sw), = qw
-    y = linear_int8(x, wq, sw, biases[0], ACT_RELU, taps, "l0.")
+    y = linear_int8(x, wq, sw, biases[0], ACT_RELU, taps, "l0.", None if act_scales is None else act_scales[0])
     taps["a_ref"] = y
     return taps
 
@@ -213,27 +213,32 @@ def _conv_int8(xq, sx, wq, sw, bias, pad, act, residual, taps, tag):
     return y
 
 
-def basic_block(x, qw, biases, has_residual=True):
-    """conv3x3 -> ReLU -> conv3x3 (+ dequantised input) -> ReLU, all NCHW."""
+def basic_block(x, qw, biases, has_residual=True, act_scales=None):
+    """conv3x3 -> ReLU -> conv3x3 (+ dequantised input) -> ReLU, all NCHW.
+    act_scales: static scales of the two quantise points (Section 5: static
+    quantisation for convolutional networks), or None for dynamic ones."""
     taps = {}
-    xq, sx = quantize(x)
+    st = [None, None] if act_scales is None else act_scales
+    xq, sx = quantize(x, st[0])
     xhat = dequantize(xq, sx) if has_residual else None
     h = _conv_int8(xq, sx, qw[0][0], qw[0][1], biases[0], 1, ACT_RELU, None, taps, "l0.")
-    hq, sh = quantize(h)
+    hq, sh = quantize(h, st[1])
     y = _conv_int8(hq, sh, qw[1][0], qw[1][1], biases[1], 1, ACT_RELU, xhat, taps, "l1.")
     taps["a_ref"] = y
     return taps
 
 
-def bottleneck(x, qw, biases, has_residual=True):
-    """conv1x1 -> ReLU -> conv3x3 -> ReLU -> conv1x1 (+ dequantised input) -> ReLU."""
+def bottleneck(x, qw, biases, has_residual=True, act_scales=None):
+    """conv1x1 -> ReLU -> conv3x3 -> ReLU -> conv1x1 (+ dequantised input) -> ReLU.
+    act_scales: static scales of the three quantise points, or None."""
     taps = {}
-    xq, sx = quantize(x)
+    st = [None, None, None] if act_scales is None else act_scales
+    xq, sx = quantize(x, st[0])
     xhat = dequantize(xq, sx) if has_residual else None
     h1 = _conv_int8(xq, sx, qw[0][0], qw[0][1], biases[0], 0, ACT_RELU, None, taps, "l0.")
-    h1q, s1 = quantize(h1)
+    h1q, s1 = quantize(h1, st[1])
     h2 = _conv_int8(h1q, s1, qw[1][0], qw[1][1], biases[1], 1, ACT_RELU, None, taps, "l1.")
-    h2q, s2 = quantize(h2)
+    h2q, s2 = quantize(h2, st[2])
     y = _conv_int8(h2q, s2, qw[2][0], qw[2][1], biases[2], 0, ACT_RELU, xhat, taps, "l2.")
     taps["a_ref"] = y
     return taps
@@ -271,17 +276,21 @@ def bert_stack(x, qw, biases, heads, n_layers, ln_eps=1e-12, keep_taps=True, pro
     return taps
 
 
-def ref_forward(wl, qw=None, keep_taps=True, progress=None):
-    """Reference forward of a synthetic workload (see synth_inputs.Workload)."""
+def ref_forward(wl, qw=None, keep_taps=True, progress=None, act_scales=None):
+    """Reference forward of a synthetic workload (see synth_inputs.Workload).
+    act_scales: static activation scales, one per quantise point (FC and conv
+    kinds only; the Transformer kinds are dynamically quantised, Section 5)."""
     if qw is None:
         qw = quantize_weights(wl.weights)
     k = wl.kind
     if k == 0:
-        return fc_relu(wl.x, qw, wl.biases)
+        return fc_relu(wl.x, qw, wl.biases, act_scales)
     if k == 1:
-        return basic_block(wl.x, qw, wl.biases, bool(wl.dims["has_residual"]))
+        return basic_block(wl.x, qw, wl.biases, bool(wl.dims["has_residual"]), act_scales)
     if k == 2:
-        return bottleneck(wl.x, qw, wl.biases, bool(wl.dims["has_residual"]))
+        return bottleneck(wl.x, qw, wl.biases, bool(wl.dims["has_residual"]), act_scales)
+    if act_scales is not None:
+        raise ValueError("static activation scales are for the FC and convolution kinds")
     d = wl.dims
     if k == 3:
         out, taps = bert_layer(wl.x, qw, wl.biases, d["heads"], d["ln_eps"], {}, "L0.")

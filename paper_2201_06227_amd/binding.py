@@ -42,7 +42,7 @@ class Norm(ctypes.Structure):
 
 class QWeights(ctypes.Structure):
     _fields_ = [("n_linear", _i32), ("linear", ctypes.POINTER(QLinear)), ("n_norm", _i32),
-                ("norm", ctypes.POINTER(Norm))]
+                ("norm", ctypes.POINTER(Norm)), ("act_scale", _vp)]
 
 
 class Tap(ctypes.Structure):
@@ -307,7 +307,8 @@ class ReferenceModel:
 
 
 def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
-                   biases: Sequence[Optional[torch.Tensor]]) -> ReferenceModel:
+                   biases: Sequence[Optional[torch.Tensor]],
+                   act_scales: Optional[torch.Tensor] = None) -> ReferenceModel:
     """Reference-model generation: quantise every weight tensor of the snapshot
     with the library (egeria_quantize_rows for [out, in], egeria_quantize_nchw for
     [out, in, kh, kw]) and marshal the result."""
@@ -327,7 +328,8 @@ def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
     qw.linear = arr
     qw.n_norm = 0
     qw.norm = None
-    return ReferenceModel(make_desc(kind, dims), qw, w_q, scales, list(biases), (arr,))
+    qw.act_scale = None if act_scales is None else _dev(act_scales).data_ptr()   # fp32 [n_linear], static scales
+    return ReferenceModel(make_desc(kind, dims), qw, w_q, scales, list(biases), (arr, act_scales))
 
 
 def workspace_bytes(desc: BlockDesc) -> int:

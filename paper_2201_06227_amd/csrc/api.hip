@@ -130,6 +130,11 @@ struct Fwd {
     int stride_amax(int i) const { return i == 0 ? 1 : kAmaxStride; }
     uint32_t *slot(int i) const { return ws_absmax(ws, i); }
     float *scale(int i) const { return ws_scale(ws, p.slots, i); }
+    // static activation scales (Section 5, convolutional networks): the scale of quantise point i
+    bool is_static() const { return qw->act_scale != nullptr; }
+    const float *sscale(int i) const { return qw->act_scale ? qw->act_scale + i : nullptr; }
+    const float *sx(int i) const { return qw->act_scale ? qw->act_scale + i : ws_scale(ws, p.slots, i); }
+    bool wants_y(int i) const { const egeria_tap *t = tap(i); return t && t->y; }
     int8_t *qbuf(int i) const { return (int8_t *)(ws + p.off_q[i]); }
     float *fbuf(int i) const { return (float *)(ws + p.off_f[i]); }
     const egeria_tap *tap(int i) const { return taps ? &taps->tap[i] : nullptr; }
@@ -170,7 +175,8 @@ struct Fwd {
 egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64_t M, int32_t N, int32_t kp,
                        bool conv, int32_t H, int32_t W, int32_t cp, const float *sx, int act,
                        const int8_t *res_q, const float *res_scale, int64_t res_ld, float *y,
-                       uint32_t *absmax_out, bool amax_pos = false, bool tap_y = true)
+                       uint32_t *absmax_out, bool amax_pos = false, bool tap_y = true, int8_t *q_out = nullptr,
+                       int64_t q_ld = 0, const float *q_scale = nullptr)
 {
     const egeria_qlinear &L = f.qw->linear[li];
     GemmArgs g;
@@ -186,20 +192,42 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     g.acc_out = t ? t->acc : nullptr;
     g.absmax_out = absmax_out;
     g.amax_pos = amax_pos ? 1 : 0;
+    g.q_out = q_out; g.q_ld = q_ld; g.q_scale = q_scale;
     EG_HIP(launch_gemm_i8(g, f.st));
-    return tap_y ? f.copy_tap_y(li, y, (size_t)M * N * 4) : EGERIA_OK;
+    return (tap_y && y) ? f.copy_tap_y(li, y, (size_t)M * N * 4) : EGERIA_OK;
 }
 
 egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
 {
     const egeria_block_desc *d = f.d;
     const int64_t kp = pad16(d->c_in);
-    EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
-    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.n_amax(0), f.stride_amax(0), nullptr, f.qbuf(0), f.scale(0),
-                                nullptr, ws_flag(f.ws), f.st));
+    if (!f.is_static()) EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
+    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0), f.stride_amax(0),
+                                f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(d->batch * kp), f.scale(0)));
-    return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.scale(0), 1,
+    return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.sx(0), 1,
                     nullptr, nullptr, 0, a_ref, nullptr);
+}
+
+// A convolution whose output only feeds the next one.  Dynamic scales: fp32
+// output + its maximum, then a quantise pass.  Static scales: the epilogue
+// writes the next layer's int8 input itself (fp32 only for an observed run).
+egeria_status conv_to_int8(Fwd &f, int li, const int8_t *a, int64_t lda, int64_t M, int32_t N, int32_t kp, bool conv,
+                           int32_t H, int32_t W, int32_t cp, int fb, int qi)
+{
+    const int32_t np = (int32_t)pad16(N);
+    if (f.is_static()) {
+        float *y = f.wants_y(li) ? f.fbuf(fb) : nullptr;
+        EG_OK(run_gemm(f, li, a, lda, M, N, kp, conv, H, W, cp, f.sx(li), 1, nullptr, nullptr, 0, y, nullptr, false, true,
+                       f.qbuf(qi), np, f.sscale(li + 1)));
+    } else {
+        EG_OK(run_gemm(f, li, a, lda, M, N, kp, conv, H, W, cp, f.sx(li), 1, nullptr, nullptr, 0, f.fbuf(fb),
+                       f.slot(li + 1)));
+        EG_HIP(launch_quantize_rows(f.fbuf(fb), EGERIA_F32, M, N, np, f.amax(li + 1), f.n_amax(li + 1),
+                                    f.stride_amax(li + 1), nullptr, f.qbuf(qi), f.scale(li + 1), nullptr, ws_flag(f.ws),
+                                    f.st));
+    }
+    return f.copy_tap_q(li + 1, f.qbuf(qi), (size_t)(M * np), f.sx(li + 1));
 }
 
 egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
@@ -208,33 +236,21 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     const int64_t M = f.p.M, hw = (int64_t)d->height * d->width;
     const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
     const int H = d->height, W = d->width;
-    EG_OK(f.input_absmax(x, dt, M * d->c_in));
-    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.n_amax(0), f.stride_amax(0), nullptr, f.qbuf(0), f.scale(0),
-                                nullptr, ws_flag(f.ws), f.st));
+    if (!f.is_static()) EG_OK(f.input_absmax(x, dt, M * d->c_in));
+    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
+                                f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));
     const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
     if (d->kind == EGERIA_BASIC_BLOCK) {
-        EG_OK(run_gemm(f, 0, f.qbuf(0), 0, M, d->c_mid, 9 * cin_p, true, H, W, cin_p, f.scale(0), 1, nullptr,
-                       nullptr, 0, f.fbuf(0), f.slot(1)));
-        EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), f.stride_amax(1), nullptr, f.qbuf(1),
-                                    f.scale(1), nullptr, ws_flag(f.ws), f.st));
-        EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
-        return run_gemm(f, 1, f.qbuf(1), 0, M, d->c_out, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, res,
-                        f.scale(0), cin_p, a_ref, nullptr);
+        EG_OK(conv_to_int8(f, 0, f.qbuf(0), 0, M, d->c_mid, 9 * cin_p, true, H, W, cin_p, 0, 1));
+        return run_gemm(f, 1, f.qbuf(1), 0, M, d->c_out, 9 * cmid_p, true, H, W, cmid_p, f.sx(1), 1, res, f.sx(0), cin_p,
+                        a_ref, nullptr);
     }
     // bottleneck: 1x1 -> 3x3 -> 1x1
-    EG_OK(run_gemm(f, 0, f.qbuf(0), cin_p, M, d->c_mid, cin_p, false, 0, 0, 0, f.scale(0), 1, nullptr, nullptr,
-                   0, f.fbuf(0), f.slot(1)));
-    EG_HIP(launch_quantize_rows(f.fbuf(0), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(1), f.n_amax(1), f.stride_amax(1), nullptr, f.qbuf(1),
-                                f.scale(1), nullptr, ws_flag(f.ws), f.st));
-    EG_OK(f.copy_tap_q(1, f.qbuf(1), (size_t)(M * cmid_p), f.scale(1)));
-    EG_OK(run_gemm(f, 1, f.qbuf(1), 0, M, d->c_mid, 9 * cmid_p, true, H, W, cmid_p, f.scale(1), 1, nullptr,
-                   nullptr, 0, f.fbuf(1), f.slot(2)));
-    EG_HIP(launch_quantize_rows(f.fbuf(1), EGERIA_F32, M, d->c_mid, cmid_p, f.amax(2), f.n_amax(2), f.stride_amax(2), nullptr, f.qbuf(2),
-                                f.scale(2), nullptr, ws_flag(f.ws), f.st));
-    EG_OK(f.copy_tap_q(2, f.qbuf(2), (size_t)(M * cmid_p), f.scale(2)));
-    return run_gemm(f, 2, f.qbuf(2), cmid_p, M, d->c_out, cmid_p, false, 0, 0, 0, f.scale(2), 1, res, f.scale(0),
-                    cin_p, a_ref, nullptr);
+    EG_OK(conv_to_int8(f, 0, f.qbuf(0), cin_p, M, d->c_mid, cin_p, false, 0, 0, 0, 0, 1));
+    EG_OK(conv_to_int8(f, 1, f.qbuf(1), 0, M, d->c_mid, 9 * cmid_p, true, H, W, cmid_p, 1, 2));
+    return run_gemm(f, 2, f.qbuf(2), cmid_p, M, d->c_out, cmid_p, false, 0, 0, 0, f.sx(2), 1, res, f.sx(0), cin_p, a_ref,
+                    nullptr);
 }
 
 // One encoder layer: `cur` -> `out`.  slot 4l must already hold absmax(cur).
@@ -297,6 +313,8 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
         if (desc->hidden / desc->heads > 64) return EGERIA_ERR_UNSUPPORTED;
     }
     if (qw->n_linear != p.n_linear || !qw->linear) return EGERIA_ERR_INVALID_ARG;
+    if (qw->act_scale && desc->kind >= EGERIA_BERT_LAYER) return EGERIA_ERR_UNSUPPORTED;
+    if (qw->act_scale && (reinterpret_cast<uintptr_t>(qw->act_scale) & 3u)) return EGERIA_ERR_INVALID_ARG;
     if (qw->norm && qw->n_norm != 2 * p.n_layers) return EGERIA_ERR_INVALID_ARG;
     for (int i = 0; i < p.n_linear; ++i) {
         const egeria_qlinear &L = qw->linear[i];

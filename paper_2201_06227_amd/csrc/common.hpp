@@ -167,6 +167,11 @@ struct GemmArgs {
     int32_t *acc_out;       // optional raw accumulators [M, N]
     uint32_t *absmax_out;   // optional: atomicMax of |y| (bit pattern)
     int32_t amax_pos;       // 1: track max(y, 0) instead of |y| (input of the fused GELU quantiser)
+    // optional: int8 codes of y under the static scale *q_scale, [M, q_ld] with zero pad
+    // columns (the next layer's input); y may then be null
+    int8_t *q_out;
+    int64_t q_ld;
+    const float *q_scale;
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 
@@ -240,6 +245,13 @@ __device__ __forceinline__ uint32_t reduce_ways(const uint32_t *slot)
     return v;
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+// int8 code of x under the multiplier inv = 1 / scale.
+__device__ __forceinline__ uint32_t quant1(float x, float inv)
+{
+    float r = rintf(x * inv);                 // one fp32 multiply, round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (uint32_t)((int)r) & 0xffu;
+}
 #endif
 
 }  // namespace egeria

@@ -93,6 +93,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     // epilogue scalars, requested now so that their latency hides behind the K loop
     const float s = (*g.sx) * (*g.sw);
     const float rs = g.res_q ? *g.res_scale : 0.0f;
+    float q_inv = 0.0f;                          // multiplier of the optional int8 output
+    if (g.q_out) q_inv = (float)(1.0 / (double)*g.q_scale);
 
     // Operands go from global memory straight into LDS (buffer loads with the
     // LDS modifier): one such instruction of a wave fills 1 KiB, lane l writing
@@ -285,15 +287,17 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     // when only positive values are wanted) order like signed integers.
     const bool pos = g.amax_pos != 0;
     int32_t amax = 0;
-    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && g.y && !g.acc_out;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (g.y || g.q_out) && !g.acc_out;
+    const uint32_t qoff = g.q_out ? (uint32_t)(lrow * g.q_ld + lcol) : 0u;
     const uint32_t yoff = (uint32_t)(lrow * g.ldy + lcol);
     const uint32_t roff = g.res_q ? (uint32_t)(lrow * g.res_ld + lcol) : 0u;
     const uint32_t aoff = (uint32_t)(lrow * g.N + lcol);
     // EDGE false: interior tile, no bounds tests, no observation outputs.
     // EDGE true : edge tiles and observed runs, every element tested.
-    auto emit = [&](auto edge_c, auto res_c, auto relu_c, auto pos_c) {
+    // QOUT (interior tiles): the tile also, or only, goes out as int8 codes.
+    auto emit = [&](auto edge_c, auto res_c, auto relu_c, auto pos_c, auto qout_c) {
         constexpr bool EDGE = decltype(edge_c)::value, RES = decltype(res_c)::value, RELU = decltype(relu_c)::value;
-        constexpr bool POS = decltype(pos_c)::value;
+        constexpr bool POS = decltype(pos_c)::value, QOUT = decltype(qout_c)::value;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col0 = n0 + (wn_u * TN + j) * 32;
@@ -305,18 +309,24 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                 float *yb = g.y + row0 * g.ldy + col0;
                 const int8_t *rb = g.res_q + row0 * g.res_ld + col0;
                 int32_t *ab = g.acc_out + row0 * g.N + col0;
+                int8_t *qb = g.q_out + row0 * g.q_ld + col0;
                 const int rows_left = EDGE ? (int)(g.M - row0 < 32 ? g.M - row0 : 32) - lrow : 32;
                 // the block stays in the accumulation registers until its turn
                 asm volatile("" : "+a"(acc[i][j]));
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rr = 8 * (r >> 2) + (r & 3);
-                    if (EDGE && !(col_ok && rr < rows_left)) continue;
+                    if (EDGE && !(col_ok && rr < rows_left)) {
+                        // pad columns of the int8 output are zero
+                        if (g.q_out && !col_ok && col0 + lcol < g.q_ld && rr < rows_left) qb[(size_t)rr * g.q_ld + qoff] = 0;
+                        continue;
+                    }
                     const int a = acc[i][j][r];
                     float v = fmaf((float)a, s, bj);
                     if (EDGE ? g.res_q != nullptr : RES) v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
                     if (EDGE ? g.act == 1 : RELU) v = v > 0.0f ? v : 0.0f;
-                    if (!EDGE || g.y) yb[(size_t)rr * g.ldy + yoff] = v;
+                    if (EDGE ? g.y != nullptr : (!QOUT || g.y != nullptr)) yb[(size_t)rr * g.ldy + yoff] = v;
+                    if (EDGE ? g.q_out != nullptr : QOUT) qb[(size_t)rr * g.q_ld + qoff] = (int8_t)quant1(v, q_inv);
                     if (EDGE && g.acc_out) ab[(size_t)rr * g.N + aoff] = a;
                     int32_t bits = (int32_t)__float_as_uint(v);
                     if (EDGE ? !(g.act == 1 || pos) : !(RELU || POS)) bits &= 0x7fffffff;
@@ -328,13 +338,14 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     };
     using T = std::true_type;
     using F = std::false_type;
-    if (!interior) emit(T{}, F{}, F{}, F{});
+    if (!interior || (g.q_out && (g.res_q || g.act != 1))) emit(T{}, F{}, F{}, F{}, F{});
+    else if (g.q_out) emit(F{}, F{}, T{}, F{}, T{});
     else if (g.res_q) {
-        if (g.act == 1) emit(F{}, T{}, T{}, F{}); else emit(F{}, T{}, F{}, F{});
+        if (g.act == 1) emit(F{}, T{}, T{}, F{}, F{}); else emit(F{}, T{}, F{}, F{}, F{});
     } else {
-        if (g.act == 1) emit(F{}, F{}, T{}, F{});
-        else if (pos) emit(F{}, F{}, F{}, T{});
-        else emit(F{}, F{}, F{}, F{});
+        if (g.act == 1) emit(F{}, F{}, T{}, F{}, F{});
+        else if (pos) emit(F{}, F{}, F{}, T{}, F{});
+        else emit(F{}, F{}, F{}, F{}, F{});
     }
     if (g.absmax_out) {
         __shared__ uint32_t sm4[4];
@@ -410,17 +421,23 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     const bool col_ok = col < g.N;
     const float bc = (g.bias && col_ok) ? g.bias[col] : 0.0f;
     const int64_t mw = ((int64_t)blockIdx.x * 4 + wave) * 32;
+    const float q_inv = g.q_out ? (float)(1.0 / (double)*g.q_scale) : 0.0f;
     uint32_t amax = 0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int64_t row = mw + (r >> 2) * 8 + h * 4 + (r & 3);
-        if (!col_ok || row >= g.M) continue;
+        if (row >= g.M) continue;
+        if (!col_ok) {
+            if (g.q_out && col < g.q_ld) g.q_out[row * g.q_ld + col] = 0;     // pad columns of the int8 output
+            continue;
+        }
         const int a = acc[r];
         if (g.acc_out) g.acc_out[row * g.N + col] = a;
         float v = fmaf((float)a, s, bc);
         if (g.res_q) v = v + (float)g.res_q[row * g.res_ld + col] * rs;
         if (g.act == 1) v = v > 0.0f ? v : 0.0f;
-        g.y[row * g.ldy + col] = v;
+        if (g.y) g.y[row * g.ldy + col] = v;
+        if (g.q_out) g.q_out[row * g.q_ld + col] = (int8_t)quant1(v, q_inv);
         const uint32_t ab = g.amax_pos ? (v > 0.0f ? __float_as_uint(v) : 0u) : abs_bits(v);
         amax = amax > ab ? amax : ab;
     }

@@ -151,13 +151,6 @@ __device__ __forceinline__ void publish(float scale, bool bad, float *scale_out,
     }
 }
 
-__device__ __forceinline__ uint32_t quant1(float x, float inv)
-{
-    float r = rintf(x * inv);                 // one fp32 multiply, round half to even
-    r = fminf(fmaxf(r, -127.0f), 127.0f);
-    return (uint32_t)((int)r) & 0xffu;
-}
-
 template <bool BF16>
 __device__ __forceinline__ float load_elem(const void *x, int64_t i)
 {

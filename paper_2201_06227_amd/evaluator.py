@@ -21,7 +21,8 @@ class PlasticityEvaluator:
     current stream; scores land in `self.p_out`."""
 
     def __init__(self, kind: int, dims: dict, weights: Sequence[torch.Tensor],
-                 biases: Sequence[Optional[torch.Tensor]], device="cuda"):
+                 biases: Sequence[Optional[torch.Tensor]], device="cuda",
+                 act_scales: Optional[torch.Tensor] = None):
         self.weights = [w.contiguous() for w in weights]
         self.biases = list(biases)
         self.desc = eg.make_desc(kind, dims)
@@ -45,6 +46,9 @@ class PlasticityEvaluator:
         self.qw.linear = self._lin
         self.qw.n_norm = 0
         self.qw.norm = None
+        # static activation scales (fp32 [n_linear] on the device) or None for dynamic ones
+        self.act_scales = act_scales
+        self.qw.act_scale = None if act_scales is None else act_scales.data_ptr()
         self.qws = eg.workspace(eg.quantize_weights_workspace_bytes(len(self.weights)), device)
         self._wtab = eg.weight_table(self.weights, self.w_q, self.scales)
         nbytes = eg.workspace_bytes(self.desc)

@@ -39,10 +39,11 @@ def tap_shapes(wl):
     return one * d["n_layers"]
 
 
-def build_reference(wl):
+def build_reference(wl, act_scales=None):
     W = [to_dev(w) for w in wl.weights]
     B = [None if b is None else to_dev(b) for b in wl.biases]
-    return eg.make_reference(wl.kind, wl.dims, W, B)
+    st = None if act_scales is None else to_dev(np.asarray(act_scales, np.float32))
+    return eg.make_reference(wl.kind, wl.dims, W, B, st)
 
 
 def a_ref_numel(wl):
@@ -54,9 +55,9 @@ def a_ref_numel(wl):
     return d["n_layers"] * d["batch"] * d["seq"] * d["hidden"]
 
 
-def run_forward(wl, with_taps=True):
+def run_forward(wl, with_taps=True, act_scales=None):
     """Returns (a_ref [n_layers, b, D] numpy, list of tap dicts of numpy arrays, ref)."""
-    ref = build_reference(wl)
+    ref = build_reference(wl, act_scales)
     x = to_dev(wl.x)
     n_layers = wl.dims.get("n_layers", 1)
     a_ref = torch.empty(a_ref_numel(wl), dtype=torch.float32, device=DEV)

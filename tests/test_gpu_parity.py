@@ -196,6 +196,77 @@ def test_bottleneck_bit_exact(eg, gc, orc, kw):
     assert (a_ref[0].reshape(-1, kw["c_in"]) == gc.nhwc(ot["a_ref"])).all()
 
 
+STATIC_CASES = [("fc", dict(b=5, k=100, n=7)), ("fc", dict(b=130, k=200, n=257)),
+                ("basic", dict(b=3, c=8, h=7, w=6)), ("basic", dict(b=2, c=20, h=9, w=11)),
+                ("basic", dict(b=5, c=16, h=32, w=32)), ("basic", dict(b=2, c=64, h=13, w=13)),
+                ("bottleneck", dict(b=2, c_in=32, c_mid=16, h=5, w=5)),
+                ("bottleneck", dict(b=1, c_in=40, c_mid=24, h=7, w=3)),
+                ("bottleneck", dict(b=3, c_in=256, c_mid=64, h=14, w=14))]
+
+
+def _static_workload(kind, kw):
+    if kind == "fc":
+        return si.make_fc(seed=700 + kw["k"], **kw), False
+    if kind == "basic":
+        return si.make_basic_block(seed=710 + kw["c"], **kw), True
+    return si.make_bottleneck(seed=720 + kw["c_in"], **kw), True
+
+
+def _check_static(gc, orc, wl, conv, scales, with_taps):
+    a_ref, taps, _ = gc.run_forward(wl, with_taps=with_taps, act_scales=scales)
+    ot = orc.ref_forward(wl, act_scales=scales)
+    if with_taps:
+        for i in range(len(taps)):
+            _check_linear_taps(gc, taps[i], ot, f"l{i}.", conv=conv)
+    want = gc.nhwc(ot["a_ref"]).reshape(wl.batch, -1) if conv else ot["a_ref"]
+    assert (a_ref[0] == want).all()
+    return want
+
+
+@pytest.mark.parametrize("kind,kw", STATIC_CASES, ids=lambda v: v if isinstance(v, str) else "_".join(f"{k}{x}" for k, x in v.items()))
+def test_static_scales_bit_exact(eg, gc, orc, kind, kw):
+    """Static activation scales (Section 5, convolutional networks): calibrated on the batch itself they
+    reproduce the dynamic forward; halved they saturate; observed and unobserved runs agree with the oracle."""
+    wl, conv = _static_workload(kind, kw)
+    dyn = orc.ref_forward(wl)
+    n = len(wl.weights)
+    scales = [float(dyn[f"l{i}.sx"]) for i in range(n)]
+    want = _check_static(gc, orc, wl, conv, scales, True)
+    dyn_want = gc.nhwc(dyn["a_ref"]).reshape(wl.batch, -1) if conv else dyn["a_ref"]
+    assert (want == dyn_want).all()                       # same scales: same forward
+    _check_static(gc, orc, wl, conv, scales, False)       # the path without fp32 round trips
+    tight = [0.5 * v for v in scales]
+    _check_static(gc, orc, wl, conv, tight, True)
+    _check_static(gc, orc, wl, conv, tight, False)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_static_scales_full_size(eg, gc, orc, cfg):
+    wl = si.make_config(cfg)
+    conv = cfg != 1
+    dyn = orc.ref_forward(wl)
+    scales = [0.9 * float(dyn[f"l{i}.sx"]) for i in range(len(wl.weights))]     # a little clipping
+    want = _check_static(gc, orc, wl, conv, scales, False)
+    a_t = si.train_forward(wl)[0]
+    p_want = orc.sp_loss(a_t.float().numpy(), want)
+    ref = gc.build_reference(wl, scales)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc))
+    p = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, gc.to_dev(wl.x), [a_t.to(gc.DEV)], p, ws)
+    torch.cuda.synchronize()
+    assert p_close(p.item(), p_want, wl.batch), (p.item(), p_want)
+
+
+def test_static_scales_rejected_for_transformer_kinds(eg, gc):
+    wl = si.make_bert(b=2, s=16, hidden=64, heads=4, ffn=128, n_layers=1, seed=5)
+    ref = gc.build_reference(wl, [1.0, 1.0, 1.0, 1.0])
+    a_ref = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    with pytest.raises(eg.EgeriaError) as e:
+        eg.ref_forward(ref, gc.to_dev(wl.x), a_ref, ws, None)
+    assert e.value.code == eg.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3])
 def test_full_size_configs_bit_exact_and_scored(eg, gc, orc, cfg):
     """Configs 1-3 at full size: every observation point bit-exact, and the

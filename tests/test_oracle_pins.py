@@ -418,3 +418,23 @@ def test_plasticity_of_config_like_blocks_is_small_and_positive(orc):
     a_t = si.train_forward(wl)[0].numpy()
     p = orc.sp_loss(a_t, a_ref)
     assert 0 < p < 1e-3
+
+
+def test_static_scales_reduce_to_dynamic_and_saturate(orc):
+    """Static activation scales (Section 5): with each scale equal to the tensor's own absmax / 127 the
+    forward is the dynamic one bit for bit; with a smaller scale values saturate at +-127 and the
+    round-trip error of an unsaturated value is still at most scale / 2."""
+    import synth_inputs as si
+    for wl in (si.make_fc(b=6, k=40, n=9, seed=11), si.make_basic_block(b=2, c=5, h=6, w=5, seed=12),
+               si.make_bottleneck(b=2, c_in=12, c_mid=6, h=4, w=5, seed=13)):
+        dyn = orc.ref_forward(wl)
+        scales = [float(dyn[f"l{i}.sx"]) for i in range(len(wl.weights))]
+        st = orc.ref_forward(wl, act_scales=scales)
+        for k in dyn:
+            assert np.array_equal(np.asarray(dyn[k]), np.asarray(st[k])), k
+    x = np.linspace(-3, 3, 61).astype(np.float32)
+    q, s = orc.quantize(x, fixed_scale=0.01)
+    assert s == np.float32(0.01)
+    assert q.min() == -127 and q.max() == 127 and (q[np.abs(x) > 1.28] != 0).all()
+    inside = np.abs(x) <= 1.27
+    assert (np.abs(x[inside] - q[inside].astype(np.float32) * s) <= 0.005 * (1 + 1e-4)).all()
