@@ -473,6 +473,33 @@ size_t egeria_workspace_bytes(const egeria_block_desc *desc)
     return p.ok ? p.total : 0;
 }
 
+// Side stream of egeria_plasticity_eval for layer stacks, with the events that
+// order it against the caller's stream.  Created once per device on first use
+// (default priority); calls that use it must not overlap in time.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t produced[2] = {nullptr, nullptr};
+    hipEvent_t scored[2] = {nullptr, nullptr};
+};
+
+static SideStream *side_stream()
+{
+    static SideStream per_device[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    SideStream &s = per_device[dev];
+    if (!s.stream) {
+        hipStream_t st = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        for (int i = 0; i < 2; ++i) {
+            if (hipEventCreateWithFlags(&s.produced[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&s.scored[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+        }
+        s.stream = st;
+    }
+    return &s;
+}
+
 static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
                                   egeria_dtype x_dt, float *a_ref, const egeria_taps *taps,
                                   const void *const *a_train, egeria_dtype t_dt, float *p_out, void *ws,
@@ -491,13 +518,32 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     }
     EG_OK(f.input_absmax(x, x_dt, p.M * desc->hidden));
     const float *cur = (const float *)x;
+    // The score of layer l only needs that layer's output, so it runs on a side
+    // stream while the main stream goes on with layer l + 1 (the score is bound
+    // by fp32 MFMA and HBM, the next layer starts with HBM-bound kernels).  The two
+    // A_R buffers alternate: layer l + 2 may overwrite the buffer only after the
+    // score of layer l has read it.  The side stream joins the main one at the end.
+    SideStream *side = (eval && p.n_layers > 1) ? side_stream() : nullptr;
+    if (eval && p.n_layers > 1 && !side) return EGERIA_ERR_HIP;
     for (int l = 0; l < p.n_layers; ++l) {
         float *out = a_ref ? a_ref + (size_t)l * aref_elems : (float *)(f.ws + p.off_aref[l & 1]);
+        if (side && l >= 2) EG_HIP(hipStreamWaitEvent(st, side->scored[l & 1], 0));
         EG_OK(forward_bert_layer(f, l, cur, out, l + 1 == p.n_layers));
-        if (eval)
+        if (eval) {
+            hipStream_t ms = side ? side->stream : st;
+            if (side) {
+                EG_HIP(hipEventRecord(side->produced[l & 1], st));
+                EG_HIP(hipStreamWaitEvent(ms, side->produced[l & 1], 0));
+            }
             EG_HIP(launch_plasticity(a_train[l], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out + l,
-                                     f.ws + p.off_part, st));
+                                     f.ws + p.off_part, ms));
+            if (side) EG_HIP(hipEventRecord(side->scored[l & 1], ms));
+        }
         cur = out;
+    }
+    if (side) {
+        EG_HIP(hipStreamWaitEvent(st, side->scored[(p.n_layers - 1) & 1], 0));
+        EG_HIP(hipStreamWaitEvent(st, side->scored[(p.n_layers - 2) & 1], 0));
     }
     return EGERIA_OK;
 }
