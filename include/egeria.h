@@ -94,8 +94,9 @@ typedef struct {
  *   bias  : fp32 [out] or NULL. */
 typedef struct {
     const int8_t *w_q;
-    const float *scale;
+    const float *scale;             /* 1 fp32, or fp32 [out] when per_channel */
     const float *bias;
+    int32_t per_channel;            /* 0: one scale for the tensor; 1: one per output channel */
 } egeria_qlinear;
 
 /* HOST struct.  Affine parameters of one layer norm (each fp32 [hidden] or NULL
@@ -176,7 +177,9 @@ typedef struct {
     int32_t dtype;                  /* egeria_dtype */
     int32_t out, in, kh, kw;
     int8_t *w_q;                    /* out: int8 [out, kh, kw, egeria_padded(in)], pad zero */
-    float *scale;                   /* out: 1 fp32 */
+    float *scale;                   /* out: 1 fp32, or fp32 [out] when per_channel */
+    int32_t per_channel;            /* 0: one scale for the tensor; 1: the same rule applied to every
+                                       output channel w[o] on its own (one scale per channel) */
 } egeria_weight;
 
 /* Section 4.1, reference-model generation: quantises all n weight tensors of

@@ -158,6 +158,32 @@ void orc_dequant_bias_act(const int32_t *acc, int64_t outer, int64_t channels, i
         }
 }
 
+/* The same epilogue for weights quantised per output channel (one scale per
+ * row of the weight matrix / per output channel of the kernel): the scale of
+ * channel c is s_c = sx * sw[c], again one fp32 multiply. */
+void orc_dequant_bias_act_pc(const int32_t *acc, int64_t outer, int64_t channels, int64_t inner,
+                             float sx, const float *sw, const float *bias, int act,
+                             const float *residual, float *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o)
+        for (int64_t c = 0; c < channels; ++c) {
+            const float s = sx * sw[c];
+            const float bc = bias ? bias[c] : 0.0f;
+            for (int64_t i = 0; i < inner; ++i) {
+                int64_t idx = (o * channels + c) * inner + i;
+                float v = fmaf((float)acc[idx], s, bc);
+                if (residual) v = v + residual[idx];
+                if (act == 1) v = v > 0.0f ? v : 0.0f;
+                else if (act == 2) {
+                    double d = (double)v;
+                    v = (float)(0.5 * d * (1.0 + erf(d * 0.70710678118654752440)));
+                }
+                y[idx] = v;
+            }
+        }
+}
+
 /* ---- fp32 glue of a Transformer encoder layer (not quantised under dynamic
  * quantisation, Section 5) ------------------------------------------------- */
 

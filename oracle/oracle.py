@@ -53,6 +53,9 @@ def lib():
         L.orc_gemm_i8.argtypes = [_i8p, _i8p, _i64, _i64, _i64, _i32p]
         L.orc_conv2d_i8.restype = None
         L.orc_conv2d_i8.argtypes = [_i8p, _i8p] + [_i64] * 8 + [_i32p]
+        L.orc_dequant_bias_act_pc.restype = None
+        L.orc_dequant_bias_act_pc.argtypes = [_i32p, _i64, _i64, _i64, ctypes.c_float, _f32p, _f32p, ctypes.c_int,
+                                              _f32p, _f32p]
         L.orc_dequant_bias_act.restype = None
         L.orc_dequant_bias_act.argtypes = [_i32p, _i64, _i64, _i64, ctypes.c_float, ctypes.c_float,
                                            _f32p, ctypes.c_int, _f32p, _f32p]
@@ -138,8 +141,14 @@ def dequant_bias_act(acc, sx, sw, bias=None, act=ACT_NONE, residual=None):
     if residual is not None:
         assert residual.shape == acc.shape
     y = np.empty(acc.shape, np.float32)
-    lib().orc_dequant_bias_act(_p(acc, _i32p), outer, channels, inner, float(sx), float(sw),
-                               _p(bias, _f32p), int(act), _p(residual, _f32p), _p(y, _f32p))
+    if np.ndim(sw) == 0:
+        lib().orc_dequant_bias_act(_p(acc, _i32p), outer, channels, inner, float(sx), float(sw),
+                                   _p(bias, _f32p), int(act), _p(residual, _f32p), _p(y, _f32p))
+    else:                                        # one weight scale per output channel
+        swv = _c(sw, np.float32)
+        assert swv.shape == (channels,)
+        lib().orc_dequant_bias_act_pc(_p(acc, _i32p), outer, channels, inner, float(sx), _p(swv, _f32p),
+                                      _p(bias, _f32p), int(act), _p(residual, _f32p), _p(y, _f32p))
     return y
 
 
@@ -180,9 +189,21 @@ def sp_loss(a_t, a_r, return_grams=False):
 
 # ---- layer modules -----------------------------------------------------------
 
-def quantize_weights(weights):
-    """Reference-model generation: per-tensor int8 of every snapshot tensor."""
-    return [quantize(w) for w in weights]
+def quantize_per_channel(w):
+    """int8 codes of a weight tensor [out, ...] with one symmetric scale per
+    output channel: the per-tensor rule applied to every w[o] on its own."""
+    w = _c(w, np.float32)
+    q = np.empty(w.shape, np.int8)
+    s = np.empty(w.shape[0], np.float32)
+    for o in range(w.shape[0]):
+        q[o], s[o] = quantize(w[o])
+    return q, s
+
+
+def quantize_weights(weights, per_channel=False):
+    """Reference-model generation: int8 of every snapshot tensor, with one
+    scale per tensor or one per output channel."""
+    return [quantize_per_channel(w) if per_channel else quantize(w) for w in weights]
 
 
 def linear_int8(x, wq, sw, bias, act=ACT_NONE, taps=None, tag="", act_scale=None):

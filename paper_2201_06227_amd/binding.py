@@ -33,7 +33,7 @@ class BlockDesc(ctypes.Structure):
 
 
 class QLinear(ctypes.Structure):
-    _fields_ = [("w_q", _vp), ("scale", _vp), ("bias", _vp)]
+    _fields_ = [("w_q", _vp), ("scale", _vp), ("bias", _vp), ("per_channel", _i32)]
 
 
 class Norm(ctypes.Structure):
@@ -55,7 +55,7 @@ class Taps(ctypes.Structure):
 
 class Weight(ctypes.Structure):
     _fields_ = [("w", _vp), ("dtype", _i32), ("out", _i32), ("in_", _i32), ("kh", _i32), ("kw", _i32),
-                ("w_q", _vp), ("scale", _vp)]
+                ("w_q", _vp), ("scale", _vp), ("per_channel", _i32)]
 
 
 FREEZE_MAX_W = 256
@@ -239,10 +239,12 @@ def quantize_nchw(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, w
     return q, scale
 
 
-def weight_table(weights: Sequence[torch.Tensor], w_q: Sequence[torch.Tensor], scales: Sequence[torch.Tensor]):
+def weight_table(weights: Sequence[torch.Tensor], w_q: Sequence[torch.Tensor], scales: Sequence[torch.Tensor],
+                 per_channel: bool = False):
     """HOST array of egeria_weight descriptors for egeria_quantize_weights."""
     tab = (Weight * len(weights))()
     for t, w, q, s in zip(tab, weights, w_q, scales):
+        t.per_channel = 1 if per_channel else 0
         _dev(w)
         if w.dim() == 4:
             t.out, t.in_, t.kh, t.kw = w.shape
@@ -257,18 +259,19 @@ def quantize_weights_workspace_bytes(n: int) -> int:
     return int(lib().egeria_quantize_weights_workspace_bytes(int(n)))
 
 
-def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor] = None):
+def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor] = None, per_channel: bool = False):
     """egeria_quantize_weights: every tensor of a snapshot in one call.  Returns
-    the int8 tensors ([out, padded(in)] or [out, kh, kw, padded(in)]) and scales."""
+    the int8 tensors ([out, padded(in)] or [out, kh, kw, padded(in)]) and scales
+    (1 value per tensor, or [out] values with per_channel)."""
     dev = weights[0].device if weights else "cuda"
     w_q, scales = [], []
     for w in weights:
         shape = (w.shape[0], w.shape[2], w.shape[3], padded(w.shape[1])) if w.dim() == 4 else \
             (w.shape[0], padded(w.shape[1]))
         w_q.append(torch.empty(shape, dtype=torch.int8, device=dev))
-        scales.append(torch.empty(1, dtype=torch.float32, device=dev))
+        scales.append(torch.empty(w.shape[0] if per_channel else 1, dtype=torch.float32, device=dev))
     ws = workspace(quantize_weights_workspace_bytes(len(weights)), dev) if ws is None else ws
-    tab = weight_table(weights, w_q, scales)
+    tab = weight_table(weights, w_q, scales, per_channel)
     rc = lib().egeria_quantize_weights(tab, len(weights), _ptr(ws), ws.numel(), _stream())
     _check(rc, "egeria_quantize_weights")
     return w_q, scales
@@ -308,18 +311,22 @@ class ReferenceModel:
 
 def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
                    biases: Sequence[Optional[torch.Tensor]],
-                   act_scales: Optional[torch.Tensor] = None) -> ReferenceModel:
+                   act_scales: Optional[torch.Tensor] = None, per_channel: bool = False) -> ReferenceModel:
     """Reference-model generation: quantise every weight tensor of the snapshot
     with the library (egeria_quantize_rows for [out, in], egeria_quantize_nchw for
     [out, in, kh, kw]) and marshal the result."""
     w_q, scales = [], []
-    ws = workspace(quantize_workspace_bytes(), weights[0].device)
-    for w in weights:
-        q, s = quantize_nchw(w, ws=ws) if w.dim() == 4 else quantize_rows(w, ws=ws)
-        w_q.append(q)
-        scales.append(s)
+    if per_channel:
+        w_q, scales = quantize_weights(list(weights), per_channel=True)
+    else:
+        ws = workspace(quantize_workspace_bytes(), weights[0].device)
+        for w in weights:
+            q, s = quantize_nchw(w, ws=ws) if w.dim() == 4 else quantize_rows(w, ws=ws)
+            w_q.append(q)
+            scales.append(s)
     arr = (QLinear * len(weights))()
     for i in range(len(weights)):
+        arr[i].per_channel = 1 if per_channel else 0
         arr[i].w_q = w_q[i].data_ptr()
         arr[i].scale = scales[i].data_ptr()
         arr[i].bias = 0 if biases[i] is None else biases[i].data_ptr()

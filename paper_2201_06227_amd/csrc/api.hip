@@ -185,7 +185,7 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     g.w_bytes = (int64_t)N * kp;
     if (g.a_bytes >= (1LL << 31) || g.w_bytes >= (1LL << 31)) return EGERIA_ERR_UNSUPPORTED;
     g.conv3x3 = conv ? 1 : 0; g.H = H; g.W = W; g.cp = cp;
-    g.sx = sx; g.sw = L.scale; g.bias = L.bias; g.act = act;
+    g.sx = sx; g.sw = L.scale; g.sw_per_n = L.per_channel ? 1 : 0; g.bias = L.bias; g.act = act;
     g.res_q = res_q; g.res_scale = res_scale; g.res_ld = res_ld;
     g.y = y; g.ldy = N;
     const egeria_tap *t = f.tap(li);
@@ -424,37 +424,44 @@ egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *w
     }
     hipStream_t st = (hipStream_t)stream;
     uint32_t *partials = (uint32_t *)ws + kHeaderFixedWords;
-    int i = 0;
-    while (i < n) {
-        WeightBatch b;
-        b.n = 0;
-        int blocks = 0;
-        bool one = true;
-        for (; i < n && b.n < kWeightBatch; ++i) {
-            const egeria_weight &t = w[i];
-            const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
-            WeightJob &jb = b.job[b.n++];
-            jb.x = t.w;
-            jb.q = t.w_q;
-            jb.scale = t.scale;
-            jb.o = t.out;
-            jb.c = t.in;
-            jb.hw = t.kh * t.kw;
-            jb.cp = (int32_t)pad16(t.in);
-            jb.bf16 = t.dtype == EGERIA_BF16;
-            // one workgroup for a small tensor, else about four 16-byte loads per thread
-            int64_t nblk = total <= kSmallTensor ? 1 : (total + 4095) / 4096;
-            if (nblk > kAbsPartials) nblk = kAbsPartials;
-            const int64_t units = (int64_t)t.out * jb.hw * (jb.cp / 16);
-            jb.first_block = blocks;
-            jb.nblk = (int32_t)nblk;
-            jb.epb = (int32_t)(((total + nblk - 1) / nblk + 7) / 8 * 8);
-            jb.upb = (int32_t)((units + nblk - 1) / nblk);
-            jb.pad_ = 0;
-            blocks += (int)nblk;
-            one = one && nblk == 1;
+    // tensors with one scale are batched separately from those with one scale per output channel
+    for (int pc = 0; pc < 2; ++pc) {
+        int i = 0;
+        while (i < n) {
+            WeightBatch b;
+            b.n = 0;
+            int blocks = 0;
+            bool one = true;
+            for (; i < n && b.n < kWeightBatch; ++i) {
+                const egeria_weight &t = w[i];
+                if ((t.per_channel != 0) != (pc != 0)) continue;
+                const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
+                WeightJob &jb = b.job[b.n++];
+                jb.x = t.w;
+                jb.q = t.w_q;
+                jb.scale = t.scale;
+                jb.o = t.out;
+                jb.c = t.in;
+                jb.hw = t.kh * t.kw;
+                jb.cp = (int32_t)pad16(t.in);
+                jb.bf16 = t.dtype == EGERIA_BF16;
+                jb.per_channel = pc;
+                // one workgroup for a small tensor, else about four 16-byte loads per thread
+                int64_t nblk = total <= kSmallTensor ? 1 : (total + 4095) / 4096;
+                if (nblk > kAbsPartials) nblk = kAbsPartials;
+                if (pc) nblk = ((int64_t)t.out + 3) / 4;
+                const int64_t units = (int64_t)t.out * jb.hw * (jb.cp / 16);
+                jb.first_block = blocks;
+                jb.nblk = (int32_t)nblk;
+                jb.epb = (int32_t)(((total + nblk - 1) / (nblk > 0 ? nblk : 1) + 7) / 8 * 8);
+                jb.upb = (int32_t)((units + nblk - 1) / (nblk > 0 ? nblk : 1));
+                blocks += (int)nblk;
+                one = one && nblk == 1;
+            }
+            if (b.n == 0 || blocks == 0) continue;
+            if (pc) EG_HIP(launch_quantize_weights_pc(b, blocks, ws_flag(ws), st));
+            else EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st));
         }
-        EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st));
     }
     return EGERIA_OK;
 }

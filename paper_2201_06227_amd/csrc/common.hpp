@@ -130,7 +130,7 @@ struct WeightJob {
     int32_t nblk;           // workgroups of this tensor (<= kAbsPartials)
     int32_t epb;            // input values per workgroup (multiple of 8)
     int32_t upb;            // 16-byte output units per workgroup
-    int32_t pad_;
+    int32_t per_channel;    // one scale per output channel: a wave per channel, nblk = ceil(o / 4)
 };
 constexpr int kWeightBatch = 32;
 struct WeightBatch {
@@ -140,6 +140,8 @@ struct WeightBatch {
 // one_launch: every job has nblk == 1.  partials: total_blocks words.
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
                                    uint32_t *flag, hipStream_t st);
+// The same for jobs with one scale per output channel (job.scale is [o]); four channels per workgroup.
+hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, uint32_t *flag, hipStream_t st);
 
 hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
 
@@ -156,7 +158,8 @@ struct GemmArgs {
     int32_t conv3x3;        // 0: rows of `a` are contiguous; 1: 3x3 window gather, zero padding 1
     int32_t H, W, cp;       // image height, width and padded channels (conv3x3 mode)
     const float *sx;        // 1 fp32: scale of the activations
-    const float *sw;        // 1 fp32: scale of the weights
+    const float *sw;        // scale of the weights: 1 fp32, or fp32 [N] when sw_per_n
+    int32_t sw_per_n;
     const float *bias;      // [N] or null
     int32_t act;            // 0 none, 1 ReLU
     const int8_t *res_q;    // optional residual as int8 [M, res_ld] with scale *res_scale

@@ -91,7 +91,8 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
     const int64_t m0 = tile_m * BM;
     const int n0 = tile_n * BN;
     // epilogue scalars, requested now so that their latency hides behind the K loop
-    const float s = (*g.sx) * (*g.sw);
+    const float sxv = *g.sx;
+    const float s = g.sw_per_n ? 0.0f : sxv * (*g.sw);
     const float rs = g.res_q ? *g.res_scale : 0.0f;
     float q_inv = 0.0f;                          // multiplier of the optional int8 output
     if (g.q_out) q_inv = (float)(1.0 / (double)*g.q_scale);
@@ -303,6 +304,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
             const int col0 = n0 + (wn_u * TN + j) * 32;
             const bool col_ok = !EDGE || col0 + lcol < g.N;
             const float bj = (g.bias && col_ok) ? g.bias[col0 + lcol] : 0.0f;
+            const float sj = g.sw_per_n ? (col_ok ? sxv * g.sw[col0 + lcol] : 0.0f) : s;   // one fp32 multiply
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int64_t row0 = m0 + (wm_u * TM + i) * 32;
@@ -322,7 +324,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
                         continue;
                     }
                     const int a = acc[i][j][r];
-                    float v = fmaf((float)a, s, bj);
+                    float v = fmaf((float)a, sj, bj);
                     if (EDGE ? g.res_q != nullptr : RES) v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
                     if (EDGE ? g.act == 1 : RELU) v = v > 0.0f ? v : 0.0f;
                     if (EDGE ? g.y != nullptr : (!QOUT || g.y != nullptr)) yb[(size_t)rr * g.ldy + yoff] = v;
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     const int64_t m = ((int64_t)blockIdx.x * 4 + wave) * 32 + p;
     const bool m_ok = m < g.M;
     const int ow = (int)(m % g.W), oh = (int)((m / g.W) % g.H);
-    const float s = (*g.sx) * (*g.sw);
+    const float s = (*g.sx) * (g.sw_per_n ? (p < g.N ? g.sw[p] : 0.0f) : *g.sw);   // lane's output channel is p
     const float rs = g.res_q ? *g.res_scale : 0.0f;
     v4i fa[5], fb[5];
 #pragma unroll

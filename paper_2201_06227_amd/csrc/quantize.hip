@@ -110,16 +110,9 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *pa
 // Called by every thread at the top of a quantise kernel.  Reduces the n_slot
 // candidate maxima, returns the multiplier inv and the scale; *bad is set when
 // the tensor holds a NaN or an infinity.
-__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
-                                             const float *__restrict__ fixed_scale, float *scale, bool *bad)
+__device__ __forceinline__ float scale_from_bits(uint32_t bits, const float *__restrict__ fixed_scale, float *scale,
+                                                 bool *bad)
 {
-    uint32_t bits = 0;
-    const int lane = threadIdx.x & 63;
-    for (int i = lane; i < n_slot; i += 64) {
-        const uint32_t v = slot[(size_t)i * slot_stride];
-        bits = bits > v ? bits : v;
-    }
-    bits = wave_max_u32(bits);
     float inv, sc;
     *bad = bits >= 0x7f800000u;
     if (fixed_scale) {
@@ -134,6 +127,19 @@ __device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, 
     if (!(inv <= 3.402823466e+38f) || !(sc > 0.0f)) { sc = 1.0f; inv = 0.0f; }
     *scale = sc;
     return inv;
+}
+
+__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+                                             const float *__restrict__ fixed_scale, float *scale, bool *bad)
+{
+    uint32_t bits = 0;
+    const int lane = threadIdx.x & 63;
+    for (int i = lane; i < n_slot; i += 64) {
+        const uint32_t v = slot[(size_t)i * slot_stride];
+        bits = bits > v ? bits : v;
+    }
+    bits = wave_max_u32(bits);
+    return scale_from_bits(bits, fixed_scale, scale, bad);
 }
 
 // Only thread 0 of block 0 of a quantise kernel reads or writes the flag word,
@@ -516,6 +522,50 @@ __global__ __launch_bounds__(256) void quantize_weights_kernel(const WeightBatch
     }
     if (lb == 0 && threadIdx.x == 0) publish_shared(scale, bad, jb.scale, flag);
     job_share_quantize(jb, lb, inv);
+}
+
+// One scale per output channel: a wave owns channel oc of its tensor, takes the
+// maximum of the channel's c * hw values, publishes the scale and writes the
+// channel's codes [hw][cp].  No barrier, one launch.
+__global__ __launch_bounds__(256) void quantize_weights_pc_kernel(const WeightBatch b, uint32_t *__restrict__ flag)
+{
+    const int j = find_job(b, (int)blockIdx.x);
+    const WeightJob &jb = b.job[j];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int oc = ((int)blockIdx.x - jb.first_block) * 4 + wave;
+    if (oc >= jb.o) return;
+    const int64_t n_row = (int64_t)jb.c * jb.hw, base = (int64_t)oc * n_row;
+    uint32_t m = 0;
+    for (int64_t k = lane; k < n_row; k += 64) {
+        const float v = jb.bf16 ? bf16_to_f32(((const uint16_t *)jb.x)[base + k]) : ((const float *)jb.x)[base + k];
+        const uint32_t a = abs_bits(v);
+        m = m > a ? m : a;
+    }
+    m = wave_max_u32(m);
+    float scale;
+    bool bad;
+    const float inv = scale_from_bits(m, nullptr, &scale, &bad);
+    if (lane == 0) publish_shared(scale, bad, jb.scale + oc, flag);
+    const int cpu = jb.cp >> 4;
+    const int units = jb.hw * cpu;
+    for (int u = lane; u < units; u += 64) {
+        const int pix = u / cpu, c0 = (u - pix * cpu) << 4;
+        uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (c0 + e < jb.c) {
+                const int64_t idx = base + (int64_t)(c0 + e) * jb.hw + pix;
+                const float v = jb.bf16 ? bf16_to_f32(((const uint16_t *)jb.x)[idx]) : ((const float *)jb.x)[idx];
+                w[e >> 2] |= quant1(v, inv) << ((e & 3) * 8);
+            }
+        *(uint4 *)(jb.q + ((int64_t)oc * units + u) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, uint32_t *flag, hipStream_t st)
+{
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_pc_kernel, dim3((unsigned)total_blocks), dim3(256), 0, st, b,
+                    flag);
 }
 
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,

@@ -22,7 +22,7 @@ class PlasticityEvaluator:
 
     def __init__(self, kind: int, dims: dict, weights: Sequence[torch.Tensor],
                  biases: Sequence[Optional[torch.Tensor]], device="cuda",
-                 act_scales: Optional[torch.Tensor] = None):
+                 act_scales: Optional[torch.Tensor] = None, per_channel: bool = False):
         self.weights = [w.contiguous() for w in weights]
         self.biases = list(biases)
         self.desc = eg.make_desc(kind, dims)
@@ -35,9 +35,10 @@ class PlasticityEvaluator:
             else:
                 shape = (w.shape[0], eg.padded(w.shape[1]))
             self.w_q.append(torch.empty(shape, dtype=torch.int8, device=device))
-            self.scales.append(torch.empty(1, dtype=torch.float32, device=device))
+            self.scales.append(torch.empty(w.shape[0] if per_channel else 1, dtype=torch.float32, device=device))
         self._lin = (eg.QLinear * len(self.weights))()
         for i in range(len(self.weights)):
+            self._lin[i].per_channel = 1 if per_channel else 0
             self._lin[i].w_q = self.w_q[i].data_ptr()
             self._lin[i].scale = self.scales[i].data_ptr()
             self._lin[i].bias = 0 if self.biases[i] is None else self.biases[i].data_ptr()
@@ -50,7 +51,7 @@ class PlasticityEvaluator:
         self.act_scales = act_scales
         self.qw.act_scale = None if act_scales is None else act_scales.data_ptr()
         self.qws = eg.workspace(eg.quantize_weights_workspace_bytes(len(self.weights)), device)
-        self._wtab = eg.weight_table(self.weights, self.w_q, self.scales)
+        self._wtab = eg.weight_table(self.weights, self.w_q, self.scales, per_channel)
         nbytes = eg.workspace_bytes(self.desc)
         if nbytes == 0:
             raise ValueError("invalid layer-module description")

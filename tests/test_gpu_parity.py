@@ -474,3 +474,54 @@ def test_bert_stack_full_size(eg, gc, orc):
     for l in range(2):
         want = orc.sp_loss(a_t[l].cpu().numpy(), ot["a_ref"][l])
         assert p_close(p[l].item(), want, b), (l, p[l].item(), want)
+
+
+PER_CHANNEL_CASES = [("fc", dict(b=5, k=100, n=7)), ("fc", dict(b=130, k=200, n=257)),
+                     ("basic", dict(b=2, c=20, h=9, w=11)), ("basic", dict(b=5, c=16, h=32, w=32)),
+                     ("bottleneck", dict(b=1, c_in=40, c_mid=24, h=7, w=3)),
+                     ("bottleneck", dict(b=3, c_in=256, c_mid=64, h=14, w=14)),
+                     ("bert", dict(b=3, s=40, hidden=128, heads=4, ffn=200, n_layers=2))]
+
+
+@pytest.mark.parametrize("kind,kw", PER_CHANNEL_CASES,
+                         ids=lambda v: v if isinstance(v, str) else "_".join(f"{k}{x}" for k, x in v.items()))
+def test_per_channel_weights_bit_exact(eg, gc, orc, kind, kw):
+    """Weights quantised with one scale per output channel: the library's codes and scales, every
+    observation point of the forward and the score agree with the oracle."""
+    if kind == "bert":
+        wl, conv = si.make_bert(seed=740, train_act_dtype="f32", **kw), False
+    else:
+        wl, conv = _static_workload(kind, kw)
+    # channels of very different magnitude, so that one scale per tensor would not do
+    rng = np.random.default_rng(9)
+    wl.weights = [(w * np.exp(rng.uniform(-2, 2, size=(w.shape[0],) + (1,) * (w.ndim - 1)))).astype(np.float32)
+                  for w in wl.weights]
+    W = [gc.to_dev(w) for w in wl.weights]
+    B = [None if b is None else gc.to_dev(b) for b in wl.biases]
+    ref = eg.make_reference(wl.kind, wl.dims, W, B, None, per_channel=True)
+    oqw = orc.quantize_weights(wl.weights, per_channel=True)
+    for (wq, sw), q, s_ in zip(oqw, ref.w_q, ref.scales):
+        assert np.array_equal(s_.cpu().numpy(), sw)
+        if wq.ndim == 4:
+            gc.assert_conv_q(q.cpu().numpy().reshape(-1, q.shape[-1]), wq)
+        else:
+            gc.assert_int8_rows(q.cpu().numpy(), wq)
+    ot = orc.ref_forward(wl, oqw)
+    x = gc.to_dev(wl.x)
+    n_layers = wl.dims.get("n_layers", 1)
+    a_ref = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    taps, bufs, _keep = eg.make_taps(ref, gc.tap_shapes(wl), gc.DEV)
+    eg.ref_forward(ref, x, a_ref, ws, taps)
+    torch.cuda.synchronize()
+    assert eg.check(ws) == eg.OK
+    got = a_ref.cpu().numpy().reshape(n_layers, wl.batch, -1)
+    if kind == "bert":
+        for l in range(n_layers):
+            assert np.array_equal(got[l], np.asarray(ot["a_ref"][l]).reshape(wl.batch, -1))
+            _check_bert_layer_taps(gc, [{k: v.cpu().numpy() for k, v in b.items()} for b in bufs], ot, l)
+    else:
+        for i in range(len(bufs)):
+            _check_linear_taps(gc, {k: v.cpu().numpy() for k, v in bufs[i].items()}, ot, f"l{i}.", conv=conv)
+        want = gc.nhwc(ot["a_ref"]).reshape(wl.batch, -1) if conv else ot["a_ref"]
+        assert np.array_equal(got[0], want)

@@ -438,3 +438,38 @@ def test_static_scales_reduce_to_dynamic_and_saturate(orc):
     assert q.min() == -127 and q.max() == 127 and (q[np.abs(x) > 1.28] != 0).all()
     inside = np.abs(x) <= 1.27
     assert (np.abs(x[inside] - q[inside].astype(np.float32) * s) <= 0.005 * (1 + 1e-4)).all()
+
+
+def test_per_channel_weight_scales(orc):
+    """One scale per output channel: every channel obeys the per-tensor rule on its own (its largest
+    weight maps to +-127, round-trip error <= scale_c / 2); a channel-wise rescaling of the weights leaves
+    the codes unchanged and, with power-of-two factors, rescales the outputs exactly; and a matrix whose rows
+    differ by orders of magnitude is represented far better than with one scale."""
+    import synth_inputs as si
+    rng = np.random.default_rng(3)
+    w = rng.standard_normal((12, 40)).astype(np.float32) * np.logspace(-3, 1, 12, dtype=np.float32)[:, None]
+    q, s = orc.quantize_per_channel(w)
+    assert s.shape == (12,) and (np.abs(q).max(axis=1) == 127).all()
+    assert (np.abs(w - q.astype(np.float32) * s[:, None]) <= 0.5 * s[:, None] * (1 + 1e-4)).all()
+    for o in range(12):
+        qo, so = orc.quantize(w[o])
+        assert so == s[o] and np.array_equal(qo, q[o])
+    qt, st = orc.quantize(w)
+    err_pc = np.abs(w - q.astype(np.float32) * s[:, None]).sum(axis=1) / np.abs(w).sum(axis=1)
+    err_pt = np.abs(w - qt.astype(np.float32) * st).sum(axis=1) / np.abs(w).sum(axis=1)
+    assert err_pc.max() < 0.02 and err_pt[0] > 0.9          # the small rows vanish under one scale
+    # channel-wise power-of-two rescaling: same codes, outputs scaled exactly
+    wl = si.make_fc(b=5, k=24, n=6, seed=21)
+    f = np.array([1, 2, 0.5, 4, 8, 0.25], np.float32)
+    qw1 = orc.quantize_weights(wl.weights, per_channel=True)
+    qw2 = orc.quantize_weights([wl.weights[0] * f[:, None]], per_channel=True)
+    assert np.array_equal(qw1[0][0], qw2[0][0]) and np.array_equal(qw1[0][1] * f, qw2[0][1])
+    nb = [None]
+    y1 = orc.fc_relu(wl.x, qw1, nb)["a_ref"]
+    y2 = orc.fc_relu(wl.x, qw2, nb)["a_ref"]
+    assert np.array_equal(y1 * f[None, :], y2)
+    # a uniform scale vector is the per-tensor epilogue
+    acc = rng.integers(-5000, 5000, size=(7, 6)).astype(np.int32)
+    a = orc.dequant_bias_act(acc, 0.01, np.float32(0.03), None, orc.ACT_RELU)
+    b = orc.dequant_bias_act(acc, 0.01, np.full(6, 0.03, np.float32), None, orc.ACT_RELU)
+    assert np.array_equal(a, b)
