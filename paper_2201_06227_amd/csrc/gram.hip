@@ -15,11 +15,19 @@
 // Kernel 1 (gram_partial): split-K over D.  A workgroup owns one chunk of D and
 //   one macro tile of both products: 64x64 (four 32x32 blocks, one per wave) for
 //   b > 32, or the single 32x32 block for b <= 32 with the four waves splitting
-//   each K tile.  Sample rows are fetched with full-line coalesced loads into a
-//   double-buffered LDS stage (the next tile's loads are in flight while the
-//   current one is contracted) and read back as 128-bit v_mfma_f32_32x32x2f32
-//   operands: lane l takes row l % 32 and four consecutive k at 8s + 4(l / 32),
-//   A and B operand alike, so the order of k inside the sum never matters.
+//   each K tile.  Every fp32 product of the two contractions is formed exactly
+//   on the bf16 matrix cores: an fp32 value is the sum of three bf16 values
+//   (8 + 8 + 8 significant bits, obtained by truncation and exact subtraction),
+//   so x * y = sum of nine bf16 x bf16 products, each exact in fp32; the six
+//   largest are issued (v_mfma_f32_32x32x16_bf16, fp32 accumulation), the three
+//   dropped ones sum to less than 2^-21 of the product.  Six bf16 MFMAs cost 0.375 of the
+//   eight fp32 MFMAs they replace.  Sample rows are fetched with coalesced loads
+//   one K tile ahead into registers, split once per element, and written to LDS
+//   as bf16 planes (hi / mid / lo of T-R, T+R and R) in 16-byte units whose
+//   position is xor-rotated by the row so that writes and the 128-bit operand
+//   reads are bank-conflict free.  Lane l supplies row l % 32 and the 8 values of
+//   unit l / 32 of a 16-deep slab, A and B operand alike, so the order of k
+//   inside the sum never matters.
 //   Each workgroup stores its M block twice, as is and transposed, so that
 //   the next kernel reads rows only.
 // Kernel 2 (sp_finalize): one workgroup per row i of the b x b matrices.  It
@@ -33,12 +41,14 @@
 namespace egeria {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 struct GramPlan {
     int mt;          // blocks of 32 per macro-tile side: 1 (b <= 32) or 2
     int nm;          // macro tiles per side
     int nmacro;      // nm * nm
-    int kt;          // K tile in floats: 128 (mt = 1) or 32 (mt = 2)
+    int kt;          // features per K tile: 64 (mt = 1) or 32 (mt = 2)
     int nsplit;      // chunks of D
     int nsplit_pad;  // rounded up to a multiple of 8 (chunks are dealt to XCDs)
     int64_t kc;      // chunk length, multiple of kt
@@ -50,7 +60,7 @@ static GramPlan plan_gram(int32_t b, int64_t D)
     p.mt = b <= 32 ? 1 : 2;
     p.nm = p.mt == 1 ? 1 : (b + 63) / 64;
     p.nmacro = p.nm * p.nm;
-    p.kt = p.mt == 1 ? 128 : 32;
+    p.kt = p.mt == 1 ? 64 : 32;
     int64_t want = (512 + p.nmacro - 1) / p.nmacro;       // about two workgroups per CU
     int64_t cap = D / ((p.mt == 1 ? 4 : 2) * (int64_t)b);  // bound the partials by a fraction of the input bytes
     if (cap < 1) cap = 1;
@@ -73,16 +83,19 @@ size_t plasticity_partial_bytes(int32_t b, int64_t D)
     return off_partials(b) + align_up((size_t)p.nsplit * 3 * (size_t)b * b * sizeof(float), 256);
 }
 
-// ---- global -> register staging of one [rows x KT] tile -------------------------------
-// Thread `tid` owns float4 slots tid, tid + 256, ... of the tile (row-major
-// slots, KT/4 per row), so that a wave reads whole 128-byte lines.
-template <int DT>
+// ---- four consecutive features of one sample row, as fp32 -------------------------------
+// FAST: rows are 16-byte aligned and every K tile is whole, so the load is
+// unconditional (the caller clamps row and tile to valid ones; what a clamped
+// load returns only reaches outputs that are never stored).  Unconditional
+// loads also let the compiler count outstanding requests exactly, which the
+// two-tile-deep prefetch depends on.  Otherwise: zeros for a row beyond b or
+// features beyond the chunk's end, scalar loads.
+template <int DT, bool FAST>
 __device__ __forceinline__ float4 load4(const void *__restrict__ base, int64_t row, bool row_ok,
-                                        int64_t D, int64_t k, int64_t kend, bool vec)
+                                        int64_t D, int64_t k, int64_t kend)
 {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (!row_ok || k >= kend) return v;
-    if (vec && k + 4 <= kend) {
+    if (FAST) {
         if (DT == 0) {
             v = *(const float4 *)((const float *)base + row * D + k);
         } else {
@@ -92,33 +105,64 @@ __device__ __forceinline__ float4 load4(const void *__restrict__ base, int64_t r
             v.z = __uint_as_float(q.y << 16);
             v.w = __uint_as_float(q.y & 0xffff0000u);
         }
-    } else {
-        float e[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (k + i < kend)
-                e[i] = DT == 0 ? ((const float *)base)[row * D + k + i]
-                               : bf16_to_f32(((const uint16_t *)base)[row * D + k + i]);
-        v = make_float4(e[0], e[1], e[2], e[3]);
+        return v;
     }
-    return v;
+    if (!row_ok || k >= kend) return v;
+    float e[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (k + i < kend)
+            e[i] = DT == 0 ? ((const float *)base)[row * D + k + i]
+                           : bf16_to_f32(((const uint16_t *)base)[row * D + k + i]);
+    return make_float4(e[0], e[1], e[2], e[3]);
 }
 
-template <int MT, int TDT, int RDT>
+// The three bf16 parts of eight fp32 values, packed as the 16-byte operand unit
+// of the bf16 MFMA.  hi = the value truncated to bf16, mid = the remainder
+// truncated, lo = what is left; both subtractions are exact and lo has at most
+// eight significant bits, so hi + mid + lo == x exactly.
+struct Split8 {
+    v4u h, m, l;
+};
+__device__ __forceinline__ uint32_t pack_hi16(float x1, float x0)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
+}
+__device__ __forceinline__ Split8 split8(const float (&x)[8])
+{
+    Split8 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float x0 = x[2 * e], x1 = x[2 * e + 1];
+        const float r0 = x0 - __uint_as_float(__float_as_uint(x0) & 0xffff0000u);
+        const float r1 = x1 - __uint_as_float(__float_as_uint(x1) & 0xffff0000u);
+        const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
+        const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+        o.h[e] = pack_hi16(x1, x0);
+        o.m[e] = pack_hi16(r1, r0);
+        o.l[e] = pack_hi16(l1, l0);
+    }
+    return o;
+}
+
+template <int MT, bool OFFD, int TDT, int RDT, bool FAST>
 __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restrict__ at,
                                                            const void *__restrict__ ar, int b,
-                                                           int64_t D, GramPlan p, bool vec,
+                                                           int64_t D, GramPlan p,
                                                            float *__restrict__ part,
                                                            uint32_t *__restrict__ counter)
 {
     constexpr int ROWS = MT * 32;                 // rows per side of the macro tile
-    constexpr int KT = MT == 1 ? 128 : 32;        // floats per K tile
-    constexpr int LD = KT + 4;                    // padded LDS row
-    constexpr int SLOTS = ROWS * KT / 4;          // float4 slots of one tensor tile
-    constexpr int NIT = SLOTS / 256;              // slots per thread
-    constexpr int NTEN = MT == 1 ? 2 : 4;         // tensors staged: T_i, R_i (, T_j, R_j)
-    static_assert(SLOTS % 256 == 0, "tile must divide over the workgroup");
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // [2 stages][NTEN][ROWS][LD]
+    constexpr int KT = MT == 1 ? 64 : 32;         // features per K tile
+    constexpr int UPR = KT / 8;                   // 16-byte units (8 bf16) per row of a plane
+    constexpr int SWR = 16 / UPR;                 // rows that share a rotation of the units
+    constexpr int PLANE = ROWS * KT * 2;          // bytes of one bf16 plane
+    constexpr int STAGE = (OFFD ? 12 : 9) * PLANE;
+    static_assert(MT == 2 || !OFFD, "a macro tile of one block has no off-diagonal neighbours");
+    static_assert(ROWS * UPR == 256, "one unit per thread and plane");
+    // planes: 0-2 hi/mid/lo of T-R (rows i), 3-5 of R (rows i), 6-8 of T+R (rows j),
+    // 9-11 of R (rows j; off-diagonal macro tiles only, else planes 3-5 serve)
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // [2 stages][planes][ROWS][KT] bf16
 
     // consecutive workgroup ids land on different XCDs: all macro tiles of one
     // chunk go to the same XCD so that its L2 serves the re-reads of that chunk
@@ -128,7 +172,7 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     const int mtile = slot % p.nmacro;
     if (chunk >= p.nsplit) return;
     const int mi = mtile / p.nm, mj = mtile % p.nm;
-    const bool diag = MT == 1 || mi == mj;
+    const bool diag = !OFFD || mi == mj;
     const int64_t k0 = (int64_t)chunk * p.kc;
     const int64_t k1 = k0 + p.kc < D ? k0 + p.kc : D;
     const int ntiles = (int)((k1 - k0 + KT - 1) / KT);
@@ -136,41 +180,60 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
 
-    // rows / columns this thread stages
-    int srow[NIT], scol[NIT];
+    // Staging: thread tid owns unit tid % UPR of row tid / UPR.  Its eight values
+    // are features 4u .. 4u+3 and KT/2 + 4u .. KT/2 + 4u+3 of the tile (two 16-byte
+    // loads, each contiguous over the threads of a row); which features share a
+    // unit is free as long as every plane uses the same assignment.
+    const int srow = tid / UPR, su = tid % UPR;
+    int64_t row_i = (int64_t)mi * ROWS + srow, row_j = (int64_t)mj * ROWS + srow;
+    const bool ok_i = row_i < b, ok_j = row_j < b;
+    row_i = ok_i ? row_i : 0;                     // rows beyond b: a valid address for the unconditional loads
+    row_j = ok_j ? row_j : 0;
+    const uint32_t soff = (uint32_t)(srow * (UPR * 16) + ((su ^ ((srow / SWR) % UPR)) * 16));
+    struct Staged {
+        float4 t[2], r[2], tj[2], rj[2];
+    };
+    auto fetch = [&](int t, Staged &s) {
+        // past the chunk's end: the last tile again (FAST; such a tile is never contracted) or zeros
+        const int tt = FAST ? (t < ntiles ? t : ntiles - 1) : t;
+        const int64_t kb = k0 + (int64_t)tt * KT + 4 * su;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int s = tid + it * 256;
-        srow[it] = s / (KT / 4);
-        scol[it] = (s % (KT / 4)) * 4;
-    }
-    // Two register sets: global loads run two K tiles ahead of the MFMAs (one
-    // tile of MFMAs is shorter than an HBM round trip), LDS holds two stages.
-    auto fetch = [&](int t, float4 (&st)[NTEN][NIT]) {
-        const int64_t kb = k0 + (int64_t)t * KT;       // past the chunk's end load4 returns zeros
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int64_t ri = (int64_t)mi * ROWS + srow[it];
-            st[0][it] = load4<TDT>(at, ri, ri < b, D, kb + scol[it], k1, vec);
-            st[1][it] = load4<RDT>(ar, ri, ri < b, D, kb + scol[it], k1, vec);
-            if (NTEN == 4 && !diag) {
-                const int64_t rj = (int64_t)mj * ROWS + srow[it];
-                st[2][it] = load4<TDT>(at, rj, rj < b, D, kb + scol[it], k1, vec);
-                st[3][it] = load4<RDT>(ar, rj, rj < b, D, kb + scol[it], k1, vec);
+        for (int q = 0; q < 2; ++q) {
+            const int64_t k = kb + q * (KT / 2);
+            s.t[q] = load4<TDT, FAST>(at, row_i, ok_i, D, k, k1);
+            s.r[q] = load4<RDT, FAST>(ar, row_i, ok_i, D, k, k1);
+            if (OFFD && !diag) {
+                s.tj[q] = load4<TDT, FAST>(at, row_j, ok_j, D, k, k1);
+                s.rj[q] = load4<RDT, FAST>(ar, row_j, ok_j, D, k, k1);
             }
         }
     };
-    auto stash = [&](int stage, const float4 (&st)[NTEN][NIT]) {
-        float *base = lds + (size_t)stage * NTEN * ROWS * LD;
+    auto put = [&](int stage, int plane, const float (&x)[8]) {
+        const Split8 sp = split8(x);
+        uint8_t *base = lds + stage * STAGE + plane * PLANE + soff;
+        *(v4u *)(base) = sp.h;
+        *(v4u *)(base + PLANE) = sp.m;
+        *(v4u *)(base + 2 * PLANE) = sp.l;
+    };
+    auto stash = [&](int stage, const Staged &s) {
+        const float t8[8] = {s.t[0].x, s.t[0].y, s.t[0].z, s.t[0].w, s.t[1].x, s.t[1].y, s.t[1].z, s.t[1].w};
+        const float r8[8] = {s.r[0].x, s.r[0].y, s.r[0].z, s.r[0].w, s.r[1].x, s.r[1].y, s.r[1].z, s.r[1].w};
+        float d8[8], s8[8];
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int o = srow[it] * LD + scol[it];
-            *(float4 *)&base[0 * ROWS * LD + o] = st[0][it];
-            *(float4 *)&base[1 * ROWS * LD + o] = st[1][it];
-            if (NTEN == 4 && !diag) {
-                *(float4 *)&base[2 * ROWS * LD + o] = st[2][it];
-                *(float4 *)&base[3 * ROWS * LD + o] = st[3][it];
-            }
+        for (int e = 0; e < 8; ++e) d8[e] = t8[e] - r8[e];
+        put(stage, 0, d8);
+        put(stage, 3, r8);
+        if (OFFD && !diag) {
+            const float tj8[8] = {s.tj[0].x, s.tj[0].y, s.tj[0].z, s.tj[0].w, s.tj[1].x, s.tj[1].y, s.tj[1].z, s.tj[1].w};
+            const float rj8[8] = {s.rj[0].x, s.rj[0].y, s.rj[0].z, s.rj[0].w, s.rj[1].x, s.rj[1].y, s.rj[1].z, s.rj[1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s8[e] = tj8[e] + rj8[e];
+            put(stage, 6, s8);
+            put(stage, 9, rj8);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s8[e] = t8[e] + r8[e];
+            put(stage, 6, s8);
         }
     };
 
@@ -181,50 +244,69 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     // operand rows of this wave inside the macro tile
     const int bi = MT == 1 ? 0 : (wave >> 1), bj = MT == 1 ? 0 : (wave & 1);
     const int rowA = bi * 32 + r, rowB = bj * 32 + r;
-    const int kw0 = MT == 1 ? wave * 32 : 0;      // this wave's 32-float slice of the K tile
+    const uint32_t offA = (uint32_t)(rowA * (UPR * 16)), swA = (uint32_t)((rowA / SWR) % UPR);
+    const uint32_t offB = (uint32_t)(rowB * (UPR * 16)), swB = (uint32_t)((rowB / SWR) % UPR);
+    const int planeRj = diag ? 3 : 9;
 
-    auto contract = [&](int stage) {
-        const float *base = lds + (size_t)stage * NTEN * ROWS * LD;
-        const float *pTi = base + 0 * ROWS * LD + rowA * LD + kw0 + 4 * h;
-        const float *pRi = base + 1 * ROWS * LD + rowA * LD + kw0 + 4 * h;
-        const float *pTj = base + (diag ? 0 : 2) * ROWS * LD + rowB * LD + kw0 + 4 * h;
-        const float *pRj = base + (diag ? 1 : 3) * ROWS * LD + rowB * LD + kw0 + 4 * h;
-        float4 ti[4], ri[4], tj[4], rj[4];
+    // One 16-deep slab: unit 2 * slab + h of the operand rows, six partial
+    // products per fp32 product, smallest first.
+    auto slab = [&](int stage, int sl) {
+        const uint32_t u = (uint32_t)(2 * sl + h);
+        const uint8_t *pa = lds + stage * STAGE + offA + ((u ^ swA) * 16);
+        const uint8_t *pb = lds + stage * STAGE + offB + ((u ^ swB) * 16);
+        v8bf dA[3], rA[3], sB[3], rB[3];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            ti[s] = *(const float4 *)(pTi + 8 * s);
-            ri[s] = *(const float4 *)(pRi + 8 * s);
-            tj[s] = *(const float4 *)(pTj + 8 * s);
-            rj[s] = *(const float4 *)(pRj + 8 * s);
+        for (int c = 0; c < 3; ++c) {
+            dA[c] = __builtin_bit_cast(v8bf, *(const v4u *)(pa + (0 + c) * PLANE));
+            rA[c] = __builtin_bit_cast(v8bf, *(const v4u *)(pa + (3 + c) * PLANE));
+            sB[c] = __builtin_bit_cast(v8bf, *(const v4u *)(pb + (6 + c) * PLANE));
+            rB[c] = __builtin_bit_cast(v8bf, *(const v4u *)(pb + (planeRj + c) * PLANE));
         }
+        constexpr int ia[6] = {2, 0, 1, 1, 0, 0}, ib[6] = {0, 2, 1, 0, 1, 0};   // (lo,hi) (hi,lo) (mid,mid) (mid,hi) (hi,mid) (hi,hi)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].x - ri[s].x, tj[s].x + rj[s].x, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].x, rj[s].x, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].y - ri[s].y, tj[s].y + rj[s].y, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].y, rj[s].y, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].z - ri[s].z, tj[s].z + rj[s].z, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].z, rj[s].z, accB, 0, 0, 0);
-            accM = __builtin_amdgcn_mfma_f32_32x32x2f32(ti[s].w - ri[s].w, tj[s].w + rj[s].w, accM, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_f32_32x32x2f32(ri[s].w, rj[s].w, accB, 0, 0, 0);
+        for (int q = 0; q < 6; ++q) {
+            accM = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dA[ia[q]], sB[ib[q]], accM, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rA[ia[q]], rB[ib[q]], accB, 0, 0, 0);
         }
     };
 
-    float4 st0[NTEN][NIT], st1[NTEN][NIT];
+    // Software pipeline: during step t the matrix cores contract tile t from LDS
+    // stage t & 1 while tile t + 1, already in registers, is split into the other
+    // stage; tile t + 2 is in flight (requested one step ago) and tile t + 3 is
+    // requested into the registers that tile t + 1 has just left.  One barrier
+    // per tile.
+    auto contract = [&](int stage) {
+        if (MT == 1) {
+            slab(stage, wave);
+        } else {
+            slab(stage, 0);
+            slab(stage, 1);
+        }
+    };
+    Staged st0, st1;
     fetch(0, st0);
     fetch(1, st1);
     stash(0, st0);
+    fetch(2, st0);
     __syncthreads();
-    // step t: tile t is in LDS stage t & 1, tile t + 1 in the set `rs`, tile t + 2 is requested into `rl`
-    auto step = [&](int t, float4 (&rs)[NTEN][NIT], float4 (&rl)[NTEN][NIT]) {
-        fetch(t + 2, rl);
+    auto step = [&](int t, Staged &next) {
         contract(t & 1);
-        stash((t + 1) & 1, rs);
+        stash((t + 1) & 1, next);
+        fetch(t + 3, next);
+        // issue order: the splitting arithmetic of the next tile between the MFMAs
+        // of this one (an MFMA occupies the matrix pipe for 8 passes, the vector
+        // ALU is free meanwhile)
+        constexpr int NMF = MT == 1 ? 12 : 24;
+#pragma unroll
+        for (int i = 0; i < NMF; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, MT == 1 ? 12 : 6, 0);     // vector ALU
+        }
         __syncthreads();
     };
-    for (int t = 0; t < ntiles; t += 2) {         // an odd count runs one extra step on zeros
-        step(t, st1, st0);
-        step(t + 1, st0, st1);
+    for (int t = 0; t < ntiles; t += 2) {
+        step(t, st1);
+        if (t + 1 < ntiles) step(t + 1, st0);
     }
 
     // lane l of a 32x32 block holds column l % 32, rows 8 * (i / 4) + 4 * (l / 32) + i % 4
@@ -233,7 +315,7 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
     if (id == 0 && tid == 0) *counter = 0u;                       // ticket of the finaliser
     if (MT == 1) {
         // the four waves hold partial sums over disjoint k: add them through LDS
-        float *red = lds;                         // [4][2][1024], the stage memory is free now
+        float *red = (float *)lds;                // [4][2][1024], the stage memory is free now
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             red[(wave * 2 + 0) * 1024 + i * 64 + lane] = accM[i];
@@ -372,36 +454,43 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     uint32_t *counter = (uint32_t *)ws_part;
     double *rowsum = (double *)((char *)ws_part + off_rowsum());
     float *part = (float *)((char *)ws_part + off_partials(b));
-    const bool vec = (t_dt == EGERIA_F32 ? (D % 4 == 0) : (D % 8 == 0)) &&
-                     (r_dt == EGERIA_F32 ? (D % 4 == 0) : (D % 8 == 0));
+    // whole K tiles and 16-byte aligned rows: the unconditional-load variant
+    const bool vec = D % p.kt == 0;
     const dim3 grid((unsigned)(p.nsplit_pad * p.nmacro)), block(256);
     const int tcode = t_dt == EGERIA_BF16 ? 1 : 0, rcode = r_dt == EGERIA_BF16 ? 1 : 0;
     hipError_t e = hipSuccess;
-#define EGERIA_GRAM(MTV, T, R)                                                                         \
+#define EGERIA_GRAM(MTV, OFF, T, R, V)                                                                 \
     do {                                                                                               \
-        constexpr int rows = MTV * 32, kt = MTV == 1 ? 128 : 32, nten = MTV == 1 ? 2 : 4;              \
-        constexpr size_t smem = (size_t)2 * nten * rows * (kt + 4) * sizeof(float);                    \
+        /* two stages of nine bf16 planes of 4 KiB, twelve when off-diagonal macro tiles exist */      \
+        constexpr size_t smem = (size_t)2 * (OFF ? 12 : 9) * 4096;                                     \
         static bool attr_set = false;                                                                  \
         if (!attr_set) {                                                                               \
-            e = hipFuncSetAttribute((const void *)gram_partial_kernel<MTV, T, R>,                      \
+            e = hipFuncSetAttribute((const void *)gram_partial_kernel<MTV, OFF, T, R, V>,              \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);            \
             if (e != hipSuccess) return e;                                                             \
             attr_set = true;                                                                           \
         }                                                                                              \
-        e = launch_k(EGERIA_KERNEL_GRAM, gram_partial_kernel<MTV, T, R>, grid, block, smem, st, a_t,   \
-                     a_r, (int)b, D, p, vec, part, counter);                                           \
+        e = launch_k(EGERIA_KERNEL_GRAM, gram_partial_kernel<MTV, OFF, T, R, V>, grid, block, smem,    \
+                     st, a_t, a_r, (int)b, D, p, part, counter);                                       \
     } while (0)
-    if (p.mt == 1) {
-        if (!tcode && !rcode) EGERIA_GRAM(1, 0, 0);
-        else if (tcode && !rcode) EGERIA_GRAM(1, 1, 0);
-        else if (!tcode && rcode) EGERIA_GRAM(1, 0, 1);
-        else EGERIA_GRAM(1, 1, 1);
-    } else {
-        if (!tcode && !rcode) EGERIA_GRAM(2, 0, 0);
-        else if (tcode && !rcode) EGERIA_GRAM(2, 1, 0);
-        else if (!tcode && rcode) EGERIA_GRAM(2, 0, 1);
-        else EGERIA_GRAM(2, 1, 1);
-    }
+#define EGERIA_GRAM_DT(MTV, OFF)                                                                       \
+    do {                                                                                               \
+        if (vec) {                                                                                     \
+            if (!tcode && !rcode) EGERIA_GRAM(MTV, OFF, 0, 0, true);                                   \
+            else if (tcode && !rcode) EGERIA_GRAM(MTV, OFF, 1, 0, true);                               \
+            else if (!tcode && rcode) EGERIA_GRAM(MTV, OFF, 0, 1, true);                               \
+            else EGERIA_GRAM(MTV, OFF, 1, 1, true);                                                    \
+        } else {                                                                                       \
+            if (!tcode && !rcode) EGERIA_GRAM(MTV, OFF, 0, 0, false);                                  \
+            else if (tcode && !rcode) EGERIA_GRAM(MTV, OFF, 1, 0, false);                              \
+            else if (!tcode && rcode) EGERIA_GRAM(MTV, OFF, 0, 1, false);                              \
+            else EGERIA_GRAM(MTV, OFF, 1, 1, false);                                                   \
+        }                                                                                              \
+    } while (0)
+    if (p.mt == 1) EGERIA_GRAM_DT(1, false);
+    else if (p.nm == 1) EGERIA_GRAM_DT(2, false);
+    else EGERIA_GRAM_DT(2, true);
+#undef EGERIA_GRAM_DT
 #undef EGERIA_GRAM
     if (e != hipSuccess) return e;
     return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(256), 0, st, (const float *)part,
