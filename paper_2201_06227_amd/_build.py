@@ -16,6 +16,10 @@ FLAGS = [
     "-ffp-contract=off",
     # do not form packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the epilogues index their accumulator arrays with fully unrolled loops (up to 4 x 4 x 16
+    # iterations of a long body); at the default limit the largest tile's loops stay rolled and
+    # its accumulators end up in scratch memory
+    "-mllvm", "-pragma-unroll-threshold=200000",
 ]
 
 

@@ -6,17 +6,17 @@
 //   y[m, n]   = act( fma((float)acc, sx*sw, bias[n]) [+ residual] )
 //
 // One workgroup of 4 waves owns a BM x BN tile of the output (256x256 down to
-// 128x32, chosen so that the grid still fills the chip).  Per K step of 64
-// bytes the tile's A and W rows are staged through a double-buffered LDS stage
-// (16-byte units, rows padded to 80 bytes so that the 128-bit operand reads of
-// a wave fall on distinct banks): the next step's global loads are issued
-// before the current step's MFMAs and land in the other buffer after them, so
-// there is one barrier per step.  Each wave issues v_mfma_i32_32x32x32_i8:
-// lane l supplies 16 consecutive K bytes of row (l % 32) at K offset
-// 16 * (l / 32) for A and for W alike, so the product is exact whatever the
-// instruction's internal K order is.  Workgroup ids are dealt so that each XCD
-// works on a contiguous range of tiles (N fastest) and its L2 serves the
-// re-reads of A rows and of the weights.
+// 128x32, chosen so that the grid still fills the chip).  Per K step of 64 or
+// 128 bytes the tile's A and W rows go from global memory straight into a ring
+// of LDS stages (buffer loads with the LDS modifier; 16-byte units, rotated by
+// an exclusive-or of the row so that the 128-bit operand reads of a wave fall
+// on distinct banks): while the matrix cores work on one stage the following
+// steps are landing in the others, one barrier per step.  Each wave issues
+// v_mfma_i32_32x32x32_i8: lane l supplies 16 consecutive K bytes of row
+// (l % 32) at K offset 16 * (l / 32) for A and for W alike, so the product is
+// exact whatever the instruction's internal K order is.  Workgroup ids are
+// dealt so that each XCD works on a contiguous range of tiles (N fastest) and
+// its L2 serves the re-reads of A rows and of the weights.
 #include "common.hpp"
 #include <type_traits>
 
@@ -58,8 +58,17 @@ __device__ __forceinline__ void load_to_lds_b128(v4i rsrc, uint32_t lds_base, ui
                  : "memory", "m0");
 }
 
+// Workgroups of a tile shape that are meant to share a CU (one wave of each per
+// SIMD): the register allocation is held to 512 / that many registers per lane,
+// so that one workgroup's epilogue overlaps another's K loop.
+constexpr int resident_target(int bm, int bn)
+{
+    return bm * bn > 256 * 128 ? 1 : (bm * bn > 128 * 128 ? 2 : 3);
+}
+
 template <int BM, int BN, int WM, int WN, bool CONV, int BK>
-__global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tiles, int tiles_per_xcd)
+__global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(const GemmArgs g, int tiles,
+                                                                               int tiles_per_xcd)
 {
     static_assert(BK == 64 || BK == 128, "K step of 64 or 128 bytes");
     constexpr int kBK = BK;
@@ -273,6 +282,14 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(const GemmArgs g, int tile
         mfma_all(fa1, fb1);
         hint();
         st = st1;
+        if (TM * TN == 16) {
+            // 256 accumulators per lane: name the accumulation registers as their home, or the
+            // allocator splits them between the two register files and spills inside the loop
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the zero-filled K steps past the end
 
@@ -459,7 +476,7 @@ struct TileShape {
 };
 constexpr int kNumShapes = 9;
 static const TileShape kShapes[kNumShapes] = {
-    {256, 256, 128, 1, 1.00}, {256, 192, 128, 1, 1.03}, {256, 128, 64, 2, 1.06}, {128, 192, 64, 2, 1.10},
+    {256, 256, 64, 1, 1.00},  {256, 192, 128, 1, 1.03}, {256, 128, 64, 2, 1.06}, {128, 192, 64, 2, 1.10},
     {128, 128, 64, 3, 1.20},  {128, 128, 128, 2, 1.22}, {128, 64, 64, 4, 1.40},  {128, 64, 128, 3, 1.38},
     {256, 128, 128, 1, 1.05},
 };
@@ -467,7 +484,7 @@ static const TileShape kShapes[kNumShapes] = {
 static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
 {
     switch (i) {
-    case 0: return launch_variant<256, 256, 2, 2, 128>(g, st);
+    case 0: return launch_variant<256, 256, 2, 2, 64>(g, st);
     case 1: return launch_variant<256, 192, 2, 2, 128>(g, st);
     case 2: return launch_variant<256, 128, 2, 2, 64>(g, st);
     case 3: return launch_variant<128, 192, 2, 2, 64>(g, st);

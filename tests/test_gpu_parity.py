@@ -395,6 +395,11 @@ def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
     for l in range(kw["n_layers"]):
         _check_bert_layer_taps(gc, taps, ot, l)
         assert (a_ref[l] == ot["a_ref"][l].reshape(kw["b"], -1)).all()
+    # an unobserved run never stores the first feed-forward layer's pre-activations (the
+    # GEMM runs as a maximum pass and a pass that writes the codes of gelu(y)): same bits
+    plain, _, _ = gc.run_forward(wl, with_taps=False)
+    for l in range(kw["n_layers"]):
+        assert (plain[l] == ot["a_ref"][l].reshape(kw["b"], -1)).all(), l
     a_t = si.train_forward(wl)
     ws = eg.workspace(eg.workspace_bytes(ref.desc))
     p = torch.zeros(kw["n_layers"], dtype=torch.float32, device=gc.DEV)
@@ -417,6 +422,10 @@ def test_bert_small_preactivations(eg, gc, orc):
     for l in range(2):
         _check_bert_layer_taps(gc, taps, ot, l)
         assert (a_ref[l] == ot["a_ref"][l].reshape(2, -1)).all()
+    # unobserved run: the exact maximum comes from a GEMM pass of its own
+    plain, _, _ = gc.run_forward(wl, with_taps=False)
+    for l in range(2):
+        assert (plain[l] == ot["a_ref"][l].reshape(2, -1)).all(), l
 
 
 def test_bert_layer_full_size(eg, gc, orc):
@@ -426,6 +435,8 @@ def test_bert_layer_full_size(eg, gc, orc):
     ot = orc.ref_forward(wl)
     _check_bert_layer_taps(gc, taps, ot, 0)
     assert (a_ref[0] == ot["a_ref"][0].reshape(32, -1)).all()
+    plain, _, _ = gc.run_forward(wl, with_taps=False)
+    assert (plain[0] == ot["a_ref"][0].reshape(32, -1)).all()
     a_t = si.train_forward(wl)
     assert a_t[0].dtype == torch.bfloat16
     ws = eg.workspace(eg.workspace_bytes(ref.desc))
@@ -520,6 +531,11 @@ def test_per_channel_weights_bit_exact(eg, gc, orc, kind, kw):
         for l in range(n_layers):
             assert np.array_equal(got[l], np.asarray(ot["a_ref"][l]).reshape(wl.batch, -1))
             _check_bert_layer_taps(gc, [{k: v.cpu().numpy() for k, v in b.items()} for b in bufs], ot, l)
+        # unobserved run (per-column scales in the GELU-fused passes of the first feed-forward layer)
+        plain = torch.empty_like(a_ref)
+        eg.ref_forward(ref, x, plain, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(plain.cpu().numpy().reshape(n_layers, wl.batch, -1), got)
     else:
         for i in range(len(bufs)):
             _check_linear_taps(gc, {k: v.cpu().numpy() for k, v in bufs[i].items()}, ot, f"l{i}.", conv=conv)
