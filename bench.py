@@ -29,8 +29,12 @@ WORKLOAD_NAMES = {
 
 PEAK_HBM_GBS = 8000.0
 PEAK_I8_TOPS = 5033.0        # dense int8 MFMA, 256 CUs x 8192 op/clk x 2.4 GHz
-PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_F64_MFMA_TFLOPS = 78.6
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+# The metric's two Gram products multiply fp32 values exactly on the bf16 matrix cores: six bf16
+# partial products per fp32 product, so the rate of fp32-product flops the matrix cores can sustain
+# is a sixth of the bf16 peak.  The algorithmic flop count (2 b^2 D per product) is priced against it.
+PEAK_GRAM_TFLOPS = PEAK_BF16_MFMA_TFLOPS / 6.0
 
 
 def algorithmic_work(wl, cls, eg):
@@ -127,7 +131,8 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None):
     elif cls == eg.KERNEL_ATTENTION:
         peak_c, unit_c, scale = PEAK_F64_MFMA_TFLOPS, "TFLOP/s", 1e12
     else:
-        peak_c, unit_c, scale = PEAK_F32_MFMA_TFLOPS, "TFLOP/s", 1e12
+        # the Gram products are fp32 x fp32 formed exactly as six bf16 partial products each
+        peak_c, unit_c, scale = PEAK_GRAM_TFLOPS, "TFLOP/s", 1e12
     ridge = peak_c * scale / (PEAK_HBM_GBS * 1e9)
     if intensity >= ridge:
         achieved, peak, unit, bound = ops / total_s / scale, peak_c, unit_c, "mfma"
@@ -319,6 +324,53 @@ def freeze_decision_timing(eg, with_oracle):
     return out
 
 
+def activation_cache_timing(eg, device, with_oracle):
+    """Activation cache (Section 4.3): a mini-batch of activations put in and read back by sample id,
+    rows of the default workload's shape, window of five.  The row copies are bound by HBM: each row is
+    read once and written once, 2 * row bytes; their launches are timed with HIP events."""
+    import numpy as np
+    import torch
+    b, D, window, reps = 128, 16384, 5, 40
+    cache = eg.ActivationCache(window, b, D, torch.float32, device)
+    rows = torch.randn((b, D), device=device)
+    out = torch.empty_like(rows)
+    hit = torch.zeros(b, dtype=torch.uint8, device=device)
+    ids = [torch.arange(b, device=device, dtype=torch.int64) + b * t for t in range(reps + 5)]
+    for t in range(5):
+        cache.put(ids[t], rows)
+        cache.get(ids[t], out, hit)
+    torch.cuda.synchronize()
+    eg.profile_begin(eg.KERNEL_CACHE_COPY, 2 * reps)
+    t0 = time.perf_counter()
+    for t in range(reps):
+        cache.put(ids[5 + t], rows)
+        cache.get(ids[5 + t], out, hit)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    ms = eg.profile_end(2 * reps)
+    ok = bool(hit.all().item()) and bool(torch.equal(out, rows))
+    byts = 2.0 * b * D * 4
+    avg_s = sum(ms) * 1e-3 / len(ms)
+    res = {"rows": f"{b} x {D} fp32 (8.4 MB per mini-batch), window {window}", "put_plus_get_us": round(dt * 1e6, 2),
+           "minibatches_per_s": round(1.0 / dt, 1), "served_rows_match": ok,
+           "roofline": {"kernel": "cache_scatter_kernel / cache_gather_kernel", "bound": "hbm",
+                        "achieved": round(byts / avg_s / 1e9, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(byts / avg_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                        "avg_launch_us": round(avg_s * 1e6, 3), "algorithmic_bytes_per_launch": byts}}
+    if with_oracle:
+        from oracle.cache_oracle import CacheOracle
+        o = CacheOracle(window)
+        r = rows.cpu().numpy()
+        w = np.empty_like(r)
+        idn = [i.cpu().numpy() for i in ids[:8]]
+        t0 = time.perf_counter()
+        for t in range(8):
+            o.put(idn[t], r)
+            o.get(idn[t], w)
+        res["oracle_put_plus_get_us"] = round((time.perf_counter() - t0) / 8 * 1e6, 1)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -437,6 +489,7 @@ def main():
         del q, out
     result["static_scale_mode"] = static_mode(args.workload, device, args.steps)
     result["freeze_decision"] = freeze_decision_timing(eg, not args.no_cpu)
+    result["activation_cache"] = activation_cache_timing(eg, device, not args.no_cpu)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(result))

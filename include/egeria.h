@@ -300,6 +300,52 @@ egeria_status egeria_freeze_init(egeria_freeze_state *st, int32_t n_modules, int
 egeria_status egeria_freeze_observe(egeria_freeze_state *st, double p, double lr,
                                     egeria_freeze_decision *out);
 
+/* ---------------------------------------------------------------------------
+ * Activation cache (Section 4.3 of the paper, "Caching frozen layers'
+ * activations", Figure 6): a table in GPU memory whose key is the sample id and
+ * whose value is that sample's activation at the last frozen layer.  The
+ * activations of coming mini-batches are put in ahead of the forward pass
+ * (egeria_cache_put; where they come from - storage, an earlier epoch - is the
+ * caller's business), the forward pass of the active layers reads them back by
+ * sample id (egeria_cache_get), and only the most recent `window` mini-batches
+ * are kept (five in the paper).
+ *
+ * Semantics: a put makes its mini-batch the newest one; when `window`
+ * mini-batches are already held the oldest is dropped with its samples, except
+ * those that a newer mini-batch has put in again (they are served from the
+ * newer one).  An id that occurs twice in one put keeps its last row.  Negative
+ * ids are not samples: never stored, never found.  A get copies the row of
+ * every id that is held to out[i] and sets hit[i] = 1; for the others hit[i] = 0
+ * and out[i] is left untouched.
+ *
+ * The cache lives in caller-owned DEVICE memory of egeria_cache_bytes(desc)
+ * bytes (header, ids of the window * batch row slots, an open-addressing table
+ * of at least twice that many entries rebuilt by every put, the rows
+ * themselves), 16-byte aligned.  egeria_cache_init must run once before the
+ * first put.  Calls on one cache must be ordered on one stream; nothing
+ * synchronises, the put counter lives in the cache's own memory, so all three
+ * calls can be captured into a HIP graph.
+ * Limits: 1 <= window, 1 <= batch <= 65535, window * batch <= 2^20, row_elems >= 1;
+ * a put takes at most `batch` ids, a get at most 65535.  ids, rows, out and hit are
+ * DEVICE pointers; rows and out are [n, row_elems] row-major of type `dtype`.
+ * Errors: EGERIA_ERR_INVALID_ARG for a bad descriptor, a null or misaligned
+ * pointer or n out of range; EGERIA_ERR_WORKSPACE_TOO_SMALL when cache_bytes is
+ * below egeria_cache_bytes(desc).
+ * ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t window;        /* mini-batches kept */
+    int32_t batch;         /* most samples one put may bring */
+    int64_t row_elems;     /* elements of one sample's activation */
+    int32_t dtype;         /* egeria_dtype of the rows */
+} egeria_cache_desc;
+
+size_t egeria_cache_bytes(const egeria_cache_desc *desc);                       /* 0 for a bad descriptor */
+egeria_status egeria_cache_init(const egeria_cache_desc *desc, void *cache, size_t cache_bytes, void *stream);
+egeria_status egeria_cache_put(const egeria_cache_desc *desc, void *cache, size_t cache_bytes,
+                               const int64_t *ids, int32_t n, const void *rows, void *stream);
+egeria_status egeria_cache_get(const egeria_cache_desc *desc, const void *cache, size_t cache_bytes,
+                               const int64_t *ids, int64_t n, void *out, uint8_t *hit, void *stream);
+
 /* Instrumentation for benchmarks (not part of the method): time every launch
  * of one kernel class with a pair of HIP events recorded on the launch's own
  * stream, so that a caller can time that kernel inside a larger timed region.
@@ -316,7 +362,8 @@ typedef enum {
     EGERIA_KERNEL_GEMM = 3,         /* int8 GEMM / implicit-GEMM convolution */
     EGERIA_KERNEL_GRAM = 4,         /* split-K Gram partials of the metric   */
     EGERIA_KERNEL_ATTENTION = 5,
-    EGERIA_KERNEL_LAYERNORM = 6
+    EGERIA_KERNEL_LAYERNORM = 6,
+    EGERIA_KERNEL_CACHE_COPY = 7    /* row copies of the activation cache    */
 } egeria_kernel_class;
 
 egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches);

@@ -75,6 +75,10 @@ class FreezeDecision(ctypes.Structure):
                 ("slope", ctypes.c_double), ("T", ctypes.c_double)]
 
 
+class CacheDesc(ctypes.Structure):
+    _fields_ = [("window", _i32), ("batch", _i32), ("row_elems", _i64), ("dtype", _i32)]
+
+
 class EgeriaError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -90,9 +94,11 @@ EXPORTS = [
     "egeria_workspace_bytes", "egeria_check", "egeria_status_string", "egeria_profile_begin",
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
     "egeria_freeze_init", "egeria_freeze_observe",
+    "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get",
 ]
 
-KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM = range(7)
+(KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
+ KERNEL_CACHE_COPY) = range(8)
 
 
 def library_path() -> str:
@@ -148,6 +154,14 @@ def lib():
     L.egeria_freeze_observe.restype = ctypes.c_int
     L.egeria_freeze_observe.argtypes = [ctypes.POINTER(FreezeState), ctypes.c_double, ctypes.c_double,
                                         ctypes.POINTER(FreezeDecision)]
+    L.egeria_cache_bytes.restype = _sz
+    L.egeria_cache_bytes.argtypes = [ctypes.POINTER(CacheDesc)]
+    L.egeria_cache_init.restype = ctypes.c_int
+    L.egeria_cache_init.argtypes = [ctypes.POINTER(CacheDesc), _vp, _sz, _vp]
+    L.egeria_cache_put.restype = ctypes.c_int
+    L.egeria_cache_put.argtypes = [ctypes.POINTER(CacheDesc), _vp, _sz, _vp, _i32, _vp, _vp]
+    L.egeria_cache_get.restype = ctypes.c_int
+    L.egeria_cache_get.argtypes = [ctypes.POINTER(CacheDesc), _vp, _sz, _vp, _i64, _vp, _vp, _vp]
     L.egeria_status_string.restype = ctypes.c_char_p
     L.egeria_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -425,6 +439,32 @@ class FreezeController:
         _check(lib().egeria_freeze_observe(ctypes.byref(self.state), float(p), float(lr), ctypes.byref(d)),
                "egeria_freeze_observe")
         return d
+
+
+class ActivationCache:
+    """egeria_cache_*: the descriptor and the cache memory (a torch byte tensor) held together."""
+
+    def __init__(self, window: int, batch: int, row_elems: int, dtype: torch.dtype = torch.float32,
+                 device: str = "cuda:0"):
+        self.desc = CacheDesc(int(window), int(batch), int(row_elems), BF16 if dtype == torch.bfloat16 else F32)
+        nbytes = int(lib().egeria_cache_bytes(ctypes.byref(self.desc)))
+        if nbytes == 0:
+            raise EgeriaError(ERR_INVALID_ARG, "egeria_cache_bytes")
+        self.mem = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _check(lib().egeria_cache_init(ctypes.byref(self.desc), _ptr(self.mem), nbytes, _stream()), "egeria_cache_init")
+
+    def put(self, ids: torch.Tensor, rows: torch.Tensor) -> None:
+        n = int(ids.numel())
+        _check(lib().egeria_cache_put(ctypes.byref(self.desc), _ptr(self.mem), self.mem.numel(),
+                                      _ptr(_dev(ids)) if n else None, n, _ptr(_dev(rows)) if n else None, _stream()),
+               "egeria_cache_put")
+
+    def get(self, ids: torch.Tensor, out: torch.Tensor, hit: torch.Tensor) -> torch.Tensor:
+        n = int(ids.numel())
+        _check(lib().egeria_cache_get(ctypes.byref(self.desc), _ptr(self.mem), self.mem.numel(),
+                                      _ptr(_dev(ids)) if n else None, n, _ptr(_dev(out)) if n else None,
+                                      _ptr(hit) if n else None, _stream()), "egeria_cache_get")
+        return hit
 
 
 def profile_begin(kernel_class: int, max_launches: int) -> None:

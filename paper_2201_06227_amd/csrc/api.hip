@@ -620,7 +620,7 @@ egeria_status egeria_check(void *ws, void *stream)
 egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches)
 {
     static std::vector<hipEvent_t> starts, stops;
-    if (kernel_class <= EGERIA_KERNEL_NONE || kernel_class > EGERIA_KERNEL_LAYERNORM || max_launches < 1)
+    if (kernel_class <= EGERIA_KERNEL_NONE || kernel_class > EGERIA_KERNEL_CACHE_COPY || max_launches < 1)
         return EGERIA_ERR_INVALID_ARG;
     while ((int)starts.size() < max_launches) {
         hipEvent_t a, b;

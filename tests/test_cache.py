@@ -82,3 +82,100 @@ def test_oracle_against_replay(window, batch, universe):
         assert np.array_equal(hit, want_hit)
         for i, k in enumerate(query):
             assert np.array_equal(out[i], table[int(k)] if hit[i] else np.full(D, 9.0, np.float32))
+
+
+# ----------------------------------------------------------------------------- host-side C-ABI checks
+
+def test_cache_arguments_are_checked_on_the_host():
+    import ctypes
+    from paper_2201_06227_amd import _build, binding as eg
+    if _build.is_stale():
+        _build.build_library()
+    L = eg.lib()
+    null, fake, odd = ctypes.c_void_p(0), ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    d = eg.CacheDesc(5, 8, 16, eg.F32)
+    need = L.egeria_cache_bytes(ctypes.byref(d))
+    assert need >= 256 + 40 * 8 + 2 * 80 * 8 + 40 * 64    # header, ids, table of >= 80 entries, rows
+    for bad in (eg.CacheDesc(0, 8, 16, eg.F32), eg.CacheDesc(5, 0, 16, eg.F32), eg.CacheDesc(5, 8, 0, eg.F32),
+                eg.CacheDesc(5, 8, 16, 7), eg.CacheDesc(1 << 12, 1 << 12, 16, eg.F32)):
+        assert L.egeria_cache_bytes(ctypes.byref(bad)) == 0
+        assert L.egeria_cache_init(ctypes.byref(bad), fake, 1 << 30, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_cache_init(ctypes.byref(d), fake, need - 1, null) == eg.ERR_WORKSPACE_TOO_SMALL
+    assert L.egeria_cache_init(ctypes.byref(d), odd, need, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_cache_put(ctypes.byref(d), fake, need, fake, 9, fake, null) == eg.ERR_INVALID_ARG   # more than `batch`
+    assert L.egeria_cache_put(ctypes.byref(d), fake, need, null, 3, fake, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_cache_put(ctypes.byref(d), fake, need - 1, fake, 3, fake, null) == eg.ERR_WORKSPACE_TOO_SMALL
+    assert L.egeria_cache_get(ctypes.byref(d), fake, need, fake, 70000, fake, fake, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_cache_get(ctypes.byref(d), fake, need, fake, 3, null, fake, null) == eg.ERR_INVALID_ARG
+    assert L.egeria_cache_get(ctypes.byref(d), fake, need, null, 0, null, null, null) == eg.OK           # nothing to do
+
+
+# ----------------------------------------------------------------------------- GPU parity
+
+CACHE_CASES = [dict(window=5, batch=8, D=4, dt="f32", universe=30),       # 16-byte rows
+               dict(window=5, batch=16, D=5, dt="f32", universe=40),      # 20-byte rows: 4-byte copies
+               dict(window=3, batch=7, D=3, dt="bf16", universe=20),      # 6-byte rows: 2-byte copies
+               dict(window=1, batch=4, D=64, dt="f32", universe=6),
+               dict(window=5, batch=128, D=16384, dt="f32", universe=2000),   # rows of the basic block, two chunks each
+               dict(window=2, batch=64, D=50180, dt="bf16", universe=100)]    # ragged last chunk
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw", CACHE_CASES, ids=lambda k: "w{window}_b{batch}_D{D}_{dt}".format(**k))
+def test_cache_matches_oracle(kw):
+    import torch
+    from paper_2201_06227_amd import binding as eg
+    dev = "cuda:0"
+    tdt = torch.float32 if kw["dt"] == "f32" else torch.bfloat16
+    rng = np.random.default_rng(kw["D"] + kw["batch"])
+    cache = eg.ActivationCache(kw["window"], kw["batch"], kw["D"], tdt, dev)
+    o = CacheOracle(kw["window"])
+    D = kw["D"]
+    for step in range(14):
+        n = int(rng.integers(0, kw["batch"] + 1)) if step % 5 else kw["batch"]
+        ids = rng.integers(-2, kw["universe"], size=n)
+        rows = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32)).to(tdt)
+        cache.put(torch.from_numpy(ids).to(dev), rows.to(dev))
+        o.put(ids, rows.view(torch.int16).numpy() if tdt == torch.bfloat16 else rows.numpy())
+        nq = int(rng.integers(1, 2 * kw["batch"] + 2))
+        query = rng.integers(-2, kw["universe"], size=nq)
+        sentinel = torch.full((nq, D), 7.0, dtype=tdt)
+        out = sentinel.clone().to(dev)
+        hit = torch.full((nq,), 9, dtype=torch.uint8, device=dev)
+        cache.get(torch.from_numpy(query).to(dev), out, hit)
+        want = (sentinel.view(torch.int16) if tdt == torch.bfloat16 else sentinel).numpy().copy()
+        want_hit = o.get(query, want)
+        torch.cuda.synchronize()
+        assert np.array_equal(hit.cpu().numpy(), want_hit), step
+        got = out.cpu()
+        got = got.view(torch.int16).numpy() if tdt == torch.bfloat16 else got.numpy()
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), step   # bit for bit, untouched rows included
+
+
+@pytest.mark.gpu
+def test_cache_full_size_rows():
+    """Rows of the bottleneck block's activation (64 x 200704 fp32, 0.8 MB each), window of five."""
+    import torch
+    from paper_2201_06227_amd import binding as eg
+    dev, b, D = "cuda:0", 64, 200704
+    cache = eg.ActivationCache(5, b, D, torch.float32, dev)
+    o = CacheOracle(5)
+    g = torch.Generator(device=dev).manual_seed(5)
+    for t in range(7):
+        ids = np.arange(b) + 40 * t                       # overlaps the previous mini-batch by 24 ids
+        rows = torch.randn((b, D), generator=g, device=dev)
+        cache.put(torch.from_numpy(ids).to(dev), rows)
+        o.put(ids, rows[:, :8].cpu().numpy())             # the oracle follows the first 8 columns
+        query = np.arange(0, 40 * (t + 1) + b, 3)[-300:]
+        out = torch.zeros((len(query), D), device=dev)
+        hit = torch.zeros(len(query), dtype=torch.uint8, device=dev)
+        cache.get(torch.from_numpy(query).to(dev), out, hit)
+        want = np.zeros((len(query), 8), np.float32)
+        want_hit = o.get(query, want)
+        assert np.array_equal(hit.cpu().numpy(), want_hit)
+        assert np.array_equal(out[:, :8].cpu().numpy(), want)
+        # whole rows: a hit row equals the row that was put in under that id most recently
+        newest = {int(k): i for i, k in enumerate(ids)}
+        for qi, k in enumerate(query):
+            if int(k) in newest:
+                assert torch.equal(out[qi], rows[newest[int(k)]])
