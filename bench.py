@@ -217,6 +217,29 @@ def time_steps(ev, x, a_t, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+def step_distribution(ev, x, a_t, steps, cold):
+    """GPU time of single steps between a pair of events on the launch stream: median, 10th and
+    90th percentile.  cold: a 512 MiB buffer is streamed (read and written) before every step, so
+    that neither the L2 caches nor the 256 MB memory-side cache still hold the step's tensors."""
+    import torch
+    scratch = torch.zeros(128 << 20, dtype=torch.float32, device=x.device) if cold else None
+    ts = []
+    for i in range(steps + 3):
+        if cold:
+            scratch.add_(1.0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ev.step(x, a_t)
+        e1.record()
+        e1.synchronize()
+        if i >= 3:
+            ts.append(e0.elapsed_time(e1))
+    ts.sort()
+    q = lambda f: round(ts[min(len(ts) - 1, int(f * len(ts)))], 4)
+    return {"steps": steps, "median_ms": q(0.5), "p10_ms": q(0.1), "p90_ms": q(0.9),
+            "evals_per_s_at_median": round(ev.n_layers / (q(0.5) * 1e-3), 2)}
+
+
 def kernel_breakdown(ev, x, a_t, eg, wl, steps=5):
     """Average time per step of each kernel class (one class per pass)."""
     import torch
@@ -452,6 +475,11 @@ def main():
         torch.cuda.synchronize()
         others_roof[name] = roofline_for(wl, c, eg.profile_end(n), eg, 20, args.workload)
     result["roofline_other_kernels"] = others_roof
+    # single steps between events (one step in flight at a time, so launch latency is exposed):
+    # warm = tensors of the previous step still in the caches, cold = caches flushed before every step
+    n_dist = 100 if args.workload != 5 else 20
+    result["step_time_warm"] = step_distribution(ev, x, a_t, n_dist, False)
+    result["step_time_cold"] = step_distribution(ev, x, a_t, n_dist, True)
     result["graph"] = graph_replay(ev, x, a_t, args.steps, eager_p)
 
     if not args.no_others:
