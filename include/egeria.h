@@ -59,6 +59,15 @@ typedef enum {
 
 typedef enum { EGERIA_F32 = 0, EGERIA_BF16 = 1 } egeria_dtype;
 
+/* Precision of the reference model (Section 6.4 of the paper, Table 2: int8 by
+ * default, float16 and float32 as the fallback when int8 fails).  At the float
+ * precisions weights and every layer's input are rounded to nearest even to
+ * that precision, products are summed in fp32 on the matrix cores, the epilogue
+ * is y = act(sum + bias [+ block input as cast]) in fp32; there are no scales.
+ * FC and convolution modules only (BERT kinds: EGERIA_ERR_UNSUPPORTED), no
+ * static activation scales, no per-channel scales. */
+typedef enum { EGERIA_REF_INT8 = 0, EGERIA_REF_F16 = 1, EGERIA_REF_F32 = 2 } egeria_ref_precision;
+
 /* Kinds of layer module the reference forward knows. */
 typedef enum {
     EGERIA_FC_RELU = 0,      /* y = ReLU(x W^T + bias)                                   */
@@ -84,6 +93,7 @@ typedef struct {
     int32_t seq, hidden, heads, ffn;
     int32_t n_layers;
     float ln_eps;
+    int32_t ref_precision;          /* egeria_ref_precision; 0 = int8 */
 } egeria_block_desc;
 
 /* HOST struct.  One quantised linear / convolution layer of the reference model.
@@ -93,7 +103,8 @@ typedef struct {
  *   scale : 1 fp32, the tensor's scale.
  *   bias  : fp32 [out] or NULL. */
 typedef struct {
-    const int8_t *w_q;
+    const int8_t *w_q;              /* at a float reference precision: float16 / float32 values, rows padded
+                                       to 16 bytes, as egeria_quantize_weights writes them; scale unused */
     const float *scale;             /* 1 fp32, or fp32 [out] when per_channel */
     const float *bias;
     int32_t per_channel;            /* 0: one scale for the tensor; 1: one per output channel */
@@ -130,7 +141,10 @@ typedef struct {
  * parity tests: for sub-layer i (same order as egeria_qweights.linear) the int8
  * input in the layout the GEMM consumes ([M, egeria_padded(K)], NHWC for
  * convolutions), its scale, the raw int32 accumulators [M, out] and the fp32
- * output after the epilogue [M, out].  Any pointer may be NULL. */
+ * output after the epilogue [M, out].  Any pointer may be NULL.  At a float
+ * reference precision x_q receives the cast operand rows (float16 / float32,
+ * each row padded to 16 bytes), acc the bit patterns of the fp32 sums, x_scale
+ * is not written. */
 typedef struct {
     int8_t *x_q;
     float *x_scale;
@@ -180,6 +194,9 @@ typedef struct {
     float *scale;                   /* out: 1 fp32, or fp32 [out] when per_channel */
     int32_t per_channel;            /* 0: one scale for the tensor; 1: the same rule applied to every
                                        output channel w[o] on its own (one scale per channel) */
+    int32_t precision;              /* egeria_ref_precision.  Float precisions: w_q receives float16 / float32
+                                       values [out, kh, kw, cp], cp = `in` padded with zeros to a whole number of
+                                       16-byte units (8 / 4 values); scale is not written and may be NULL */
 } egeria_weight;
 
 /* Section 4.1, reference-model generation: quantises all n weight tensors of

@@ -17,6 +17,7 @@ from . import _build
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_NONFINITE, ERR_HIP = range(6)
 F32, BF16 = 0, 1
+REF_INT8, REF_F16, REF_F32 = 0, 1, 2
 FC_RELU, BASIC_BLOCK, BOTTLENECK, BERT_LAYER, BERT_STACK = range(5)
 
 _vp = ctypes.c_void_p
@@ -29,7 +30,7 @@ class BlockDesc(ctypes.Structure):
     _fields_ = [("kind", _i32), ("batch", _i32), ("c_in", _i32), ("c_mid", _i32), ("c_out", _i32),
                 ("height", _i32), ("width", _i32), ("has_residual", _i32), ("seq", _i32),
                 ("hidden", _i32), ("heads", _i32), ("ffn", _i32), ("n_layers", _i32),
-                ("ln_eps", ctypes.c_float)]
+                ("ln_eps", ctypes.c_float), ("ref_precision", _i32)]
 
 
 class QLinear(ctypes.Structure):
@@ -55,7 +56,7 @@ class Taps(ctypes.Structure):
 
 class Weight(ctypes.Structure):
     _fields_ = [("w", _vp), ("dtype", _i32), ("out", _i32), ("in_", _i32), ("kh", _i32), ("kw", _i32),
-                ("w_q", _vp), ("scale", _vp), ("per_channel", _i32)]
+                ("w_q", _vp), ("scale", _vp), ("per_channel", _i32), ("precision", _i32)]
 
 
 FREEZE_MAX_W = 256
@@ -308,6 +309,7 @@ def make_desc(kind: int, dims: dict) -> BlockDesc:
         setattr(d, k, int(dims.get(k, 0)))
     d.n_layers = int(dims.get("n_layers", 1))
     d.ln_eps = float(dims.get("ln_eps", 0.0))
+    d.ref_precision = int(dims.get("ref_precision", REF_INT8))
     return d
 
 
@@ -351,6 +353,35 @@ def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
     qw.norm = None
     qw.act_scale = None if act_scales is None else _dev(act_scales).data_ptr()   # fp32 [n_linear], static scales
     return ReferenceModel(make_desc(kind, dims), qw, w_q, scales, list(biases), (arr, act_scales))
+
+
+def op_row_bytes(c: int, precision: int) -> int:
+    """Bytes of one operand row of c values at a reference precision (padded to 16)."""
+    return padded(c * {REF_INT8: 1, REF_F16: 2, REF_F32: 4}[precision])
+
+
+def make_float_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
+                         biases: Sequence[Optional[torch.Tensor]], precision: int) -> ReferenceModel:
+    """Reference model at float16 / float32 precision: every weight tensor cast by
+    egeria_quantize_weights (precision field) into the GEMM's layout."""
+    dev = weights[0].device
+    w_q = []
+    for w in weights:
+        taps_ = w.shape[2] * w.shape[3] if w.dim() == 4 else 1
+        w_q.append(torch.empty((w.shape[0], taps_ * op_row_bytes(w.shape[1], precision)), dtype=torch.uint8, device=dev))
+    tab = weight_table(weights, w_q, [w_q[0]] * len(weights))
+    for t in tab:
+        t.scale, t.precision = None, precision
+    ws = workspace(quantize_weights_workspace_bytes(len(weights)), dev)
+    _check(lib().egeria_quantize_weights(tab, len(weights), _ptr(ws), ws.numel(), _stream()), "egeria_quantize_weights")
+    arr = (QLinear * len(weights))()
+    for i in range(len(weights)):
+        arr[i].w_q = w_q[i].data_ptr()
+        arr[i].scale = None
+        arr[i].bias = 0 if biases[i] is None else biases[i].data_ptr()
+    qw = QWeights()
+    qw.n_linear, qw.linear, qw.n_norm, qw.norm, qw.act_scale = len(weights), arr, 0, None, None
+    return ReferenceModel(make_desc(kind, dict(dims, ref_precision=precision)), qw, w_q, [], list(biases), (arr,))
 
 
 def workspace_bytes(desc: BlockDesc) -> int:

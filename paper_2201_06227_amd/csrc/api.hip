@@ -37,9 +37,16 @@ struct Plan {
     size_t total = 0;
 };
 
+// bytes of one operand row of c values at the module's reference precision, padded to 16
+inline int64_t op_bytes(const egeria_block_desc *d, int64_t c)
+{
+    return pad16(c * (d->ref_precision == EGERIA_REF_F16 ? 2 : (d->ref_precision == EGERIA_REF_F32 ? 4 : 1)));
+}
+
 bool valid_desc(const egeria_block_desc *d)
 {
     if (!d || d->batch < 1) return false;
+    if (d->ref_precision < EGERIA_REF_INT8 || d->ref_precision > EGERIA_REF_F32) return false;
     switch (d->kind) {
     case EGERIA_FC_RELU:
         return d->c_in >= 1 && d->c_out >= 1;
@@ -68,12 +75,12 @@ Plan make_plan(const egeria_block_desc *d)
     case EGERIA_FC_RELU:
         p.slots = 1; p.n_linear = 1; p.M = b; p.D = d->c_out;
         take(header_bytes(p.slots));
-        p.off_q[0] = take((size_t)(b * pad16(d->c_in)));
+        p.off_q[0] = take((size_t)(b * op_bytes(d, d->c_in)));
         break;
     case EGERIA_BASIC_BLOCK: {
         p.slots = 2; p.n_linear = 2; p.M = b * d->height * d->width; p.D = (int64_t)d->height * d->width * d->c_out;
         take(header_bytes(p.slots));
-        const int64_t cp = pad16(d->c_in);
+        const int64_t cp = op_bytes(d, d->c_in);
         p.off_q[0] = take((size_t)(p.M * cp));
         p.off_q[1] = take((size_t)(p.M * cp));
         p.off_f[0] = take((size_t)(p.M * d->c_in) * 4);
@@ -82,9 +89,9 @@ Plan make_plan(const egeria_block_desc *d)
     case EGERIA_BOTTLENECK: {
         p.slots = 3; p.n_linear = 3; p.M = b * d->height * d->width; p.D = (int64_t)d->height * d->width * d->c_out;
         take(header_bytes(p.slots));
-        p.off_q[0] = take((size_t)(p.M * pad16(d->c_in)));
-        p.off_q[1] = take((size_t)(p.M * pad16(d->c_mid)));
-        p.off_q[2] = take((size_t)(p.M * pad16(d->c_mid)));
+        p.off_q[0] = take((size_t)(p.M * op_bytes(d, d->c_in)));
+        p.off_q[1] = take((size_t)(p.M * op_bytes(d, d->c_mid)));
+        p.off_q[2] = take((size_t)(p.M * op_bytes(d, d->c_mid)));
         p.off_f[0] = take((size_t)(p.M * d->c_mid) * 4);
         p.off_f[1] = take((size_t)(p.M * d->c_mid) * 4);
         break;
@@ -179,13 +186,15 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
                        int64_t q_ld = 0, const float *q_scale = nullptr)
 {
     const egeria_qlinear &L = f.qw->linear[li];
-    GemmArgs g;
+    GemmArgs g{};
     g.a = a; g.w = L.w_q; g.M = M; g.N = N; g.kp = kp; g.lda = lda;
     g.a_bytes = conv ? M * (int64_t)cp : M * lda;
     g.w_bytes = (int64_t)N * kp;
     if (g.a_bytes >= (1LL << 31) || g.w_bytes >= (1LL << 31)) return EGERIA_ERR_UNSUPPORTED;
     g.conv3x3 = conv ? 1 : 0; g.H = H; g.W = W; g.cp = cp;
     g.sx = sx; g.sw = L.scale; g.sw_per_n = L.per_channel ? 1 : 0; g.bias = L.bias; g.act = act;
+    g.et = f.d->ref_precision;
+    if (g.et != EGERIA_REF_INT8) { g.sw = sx; g.sw_per_n = 0; }     // float sums: both scales are the 1.0f at sx
     g.res_q = res_q; g.res_scale = res_scale; g.res_ld = res_ld;
     g.y = y; g.ldy = N;
     const egeria_tap *t = f.tap(li);
@@ -253,6 +262,58 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
                     nullptr);
 }
 
+// The FC and convolution modules at float16 / float32 reference precision
+// (Section 6.4, Table 2).  Every layer input is cast to the reference precision
+// in the layout the GEMM consumes; sums and outputs are fp32; the skip
+// connection adds the cast block input.  Observation points: x_q receives the
+// cast operand rows, acc the bit patterns of the fp32 sums, y the output.
+egeria_status forward_float(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
+{
+    const egeria_block_desc *d = f.d;
+    const int et = d->ref_precision, es = et == EGERIA_REF_F16 ? 2 : 4;
+    float *one = f.scale(0);
+    auto cast = [&](const void *src, egeria_dtype sdt, int64_t n, int64_t c, int64_t hw, int qi) -> egeria_status {
+        EG_HIP(launch_cast_chlast(src, sdt, n, c, hw, op_bytes(d, c) / es, et, f.qbuf(qi), one, f.st));
+        return EGERIA_OK;
+    };
+    auto tap_x = [&](int li, int qi, int64_t bytes) -> egeria_status {
+        const egeria_tap *t = f.tap(li);
+        if (t && t->x_q) EG_HIP(hipMemcpyAsync(t->x_q, f.qbuf(qi), (size_t)bytes, hipMemcpyDeviceToDevice, f.st));
+        return EGERIA_OK;
+    };
+    if (d->kind == EGERIA_FC_RELU) {
+        const int64_t kb = op_bytes(d, d->c_in);
+        EG_OK(cast(x, dt, d->batch, d->c_in, 1, 0));
+        EG_OK(tap_x(0, 0, d->batch * kb));
+        return run_gemm(f, 0, f.qbuf(0), kb, d->batch, d->c_out, (int32_t)kb, false, 0, 0, 0, one, 1, nullptr, nullptr, 0,
+                        a_ref, nullptr);
+    }
+    const int64_t M = f.p.M, hw = (int64_t)d->height * d->width;
+    const int32_t cin_b = (int32_t)op_bytes(d, d->c_in), cmid_b = (int32_t)op_bytes(d, d->c_mid);
+    const int H = d->height, W = d->width;
+    EG_OK(cast(x, dt, d->batch, d->c_in, hw, 0));
+    EG_OK(tap_x(0, 0, M * cin_b));
+    const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
+    const int64_t res_ld = cin_b / es;
+    if (d->kind == EGERIA_BASIC_BLOCK) {
+        EG_OK(run_gemm(f, 0, f.qbuf(0), 0, M, d->c_mid, 9 * cin_b, true, H, W, cin_b, one, 1, nullptr, nullptr, 0, f.fbuf(0),
+                       nullptr));
+        EG_OK(cast(f.fbuf(0), EGERIA_F32, M, d->c_mid, 1, 1));
+        EG_OK(tap_x(1, 1, M * cmid_b));
+        return run_gemm(f, 1, f.qbuf(1), 0, M, d->c_out, 9 * cmid_b, true, H, W, cmid_b, one, 1, res, one, res_ld, a_ref,
+                        nullptr);
+    }
+    EG_OK(run_gemm(f, 0, f.qbuf(0), cin_b, M, d->c_mid, cin_b, false, 0, 0, 0, one, 1, nullptr, nullptr, 0, f.fbuf(0),
+                   nullptr));
+    EG_OK(cast(f.fbuf(0), EGERIA_F32, M, d->c_mid, 1, 1));
+    EG_OK(tap_x(1, 1, M * cmid_b));
+    EG_OK(run_gemm(f, 1, f.qbuf(1), 0, M, d->c_mid, 9 * cmid_b, true, H, W, cmid_b, one, 1, nullptr, nullptr, 0, f.fbuf(1),
+                   nullptr));
+    EG_OK(cast(f.fbuf(1), EGERIA_F32, M, d->c_mid, 1, 2));
+    EG_OK(tap_x(2, 2, M * cmid_b));
+    return run_gemm(f, 2, f.qbuf(2), cmid_b, M, d->c_out, cmid_b, false, 0, 0, 0, one, 1, res, one, res_ld, a_ref, nullptr);
+}
+
 // One encoder layer: `cur` -> `out`.  slot 4l must already hold absmax(cur).
 egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *out, bool last)
 {
@@ -308,6 +369,8 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
     p = make_plan(desc);
     if (!p.ok) return EGERIA_ERR_INVALID_ARG;
     if (x_dt != EGERIA_F32 && x_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    if (desc->ref_precision != EGERIA_REF_INT8 && (desc->kind >= EGERIA_BERT_LAYER || qw->act_scale))
+        return EGERIA_ERR_UNSUPPORTED;
     if (desc->kind >= EGERIA_BERT_LAYER) {
         if (x_dt != EGERIA_F32) return EGERIA_ERR_UNSUPPORTED;
         if (desc->hidden / desc->heads > 64) return EGERIA_ERR_UNSUPPORTED;
@@ -318,7 +381,9 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
     if (qw->norm && qw->n_norm != 2 * p.n_layers) return EGERIA_ERR_INVALID_ARG;
     for (int i = 0; i < p.n_linear; ++i) {
         const egeria_qlinear &L = qw->linear[i];
-        if (!L.w_q || !L.scale || !aligned16(L.w_q)) return EGERIA_ERR_INVALID_ARG;
+        if (!L.w_q || !aligned16(L.w_q)) return EGERIA_ERR_INVALID_ARG;
+        if (desc->ref_precision == EGERIA_REF_INT8 && !L.scale) return EGERIA_ERR_INVALID_ARG;
+        if (desc->ref_precision != EGERIA_REF_INT8 && L.per_channel) return EGERIA_ERR_INVALID_ARG;
     }
     if (taps && (taps->n != p.n_linear || !taps->tap)) return EGERIA_ERR_INVALID_ARG;
     if (p.M > 0x7fffffffLL || p.slots > 256) return EGERIA_ERR_UNSUPPORTED;
@@ -415,14 +480,26 @@ egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *w
     if (ws_bytes < egeria_quantize_weights_workspace_bytes(n)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
     for (int i = 0; i < n; ++i) {
         const egeria_weight &t = w[i];
-        if (t.out < 0 || t.in < 0 || t.kh < 1 || t.kw < 1 || !t.scale) return EGERIA_ERR_INVALID_ARG;
+        if (t.out < 0 || t.in < 0 || t.kh < 1 || t.kw < 1) return EGERIA_ERR_INVALID_ARG;
+        if (t.precision == EGERIA_REF_INT8 && !t.scale) return EGERIA_ERR_INVALID_ARG;
         if (t.dtype != EGERIA_F32 && t.dtype != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+        if (t.precision < EGERIA_REF_INT8 || t.precision > EGERIA_REF_F32) return EGERIA_ERR_INVALID_ARG;
+        if (t.precision != EGERIA_REF_INT8 && t.per_channel) return EGERIA_ERR_INVALID_ARG;
         const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
         if (total > 0 && (!t.w || !t.w_q)) return EGERIA_ERR_INVALID_ARG;
         if (!aligned16(t.w) || !aligned16(t.w_q)) return EGERIA_ERR_INVALID_ARG;
-        if ((int64_t)t.out * t.kh * t.kw * pad16(t.in) >= ((int64_t)1 << 31)) return EGERIA_ERR_UNSUPPORTED;
+        const int es = t.precision == EGERIA_REF_F16 ? 2 : (t.precision == EGERIA_REF_F32 ? 4 : 1);
+        if ((int64_t)t.out * t.kh * t.kw * pad16((int64_t)t.in * es) >= ((int64_t)1 << 31)) return EGERIA_ERR_UNSUPPORTED;
     }
     hipStream_t st = (hipStream_t)stream;
+    // tensors of a float16 / float32 reference model: a cast into the GEMM's layout, no scale
+    for (int i = 0; i < n; ++i) {
+        const egeria_weight &t = w[i];
+        if (t.precision == EGERIA_REF_INT8 || (int64_t)t.out * t.in == 0) continue;
+        const int es = t.precision == EGERIA_REF_F16 ? 2 : 4;
+        EG_HIP(launch_cast_chlast(t.w, (egeria_dtype)t.dtype, t.out, t.in, (int64_t)t.kh * t.kw,
+                                  pad16((int64_t)t.in * es) / es, t.precision, t.w_q, nullptr, st));
+    }
     uint32_t *partials = (uint32_t *)ws + kHeaderFixedWords;
     // tensors with one scale are batched separately from those with one scale per output channel
     for (int pc = 0; pc < 2; ++pc) {
@@ -434,7 +511,7 @@ egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *w
             bool one = true;
             for (; i < n && b.n < kWeightBatch; ++i) {
                 const egeria_weight &t = w[i];
-                if ((t.per_channel != 0) != (pc != 0)) continue;
+                if (t.precision != EGERIA_REF_INT8 || (t.per_channel != 0) != (pc != 0)) continue;
                 const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
                 WeightJob &jb = b.job[b.n++];
                 jb.x = t.w;
@@ -517,7 +594,8 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     const size_t aref_elems = (size_t)desc->batch * (size_t)p.D;
     if (desc->kind < EGERIA_BERT_LAYER) {
         float *out = a_ref ? a_ref : (float *)(f.ws + p.off_aref[0]);
-        if (desc->kind == EGERIA_FC_RELU) EG_OK(forward_fc(f, x, x_dt, out));
+        if (desc->ref_precision != EGERIA_REF_INT8) EG_OK(forward_float(f, x, x_dt, out));
+        else if (desc->kind == EGERIA_FC_RELU) EG_OK(forward_fc(f, x, x_dt, out));
         else EG_OK(forward_conv_block(f, x, x_dt, out));
         if (eval)
             EG_HIP(launch_plasticity(a_train[0], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out, f.ws + p.off_part, st));

@@ -145,6 +145,13 @@ hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, ui
 
 hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, hipStream_t st);
 
+// Reference precisions float16 (et = 1) and float32 (et = 2): [n, c, hw] of type dt ->
+// [n, hw, cpe] of the reference precision, channels rounded to nearest even and padded with
+// zeros to cpe elements (a whole number of 16-byte units).  hw = 1: the rows of a matrix.
+// `one` (nullable) receives 1.0f: the scale the GEMM epilogue multiplies float sums by.
+hipError_t launch_cast_chlast(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw, int64_t cpe, int et,
+                              void *out, float *one, hipStream_t st);
+
 // int8 GEMM / implicit-GEMM convolution with fused dequantising epilogue.
 struct GemmArgs {
     const int8_t *a;        // activations: [M, lda] (linear, 1x1 conv) or [B, H, W, cp] (3x3 conv)
@@ -175,6 +182,11 @@ struct GemmArgs {
     int8_t *q_out;
     int64_t q_ld;
     const float *q_scale;
+    // element type of a and w: 0 int8, 1 float16, 2 float32 (the float types: kp, lda, cp, a_bytes
+    // and w_bytes stay in bytes; sx and sw point at 1.0f; res_q holds values of the same type,
+    // res_ld in elements, res_scale unused; acc_out receives the fp32 sums' bit patterns; no q_out,
+    // no absmax_out)
+    int32_t et;
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 

@@ -42,6 +42,55 @@ constexpr int stages_for(int bm, int bn, int bk)
     return 2 * stage <= 80 * 1024 ? 2 : 3;
 }
 
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+// Element type of the two operands (ET): 0 = int8 (int32 sums, the reference
+// model's default), 1 = float16, 2 = float32 (fp32 sums; the reference model at
+// the higher precisions of the paper's Table 2).  The kernel moves bytes: a
+// 16-byte unit is 16, 8 or 4 values of K, and one unit pair per lane feeds one
+// MFMA (int8, float16) or four (float32, one value each).
+template <int ET>
+struct AccOf {
+    typedef v16i type;
+};
+template <>
+struct AccOf<1> {
+    typedef v16f type;
+};
+template <>
+struct AccOf<2> {
+    typedef v16f type;
+};
+template <int ET>
+struct ResOf {
+    typedef int8_t type;
+};
+template <>
+struct ResOf<1> {
+    typedef _Float16 type;
+};
+template <>
+struct ResOf<2> {
+    typedef float type;
+};
+template <int ET>
+__device__ __forceinline__ typename AccOf<ET>::type mma(v4i a, v4i b, typename AccOf<ET>::type c)
+{
+    if constexpr (ET == 0) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    } else if constexpr (ET == 1) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__int_as_float(a[e]), __int_as_float(b[e]), c, 0, 0, 0);
+        return c;
+    }
+}
+__device__ __forceinline__ int32_t acc_bits(int a) { return a; }
+__device__ __forceinline__ int32_t acc_bits(float a) { return __float_as_int(a); }
+
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
 // 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes
@@ -66,10 +115,12 @@ constexpr int resident_target(int bm, int bn)
     return bm * bn > 256 * 128 ? 1 : (bm * bn > 128 * 128 ? 2 : 3);
 }
 
-template <int BM, int BN, int WM, int WN, bool CONV, int BK>
+template <int BM, int BN, int WM, int WN, bool CONV, int BK, int ET>
 __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(const GemmArgs g, int tiles,
                                                                                int tiles_per_xcd)
 {
+    typedef typename AccOf<ET>::type acc_t;
+    typedef typename ResOf<ET>::type res_t;
     static_assert(BK == 64 || BK == 128, "K step of 64 or 128 bytes");
     constexpr int kBK = BK;
     constexpr int UPR = BK / 16;                 // 16-byte K units per row of a stage
@@ -102,7 +153,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     // epilogue scalars, requested now so that their latency hides behind the K loop
     const float sxv = *g.sx;
     const float s = g.sw_per_n ? 0.0f : sxv * (*g.sw);
-    const float rs = g.res_q ? *g.res_scale : 0.0f;
+    const float rs = g.res_q ? (ET == 0 ? *g.res_scale : 1.0f) : 0.0f;
     float q_inv = 0.0f;                          // multiplier of the optional int8 output
     if (g.q_out) q_inv = (float)(1.0 / (double)*g.q_scale);
 
@@ -212,7 +263,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
             fb[j] = *(const v4i *)&sB[((wn * TN + j) * 32 + frow) * kBK + koff];
     };
 
-    v16i acc[TM][TN];
+    acc_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -224,7 +275,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = mma<ET>(fa[i], fb[j], acc[i][j]);
     };
 
     // Software pipeline over a ring of NST LDS stages.  During step kt the
@@ -261,7 +312,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = mma<ET>(fa0[i], fb0[j], acc[i][j]);
                 constexpr int per = (NLD + NMF - 1) / NMF;               // requests after each MFMA
 #pragma unroll
                 for (int q = 0; q < per; ++q)
@@ -326,7 +377,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
             for (int i = 0; i < TM; ++i) {
                 const int64_t row0 = m0 + (wm_u * TM + i) * 32;
                 float *yb = g.y + row0 * g.ldy + col0;
-                const int8_t *rb = g.res_q + row0 * g.res_ld + col0;
+                const res_t *rb = (const res_t *)g.res_q + row0 * g.res_ld + col0;
                 int32_t *ab = g.acc_out + row0 * g.N + col0;
                 int8_t *qb = g.q_out + row0 * g.q_ld + col0;
                 const int rows_left = EDGE ? (int)(g.M - row0 < 32 ? g.M - row0 : 32) - lrow : 32;
@@ -340,13 +391,13 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
                         if (g.q_out && !col_ok && col0 + lcol < g.q_ld && rr < rows_left) qb[(size_t)rr * g.q_ld + qoff] = 0;
                         continue;
                     }
-                    const int a = acc[i][j][r];
+                    const auto a = acc[i][j][r];
                     float v = fmaf((float)a, sj, bj);
                     if (EDGE ? g.res_q != nullptr : RES) v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
                     if (EDGE ? g.act == 1 : RELU) v = v > 0.0f ? v : 0.0f;
                     if (EDGE ? g.y != nullptr : (!QOUT || g.y != nullptr)) yb[(size_t)rr * g.ldy + yoff] = v;
                     if (EDGE ? g.q_out != nullptr : QOUT) qb[(size_t)rr * g.q_ld + qoff] = (int8_t)quant1(v, q_inv);
-                    if (EDGE && g.acc_out) ab[(size_t)rr * g.N + aoff] = a;
+                    if (EDGE && g.acc_out) ab[(size_t)rr * g.N + aoff] = acc_bits(a);
                     int32_t bits = (int32_t)__float_as_uint(v);
                     if (EDGE ? !(g.act == 1 || pos) : !(RELU || POS)) bits &= 0x7fffffff;
                     amax = amax > bits ? amax : bits;
@@ -372,7 +423,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     }
 }
 
-template <int BM, int BN, int WM, int WN, int BK>
+template <int BM, int BN, int WM, int WN, int BK, int ET = 0>
 static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
 {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
@@ -385,23 +436,23 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     if (g.conv3x3) {
         static bool set = false;
         if (!set) {
-            e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, true, BK>,
+            e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, true, BK, ET>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
             set = true;
         }
-        return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true, BK>, grid, block, smem, st, g, (int)tiles,
-                        tpx);
+        return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true, BK, ET>, grid, block, smem, st, g,
+                        (int)tiles, tpx);
     }
     static bool set = false;
     if (!set) {
-        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK>,
+        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         set = true;
     }
-    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK>, grid, block, smem, st, g, (int)tiles,
-                    tpx);
+    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>, grid, block, smem, st, g,
+                    (int)tiles, tpx);
 }
 
 // ---- 3x3 convolution with at most 16 input channels and at most 32 outputs ----------------
@@ -505,8 +556,23 @@ static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
 // long, so for short K only shapes with two workgroups per CU are considered
 // (one is in its K loop while the other stores), and for very short K, where
 // the kernel is a stream of stores, only the small shapes.
+// The float16 / float32 reference precisions: three tile shapes, chosen by how
+// many tiles the output makes.
+template <int ET>
+static hipError_t launch_float(const GemmArgs &g, hipStream_t st)
+{
+    if (g.q_out || g.absmax_out) return hipErrorInvalidValue;
+    if (g.N <= 32) return launch_variant<128, 32, 4, 1, 64, ET>(g, st);
+    const int64_t t128 = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128);
+    if (t128 >= 512) return launch_variant<128, 128, 2, 2, 64, ET>(g, st);
+    return launch_variant<128, 64, 2, 2, 64, ET>(g, st);
+}
+
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
+    if (g.et == 1) return launch_float<1>(g, st);
+    if (g.et == 2) return launch_float<2>(g, st);
+    if (g.et != 0) return hipErrorInvalidValue;
     if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
         const int64_t blocks = (g.M + 127) / 128;
         if (blocks <= 0) return hipSuccess;

@@ -85,3 +85,114 @@ def test_oracle_skip_connection_adds_the_rounded_input():
     wl.biases = [np.zeros_like(b) for b in wl.biases]
     assert np.array_equal(fo.ref_forward(wl, "f16")["a_ref"], np.maximum(fo.r(wl.x, "f16"), 0))
     assert np.array_equal(fo.ref_forward(wl, "f32")["a_ref"], np.maximum(wl.x, 0))
+
+
+# ----------------------------------------------------------------------------- GPU parity
+# The products are exact on both sides (float16 x float16 and float32 x float32 fit the fp32 /
+# fp64 accumulators' inputs); the sums differ in accumulation order and width (fp32 on the matrix
+# cores, fp64 in the oracle), so outputs agree to fp32 rounding of a K-term sum, not bit for bit:
+#   first layer: |y - y*| <= 4e-6 * max|y*|  (K <= 2304 terms of fp32 accumulation)
+#   later layers: an input within that distance of a float16 rounding boundary may round the other
+#   way; one such input moves an output by at most one float16 ulp of it times a weight, so
+#   |y - y*| <= 4e-6 * max|y*| + 2 * 2^-10 * max|input| * max|weight| (float16; two such inputs in one
+#   receptive field are already very unlikely), and 2e-5 * max|y*| at float32.
+# The cast operands themselves (pure rounding) must be bit-identical to the oracle's.
+
+def _gpu_float_forward(wl, precision):
+    from paper_2201_06227_amd import binding as eg
+    import tests.gpu_common as gc
+    prec = {"f16": eg.REF_F16, "f32": eg.REF_F32}[precision]
+    es = 2 if precision == "f16" else 4
+    W = [gc.to_dev(w) for w in wl.weights]
+    B = [None if b is None else gc.to_dev(b) for b in wl.biases]
+    ref = eg.make_float_reference(wl.kind, wl.dims, W, B, prec)
+    shapes = gc.tap_shapes(wl)
+    cins = {si.KIND_FC_RELU: ["c_in"], si.KIND_BASIC_BLOCK: ["c_in", "c_mid"],
+            si.KIND_BOTTLENECK: ["c_in", "c_mid", "c_mid"]}[wl.kind]
+    for s, key in zip(shapes, cins):
+        s["kp"] = eg.op_row_bytes(wl.dims[key], prec)           # the operand tap holds bytes
+    taps, bufs, _keep = eg.make_taps(ref, shapes, gc.DEV)
+    a_ref = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    eg.ref_forward(ref, gc.to_dev(wl.x), a_ref, ws, taps)
+    plain = torch.empty_like(a_ref)
+    eg.ref_forward(ref, gc.to_dev(wl.x), plain, ws)
+    torch.cuda.synchronize()
+    assert eg.check(ws) == eg.OK
+    assert torch.equal(plain, a_ref)                            # observed and unobserved runs agree
+    np_dt = np.float16 if precision == "f16" else np.float32
+    out = []
+    for b_, key in zip(bufs, cins):
+        c = wl.dims[key]
+        xq = b_["x_q"].cpu().numpy().view(np_dt)[:, :c].astype(np.float32)
+        pad = b_["x_q"].cpu().numpy().view(np_dt)[:, c:]
+        assert not pad.any()
+        out.append(dict(x=xq, acc=b_["acc"].cpu().numpy().view(np.float32), y=b_["y"].cpu().numpy()))
+    return a_ref.cpu().numpy(), out, ref, ws
+
+
+def _rows(a):
+    """oracle NCHW / [b, c] tensor -> [M, C] rows as the GPU lays them out"""
+    return a if a.ndim == 2 else np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1))).reshape(-1, a.shape[1])
+
+
+FLOAT_CASES = SMALL + [("fc_cfg1", lambda: si.make_config(1)),
+                       ("basic_cfg2", lambda: si.make_config(2)),
+                       ("bottleneck_mid", lambda: si.make_bottleneck(b=4, c_in=256, c_mid=64, h=14, w=14, seed=35))]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("precision", ["f16", "f32"])
+@pytest.mark.parametrize("name,make", FLOAT_CASES, ids=[s[0] for s in FLOAT_CASES])
+def test_float_reference_matches_oracle(name, make, precision):
+    wl = make()
+    ot = fo.ref_forward(wl, precision)
+    a_ref, taps, ref, ws = _gpu_float_forward(wl, precision)
+    n = len(taps)
+    for i, t in enumerate(taps):
+        want_y = _rows(ot[f"l{i}.y"])
+        if i == 0:
+            assert np.array_equal(t["x"], _rows(ot["l0.x"]))                    # the cast: bit for bit
+            tol = 4e-6 * np.abs(want_y).max()
+        elif precision == "f32":
+            tol = 2e-5 * np.abs(want_y).max()
+        else:
+            flips = (t["x"] != _rows(ot[f"l{i}.x"])).mean()
+            assert flips <= 2e-3                                                # rare float16 boundary cases only
+            tol = 4e-6 * np.abs(want_y).max() + 2 * 2.0 ** -10 * np.abs(ot[f"l{i}.x"]).max() * np.abs(wl.weights[i]).max()
+        assert np.abs(t["y"] - want_y).max() <= tol, (i, name)
+        assert np.abs(t["acc"] - _rows(ot[f"l{i}.acc"])).max() <= tol, (i, name)
+    assert np.abs(a_ref - _rows(ot["a_ref"]).reshape(-1)).max() <= tol
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("precision", ["f16", "f32"])
+def test_float_reference_score(precision, orc):
+    """Plasticity against a float-precision reference (cfg 2): the fused call equals the metric on the
+    stored activation bit for bit, and agrees with the oracle chain + fp64 metric to 1e-3 (the score is
+    a difference of nearly equal Gram matrices, so fp32-rounding-level differences of A_R show)."""
+    from paper_2201_06227_amd import binding as eg
+    import tests.gpu_common as gc
+    wl = si.make_config(2)
+    a_ref, taps, ref, ws = _gpu_float_forward(wl, precision)
+    a_t = si.train_forward(wl)
+    p = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+    eg.plasticity_eval(ref, gc.to_dev(wl.x), [a_t[0].to(gc.DEV)], p, ws)
+    sep = eg.plasticity(a_t[0].to(gc.DEV), torch.from_numpy(a_ref).to(gc.DEV).reshape(wl.batch, -1))
+    assert p.item() == sep.item()
+    want = orc.sp_loss(a_t[0].numpy(), _rows(fo.ref_forward(wl, precision)["a_ref"]).reshape(wl.batch, -1))
+    assert p.item() == pytest.approx(want, rel=1e-3)
+
+
+@pytest.mark.gpu
+def test_float_reference_rejects_what_it_does_not_cover():
+    from paper_2201_06227_amd import binding as eg
+    import tests.gpu_common as gc
+    wl = si.make_bert(b=2, s=8, hidden=64, heads=2, ffn=64, n_layers=1, seed=3, train_act_dtype="f32")
+    ref = gc.build_reference(wl)
+    ref.desc.ref_precision = eg.REF_F16
+    ws = eg.workspace(1 << 24, gc.DEV)
+    a = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    with pytest.raises(eg.EgeriaError) as e:
+        eg.ref_forward(ref, gc.to_dev(wl.x), a, ws)
+    assert e.value.code == eg.ERR_UNSUPPORTED
