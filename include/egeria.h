@@ -384,6 +384,9 @@ typedef enum {
 } egeria_kernel_class;
 
 egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches);
+/* Between begin and end: paused != 0 stops recording (launches go out without events, which cost
+ * host time), paused == 0 resumes it.  Lets a caller sample some steps of a timed loop only. */
+egeria_status egeria_profile_pause(int32_t paused);
 egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus

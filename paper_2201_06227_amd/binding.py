@@ -95,7 +95,7 @@ EXPORTS = [
     "egeria_workspace_bytes", "egeria_check", "egeria_status_string", "egeria_profile_begin",
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
     "egeria_freeze_init", "egeria_freeze_observe",
-    "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get",
+    "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -148,6 +148,8 @@ def lib():
     L.egeria_check.argtypes = [_vp, _vp]
     L.egeria_profile_begin.restype = ctypes.c_int
     L.egeria_profile_begin.argtypes = [_i32, _i32]
+    L.egeria_profile_pause.restype = ctypes.c_int
+    L.egeria_profile_pause.argtypes = [_i32]
     L.egeria_profile_end.restype = ctypes.c_int
     L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
     L.egeria_freeze_init.restype = ctypes.c_int
@@ -500,6 +502,10 @@ class ActivationCache:
 
 def profile_begin(kernel_class: int, max_launches: int) -> None:
     _check(lib().egeria_profile_begin(int(kernel_class), int(max_launches)), "egeria_profile_begin")
+
+
+def profile_pause(paused: bool) -> None:
+    lib().egeria_profile_pause(1 if paused else 0)
 
 
 def profile_end(capacity: int):

@@ -695,6 +695,8 @@ egeria_status egeria_check(void *ws, void *stream)
     return EGERIA_OK;
 }
 
+static int g_profile_armed_class = 0;     // class to resume after egeria_profile_pause(1)
+
 egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches)
 {
     static std::vector<hipEvent_t> starts, stops;
@@ -712,6 +714,18 @@ egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches)
     g_profile.n = max_launches;
     g_profile.count = 0;
     g_profile.cls = kernel_class;
+    g_profile_armed_class = kernel_class;
+    return EGERIA_OK;
+}
+
+egeria_status egeria_profile_pause(int32_t paused)
+{
+    if (paused) {
+        if (g_profile.cls != 0) g_profile_armed_class = g_profile.cls;
+        g_profile.cls = 0;
+    } else if (g_profile_armed_class != 0) {
+        g_profile.cls = g_profile_armed_class;
+    }
     return EGERIA_OK;
 }
 
@@ -720,6 +734,7 @@ egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out
     if (!n_out || capacity < 0 || (capacity > 0 && !ms_out)) return EGERIA_ERR_INVALID_ARG;
     const int n = g_profile.count;
     g_profile.cls = 0;
+    g_profile_armed_class = 0;
     g_profile.count = 0;
     *n_out = n;
     for (int i = 0; i < n && i < capacity; ++i) {
