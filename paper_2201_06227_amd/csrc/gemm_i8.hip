@@ -344,6 +344,30 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the zero-filled K steps past the end
 
+    // The int8 residual of the tile goes through LDS (the stage memory is free
+    // now): one coalesced pass of 16-byte loads instead of one byte load per
+    // output element issued from inside the epilogue, whose round trips would add up.
+    constexpr bool RES_LDS = ET == 0;
+    if (RES_LDS && g.res_q) {
+        constexpr int RU = BN / 16, RIT = (BM * RU + 255) / 256;     // 16-byte units per row, units per thread
+        v4i rv[RIT];
+        __syncthreads();                                              // every wave has read its last operands
+#pragma unroll
+        for (int it = 0; it < RIT; ++it) {
+            const int u = tid + it * 256, rr = u / RU, cu = u % RU;
+            const int64_t m = m0 + rr;
+            const int64_t col = n0 + cu * 16;
+            rv[it] = v4i{0, 0, 0, 0};
+            if (u < BM * RU && m < g.M && col < g.res_ld) rv[it] = *(const v4i *)(g.res_q + m * g.res_ld + col);
+        }
+#pragma unroll
+        for (int it = 0; it < RIT; ++it) {
+            const int u = tid + it * 256;
+            if (u < BM * RU) *(v4i *)&lds[(u / RU) * BN + (u % RU) * 16] = rv[it];
+        }
+        __syncthreads();
+    }
+
     // ---- epilogue, straight from the accumulators.  Lane l of a 32x32 block
     // holds column l % 32 and rows 8 * (r / 4) + 4 * (l / 32) + r % 4 (r = 0..15),
     // so for a fixed r each half of the wave owns 32 consecutive columns of one
@@ -393,7 +417,12 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
                     }
                     const auto a = acc[i][j][r];
                     float v = fmaf((float)a, sj, bj);
-                    if (EDGE ? g.res_q != nullptr : RES) v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
+                    if (EDGE ? g.res_q != nullptr : RES) {
+                        if constexpr (RES_LDS)
+                            v = v + (float)(int8_t)lds[((wm_u * TM + i) * 32 + lrow + rr) * BN + (wn_u * TN + j) * 32 + lcol] * rs;
+                        else
+                            v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
+                    }
                     if (EDGE ? g.act == 1 : RELU) v = v > 0.0f ? v : 0.0f;
                     if (EDGE ? g.y != nullptr : (!QOUT || g.y != nullptr)) yb[(size_t)rr * g.ldy + yoff] = v;
                     if (EDGE ? g.q_out != nullptr : QOUT) qb[(size_t)rr * g.q_ld + qoff] = (int8_t)quant1(v, q_inv);
@@ -471,6 +500,15 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     const int ow = (int)(m % g.W), oh = (int)((m / g.W) % g.H);
     const float s = (*g.sx) * (g.sw_per_n ? (p < g.N ? g.sw[p] : 0.0f) : *g.sw);   // lane's output channel is p
     const float rs = g.res_q ? *g.res_scale : 0.0f;
+    // the residual of the workgroup's 128 pixels (16 bytes each, contiguous): requested now with
+    // one 16-byte load per thread, handed to the epilogue through LDS
+    __shared__ __attribute__((aligned(16))) uint8_t sres[128 * 16];
+    const bool res16 = g.res_q != nullptr && g.res_ld == 16;
+    v4i resv = {0, 0, 0, 0};
+    if (res16 && threadIdx.x < 128) {
+        const int64_t pix = (int64_t)blockIdx.x * 128 + threadIdx.x;
+        if (pix < g.M) resv = *(const v4i *)(g.res_q + pix * 16);
+    }
     v4i fa[5], fb[5];
 #pragma unroll
     for (int st = 0; st < 5; ++st) {
@@ -492,6 +530,10 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     const float bc = (g.bias && col_ok) ? g.bias[col] : 0.0f;
     const int64_t mw = ((int64_t)blockIdx.x * 4 + wave) * 32;
     const float q_inv = g.q_out ? (float)(1.0 / (double)*g.q_scale) : 0.0f;
+    if (res16) {
+        if (threadIdx.x < 128) *(v4i *)&sres[threadIdx.x * 16] = resv;
+        __syncthreads();
+    }
     uint32_t amax = 0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -504,7 +546,8 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
         const int a = acc[r];
         if (g.acc_out) g.acc_out[row * g.N + col] = a;
         float v = fmaf((float)a, s, bc);
-        if (g.res_q) v = v + (float)g.res_q[row * g.res_ld + col] * rs;
+        if (res16) v = v + (float)(int8_t)sres[(wave * 32 + (r >> 2) * 8 + h * 4 + (r & 3)) * 16 + col] * rs;
+        else if (g.res_q) v = v + (float)g.res_q[row * g.res_ld + col] * rs;
         if (g.act == 1) v = v > 0.0f ? v : 0.0f;
         if (g.y) g.y[row * g.ldy + col] = v;
         if (g.q_out) g.q_out[row * g.q_ld + col] = (int8_t)quant1(v, q_inv);
