@@ -55,6 +55,13 @@ def test_workspace_sizes(eg):
     assert eg.plasticity_workspace_bytes(128, 16384) >= 2 * 128 * 128 * 8
     assert eg.plasticity_workspace_bytes(129, 16) == 0 and eg.plasticity_workspace_bytes(0, 16) == 0
     assert eg.quantize_workspace_bytes() >= 64
+    # reference precisions: float operands are 2 / 4 bytes, so the operand buffers grow; BERT kinds have none
+    conv = dict(batch=8, c_in=64, c_mid=32, c_out=64, height=14, width=14, has_residual=1)
+    sizes = [eg.workspace_bytes(eg.make_desc(eg.BOTTLENECK, dict(conv, ref_precision=p)))
+             for p in (eg.REF_INT8, eg.REF_F16, eg.REF_F32)]
+    assert 0 < sizes[0] < sizes[1] < sizes[2]
+    assert eg.workspace_bytes(eg.make_desc(eg.BOTTLENECK, dict(conv, ref_precision=3))) == 0
+    assert eg.workspace_bytes(eg.make_desc(eg.BOTTLENECK, dict(conv, ref_precision=-1))) == 0
 
 
 def test_bad_arguments_are_rejected_on_the_host(eg):
@@ -92,6 +99,13 @@ def test_bad_arguments_are_rejected_on_the_host(eg):
     qw4.n_linear, qw4.linear = 4, arr4
     assert L.egeria_ref_forward(ctypes.byref(big), ctypes.byref(qw4), fake, eg.F32, fake, None, fake, 1 << 30,
                                 null) == eg.ERR_UNSUPPORTED      # head dimension 128 > 64
+
+
+def test_profile_pause_is_harmless_when_nothing_is_armed(eg):
+    L = eg.lib()
+    assert L.egeria_profile_pause(1) == eg.OK and L.egeria_profile_pause(0) == eg.OK
+    n = ctypes.c_int32(-1)
+    assert L.egeria_profile_end(None, 0, ctypes.byref(n)) == eg.OK and n.value == 0
 
 
 def test_missing_library_fails_loudly(eg, monkeypatch, tmp_path):

@@ -179,3 +179,49 @@ def test_cache_full_size_rows():
         for qi, k in enumerate(query):
             if int(k) in newest:
                 assert torch.equal(out[qi], rows[newest[int(k)]])
+
+
+@pytest.mark.gpu
+def test_cache_put_and_get_replay_in_a_graph():
+    """The put counter lives in the cache's own memory, so a captured put + get pair can be
+    replayed: every replay puts the (refreshed) mini-batch in as the newest one."""
+    import torch
+    from paper_2201_06227_amd import binding as eg
+    dev, b, D, window = "cuda:0", 16, 256, 3
+    cache = eg.ActivationCache(window, b, D, torch.float32, dev)
+    o = CacheOracle(window)
+    ids = torch.zeros(b, dtype=torch.int64, device=dev)
+    rows = torch.zeros((b, D), device=dev)
+    query = torch.zeros(2 * b, dtype=torch.int64, device=dev)
+    out = torch.zeros((2 * b, D), device=dev)
+    hit = torch.zeros(2 * b, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        cache.put(ids, rows)
+        cache.get(query, out, hit)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    o.put(np.zeros(b, np.int64), np.zeros((b, D), np.float32))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cache.put(ids, rows)
+        cache.get(query, out, hit)
+    # capturing executes nothing: the cache still holds the warm-up mini-batch only
+    rng = np.random.default_rng(3)
+    for t in range(6):
+        new_ids = rng.integers(0, 40, size=b)
+        new_rows = rng.standard_normal((b, D)).astype(np.float32)
+        q = rng.integers(0, 40, size=2 * b)
+        ids.copy_(torch.from_numpy(new_ids))
+        rows.copy_(torch.from_numpy(new_rows))
+        query.copy_(torch.from_numpy(q))
+        out.fill_(5.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        o.put(new_ids, new_rows)
+        want = np.full((2 * b, D), 5.0, np.float32)
+        want_hit = o.get(q, want)
+        assert np.array_equal(hit.cpu().numpy(), want_hit), t
+        assert np.array_equal(out.cpu().numpy(), want), t
