@@ -501,7 +501,7 @@ def main():
                    "step": "weight quantise + int8 reference forward + plasticity score", "launch": "eager",
                    "kernel_timing": "HIP event pairs around every launch of the dominant kernel class on every 8th step "
                                     "of the timed region",
-                   "arithmetic": "int8 x int8 -> int32 contractions, fp32 epilogues and Gram products, fp64 finaliser"},
+                   "arithmetic": "int8 x int8 -> int32 contractions, fp32 epilogues, exact fp32 Gram products (bf16 partial products, fp32 sums), fp64 finaliser"},
         "roofline": roof,
         "kernel_breakdown_us_per_step": breakdown,
         "plasticity": [float(v) for v in eager_p.tolist()],
