@@ -25,6 +25,7 @@ from __future__ import annotations
 import argparse
 import csv
 import os
+import re
 import sys
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -41,6 +42,10 @@ def per_kernel(path, counter):
             if r["Counter_Name"] != counter or "egeria::" not in r["Kernel_Name"]:
                 continue
             name = r["Kernel_Name"].split("egeria::")[1].split("<")[0].split("(")[0]
+            # the GEMM kernel's last template argument is the operand type: only the int8 launches
+            # belong to the workload's step (bench.py also times float16 / float32 reference legs)
+            if name == "gemm_i8_kernel" and not re.search(r"gemm_i8_kernel<[^>]*, 0>", r["Kernel_Name"]):
+                continue
             out.setdefault(name, []).append(float(r["Counter_Value"]))
     return out
 

@@ -348,6 +348,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     // now): one coalesced pass of 16-byte loads instead of one byte load per
     // output element issued from inside the epilogue, whose round trips would add up.
     constexpr bool RES_LDS = ET == 0;
+    static_assert(!RES_LDS || (size_t)NST * STAGE >= (size_t)BM * BN, "the residual tile must fit the stage memory");
     if (RES_LDS && g.res_q) {
         constexpr int RU = BN / 16, RIT = (BM * RU + 255) / 256;     // 16-byte units per row, units per thread
         v4i rv[RIT];
