@@ -239,6 +239,52 @@ egeria_status conv_to_int8(Fwd &f, int li, const int8_t *a, int64_t lda, int64_t
     return f.copy_tap_q(li + 1, f.qbuf(qi), (size_t)(M * np), f.sx(li + 1));
 }
 
+// A basic block of at most 16 channels on an unobserved run: no int8 tensor is
+// written.  The first convolution quantises the block input while loading it;
+// the second one does the same with the first one's fp32 output (dynamic
+// scales) or reads the codes the first one's epilogue wrote (static scales),
+// and forms the skip connection from the block input the same way.
+egeria_status forward_narrow_block(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
+{
+    const egeria_block_desc *d = f.d;
+    const bool st = f.is_static();
+    auto base = [&](int li) {
+        const egeria_qlinear &L = f.qw->linear[li];
+        GemmArgs g{};
+        g.w = L.w_q; g.M = f.p.M; g.N = li == 0 ? d->c_mid : d->c_out; g.kp = 9 * 16;
+        g.w_bytes = (int64_t)g.N * g.kp;
+        g.conv3x3 = 1; g.H = d->height; g.W = d->width; g.cp = 16;
+        g.sx = f.sx(li); g.sw = L.scale; g.sw_per_n = L.per_channel ? 1 : 0; g.bias = L.bias; g.act = 1;
+        g.ldy = g.N;
+        return g;
+    };
+    GemmArgs g1 = base(0);
+    ConvFuse z1{};
+    z1.a_src = 2; z1.a_f = x; z1.a_bf16 = dt == EGERIA_BF16 ? 1 : 0; z1.c = d->c_in;
+    z1.a_slot = f.amax(0); z1.a_nslot = st ? 0 : f.n_amax(0); z1.a_stride = f.stride_amax(0); z1.a_fixed = f.sscale(0);
+    z1.a_scale_out = f.scale(0); z1.flag = ws_flag(f.ws);
+    if (st) { g1.q_out = f.qbuf(1); g1.q_ld = 16; g1.q_scale = f.sscale(1); }
+    else { g1.y = f.fbuf(0); g1.absmax_out = f.slot(1); }
+    EG_HIP(launch_conv3x3_c16_fused(g1, z1, f.st));
+
+    GemmArgs g2 = base(1);
+    ConvFuse z2{};
+    if (st) {
+        g2.a = f.qbuf(1); g2.a_bytes = f.p.M * 16;
+    } else {
+        z2.a_src = 1; z2.a_f = f.fbuf(0); z2.c = d->c_mid;
+        z2.a_slot = f.amax(1); z2.a_nslot = f.n_amax(1); z2.a_stride = f.stride_amax(1);
+        z2.a_scale_out = f.scale(1); z2.flag = ws_flag(f.ws);
+    }
+    if (d->has_residual) {
+        z2.res_src = 1; z2.res_f = x; z2.res_bf16 = z1.a_bf16; z2.res_c = d->c_in;
+        z2.res_slot = f.amax(0); z2.res_nslot = z1.a_nslot; z2.res_stride = z1.a_stride; z2.res_fixed = f.sscale(0);
+    }
+    g2.y = a_ref;
+    EG_HIP(launch_conv3x3_c16_fused(g2, z2, f.st));
+    return EGERIA_OK;
+}
+
 egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
 {
     const egeria_block_desc *d = f.d;
@@ -246,6 +292,7 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
     const int H = d->height, W = d->width;
     if (!f.is_static()) EG_OK(f.input_absmax(x, dt, M * d->c_in));
+    if (d->kind == EGERIA_BASIC_BLOCK && !f.taps && cin_p == 16 && W <= kConvFuseMaxWidth && M < (1LL << 27)) return forward_narrow_block(f, x, dt, a_ref);
     EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
                                 f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));

@@ -190,6 +190,32 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 
+// The narrow 3x3 convolution (at most 16 input channels, at most 32 outputs) with the quantiser of
+// its operands folded in: the workgroup derives the scale of the quantise point itself, maps the
+// fp32 values of its 128 output pixels and their halo to int8 codes in LDS (the same arithmetic as
+// the quantise kernels, so the codes are the same) and contracts from there; the codes never travel
+// through global memory.  The skip connection can be produced the same way from the block input.
+struct ConvFuse {
+    int32_t a_src;              // 0: g.a holds int8 codes; 1: fp32 rows [M, c]; 2: planes [n, c, H*W] (fp32 or bf16)
+    const void *a_f;            // source of a_src 1 or 2
+    int32_t a_bf16;
+    int32_t c;                  // channels of that source (<= 16)
+    const uint32_t *a_slot;     // candidate maxima of the quantise point (n, stride), or a fixed scale
+    int32_t a_nslot, a_stride;
+    const float *a_fixed;
+    float *a_scale_out;         // workgroup 0 stores the scale here (and the non-finite flag in *flag)
+    uint32_t *flag;
+    int32_t res_src;            // 0: g.res_q (int8 [M, 16]) or none; 1: planes [n, res_c, H*W] quantised on load
+    const void *res_f;
+    int32_t res_bf16;
+    int32_t res_c;
+    const uint32_t *res_slot;
+    int32_t res_nslot, res_stride;
+    const float *res_fixed;
+};
+constexpr int kConvFuseMaxWidth = 256;      // image width up to which the halo of 128 pixels is staged
+hipError_t launch_conv3x3_c16_fused(const GemmArgs &g, const ConvFuse &z, hipStream_t st);
+
 // y = LN(x + res) over rows of length H, optional atomicMax of |y|.
 hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int32_t H,
                             const float *gamma, const float *beta, float eps, float *y,
@@ -266,6 +292,85 @@ __device__ __forceinline__ uint32_t quant1(float x, float inv)
     float r = rintf(x * inv);                 // one fp32 multiply, round half to even
     r = fminf(fmaxf(r, -127.0f), 127.0f);
     return (uint32_t)((int)r) & 0xffu;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+
+// ---- scale from absmax --------------------------------------------------------------
+// Called by every thread at the top of a quantise kernel.  Reduces the n_slot
+// candidate maxima, returns the multiplier inv and the scale; *bad is set when
+// the tensor holds a NaN or an infinity.
+__device__ __forceinline__ float scale_from_bits(uint32_t bits, const float *__restrict__ fixed_scale, float *scale,
+                                                 bool *bad)
+{
+    float inv, sc;
+    *bad = bits >= 0x7f800000u;
+    if (fixed_scale) {
+        sc = *fixed_scale;
+        inv = (float)(1.0 / (double)sc);
+    } else {
+        if (*bad) bits = 0;
+        const float absmax = __uint_as_float(bits);
+        sc = (float)((double)absmax / 127.0);
+        inv = (float)(127.0 / (double)absmax);
+    }
+    if (!(inv <= 3.402823466e+38f) || !(sc > 0.0f)) { sc = 1.0f; inv = 0.0f; }
+    *scale = sc;
+    return inv;
+}
+
+// The lane's share of the n_slot candidate maxima: up to eight independent
+// loads, requested together (one memory round trip, not one per candidate).
+// The loads are unconditional (index clamped, value masked afterwards): a load
+// under a branch is awaited at the end of the branch, one round trip each.
+__device__ __forceinline__ uint32_t lane_candidates(const uint32_t *__restrict__ slot, int n_slot, int slot_stride)
+{
+    if (n_slot <= 0) return 0u;
+    const int lane = threadIdx.x & 63;
+    uint32_t v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int i = lane + 64 * k;
+        v[k] = slot[(size_t)(i < n_slot ? i : n_slot - 1) * slot_stride];
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) bits = (lane + 64 * k < n_slot && v[k] > bits) ? v[k] : bits;
+    for (int i = lane + 512; i < n_slot; i += 64) {
+        const uint32_t w = slot[(size_t)i * slot_stride];
+        bits = bits > w ? bits : w;
+    }
+    return bits;
+}
+
+__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+                                             const float *__restrict__ fixed_scale, float *scale, bool *bad)
+{
+    const uint32_t bits = wave_max_u32(lane_candidates(slot, n_slot, slot_stride));
+    return scale_from_bits(bits, fixed_scale, scale, bad);
+}
+
+// Only thread 0 of block 0 of a quantise kernel reads or writes the flag word,
+// and kernels that share a workspace are ordered on one stream, so plain
+// accesses are enough.  Memory that does not yet carry the magic is initialised.
+__device__ __forceinline__ void publish(float scale, bool bad, float *scale_out, float *scale_out2, uint32_t *flag)
+{
+    *scale_out = scale;
+    if (scale_out2) *scale_out2 = scale;
+    if (flag) {
+        uint32_t f = *flag;
+        if ((f & 0xffffff00u) != kFlagMagic) f = kFlagMagic;
+        if (bad) f |= kFlagNonFinite;
+        *flag = f;
+    }
 }
 #endif
 

@@ -498,7 +498,9 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     const int p = lane & 31, h = lane >> 5;
     const int64_t m = ((int64_t)blockIdx.x * 4 + wave) * 32 + p;
     const bool m_ok = m < g.M;
-    const int ow = (int)(m % g.W), oh = (int)((m / g.W) % g.H);
+    // the operand's extent is below 2^31 bytes, so pixel indices fit 32 bits (64-bit division is slow)
+    const uint32_t mrow = (uint32_t)m / (uint32_t)g.W;
+    const int ow = (int)((uint32_t)m - mrow * (uint32_t)g.W), oh = (int)(mrow % (uint32_t)g.H);
     const float s = (*g.sx) * (g.sw_per_n ? (p < g.N ? g.sw[p] : 0.0f) : *g.sw);   // lane's output channel is p
     const float rs = g.res_q ? *g.res_scale : 0.0f;
     // the residual of the workgroup's 128 pixels (16 bytes each, contiguous): requested now with
@@ -561,6 +563,286 @@ __global__ __launch_bounds__(256) void conv3x3_c16_kernel(const GemmArgs g)
     }
 }
 
+// ---- the same convolution with the quantiser of its operands folded in -------------------
+// A workgroup owns 128 consecutive output pixels.  It reduces the candidate
+// maxima of the operand's quantise point to the scale (as every quantise kernel
+// does), turns the fp32 values of its pixels and of the W + 1 pixels before and
+// after them into int8 codes in LDS (16 bytes per pixel), and the five MFMAs
+// of a wave read their operands from there.  The residual of the skip
+// connection is either a block of ready codes or, likewise, the block input
+// quantised on load.  Workgroup 0 stores the scales for later kernels.
+// All global reads of this kernel are raw buffer loads: a request that must not
+// happen (a pixel outside the tensor, a channel beyond c, a candidate beyond n) is
+// given an offset outside the buffer and returns zero, so no load sits under a
+// branch.  (A load under a branch is awaited where the branch ends: one memory
+// round trip per load instead of one for all of them.)  Extents are below 2^31.
+constexpr uint32_t kNoLoad = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void *p, int64_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)p, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buffer_f32(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+template <bool BF16>
+__device__ __forceinline__ float buffer_elem(__amdgpu_buffer_rsrc_t r, uint32_t index, bool ok)
+{
+    if (BF16) return __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)(ok ? index * 2 : kNoLoad), 0, 0) << 16);
+    return buffer_f32(r, ok ? index * 4 : kNoLoad);
+}
+// channels [4 gq, 4 gq + 4) of pixel pi of a [n, c, hw] tensor (zeros beyond c and where !ok)
+template <bool BF16>
+__device__ __forceinline__ float4 plane_values(__amdgpu_buffer_rsrc_t r, int c, uint32_t hw, uint32_t pi, int gq, bool ok)
+{
+    const uint32_t img = pi / hw, pp = pi - img * hw;                // pixel counts fit 31 bits here: 32-bit division
+    const uint32_t base = (img * c + gq * 4) * hw + pp;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = buffer_elem<BF16>(r, base + e * hw, ok && gq * 4 + e < c);
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+// item idx of the operand stage: four channels of one of the npix staged pixels.
+// Rows of c floats: four consecutive threads share a pixel; channel planes:
+// consecutive threads take consecutive pixels of one channel group.
+template <int A_SRC>
+__device__ __forceinline__ void operand_item(int idx, int npix, int &j, int &gq)
+{
+    if (A_SRC == 1) { j = idx >> 2; gq = idx & 3; }
+    else { gq = idx / npix; j = idx - gq * npix; }
+}
+template <int A_SRC, bool BF16, bool C16>
+__device__ __forceinline__ float4 load_operand_item(__amdgpu_buffer_rsrc_t r, int c, int M, uint32_t hw, int first_pix, int npix, int idx)
+{
+    int j, gq;
+    operand_item<A_SRC>(idx, npix, j, gq);
+    const int pi = first_pix + j;
+    const bool ok = idx < npix * 4 && pi >= 0 && pi < M;
+    if (A_SRC == 1) {
+        const uint32_t row = (uint32_t)pi * (uint32_t)c;
+        if (C16) {
+            const v4u q = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(ok ? (row + gq * 4) * 4 : kNoLoad), 0, 0);
+            return make_float4(__uint_as_float(q[0]), __uint_as_float(q[1]), __uint_as_float(q[2]), __uint_as_float(q[3]));
+        }
+        float t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = buffer_f32(r, (ok && gq * 4 + e < c) ? (row + gq * 4 + e) * 4 : kNoLoad);
+        return make_float4(t[0], t[1], t[2], t[3]);
+    }
+    return plane_values<BF16>(r, c, hw, (uint32_t)pi, gq, ok);
+}
+// the lane's share of n candidate maxima, `stride` words apart (n <= 512)
+__device__ __forceinline__ uint32_t buffer_candidates(const uint32_t *slot, int n, int stride)
+{
+    const __amdgpu_buffer_rsrc_t r = raw_buffer(slot, n > 0 ? ((int64_t)(n - 1) * stride + 1) * 4 : 0);
+    const int lane = threadIdx.x & 63;
+    uint32_t v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int i = lane + 64 * k;
+        v[k] = __builtin_amdgcn_raw_buffer_load_b32(r, (int)(i < n ? (uint32_t)(i * stride) * 4 : kNoLoad), 0, 0);
+    }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) bits = v[k] > bits ? v[k] : bits;
+    return bits;
+}
+__device__ __forceinline__ uint32_t pack_codes(float4 v, float inv)
+{
+    return quant1(v.x, inv) | quant1(v.y, inv) << 8 | quant1(v.z, inv) << 16 | quant1(v.w, inv) << 24;
+}
+
+// XBF16: the channel planes read (operand of a_src 2, residual of res_src 1) hold bf16; C16 (a_src 1): rows of 16 floats
+template <int A_SRC, bool XBF16, bool C16>
+__global__ __launch_bounds__(256) void conv3x3_c16_fused_kernel(const GemmArgs g, const ConvFuse z)
+{
+    // [128][16] residual codes, bias [32], weight scale [32], [128 + 2 (W + 1)][16] operand codes
+    extern __shared__ __attribute__((aligned(16))) uint8_t sdyn[];
+    uint8_t *sres = sdyn, *sa = sdyn + 128 * 16 + 256;
+    float *sbias = (float *)(sdyn + 128 * 16), *ssw = sbias + 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 31, h = lane >> 5;
+    const int m0 = blockIdx.x * 128, M = (int)g.M;
+    const uint32_t hw = (uint32_t)g.H * (uint32_t)g.W;
+    const int halo = g.W + 1, npix = 128 + 2 * halo;
+    const int xes = XBF16 ? 2 : 4;
+
+    // ---- every request the workgroup depends on goes out before anything is awaited:
+    // the first 1024 items of the operand stage (all of it up to 62 pixels of width), the
+    // residual, the weights and the candidate maxima
+    const __amdgpu_buffer_rsrc_t ra = raw_buffer(z.a_f, A_SRC == 0 ? 0 : (int64_t)M * z.c * (A_SRC == 1 ? 4 : xes));
+    constexpr int NB = 4;
+    float4 raw[NB];
+    if (A_SRC != 0) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) raw[b] = load_operand_item<A_SRC, XBF16, C16>(ra, z.c, M, hw, m0 - halo, npix, threadIdx.x + 256 * b);
+    }
+    // both forms of the residual are requested; the one that is not in use has an empty buffer
+    const bool res_planes = z.res_src == 1, res_codes = !res_planes && g.res_q != nullptr;
+    const __amdgpu_buffer_rsrc_t rrp = raw_buffer(z.res_f, res_planes ? (int64_t)M * z.res_c * xes : 0);
+    const __amdgpu_buffer_rsrc_t rrq = raw_buffer(g.res_q, res_codes ? (int64_t)M * 16 : 0);
+    float4 rraw[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int idx = threadIdx.x + 256 * b, gq = idx >> 7, j = idx & 127;
+        rraw[b] = plane_values<XBF16>(rrp, z.res_c, hw, (uint32_t)(m0 + j), gq, res_planes && m0 + j < M);
+    }
+    const int rpi = m0 + (int)(threadIdx.x & 127);
+    const v4i rv = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rrq, (int)((res_codes && rpi < M) ? (uint32_t)rpi * 16 : kNoLoad), 0, 0));
+    const __amdgpu_buffer_rsrc_t rw = raw_buffer(g.w, g.w_bytes);
+    v4i fb[5];
+#pragma unroll
+    for (int st = 0; st < 5; ++st) {
+        const int tap = 2 * st + h;
+        fb[st] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(
+                                             rw, (int)((p < g.N && tap < 9) ? (uint32_t)(p * g.kp + tap * 16) : kNoLoad), 0, 0));
+    }
+    // bias and weight scale of output channel t, for threads t < 32 (zero beyond N)
+    const __amdgpu_buffer_rsrc_t rb = raw_buffer(g.bias, g.bias ? (int64_t)g.N * 4 : 0);
+    const __amdgpu_buffer_rsrc_t rs_w = raw_buffer(g.sw, g.sw_per_n ? (int64_t)g.N * 4 : 4);
+    const uint32_t ct = threadIdx.x & 31;
+    const float bias_t = buffer_f32(rb, ct * 4), sw_t = buffer_f32(rs_w, g.sw_per_n ? ct * 4 : 0u);
+    uint32_t cand_a = 0, cand_r = 0;
+    if (A_SRC != 0) cand_a = buffer_candidates(z.a_slot, z.a_nslot, z.a_stride);
+    cand_r = buffer_candidates(z.res_slot, res_planes ? z.res_nslot : 0, z.res_stride);
+
+    float scale_a;
+    if (A_SRC != 0) {
+        bool bad;
+        const float inv = scale_from_bits(wave_max_u32(cand_a), z.a_fixed, &scale_a, &bad);
+        if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale_a, bad, z.a_scale_out, nullptr, z.flag);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int idx = threadIdx.x + 256 * b;
+            int j, gq;
+            operand_item<A_SRC>(idx, npix, j, gq);
+            if (idx < npix * 4) *(uint32_t *)&sa[j * 16 + gq * 4] = pack_codes(raw[b], inv);
+        }
+        for (int idx = threadIdx.x + 256 * NB; idx < npix * 4; idx += 256) {       // wide images
+            int j, gq;
+            operand_item<A_SRC>(idx, npix, j, gq);
+            *(uint32_t *)&sa[j * 16 + gq * 4] = pack_codes(load_operand_item<A_SRC, XBF16, C16>(ra, z.c, M, hw, m0 - halo, npix, idx), inv);
+        }
+    } else {
+        scale_a = *g.sx;
+    }
+    if (threadIdx.x < 32) {
+        sbias[threadIdx.x] = bias_t;
+        ssw[threadIdx.x] = (int)threadIdx.x < g.N ? sw_t : 0.0f;
+    }
+    float rs = 0.0f;
+    const bool has_res = z.res_src == 1 || g.res_q != nullptr;
+    if (z.res_src == 1) {
+        bool bad;
+        const float inv = scale_from_bits(wave_max_u32(cand_r), z.res_fixed, &rs, &bad);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int idx = threadIdx.x + 256 * b, gq = idx >> 7, j = idx & 127;
+            *(uint32_t *)&sres[j * 16 + gq * 4] = pack_codes(rraw[b], inv);
+        }
+    } else if (g.res_q) {
+        rs = *g.res_scale;
+        if (threadIdx.x < 128) *(v4i *)&sres[threadIdx.x * 16] = rv;
+    }
+    __syncthreads();
+
+    const int lp = wave * 32 + p;                                    // the lane's output pixel within the workgroup
+    const int m = m0 + lp;
+    const bool m_ok = m < M;
+    const uint32_t mrow = (uint32_t)m / (uint32_t)g.W;
+    const int ow = (int)((uint32_t)m - mrow * (uint32_t)g.W), oh = (int)(mrow % (uint32_t)g.H);
+    v4i fa[5];
+#pragma unroll
+    for (int st = 0; st < 5; ++st) {
+        const int tap = 2 * st + h;
+        const int kh = tap / 3, dh = kh - 1, dw = tap - kh * 3 - 1;
+        const bool ok = m_ok && tap < 9 && (unsigned)(oh + dh) < (unsigned)g.H && (unsigned)(ow + dw) < (unsigned)g.W;
+        if (A_SRC != 0) fa[st] = ok ? *(const v4i *)&sa[(lp + halo + dh * g.W + dw) * 16] : v4i{0, 0, 0, 0};
+        else fa[st] = ok ? *(const v4i *)(g.a + ((int64_t)m + dh * g.W + dw) * 16) : v4i{0, 0, 0, 0};
+    }
+    // Weights are the row operand and pixels the column operand, so a lane ends up with 16 output
+    // channels of ONE pixel: channels 8 (r / 4) + 4 h + r % 4 in register r, i.e. four groups of four
+    // consecutive channels, which go out as 16-byte stores.
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+#pragma unroll
+    for (int st = 0; st < 5; ++st) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[st], fa[st], acc, 0, 0, 0);
+
+    const float q_inv = g.q_out ? (float)(1.0 / (double)*g.q_scale) : 0.0f;
+    const int n_out = g.q_out && g.q_ld > g.N ? (int)g.q_ld : g.N;               // channels that receive anything
+    const bool vec = g.y && (g.N & 3) == 0 && (g.ldy & 3) == 0 && ((uintptr_t)g.y & 15) == 0;
+    uint32_t amax = 0;
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi) {
+        const int ch0 = 8 * gi + 4 * h;
+        if (8 * gi >= n_out) break;                                               // uniform
+        if (!m_ok || ch0 >= n_out) continue;
+        const float4 b4 = *(const float4 *)&sbias[ch0], w4 = *(const float4 *)&ssw[ch0];
+        const float bb[4] = {b4.x, b4.y, b4.z, b4.w}, ww[4] = {w4.x, w4.y, w4.z, w4.w};
+        const uint32_t rc = has_res ? *(const uint32_t *)&sres[lp * 16 + (ch0 & 15)] : 0u;
+        float v[4];
+        uint32_t codes = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float t = fmaf((float)acc[4 * gi + e], scale_a * ww[e], bb[e]);
+            if (has_res) t = t + (float)(int8_t)(rc >> (8 * e)) * rs;
+            if (g.act == 1) t = t > 0.0f ? t : 0.0f;
+            const bool ch_ok = ch0 + e < g.N;
+            const uint32_t ab = g.amax_pos ? (t > 0.0f ? __float_as_uint(t) : 0u) : abs_bits(t);
+            amax = (ch_ok && ab > amax) ? ab : amax;
+            codes |= (ch_ok ? quant1(t, q_inv) : 0u) << (8 * e);                  // pad columns of the int8 output are zero
+            v[e] = t;
+        }
+        if (g.y) {
+            float *dst = g.y + (int64_t)m * g.ldy + ch0;
+            if (vec) {
+                *(float4 *)dst = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (ch0 + e < g.N) dst[e] = v[e];
+            }
+        }
+        if (g.q_out && ch0 < g.q_ld) *(uint32_t *)(g.q_out + (int64_t)m * g.q_ld + ch0) = codes;
+    }
+    if (g.absmax_out) {
+        __shared__ uint32_t sm4[4];
+        block_atomic_max(amax, g.absmax_out, sm4);
+    }
+}
+
+hipError_t launch_conv3x3_c16_fused(const GemmArgs &g, const ConvFuse &z, hipStream_t st)
+{
+    // what the kernel assumes: 16-byte pixels, a residual of 16 codes per pixel at most, no raw-accumulator
+    // output, a halo that fits the LDS stage
+    if (!g.conv3x3 || g.cp != 16 || g.N < 1 || g.N > 32 || g.kp != 9 * 16 || g.et != 0 || g.acc_out) return hipErrorInvalidValue;
+    if (g.W < 1 || g.H < 1 || g.W > kConvFuseMaxWidth || g.M % ((int64_t)g.H * g.W) != 0) return hipErrorInvalidValue;
+    if (g.M > 0x7fffffffLL - 2 * (kConvFuseMaxWidth + 1) - 128) return hipErrorInvalidValue;    // 32-bit pixel arithmetic
+    if (z.a_src < 0 || z.a_src > 2 || (z.a_src != 0 && (!z.a_f || z.c < 1 || z.c > 16))) return hipErrorInvalidValue;
+    if (z.a_src == 0 && (!g.a || !g.sx)) return hipErrorInvalidValue;
+    if (z.res_src == 1 && (!z.res_f || z.res_c < 1 || z.res_c > 16 || g.N > 16)) return hipErrorInvalidValue;
+    if (z.res_src == 0 && g.res_q && (g.res_ld != 16 || g.N > 16)) return hipErrorInvalidValue;
+    const int64_t blocks = (g.M + 127) / 128;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const size_t smem = 128 * 16 + 256 + (z.a_src != 0 ? (size_t)(128 + 2 * (g.W + 1)) * 16 : 0);
+    const dim3 grid((unsigned)blocks), block(256);
+    // what the kernel's 32-bit offsets assume
+    if (g.M * 16 * 4 >= (1LL << 31) || g.w_bytes >= (1LL << 31) || z.a_nslot > 512 || z.res_nslot > 512) return hipErrorInvalidValue;
+    // XBF16: element type of the planes read (the block input: operand of a_src 2, residual of res_src 1)
+    const bool xbf16 = z.a_src == 2 ? z.a_bf16 != 0 : (z.res_src == 1 && z.res_bf16 != 0);
+    if (z.a_src == 2 && z.res_src == 1 && (z.a_bf16 != 0) != (z.res_bf16 != 0)) return hipErrorInvalidValue;
+#define EG_FUSED(A, B, C) launch_k(EGERIA_KERNEL_GEMM, conv3x3_c16_fused_kernel<A, B, C>, grid, block, smem, st, g, z)
+    if (z.a_src == 0) return xbf16 ? EG_FUSED(0, true, false) : EG_FUSED(0, false, false);
+    if (z.a_src == 1) {
+        if (z.c == 16) return xbf16 ? EG_FUSED(1, true, true) : EG_FUSED(1, false, true);
+        return xbf16 ? EG_FUSED(1, true, false) : EG_FUSED(1, false, false);
+    }
+    return xbf16 ? EG_FUSED(2, true, false) : EG_FUSED(2, false, false);
+#undef EG_FUSED
+}
+
 // The tile shapes on offer: rows x columns of the output tile, K bytes per
 // step, workgroups of that shape that fit a CU together (registers and LDS),
 // and the relative cost of a unit of tile area (smaller tiles move more LDS
@@ -620,7 +902,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
         const int64_t blocks = (g.M + 127) / 128;
         if (blocks <= 0) return hipSuccess;
-        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (g.M >= (1LL << 31)) return hipErrorInvalidValue;            // 32-bit pixel arithmetic in the kernel
         return launch_k(EGERIA_KERNEL_GEMM, conv3x3_c16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g);
     }
     if (g.N <= 32) return launch_variant<128, 32, 4, 1, 64>(g, st);

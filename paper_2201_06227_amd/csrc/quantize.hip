@@ -6,16 +6,6 @@
 namespace egeria {
 
 // ---- absolute maximum -------------------------------------------------------------
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-
 __device__ __forceinline__ uint32_t max4_bits(float4 v)
 {
     uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
@@ -104,57 +94,6 @@ hipError_t launch_absmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *pa
     if (dt == EGERIA_F32)
         return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<false>, grid, block, 0, st, x, n, partials, reset, n_reset);
     return launch_k(EGERIA_KERNEL_ABSMAX, absmax_kernel<true>, grid, block, 0, st, x, n, partials, reset, n_reset);
-}
-
-// ---- scale from absmax --------------------------------------------------------------
-// Called by every thread at the top of a quantise kernel.  Reduces the n_slot
-// candidate maxima, returns the multiplier inv and the scale; *bad is set when
-// the tensor holds a NaN or an infinity.
-__device__ __forceinline__ float scale_from_bits(uint32_t bits, const float *__restrict__ fixed_scale, float *scale,
-                                                 bool *bad)
-{
-    float inv, sc;
-    *bad = bits >= 0x7f800000u;
-    if (fixed_scale) {
-        sc = *fixed_scale;
-        inv = (float)(1.0 / (double)sc);
-    } else {
-        if (*bad) bits = 0;
-        const float absmax = __uint_as_float(bits);
-        sc = (float)((double)absmax / 127.0);
-        inv = (float)(127.0 / (double)absmax);
-    }
-    if (!(inv <= 3.402823466e+38f) || !(sc > 0.0f)) { sc = 1.0f; inv = 0.0f; }
-    *scale = sc;
-    return inv;
-}
-
-__device__ __forceinline__ float scales_from(const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
-                                             const float *__restrict__ fixed_scale, float *scale, bool *bad)
-{
-    uint32_t bits = 0;
-    const int lane = threadIdx.x & 63;
-    for (int i = lane; i < n_slot; i += 64) {
-        const uint32_t v = slot[(size_t)i * slot_stride];
-        bits = bits > v ? bits : v;
-    }
-    bits = wave_max_u32(bits);
-    return scale_from_bits(bits, fixed_scale, scale, bad);
-}
-
-// Only thread 0 of block 0 of a quantise kernel reads or writes the flag word,
-// and kernels that share a workspace are ordered on one stream, so plain
-// accesses are enough.  Memory that does not yet carry the magic is initialised.
-__device__ __forceinline__ void publish(float scale, bool bad, float *scale_out, float *scale_out2, uint32_t *flag)
-{
-    *scale_out = scale;
-    if (scale_out2) *scale_out2 = scale;
-    if (flag) {
-        uint32_t f = *flag;
-        if ((f & 0xffffff00u) != kFlagMagic) f = kFlagMagic;
-        if (bad) f |= kFlagNonFinite;
-        *flag = f;
-    }
 }
 
 template <bool BF16>

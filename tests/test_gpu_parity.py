@@ -180,6 +180,50 @@ def test_basic_block_bit_exact(eg, gc, orc, kw):
     assert (a_ref[0].reshape(-1, kw["c"]) == gc.nhwc(ot["a_ref"])).all()
 
 
+NARROW_CASES = [dict(b=1, c=1, h=1, w=1), dict(b=3, c=8, h=7, w=6), dict(b=3, c=16, h=9, w=11),
+                dict(b=5, c=16, h=32, w=32), dict(b=2, c=5, h=3, w=200), dict(b=1, c=16, h=2, w=300),
+                dict(b=2, c=20, h=9, w=11)]
+
+
+def _run_unobserved(eg, gc, wl, x_dev, act_scales=None):
+    ref = gc.build_reference(wl, act_scales)
+    a_ref = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    eg.ref_forward(ref, x_dev, a_ref, ws, None)
+    torch.cuda.synchronize()
+    return a_ref.cpu().numpy(), eg.check(ws)
+
+
+@pytest.mark.parametrize("kw", NARROW_CASES, ids=lambda k: "b{b}_c{c}_{h}x{w}".format(**k))
+@pytest.mark.parametrize("res", [1, 0])
+@pytest.mark.parametrize("xdt", ["f32", "bf16"])
+def test_basic_block_unobserved_bit_exact(eg, gc, orc, kw, res, xdt):
+    """Unobserved runs of narrow basic blocks quantise their operands inside the convolutions (no int8
+    tensor is stored); wide images and wider blocks take the general path.  Same A_R either way, with
+    dynamic and with static scales, with and without the skip connection, fp32 and bf16 block input."""
+    wl = si.make_basic_block(seed=330 + kw["c"] + kw["w"], **kw)
+    wl.dims["has_residual"] = res
+    if xdt == "bf16":
+        wl.x = torch.from_numpy(wl.x).to(torch.bfloat16).float().numpy()
+    x_dev = gc.to_dev(wl.x, torch.bfloat16 if xdt == "bf16" else None)
+    ot = orc.ref_forward(wl)
+    got, status = _run_unobserved(eg, gc, wl, x_dev)
+    assert status == eg.OK
+    assert (got.reshape(-1, kw["c"]) == gc.nhwc(ot["a_ref"])).all()
+    scales = [0.7 * float(ot[f"l{i}.sx"]) for i in range(2)]              # static, a little clipping
+    want = gc.nhwc(orc.ref_forward(wl, act_scales=scales)["a_ref"])
+    got, status = _run_unobserved(eg, gc, wl, x_dev, scales)
+    assert status == eg.OK
+    assert (got.reshape(-1, kw["c"]) == want).all()
+
+
+def test_basic_block_unobserved_reports_non_finite_input(eg, gc):
+    wl = si.make_basic_block(seed=77, b=2, c=16, h=8, w=8)
+    wl.x[1, 3, 2, 5] = np.inf
+    _, status = _run_unobserved(eg, gc, wl, gc.to_dev(wl.x))
+    assert status == eg.ERR_NONFINITE
+
+
 BOTTLENECK_CASES = [dict(b=2, c_in=32, c_mid=16, h=5, w=5), dict(b=1, c_in=40, c_mid=24, h=7, w=3),
                     dict(b=3, c_in=256, c_mid=64, h=14, w=14),
                     dict(b=2, c_in=32, c_mid=16, h=5, w=5, has_residual=0)]
@@ -541,3 +585,8 @@ def test_per_channel_weights_bit_exact(eg, gc, orc, kind, kw):
             _check_linear_taps(gc, {k: v.cpu().numpy() for k, v in bufs[i].items()}, ot, f"l{i}.", conv=conv)
         want = gc.nhwc(ot["a_ref"]).reshape(wl.batch, -1) if conv else ot["a_ref"]
         assert np.array_equal(got[0], want)
+        # unobserved run (narrow basic blocks quantise inside the convolutions there)
+        plain = torch.empty_like(a_ref)
+        eg.ref_forward(ref, x, plain, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(plain.cpu().numpy().reshape(wl.batch, -1), want)
