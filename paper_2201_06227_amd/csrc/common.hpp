@@ -285,6 +285,12 @@ __device__ __forceinline__ uint32_t reduce_ways(const uint32_t *slot)
     }
     return v;
 }
+// a / b for 0 <= a, 0 < b; in 32-bit arithmetic when `narrow` says both are below 2^32 (a 64-bit
+// integer division is a call of some 150 instructions per lane, a 32-bit one a sixth of that).
+__device__ __forceinline__ int64_t div_u(int64_t a, int64_t b, bool narrow)
+{
+    return narrow ? (int64_t)((uint32_t)a / (uint32_t)b) : a / b;
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 // int8 code of x under the multiplier inv = 1 / scale.
 __device__ __forceinline__ uint32_t quant1(float x, float inv)

@@ -119,10 +119,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t upr = (ldq + 15) >> 4;                     // 16-byte units per row
     const int64_t units = rows * upr;
+    const bool narrow = units < (1LL << 32);
     const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
     for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
          u += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = u / upr;
+        const int64_t row = div_u(u, upr, narrow);
         const int64_t c0 = (u - row * upr) << 4;
         const int64_t base = row * cols + c0;
         uint32_t w[4] = {0, 0, 0, 0};
@@ -236,10 +237,11 @@ __global__ __launch_bounds__(256) void quantize_nchw_vec_kernel(
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t pq = hw >> 2, cg = cp >> 4;
     const int64_t units = n * cg * pq;
+    const bool narrow = units < (1LL << 32);
     for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t p = (u % pq) << 2;
-        const int64_t ig = u / pq;
-        const int64_t g = ig % cg, img = ig / cg;
+        const int64_t ig = div_u(u, pq, narrow);
+        const int64_t p = (u - ig * pq) << 2;
+        const int64_t img = div_u(ig, cg, narrow), g = ig - img * cg;
         const int64_t ch0 = g << 4;
         float4 v[16];
 #pragma unroll
@@ -409,11 +411,12 @@ __device__ __forceinline__ void job_share_quantize(const WeightJob &jb, int lb, 
     int64_t end = beg + jb.upb;
     if (end > units) end = units;
     const bool rows_vec = jb.hw == 1 && !jb.bf16 && (jb.c & 3) == 0;
+    const bool narrow = units < (1LL << 32);
     for (int64_t u = beg + threadIdx.x; u < end; u += 256) {
-        const int c0 = (int)(u % cpu) << 4;
-        const int64_t op = u / cpu;                       // o * hw + pixel
-        const int pix = (int)(op % jb.hw);
-        const int64_t oc = op / jb.hw;
+        const int64_t op = div_u(u, cpu, narrow);         // o * hw + pixel
+        const int c0 = (int)(u - op * cpu) << 4;
+        const int64_t oc = div_u(op, jb.hw, narrow);
+        const int pix = (int)(op - oc * jb.hw);
         uint32_t w[4] = {0, 0, 0, 0};
         if (rows_vec && c0 + 16 <= jb.c) {
             const float4 *p = (const float4 *)((const float *)jb.x + oc * jb.c + c0);
@@ -615,10 +618,11 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, nullptr, flag);
     const int64_t upr = ldq >> 4;
     const int64_t units = rows * upr;
+    const bool narrow = units < (1LL << 32);
     const bool vec_ok = (cols & 3) == 0;
     for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
          u += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = u / upr;
+        const int64_t row = div_u(u, upr, narrow);
         const int64_t c0 = (u - row * upr) << 4;
         const int64_t base = row * cols + c0;
         uint32_t w[4] = {0, 0, 0, 0};
