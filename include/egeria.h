@@ -224,7 +224,13 @@ size_t egeria_quantize_workspace_bytes(void);
  *   a_ref  fp32 out, [n_layers][batch, D]: D = c_out (FC), h*w*c_out in NHWC
  *          order (conv kinds; the metric does not depend on the feature order),
  *          seq*hidden (BERT kinds).
- *   taps   NULL or observation points.
+ *   taps   NULL or observation points.  The int8 inputs, accumulators and
+ *          intermediate outputs are defined only where a tap asks for them: a
+ *          run without taps may keep them out of memory altogether (basic
+ *          blocks of at most 16 channels quantise their operands while the
+ *          convolutions load them), so the contents of ws after a call are
+ *          unspecified apart from what egeria_check reads.  a_ref is the same
+ *          bit for bit with and without taps.
  *   ws     at least egeria_workspace_bytes(desc) bytes.
  * Every linear / convolution input is quantised per tensor at run time
  * (dynamic scale), the contraction is int8 x int8 -> int32 on the matrix
