@@ -210,9 +210,15 @@ egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
 {
     const egeria_block_desc *d = f.d;
     const int64_t kp = pad16(d->c_in);
-    if (!f.is_static()) EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
-    EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0), f.stride_amax(0),
-                                f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
+    if (!f.is_static() && (int64_t)d->batch * d->c_in <= kSmallTensor && (int64_t)d->batch * kp < (1LL << 30)) {
+        // a small mini-batch: maximum, scale and codes in one workgroup and one launch
+        EG_HIP(launch_quantize_small(x, dt, (int)d->batch, (int)d->c_in, 1, (int)kp, f.qbuf(0), f.scale(0), ws_flag(f.ws),
+                                     f.st));
+    } else {
+        if (!f.is_static()) EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
+        EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
+                                    f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
+    }
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(d->batch * kp), f.scale(0)));
     return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.sx(0), 1,
                     nullptr, nullptr, 0, a_ref, nullptr);

@@ -103,26 +103,17 @@ __device__ __forceinline__ float load_elem(const void *x, int64_t i)
     return ((const float *)x)[i];
 }
 
-// ---- quantise [rows, cols] -> int8 [rows, ldq] ---------------------------------------
-// One thread produces 16 consecutive codes of one row (one 16-byte store).
+// The map to codes of a [rows, cols] matrix: unit u = 16 consecutive codes of one row (one
+// 16-byte store); this thread takes units first, first + stride, ...
 template <bool BF16>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(
-    const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
-    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
-    const float *__restrict__ fixed_scale,
-    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
-    uint32_t *__restrict__ flag)
+__device__ __forceinline__ void quantize_row_units(const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
+                                                   float inv, int8_t *__restrict__ q, int64_t first, int64_t stride)
 {
-    float scale;
-    bool bad;
-    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
-    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t upr = (ldq + 15) >> 4;                     // 16-byte units per row
     const int64_t units = rows * upr;
     const bool narrow = units < (1LL << 32);
     const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
-    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
-         u += (int64_t)gridDim.x * blockDim.x) {
+    for (int64_t u = first; u < units; u += stride) {
         const int64_t row = div_u(u, upr, narrow);
         const int64_t c0 = (u - row * upr) << 4;
         const int64_t base = row * cols + c0;
@@ -163,6 +154,24 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(
             for (int e = 0; e < 16 && c0 + e < ldq; ++e) dst[e] = (int8_t)((w[e >> 2] >> ((e & 3) * 8)) & 0xff);
         }
     }
+}
+
+// ---- quantise [rows, cols] -> int8 [rows, ldq] ---------------------------------------
+// One thread produces 16 consecutive codes of one row (one 16-byte store).
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(
+    const void *__restrict__ x, int64_t rows, int64_t cols, int64_t ldq,
+    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+    const float *__restrict__ fixed_scale,
+    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
+    uint32_t *__restrict__ flag)
+{
+    float scale;
+    bool bad;
+    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
+    quantize_row_units<BF16>(x, rows, cols, ldq, inv, q, (int64_t)blockIdx.x * blockDim.x + threadIdx.x,
+                             (int64_t)gridDim.x * blockDim.x);
 }
 
 hipError_t launch_quantize_rows(const void *x, egeria_dtype dt, int64_t rows, int64_t cols,
@@ -304,9 +313,32 @@ __global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restr
 {
     const int total = nimg * c * hw;
     uint32_t m = 0;
-    for (int i = threadIdx.x; i < total; i += 256) {
-        const uint32_t a = abs_bits(load_elem<BF16>(x, i));
-        m = m > a ? m : a;
+    if (!BF16 && ((uintptr_t)x & 15) == 0) {
+        // 16-byte loads, four of them requested together
+        const float4 *x4 = (const float4 *)x;
+        const int n4 = total >> 2;
+        int i = threadIdx.x;
+        for (; i + 768 < n4; i += 1024) {
+            const float4 v0 = x4[i], v1 = x4[i + 256], v2 = x4[i + 512], v3 = x4[i + 768];
+            uint32_t a = max4_bits(v0), b = max4_bits(v1), cc = max4_bits(v2), d = max4_bits(v3);
+            a = a > b ? a : b;
+            cc = cc > d ? cc : d;
+            a = a > cc ? a : cc;
+            m = m > a ? m : a;
+        }
+        for (; i < n4; i += 256) {
+            const uint32_t a = max4_bits(x4[i]);
+            m = m > a ? m : a;
+        }
+        for (int k = (n4 << 2) + threadIdx.x; k < total; k += 256) {
+            const uint32_t a = abs_bits(((const float *)x)[k]);
+            m = m > a ? m : a;
+        }
+    } else {
+        for (int i = threadIdx.x; i < total; i += 256) {
+            const uint32_t a = abs_bits(load_elem<BF16>(x, i));
+            m = m > a ? m : a;
+        }
     }
     m = wave_max_u32(m);
     __shared__ uint32_t sm[4];
@@ -316,6 +348,10 @@ __global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restr
     bool bad;
     const float inv = scales_from(sm, 4, 1, nullptr, &scale, &bad);
     if (threadIdx.x == 0) publish(scale, bad, scale_out, nullptr, flag);
+    if (hw == 1) {                                   // rows of a matrix: 16 codes per thread and store
+        quantize_row_units<BF16>(x, nimg, c, cp, inv, q, threadIdx.x, 256);
+        return;
+    }
     const int nout = nimg * hw * cp;
     for (int o = threadIdx.x; o < nout; o += 256) {
         const int ch = o % cp, pp = (o / cp) % hw, img = o / (cp * hw);

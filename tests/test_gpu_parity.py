@@ -323,6 +323,10 @@ def test_full_size_configs_bit_exact_and_scored(eg, gc, orc, cfg):
         _check_linear_taps(gc, taps[i], ot, f"l{i}.", conv=conv)
     want = gc.nhwc(ot["a_ref"]).reshape(wl.batch, -1) if conv else ot["a_ref"]
     assert (a_ref[0] == want).all()
+    # the run without observation points is the one the benchmark times (other kernels in places)
+    plain, status = _run_unobserved(eg, gc, wl, gc.to_dev(wl.x))
+    assert status == eg.OK
+    assert (plain.reshape(wl.batch, -1) == want).all()
     a_t = si.train_forward(wl)[0]
     p_want = orc.sp_loss(a_t.float().numpy(), want)
     ws = eg.workspace(eg.workspace_bytes(ref.desc))
