@@ -192,8 +192,10 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         a_ok[it] = m < g.M;
         a_base[it] = a_ok[it] ? (uint32_t)(m * (CONV ? (int64_t)g.cp : g.lda)) : 0u;
         if (CONV) {
-            a_ow[it] = (int)(m % g.W);
-            a_oh[it] = (int)((m / g.W) % g.H);
+            // the operand's extent is below 2^31 bytes, so m fits 32 bits (a 64-bit division is a long call)
+            const uint32_t mrow = (uint32_t)m / (uint32_t)g.W;
+            a_ow[it] = (int)((uint32_t)m - mrow * (uint32_t)g.W);
+            a_oh[it] = (int)(mrow % (uint32_t)g.H);
         }
     }
     uint32_t b_base[B_IT];
@@ -915,7 +917,10 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
         const int64_t slots = 256 * (int64_t)sh.resident;
         const int64_t rounds = (tiles + slots - 1) / slots;
-        const double cost = (double)rounds * sh.resident * sh.bm * sh.bn * sh.penalty;
+        double cost = (double)rounds * sh.resident * sh.bm * sh.bn * sh.penalty;
+        // K of a few steps: the kernel is a stream of fp32 stores, and the more workgroups a CU holds the
+        // better they overlap (12544 x 1024 x 256: 128x64 with four per CU 17 us, 128x128 with two 21 us)
+        if (g.kp < 512) cost *= 1.0 + 0.15 * (4 - sh.resident);
         if (best_cost == 0.0 || cost < best_cost) {
             best_cost = cost;
             best = i;
