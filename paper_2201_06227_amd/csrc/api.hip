@@ -298,7 +298,10 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
     const int H = d->height, W = d->width;
     if (!f.is_static()) EG_OK(f.input_absmax(x, dt, M * d->c_in));
-    if (d->kind == EGERIA_BASIC_BLOCK && !f.taps && cin_p == 16 && W <= kConvFuseMaxWidth && M < (1LL << 27)) return forward_narrow_block(f, x, dt, a_ref);
+    // narrow basic blocks on an unobserved run: the convolutions quantise their own operands
+    // (the kernel's 32-bit byte offsets hold 2^25 pixels of 16 fp32 channels)
+    if (d->kind == EGERIA_BASIC_BLOCK && !f.taps && cin_p == 16 && W <= kConvFuseMaxWidth && M < (1LL << 25))
+        return forward_narrow_block(f, x, dt, a_ref);
     EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
                                 f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));

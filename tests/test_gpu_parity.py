@@ -217,6 +217,29 @@ def test_basic_block_unobserved_bit_exact(eg, gc, orc, kw, res, xdt):
     assert (got.reshape(-1, kw["c"]) == want).all()
 
 
+def test_basic_block_unobserved_random_shapes(eg, gc, orc):
+    """Seeded random narrow blocks (1-16 channels, images of 1-40 x 1-70 pixels, 1-5 samples): the
+    convolutions that quantise on load against the oracle, bit for bit."""
+    rng = np.random.default_rng(20240611)
+    for case in range(24):
+        kw = dict(b=int(rng.integers(1, 6)), c=int(rng.integers(1, 17)), h=int(rng.integers(1, 41)),
+                  w=int(rng.integers(1, 71)))
+        wl = si.make_basic_block(seed=9000 + case, **kw)
+        wl.dims["has_residual"] = int(rng.integers(0, 2))
+        bf16 = bool(rng.integers(0, 2))
+        if bf16:
+            wl.x = torch.from_numpy(wl.x).to(torch.bfloat16).float().numpy()
+        x_dev = gc.to_dev(wl.x, torch.bfloat16 if bf16 else None)
+        ot = orc.ref_forward(wl)
+        scales = None
+        if rng.integers(0, 2):
+            scales = [float(rng.uniform(0.5, 1.2)) * float(ot[f"l{i}.sx"]) for i in range(2)]
+            ot = orc.ref_forward(wl, act_scales=scales)
+        got, status = _run_unobserved(eg, gc, wl, x_dev, scales)
+        assert status == eg.OK, (case, kw)
+        assert (got.reshape(-1, kw["c"]) == gc.nhwc(ot["a_ref"])).all(), (case, kw, wl.dims, bf16, scales)
+
+
 def test_basic_block_unobserved_reports_non_finite_input(eg, gc):
     wl = si.make_basic_block(seed=77, b=2, c=16, h=8, w=8)
     wl.x[1, 3, 2, 5] = np.inf
