@@ -61,7 +61,10 @@ static GramPlan plan_gram(int32_t b, int64_t D)
     p.nm = p.mt == 1 ? 1 : (b + 63) / 64;
     p.nmacro = p.nm * p.nm;
     p.kt = p.mt == 1 ? 64 : 32;
-    int64_t want = (512 + p.nmacro - 1) / p.nmacro;       // about two workgroups per CU
+    // about one workgroup per CU: measured per score (partials + finaliser, us) for targets of 128 / 256 /
+    // 512 / 1024 workgroups: b = 32, D = 98304: 19.6 / 17.6 / 20.6 / 24.6; b = 64, D = 200704: 57.7 / 43.5 /
+    // 43.8 / 55.9 (more chunks mean more partials for the finaliser to add)
+    int64_t want = (256 + p.nmacro - 1) / p.nmacro;
     int64_t cap = D / ((p.mt == 1 ? 4 : 2) * (int64_t)b);  // bound the partials by a fraction of the input bytes
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
