@@ -504,7 +504,7 @@ def main():
         "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.workload], "evals_per_step": ev.n_layers,
-                   "step": "weight quantise + int8 reference forward + plasticity score", "launch": "eager",
+                   "step": "weight quantise + int8 reference forward + plasticity score (one egeria_refresh_eval call)", "launch": "eager",
                    "kernel_timing": "HIP event pairs around every launch of the dominant kernel class on every 8th step "
                                     "of the timed region",
                    "arithmetic": "int8 x int8 -> int32 contractions, fp32 epilogues, exact fp32 Gram products (bf16 partial products, fp32 sums), fp64 finaliser"},

@@ -9,7 +9,8 @@
  *      module's output activation A_R                         (egeria_ref_forward)
  *   3. score the training model's activation A_T against A_R with the
  *      training-plasticity metric of Eq. 1 (SP loss)          (egeria_plasticity)
- * egeria_plasticity_eval chains 2 and 3 for a stack of modules.
+ * egeria_plasticity_eval chains 2 and 3 for a stack of modules,
+ * egeria_refresh_eval chains 1, 2 and 3.
  *
  * General rules of this interface
  *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The
@@ -261,6 +262,20 @@ egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria
                                      const void *x, egeria_dtype x_dt,
                                      const void *const *a_train, egeria_dtype t_dt, float *p_out,
                                      void *ws, size_t ws_bytes, void *stream);
+
+/* Sections 4.1-4.2: refresh of the reference model and evaluation in one call.
+ * The same as egeria_quantize_weights(w, n_w, ws_w, ws_w_bytes, stream) followed
+ * by egeria_plasticity_eval(desc, qw, x, ..., ws, ws_bytes, stream), and the same
+ * results bit for bit (qw must point at the tensors that w writes); the first
+ * pass over the snapshot and the maximum pass over the mini-batch, which do not
+ * depend on each other, share one kernel launch.  Arguments, ownership and
+ * errors as for the two calls; nothing is enqueued if an argument of either is
+ * rejected. */
+egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_w, size_t ws_w_bytes,
+                                  const egeria_block_desc *desc, const egeria_qweights *qw,
+                                  const void *x, egeria_dtype x_dt,
+                                  const void *const *a_train, egeria_dtype t_dt, float *p_out,
+                                  void *ws, size_t ws_bytes, void *stream);
 
 /* Host-only and pure: bytes of workspace egeria_ref_forward and
  * egeria_plasticity_eval need for this module; 0 if desc is invalid. */

@@ -96,6 +96,7 @@ EXPORTS = [
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
     "egeria_freeze_init", "egeria_freeze_observe",
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
+    "egeria_refresh_eval",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -142,6 +143,10 @@ def lib():
     L.egeria_plasticity_eval.restype = ctypes.c_int
     L.egeria_plasticity_eval.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(QWeights), _vp, ctypes.c_int,
                                          ctypes.POINTER(_vp), ctypes.c_int, _vp, _vp, _sz, _vp]
+    L.egeria_refresh_eval.restype = ctypes.c_int
+    L.egeria_refresh_eval.argtypes = [ctypes.POINTER(Weight), _i32, _vp, _sz, ctypes.POINTER(BlockDesc),
+                                      ctypes.POINTER(QWeights), _vp, ctypes.c_int, ctypes.POINTER(_vp), ctypes.c_int,
+                                      _vp, _vp, _sz, _vp]
     L.egeria_workspace_bytes.restype = _sz
     L.egeria_workspace_bytes.argtypes = [ctypes.POINTER(BlockDesc)]
     L.egeria_check.restype = ctypes.c_int

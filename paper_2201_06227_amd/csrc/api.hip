@@ -14,6 +14,11 @@ namespace {
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline int64_t pad16(int64_t k) { return (k + 15) / 16 * 16; }
+// an FC mini-batch small enough for the one-workgroup quantiser (maximum, scale and codes in one launch)
+inline bool fc_input_is_small(const egeria_block_desc *d)
+{
+    return (int64_t)d->batch * d->c_in <= kSmallTensor && (int64_t)d->batch * pad16(d->c_in) < (1LL << 30);
+}
 
 #define EG_HIP(expr)                                   \
     do {                                               \
@@ -130,6 +135,7 @@ struct Fwd {
     hipStream_t st;
 
     int n_in = 1;           // per-workgroup maxima the input's absmax kernel wrote
+    bool input_max_done = false;    // an earlier launch has already taken the input's maxima
     // where the absolute maximum of quantise point i is found: the input tensor's
     // per-workgroup maxima for point 0, an atomically combined word otherwise
     const uint32_t *amax(int i) const { return i == 0 ? ws_partials(ws, p.slots) : ws_absmax(ws, i); }
@@ -151,6 +157,7 @@ struct Fwd {
     egeria_status input_absmax(const void *x, egeria_dtype dt, int64_t n)
     {
         n_in = absmax_blocks(n, dt);
+        if (input_max_done) return EGERIA_OK;
         if (launch_absmax(x, dt, n, ws_partials(ws, p.slots), ws_absmax(ws, 0), p.slots, st) != hipSuccess)
             return EGERIA_ERR_HIP;
         return EGERIA_OK;
@@ -210,10 +217,11 @@ egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
 {
     const egeria_block_desc *d = f.d;
     const int64_t kp = pad16(d->c_in);
-    if (!f.is_static() && (int64_t)d->batch * d->c_in <= kSmallTensor && (int64_t)d->batch * kp < (1LL << 30)) {
+    if (!f.is_static() && fc_input_is_small(d)) {
         // a small mini-batch: maximum, scale and codes in one workgroup and one launch
-        EG_HIP(launch_quantize_small(x, dt, (int)d->batch, (int)d->c_in, 1, (int)kp, f.qbuf(0), f.scale(0), ws_flag(f.ws),
-                                     f.st));
+        if (!f.input_max_done)
+            EG_HIP(launch_quantize_small(x, dt, (int)d->batch, (int)d->c_in, 1, (int)kp, f.qbuf(0), f.scale(0),
+                                         ws_flag(f.ws), f.st));
     } else {
         if (!f.is_static()) EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
         EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
@@ -530,8 +538,12 @@ size_t egeria_quantize_weights_workspace_bytes(int32_t n)
     return align_up(4 * ((size_t)kHeaderFixedWords + (size_t)kWeightBatch * kAbsPartials), 256);
 }
 
-egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes, void *stream)
+// extra: a maximum pass to carry along in the first launch of the first batch of per-tensor
+// scales; *carried tells whether a launch took it.
+static egeria_status quantize_weights_impl(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes, void *stream,
+                                           const InputMaxJob *extra, bool *carried)
 {
+    if (carried) *carried = false;
     if (n < 0 || (n > 0 && !w) || !ws || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
     if (ws_bytes < egeria_quantize_weights_workspace_bytes(n)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
     for (int i = 0; i < n; ++i) {
@@ -592,11 +604,21 @@ egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *w
                 one = one && nblk == 1;
             }
             if (b.n == 0 || blocks == 0) continue;
-            if (pc) EG_HIP(launch_quantize_weights_pc(b, blocks, ws_flag(ws), st));
-            else EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st));
+            if (pc) {
+                EG_HIP(launch_quantize_weights_pc(b, blocks, ws_flag(ws), st));
+            } else {
+                const bool take = extra && carried && !*carried;
+                EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st, take ? extra : nullptr));
+                if (take) *carried = true;
+            }
         }
     }
     return EGERIA_OK;
+}
+
+egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes, void *stream)
+{
+    return quantize_weights_impl(w, n, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
 egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x, void *stream)
@@ -643,9 +665,10 @@ static SideStream *side_stream()
 static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
                                   egeria_dtype x_dt, float *a_ref, const egeria_taps *taps,
                                   const void *const *a_train, egeria_dtype t_dt, float *p_out, void *ws,
-                                  const Plan &p, hipStream_t st)
+                                  const Plan &p, hipStream_t st, bool input_max_done = false)
 {
     Fwd f{desc, qw, taps, (char *)ws, p, st};
+    f.input_max_done = input_max_done;
     const bool eval = p_out != nullptr;
     const size_t aref_elems = (size_t)desc->batch * (size_t)p.D;
     if (desc->kind < EGERIA_BERT_LAYER) {
@@ -732,6 +755,52 @@ egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria
     if (desc->batch > 128) return EGERIA_ERR_UNSUPPORTED;
     if (ws_bytes < p.total) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
     return forward_impl(desc, qw, x, x_dt, nullptr, nullptr, a_train, t_dt, p_out, ws, p, (hipStream_t)stream);
+}
+
+// Elements of the mini-batch whose maximum the forward takes in a launch of its own, or 0 if it
+// has no such launch (static scales, a float reference precision, an FC input small enough for
+// the one-launch quantiser).
+static int64_t input_max_elems(const egeria_block_desc *d, const egeria_qweights *qw, const Plan &p)
+{
+    if (qw->act_scale || d->ref_precision != EGERIA_REF_INT8) return 0;
+    if (d->kind == EGERIA_FC_RELU) return fc_input_is_small(d) ? 0 : (int64_t)d->batch * d->c_in;
+    if (d->kind == EGERIA_BASIC_BLOCK || d->kind == EGERIA_BOTTLENECK) return p.M * d->c_in;
+    return p.M * d->hidden;
+}
+
+egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_w, size_t ws_w_bytes,
+                                  const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
+                                  egeria_dtype x_dt, const void *const *a_train, egeria_dtype t_dt, float *p_out,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    Plan p;
+    EG_OK(check_common(desc, qw, x, x_dt, nullptr, ws, ws_bytes, p));
+    if (!a_train || !p_out) return EGERIA_ERR_INVALID_ARG;
+    if (t_dt != EGERIA_F32 && t_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    for (int l = 0; l < p.n_layers; ++l)
+        if (!a_train[l] || !aligned16(a_train[l])) return EGERIA_ERR_INVALID_ARG;
+    if (desc->batch > 128) return EGERIA_ERR_UNSUPPORTED;
+    if (ws_bytes < p.total) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    InputMaxJob job{};
+    job.n = input_max_elems(desc, qw, p);
+    job.x = x;
+    job.partials = ws_partials(ws, p.slots);
+    job.reset = ws_absmax(ws, 0);
+    job.n_reset = p.slots;
+    job.bf16 = x_dt == EGERIA_BF16 ? 1 : 0;
+    job.nblk = job.n > 0 ? absmax_blocks(job.n, x_dt) : 0;
+    if (desc->kind == EGERIA_FC_RELU && !qw->act_scale && desc->ref_precision == EGERIA_REF_INT8 && fc_input_is_small(desc)) {
+        // the whole quantisation of a small FC input is one workgroup's work
+        job.n = (int64_t)desc->batch * desc->c_in;
+        job.nblk = 1;
+        job.q = (int8_t *)((char *)ws + p.off_q[0]);
+        job.scale_out = ws_scale(ws, p.slots, 0);
+        job.flag = ws_flag(ws);
+        job.rows = desc->batch; job.cols = desc->c_in; job.cp = (int32_t)pad16(desc->c_in);
+    }
+    bool carried = false;
+    EG_OK(quantize_weights_impl(w, n_w, ws_w, ws_w_bytes, stream, job.n > 0 ? &job : nullptr, &carried));
+    return forward_impl(desc, qw, x, x_dt, nullptr, nullptr, a_train, t_dt, p_out, ws, p, (hipStream_t)stream, carried);
 }
 
 egeria_status egeria_check(void *ws, void *stream)

@@ -137,9 +137,25 @@ struct WeightBatch {
     WeightJob job[kWeightBatch];
     int32_t n;
 };
-// one_launch: every job has nblk == 1.  partials: total_blocks words.
+// The first pass over an unrelated tensor (the mini-batch) that rides along in the snapshot's first
+// launch.  q == nullptr: nblk = absmax_blocks(n, dt) extra workgroups doing what launch_absmax
+// would.  q != nullptr (nblk = 1): what launch_quantize_small does for a [rows, cols] matrix.
+struct InputMaxJob {
+    const void *x;
+    int64_t n;
+    uint32_t *partials;
+    uint32_t *reset;
+    int32_t n_reset;
+    int32_t bf16;
+    int32_t nblk;
+    int8_t *q;
+    float *scale_out;
+    uint32_t *flag;
+    int32_t rows, cols, cp;
+};
+// one_launch: every job has nblk == 1.  partials: total_blocks words.  extra: nullable.
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
-                                   uint32_t *flag, hipStream_t st);
+                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra);
 // The same for jobs with one scale per output channel (job.scale is [o]); four channels per workgroup.
 hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, uint32_t *flag, hipStream_t st);
 

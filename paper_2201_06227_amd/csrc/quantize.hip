@@ -16,16 +16,16 @@ __device__ __forceinline__ uint32_t max4_bits(float4 v)
 
 // Each workgroup writes the maximum of its grid-stride share to partials[blockIdx.x]
 // (bit pattern of |x|, so NaN and Inf order above every finite value).
+// (workgroup blk of nblks; a device function so that other kernels can carry the pass along).
 template <bool BF16>
-__global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv, int64_t n,
-                                                     uint32_t *__restrict__ partials,
-                                                     uint32_t *__restrict__ reset, int n_reset)
+__device__ __forceinline__ void absmax_share(const void *__restrict__ xv, int64_t n, uint32_t *__restrict__ partials,
+                                             uint32_t *__restrict__ reset, int n_reset, int blk, int nblks)
 {
-    if (blockIdx.x == 0)
+    if (blk == 0)
         for (int t = threadIdx.x; t < n_reset * kAmaxWays; t += blockDim.x)
             reset[(size_t)(t / kAmaxWays) * kAmaxWays * kAmaxStride + (t % kAmaxWays) * kAmaxStride] = 0u;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)blk * blockDim.x + threadIdx.x;
+    const int64_t nthreads = (int64_t)nblks * blockDim.x;
     uint32_t m = 0;
     if (!BF16) {
         const float *x = (const float *)xv;
@@ -74,8 +74,16 @@ __global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t a = sm[0] > sm[1] ? sm[0] : sm[1], b = sm[2] > sm[3] ? sm[2] : sm[3];
-        partials[blockIdx.x] = a > b ? a : b;
+        partials[blk] = a > b ? a : b;
     }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void absmax_kernel(const void *__restrict__ xv, int64_t n,
+                                                     uint32_t *__restrict__ partials,
+                                                     uint32_t *__restrict__ reset, int n_reset)
+{
+    absmax_share<BF16>(xv, n, partials, reset, n_reset, (int)blockIdx.x, (int)gridDim.x);
 }
 
 int absmax_blocks(int64_t n, egeria_dtype dt)
@@ -306,10 +314,9 @@ hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64
 // General form [nimg, c, hw] -> int8 [nimg, hw, cp]; a row-major matrix is the
 // case hw = 1.
 template <bool BF16>
-__global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restrict__ x, int nimg, int c, int hw,
-                                                             int cp, int8_t *__restrict__ q,
-                                                             float *__restrict__ scale_out,
-                                                             uint32_t *__restrict__ flag)
+__device__ __forceinline__ void quantize_small_body(const void *__restrict__ x, int nimg, int c, int hw, int cp,
+                                                    int8_t *__restrict__ q, float *__restrict__ scale_out,
+                                                    uint32_t *__restrict__ flag)
 {
     const int total = nimg * c * hw;
     uint32_t m = 0;
@@ -359,6 +366,15 @@ __global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restr
         if (ch < c) code = quant1(load_elem<BF16>(x, ((int64_t)img * c + ch) * hw + pp), inv);
         q[o] = (int8_t)code;
     }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void quantize_small_kernel(const void *__restrict__ x, int nimg, int c, int hw,
+                                                             int cp, int8_t *__restrict__ q,
+                                                             float *__restrict__ scale_out,
+                                                             uint32_t *__restrict__ flag)
+{
+    quantize_small_body<BF16>(x, nimg, c, hw, cp, q, scale_out, flag);
 }
 
 hipError_t launch_quantize_small(const void *x, egeria_dtype dt, int nimg, int c, int hw, int cp, int8_t *q,
@@ -476,10 +492,26 @@ __device__ __forceinline__ void job_share_quantize(const WeightJob &jb, int lb, 
 
 // PHASE 0: every tensor of the launch fits one workgroup; maximum, scale and codes in one go.
 // PHASE 1: per-workgroup maxima -> partials[blockIdx.x].   PHASE 2: scale from the partials, codes.
+// Workgroups beyond the table's total_blocks (first launch of a snapshot only) take a share of
+// an unrelated maximum pass that the caller wants in the same launch: the mini-batch the
+// refreshed reference model is about to run on.
 template <int PHASE>
 __global__ __launch_bounds__(256) void quantize_weights_kernel(const WeightBatch b, uint32_t *__restrict__ partials,
-                                                               uint32_t *__restrict__ flag)
+                                                               uint32_t *__restrict__ flag, int total_blocks,
+                                                               const InputMaxJob extra)
 {
+    if ((int)blockIdx.x >= total_blocks) {
+        const int blk = (int)blockIdx.x - total_blocks;
+        if (PHASE != 2 && extra.q) {
+            // a small mini-batch [rows, cols]: maximum, scale and codes by this one workgroup
+            if (extra.bf16) quantize_small_body<true>(extra.x, extra.rows, extra.cols, 1, extra.cp, extra.q, extra.scale_out, extra.flag);
+            else quantize_small_body<false>(extra.x, extra.rows, extra.cols, 1, extra.cp, extra.q, extra.scale_out, extra.flag);
+        } else if (PHASE != 2) {
+            if (extra.bf16) absmax_share<true>(extra.x, extra.n, extra.partials, extra.reset, extra.n_reset, blk, extra.nblk);
+            else absmax_share<false>(extra.x, extra.n, extra.partials, extra.reset, extra.n_reset, blk, extra.nblk);
+        }
+        return;
+    }
     __shared__ uint32_t sm[4];
     const int j = find_job(b, (int)blockIdx.x);
     const WeightJob &jb = b.job[j];
@@ -547,14 +579,19 @@ hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, ui
 }
 
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
-                                   uint32_t *flag, hipStream_t st)
+                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra)
 {
-    const dim3 grid((unsigned)total_blocks), block(256);
+    InputMaxJob ex{};
+    if (extra) ex = *extra;
+    const dim3 first((unsigned)(total_blocks + ex.nblk)), grid((unsigned)total_blocks), block(256);
     if (one_launch)
-        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<0>, grid, block, 0, st, b, partials, flag);
-    hipError_t e = launch_k(EGERIA_KERNEL_ABSMAX, quantize_weights_kernel<1>, grid, block, 0, st, b, partials, flag);
+        return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<0>, first, block, 0, st, b, partials, flag,
+                        total_blocks, ex);
+    hipError_t e = launch_k(EGERIA_KERNEL_ABSMAX, quantize_weights_kernel<1>, first, block, 0, st, b, partials, flag,
+                            total_blocks, ex);
     if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<2>, grid, block, 0, st, b, partials, flag);
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<2>, grid, block, 0, st, b, partials, flag, total_blocks,
+                    InputMaxJob{});
 }
 
 // ---- fused GELU + quantise ---------------------------------------------------------------

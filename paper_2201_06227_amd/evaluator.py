@@ -73,5 +73,16 @@ class PlasticityEvaluator:
         return self.p_out
 
     def step(self, x: torch.Tensor, a_train: Sequence[torch.Tensor]) -> torch.Tensor:
+        """egeria_refresh_eval: quantize_weights() + evaluate() in one call (same results; the snapshot's
+        first pass and the mini-batch's maximum pass share a launch)."""
+        ptrs = (ctypes.c_void_p * self.n_layers)(*[t.data_ptr() for t in a_train])
+        rc = self._lib.egeria_refresh_eval(self._wtab, len(self.weights), self.qws.data_ptr(), self.qws.numel(),
+                                           ctypes.byref(self.desc), ctypes.byref(self.qw), x.data_ptr(), eg._dt(x),
+                                           ptrs, eg._dt(a_train[0]), self.p_out.data_ptr(), self.ws.data_ptr(),
+                                           self.ws.numel(), eg._stream())
+        eg._check(rc, "egeria_refresh_eval")
+        return self.p_out
+
+    def step_two_calls(self, x: torch.Tensor, a_train: Sequence[torch.Tensor]) -> torch.Tensor:
         self.quantize_weights()
         return self.evaluate(x, a_train)
