@@ -266,9 +266,10 @@ egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria
 /* Sections 4.1-4.2: refresh of the reference model and evaluation in one call.
  * The same as egeria_quantize_weights(w, n_w, ws_w, ws_w_bytes, stream) followed
  * by egeria_plasticity_eval(desc, qw, x, ..., ws, ws_bytes, stream), and the same
- * results bit for bit (qw must point at the tensors that w writes); the first
- * pass over the snapshot and the maximum pass over the mini-batch, which do not
- * depend on each other, share one kernel launch.  Arguments, ownership and
+ * results bit for bit (qw must point at the tensors that w writes); passes over
+ * the snapshot and over the mini-batch that do not depend on each other share
+ * kernel launches (the snapshot's maxima with the mini-batch's maximum, the
+ * snapshot's codes with the mini-batch's codes).  Arguments, ownership and
  * errors as for the two calls; nothing is enqueued if an argument of either is
  * rejected. */
 egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_w, size_t ws_w_bytes,

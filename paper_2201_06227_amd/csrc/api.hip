@@ -14,6 +14,13 @@ namespace {
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 inline int64_t pad16(int64_t k) { return (k + 15) / 16 * 16; }
+// a basic block whose convolutions quantise their own operands on an unobserved run: at most 16
+// channels, an image row that fits the LDS stage, and pixel counts the kernel's 32-bit byte
+// offsets hold (2^25 pixels of 16 fp32 channels)
+inline bool narrow_block(const egeria_block_desc *d, int64_t M)
+{
+    return d->kind == EGERIA_BASIC_BLOCK && d->c_in <= 16 && d->width <= kConvFuseMaxWidth && M < (1LL << 25);
+}
 // an FC mini-batch small enough for the one-workgroup quantiser (maximum, scale and codes in one launch)
 inline bool fc_input_is_small(const egeria_block_desc *d)
 {
@@ -136,6 +143,7 @@ struct Fwd {
 
     int n_in = 1;           // per-workgroup maxima the input's absmax kernel wrote
     bool input_max_done = false;    // an earlier launch has already taken the input's maxima
+    bool input_codes_done = false;  // ... and its int8 codes and scale as well
     // where the absolute maximum of quantise point i is found: the input tensor's
     // per-workgroup maxima for point 0, an atomically combined word otherwise
     const uint32_t *amax(int i) const { return i == 0 ? ws_partials(ws, p.slots) : ws_absmax(ws, i); }
@@ -224,8 +232,10 @@ egeria_status forward_fc(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
                                          ws_flag(f.ws), f.st));
     } else {
         if (!f.is_static()) EG_OK(f.input_absmax(x, dt, (int64_t)d->batch * d->c_in));
-        EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
-                                    f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
+        if (!f.input_codes_done)
+            EG_HIP(launch_quantize_rows(x, dt, d->batch, d->c_in, kp, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
+                                        f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws),
+                                        f.st));
     }
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(d->batch * kp), f.scale(0)));
     return run_gemm(f, 0, f.qbuf(0), kp, d->batch, d->c_out, (int32_t)kp, false, 0, 0, 0, f.sx(0), 1,
@@ -306,12 +316,10 @@ egeria_status forward_conv_block(Fwd &f, const void *x, egeria_dtype dt, float *
     const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
     const int H = d->height, W = d->width;
     if (!f.is_static()) EG_OK(f.input_absmax(x, dt, M * d->c_in));
-    // narrow basic blocks on an unobserved run: the convolutions quantise their own operands
-    // (the kernel's 32-bit byte offsets hold 2^25 pixels of 16 fp32 channels)
-    if (d->kind == EGERIA_BASIC_BLOCK && !f.taps && cin_p == 16 && W <= kConvFuseMaxWidth && M < (1LL << 25))
-        return forward_narrow_block(f, x, dt, a_ref);
-    EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
-                                f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
+    if (!f.taps && narrow_block(d, M)) return forward_narrow_block(f, x, dt, a_ref);
+    if (!f.input_codes_done)
+        EG_HIP(launch_quantize_nchw(x, dt, d->batch, d->c_in, hw, cin_p, f.amax(0), f.is_static() ? 0 : f.n_amax(0),
+                                    f.stride_amax(0), f.sscale(0), f.qbuf(0), f.scale(0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(0, f.qbuf(0), (size_t)(M * cin_p), f.scale(0)));
     const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
     if (d->kind == EGERIA_BASIC_BLOCK) {
@@ -390,8 +398,9 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     float *qkv = f.fbuf(0), *ctx = f.fbuf(1), *proj = f.fbuf(2), *y1 = f.fbuf(3), *ff = f.fbuf(4);
     int8_t *xq = f.qbuf(0);
 
-    EG_HIP(launch_quantize_rows(cur, EGERIA_F32, M, Hd, hp, f.amax(s0), f.n_amax(s0), f.stride_amax(s0), nullptr, xq, f.scale(s0), nullptr,
-                                ws_flag(f.ws), f.st));
+    if (!(l == 0 && f.input_codes_done))
+        EG_HIP(launch_quantize_rows(cur, EGERIA_F32, M, Hd, hp, f.amax(s0), f.n_amax(s0), f.stride_amax(s0), nullptr, xq,
+                                    f.scale(s0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
     EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
     EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
@@ -541,9 +550,11 @@ size_t egeria_quantize_weights_workspace_bytes(int32_t n)
 // extra: a maximum pass to carry along in the first launch of the first batch of per-tensor
 // scales; *carried tells whether a launch took it.
 static egeria_status quantize_weights_impl(const egeria_weight *w, int32_t n, void *ws, size_t ws_bytes, void *stream,
-                                           const InputMaxJob *extra, bool *carried)
+                                           const InputMaxJob *extra, bool *carried, const InputQuantJob *xq = nullptr,
+                                           bool *xq_carried = nullptr)
 {
     if (carried) *carried = false;
+    if (xq_carried) *xq_carried = false;
     if (n < 0 || (n > 0 && !w) || !ws || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
     if (ws_bytes < egeria_quantize_weights_workspace_bytes(n)) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
     for (int i = 0; i < n; ++i) {
@@ -608,8 +619,11 @@ static egeria_status quantize_weights_impl(const egeria_weight *w, int32_t n, vo
                 EG_HIP(launch_quantize_weights_pc(b, blocks, ws_flag(ws), st));
             } else {
                 const bool take = extra && carried && !*carried;
-                EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st, take ? extra : nullptr));
+                const bool take_q = take && xq && xq_carried && !one;
+                EG_HIP(launch_quantize_weights(b, blocks, one, partials, ws_flag(ws), st, take ? extra : nullptr,
+                                               take_q ? xq : nullptr));
                 if (take) *carried = true;
+                if (take_q) *xq_carried = true;
             }
         }
     }
@@ -665,10 +679,12 @@ static SideStream *side_stream()
 static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
                                   egeria_dtype x_dt, float *a_ref, const egeria_taps *taps,
                                   const void *const *a_train, egeria_dtype t_dt, float *p_out, void *ws,
-                                  const Plan &p, hipStream_t st, bool input_max_done = false)
+                                  const Plan &p, hipStream_t st, bool input_max_done = false,
+                                  bool input_codes_done = false)
 {
     Fwd f{desc, qw, taps, (char *)ws, p, st};
     f.input_max_done = input_max_done;
+    f.input_codes_done = input_codes_done;
     const bool eval = p_out != nullptr;
     const size_t aref_elems = (size_t)desc->batch * (size_t)p.D;
     if (desc->kind < EGERIA_BERT_LAYER) {
@@ -798,9 +814,36 @@ egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_
         job.flag = ws_flag(ws);
         job.rows = desc->batch; job.cols = desc->c_in; job.cp = (int32_t)pad16(desc->c_in);
     }
-    bool carried = false;
-    EG_OK(quantize_weights_impl(w, n_w, ws_w, ws_w_bytes, stream, job.n > 0 ? &job : nullptr, &carried));
-    return forward_impl(desc, qw, x, x_dt, nullptr, nullptr, a_train, t_dt, p_out, ws, p, (hipStream_t)stream, carried);
+    // the codes of the mini-batch (a separate launch of the forward otherwise) can ride in the snapshot's
+    // second launch: rows of an FC or Transformer input, fp32 channel planes of a convolution module that
+    // does not quantise inside its convolutions
+    InputQuantJob qj{};
+    if (job.n > 0 && !job.q) {
+        qj.x = x; qj.bf16 = job.bf16; qj.slot = job.partials; qj.n_slot = job.nblk;
+        qj.q = (int8_t *)((char *)ws + p.off_q[0]); qj.scale_out = ws_scale(ws, p.slots, 0); qj.flag = ws_flag(ws);
+        int64_t units = 0;
+        if (desc->kind == EGERIA_FC_RELU) {
+            qj.kind = 1; qj.rows = desc->batch; qj.cols = desc->c_in; qj.ldq = pad16(desc->c_in);
+            units = qj.rows * (qj.ldq / 16);
+        } else if (desc->kind == EGERIA_BERT_LAYER || desc->kind == EGERIA_BERT_STACK) {
+            qj.kind = 1; qj.rows = p.M; qj.cols = desc->hidden; qj.ldq = pad16(desc->hidden);
+            units = qj.rows * (qj.ldq / 16);
+        } else {
+            const int64_t hw = (int64_t)desc->height * desc->width, cp = pad16(desc->c_in);
+            if (!narrow_block(desc, p.M) && x_dt == EGERIA_F32 && (hw & 3) == 0) {
+                qj.kind = 2; qj.rows = desc->batch; qj.cols = desc->c_in; qj.hw = hw; qj.ldq = cp;
+                units = qj.rows * (cp / 16) * (hw / 4);
+            }
+        }
+        int64_t blocks = (units + 255) / 256;
+        qj.nblk = (int32_t)(blocks > 8192 ? 8192 : blocks);
+        if (qj.nblk < 1) qj.kind = 0;
+    }
+    bool carried = false, codes = false;
+    EG_OK(quantize_weights_impl(w, n_w, ws_w, ws_w_bytes, stream, job.n > 0 ? &job : nullptr, &carried,
+                                qj.kind != 0 ? &qj : nullptr, &codes));
+    return forward_impl(desc, qw, x, x_dt, nullptr, nullptr, a_train, t_dt, p_out, ws, p, (hipStream_t)stream, carried,
+                        codes);
 }
 
 egeria_status egeria_check(void *ws, void *stream)

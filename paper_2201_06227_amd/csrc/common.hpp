@@ -153,9 +153,26 @@ struct InputMaxJob {
     uint32_t *flag;
     int32_t rows, cols, cp;
 };
-// one_launch: every job has nblk == 1.  partials: total_blocks words.  extra: nullable.
+// The map to codes of that tensor, riding along in the snapshot's second launch (two-launch
+// snapshots only): kind 1 = rows [rows, cols] -> [rows, ldq]; kind 2 = fp32 planes [rows = n,
+// cols = c, hw] -> [n, hw, ldq = cp] with hw % 4 == 0.  slot: the n_slot maxima the first launch
+// stored.  nblk extra workgroups.
+struct InputQuantJob {
+    int32_t kind;
+    const void *x;
+    int32_t bf16;
+    int64_t rows, cols, hw, ldq;
+    const uint32_t *slot;
+    int32_t n_slot;
+    int8_t *q;
+    float *scale_out;
+    uint32_t *flag;
+    int32_t nblk;
+};
+// one_launch: every job has nblk == 1.  partials: total_blocks words.  extra, xq: nullable; xq is
+// taken only together with extra and only by a two-launch snapshot.
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
-                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra);
+                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra, const InputQuantJob *xq);
 // The same for jobs with one scale per output channel (job.scale is [o]); four channels per workgroup.
 hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, uint32_t *flag, hipStream_t st);
 

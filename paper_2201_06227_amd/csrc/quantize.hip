@@ -241,21 +241,15 @@ __global__ __launch_bounds__(256) void quantize_nchw_kernel(
 // multiple of 4: a thread owns 4 consecutive pixels x 16 channels (sixteen
 // 16-byte loads, lanes along the pixel axis, all in flight together) and
 // writes four 16-byte channel groups.
-__global__ __launch_bounds__(256) void quantize_nchw_vec_kernel(
-    const float *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
-    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
-    const float *__restrict__ fixed_scale,
-    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
-    uint32_t *__restrict__ flag)
+// (this thread takes units first, first + stride, ...)
+__device__ __forceinline__ void quantize_nchw_vec_units(const float *__restrict__ x, int64_t n, int64_t c, int64_t hw,
+                                                        int64_t cp, float inv, int8_t *__restrict__ q, int64_t first,
+                                                        int64_t stride)
 {
-    float scale;
-    bool bad;
-    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
-    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
     const int64_t pq = hw >> 2, cg = cp >> 4;
     const int64_t units = n * cg * pq;
     const bool narrow = units < (1LL << 32);
-    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += (int64_t)gridDim.x * blockDim.x) {
+    for (int64_t u = first; u < units; u += stride) {
         const int64_t ig = div_u(u, pq, narrow);
         const int64_t p = (u - ig * pq) << 2;
         const int64_t img = div_u(ig, cg, narrow), g = ig - img * cg;
@@ -283,6 +277,21 @@ __global__ __launch_bounds__(256) void quantize_nchw_vec_kernel(
 #pragma unroll
         for (int k = 0; k < 4; ++k) *(uint4 *)(dst + k * cp) = make_uint4(w[k][0], w[k][1], w[k][2], w[k][3]);
     }
+}
+
+__global__ __launch_bounds__(256) void quantize_nchw_vec_kernel(
+    const float *__restrict__ x, int64_t n, int64_t c, int64_t hw, int64_t cp,
+    const uint32_t *__restrict__ slot, int n_slot, int slot_stride,
+    const float *__restrict__ fixed_scale,
+    int8_t *__restrict__ q, float *__restrict__ scale_out, float *__restrict__ scale_out2,
+    uint32_t *__restrict__ flag)
+{
+    float scale;
+    bool bad;
+    const float inv = scales_from(slot, n_slot, slot_stride, fixed_scale, &scale, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, scale_out2, flag);
+    quantize_nchw_vec_units(x, n, c, hw, cp, inv, q, (int64_t)blockIdx.x * blockDim.x + threadIdx.x,
+                            (int64_t)gridDim.x * blockDim.x);
 }
 
 hipError_t launch_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw,
@@ -498,10 +507,22 @@ __device__ __forceinline__ void job_share_quantize(const WeightJob &jb, int lb, 
 template <int PHASE>
 __global__ __launch_bounds__(256) void quantize_weights_kernel(const WeightBatch b, uint32_t *__restrict__ partials,
                                                                uint32_t *__restrict__ flag, int total_blocks,
-                                                               const InputMaxJob extra)
+                                                               const InputMaxJob extra, const InputQuantJob xq)
 {
     if ((int)blockIdx.x >= total_blocks) {
         const int blk = (int)blockIdx.x - total_blocks;
+        if (PHASE == 2 && xq.kind != 0) {
+            // second launch: the codes of the mini-batch whose maxima the first launch took
+            float scale;
+            bool bad;
+            const float inv = scales_from(xq.slot, xq.n_slot, 1, nullptr, &scale, &bad);
+            if (blk == 0 && threadIdx.x == 0) publish(scale, bad, xq.scale_out, nullptr, xq.flag);
+            const int64_t first = (int64_t)blk * 256 + threadIdx.x, stride = (int64_t)xq.nblk * 256;
+            if (xq.kind == 2) quantize_nchw_vec_units((const float *)xq.x, xq.rows, xq.cols, xq.hw, xq.ldq, inv, xq.q, first, stride);
+            else if (xq.bf16) quantize_row_units<true>(xq.x, xq.rows, xq.cols, xq.ldq, inv, xq.q, first, stride);
+            else quantize_row_units<false>(xq.x, xq.rows, xq.cols, xq.ldq, inv, xq.q, first, stride);
+            return;
+        }
         if (PHASE != 2 && extra.q) {
             // a small mini-batch [rows, cols]: maximum, scale and codes by this one workgroup
             if (extra.bf16) quantize_small_body<true>(extra.x, extra.rows, extra.cols, 1, extra.cp, extra.q, extra.scale_out, extra.flag);
@@ -579,19 +600,21 @@ hipError_t launch_quantize_weights_pc(const WeightBatch &b, int total_blocks, ui
 }
 
 hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool one_launch, uint32_t *partials,
-                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra)
+                                   uint32_t *flag, hipStream_t st, const InputMaxJob *extra, const InputQuantJob *xq)
 {
     InputMaxJob ex{};
+    InputQuantJob qj{};
     if (extra) ex = *extra;
-    const dim3 first((unsigned)(total_blocks + ex.nblk)), grid((unsigned)total_blocks), block(256);
+    if (extra && xq && !one_launch) qj = *xq;               // the codes need the maxima of an earlier launch
+    const dim3 first((unsigned)(total_blocks + ex.nblk)), second((unsigned)(total_blocks + qj.nblk)), block(256);
     if (one_launch)
         return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<0>, first, block, 0, st, b, partials, flag,
-                        total_blocks, ex);
+                        total_blocks, ex, InputQuantJob{});
     hipError_t e = launch_k(EGERIA_KERNEL_ABSMAX, quantize_weights_kernel<1>, first, block, 0, st, b, partials, flag,
-                            total_blocks, ex);
+                            total_blocks, ex, InputQuantJob{});
     if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<2>, grid, block, 0, st, b, partials, flag, total_blocks,
-                    InputMaxJob{});
+    return launch_k(EGERIA_KERNEL_QUANTIZE, quantize_weights_kernel<2>, second, block, 0, st, b, partials, flag,
+                    total_blocks, InputMaxJob{}, qj);
 }
 
 // ---- fused GELU + quantise ---------------------------------------------------------------

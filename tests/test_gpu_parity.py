@@ -631,10 +631,15 @@ def _refresh_workload(name):
         return si.make_basic_block(seed=814, b=2, c=20, h=9, w=11)
     if name == "bottleneck":
         return si.make_bottleneck(seed=815, b=3, c_in=256, c_mid=64, h=14, w=14)
+    if name == "bottleneck_odd":
+        return si.make_bottleneck(seed=817, b=2, c_in=256, c_mid=64, h=7, w=7)
+    if name == "basic_wide64":
+        return si.make_basic_block(seed=818, b=2, c=64, h=16, w=12)
     return si.make_bert(seed=816, b=3, s=40, hidden=128, heads=4, ffn=200, n_layers=2, train_act_dtype="f32")
 
 
-@pytest.mark.parametrize("name", ["fc_small", "fc", "basic_narrow", "basic_wide", "bottleneck", "bert"])
+@pytest.mark.parametrize("name", ["fc_small", "fc", "basic_narrow", "basic_wide", "basic_wide64", "bottleneck",
+                                  "bottleneck_odd", "bert"])
 @pytest.mark.parametrize("mode", ["dynamic", "static", "per_channel", "bf16_x"])
 def test_refresh_eval_equals_two_calls(eg, gc, orc, name, mode):
     """egeria_refresh_eval against egeria_quantize_weights + egeria_plasticity_eval: the same codes, scales and
