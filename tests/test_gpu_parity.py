@@ -182,7 +182,7 @@ def test_basic_block_bit_exact(eg, gc, orc, kw):
 
 NARROW_CASES = [dict(b=1, c=1, h=1, w=1), dict(b=3, c=8, h=7, w=6), dict(b=3, c=16, h=9, w=11),
                 dict(b=5, c=16, h=32, w=32), dict(b=2, c=5, h=3, w=200), dict(b=1, c=16, h=2, w=300),
-                dict(b=2, c=20, h=9, w=11)]
+                dict(b=1, c=3, h=2, w=256), dict(b=2, c=20, h=9, w=11)]
 
 
 def _run_unobserved(eg, gc, wl, x_dev, act_scales=None):
