@@ -61,14 +61,30 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restr
     const int nv = H >> 2;
     uint32_t amax = 0;
     if (row < rows) {
+        // Every load of the row goes out before the first wait: unconditional, with the index clamped
+        // and the value replaced afterwards (a load under a per-lane condition is awaited on its own,
+        // and a row would cost a dozen memory round trips instead of one).  Absent operands read x.
         const float4 *xr = reinterpret_cast<const float4 *>(x + row * H);
-        const float4 *rr = res ? reinterpret_cast<const float4 *>(res + row * H) : nullptr;
-        float4 xv[NV], rv[NV];
+        const float4 *rr = reinterpret_cast<const float4 *>((res ? res : x) + row * H);
+        const float4 *gr = reinterpret_cast<const float4 *>(gamma ? gamma : x + row * H);
+        const float4 *br = reinterpret_cast<const float4 *>(beta ? beta : x + row * H);
+        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), one4 = make_float4(1.f, 1.f, 1.f, 1.f);
+        float4 xv[NV], rv[NV], gmv[NV], btv[NV];
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            const int c = lane + 64 * i;
-            xv[i] = c < nv ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-            rv[i] = (rr && c < nv) ? rr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int c = lane + 64 * i, cc = c < nv ? c : nv - 1;
+            xv[i] = xr[cc];
+            rv[i] = rr[cc];
+            gmv[i] = gr[cc];
+            btv[i] = br[cc];
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const bool in = lane + 64 * i < nv;
+            if (!in) xv[i] = zero4;
+            if (!in || !res) rv[i] = zero4;
+            if (!gamma) gmv[i] = one4;
+            if (!beta) btv[i] = zero4;
         }
         double v[NV][4];
         double s = 0.0;
@@ -97,8 +113,7 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restr
         for (int i = 0; i < NV; ++i) {
             const int c = lane + 64 * i;
             if (c < nv) {
-                const float4 gm = gamma ? reinterpret_cast<const float4 *>(gamma)[c] : make_float4(1.f, 1.f, 1.f, 1.f);
-                const float4 bt = beta ? reinterpret_cast<const float4 *>(beta)[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float4 gm = gmv[i], bt = btv[i];
                 float4 o;
                 o.x = (float)(v[i][0] * rstd * (double)gm.x + (double)bt.x);
                 o.y = (float)(v[i][1] * rstd * (double)gm.y + (double)bt.y);
@@ -184,19 +199,41 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
     const int64_t ld = 3 * (int64_t)Hd;
     const float *qbase = qkv + hd * dh, *kbase = qbase + Hd, *vbase = qbase + 2 * Hd;
 
-    // query rows as the B operand of S^T = K Q^T: d = 16u + 4g + e (u, e = 0..3)
+    // query rows as the B operand of S^T = K Q^T: d = 16u + 4g + e (u, e = 0..3).  The loads are
+    // unconditional (row and column clamped to valid ones, the value discarded afterwards): loads
+    // under a per-lane condition are awaited one by one, sixteen memory round trips before the
+    // first key tile instead of one.
+    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
     double qr[QB][16];
     int qidx[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const int q = qt * QT + wave * (16 * QB) + qb * 16 + c;
         qidx[qb] = q;
+        const float *qrow = qbase + (tok0 + (q < S ? q : S - 1)) * ld;
+        float qv[16];
+        if (vec4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int d0 = 16 * u + 4 * g;
+                const float4 v = *(const float4 *)(qrow + (d0 < dh ? d0 : 0));
+                qv[4 * u] = v.x; qv[4 * u + 1] = v.y; qv[4 * u + 2] = v.z; qv[4 * u + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int d = 16 * u + 4 * g + e;
+                    qv[4 * u + e] = qrow[d < dh ? d : 0];
+                }
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int d = 16 * u + 4 * g + e;
-                qr[qb][4 * u + e] = (q < S && d < dh) ? (double)qbase[(tok0 + q) * ld + d] * scale : 0.0;
+                qr[qb][4 * u + e] = (q < S && d < dh) ? (double)qv[4 * u + e] * scale : 0.0;
             }
     }
 
@@ -214,7 +251,6 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
     // Key / value tiles: thread t stages float4 slots t and t + 256 of the
     // 32 x 64 tile (row = slot / 16); the next tile's global loads are issued
     // before the current tile is contracted and land in the other LDS stage.
-    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
     float4 pk[2], pv[2];
     auto fetch = [&](int j0) {
 #pragma unroll
