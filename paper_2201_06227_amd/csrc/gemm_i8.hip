@@ -410,6 +410,14 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
                 const int rows_left = EDGE ? (int)(g.M - row0 < 32 ? g.M - row0 : 32) - lrow : 32;
                 // the block stays in the accumulation registers until its turn
                 asm volatile("" : "+a"(acc[i][j]));
+                // float residuals of an interior block: all sixteen requested before the first is used
+                // (interleaved with the stores of y the compiler keeps each load behind the store before it)
+                float rpre[16];
+                if constexpr (!RES_LDS && !EDGE && RES) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        rpre[r] = (float)rb[(size_t)(8 * (r >> 2) + (r & 3)) * g.res_ld + roff];
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rr = 8 * (r >> 2) + (r & 3);
@@ -423,6 +431,8 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
                     if (EDGE ? g.res_q != nullptr : RES) {
                         if constexpr (RES_LDS)
                             v = v + (float)(int8_t)lds[((wm_u * TM + i) * 32 + lrow + rr) * BN + (wn_u * TN + j) * 32 + lcol] * rs;
+                        else if constexpr (!EDGE && RES)
+                            v = v + rpre[r] * rs;
                         else
                             v = v + (float)rb[(size_t)rr * g.res_ld + roff] * rs;
                     }
