@@ -296,14 +296,15 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
         contract(t & 1);
         stash((t + 1) & 1, next);
         fetch(t + 3, next);
-        // issue order: the splitting arithmetic of the next tile between the MFMAs
-        // of this one (an MFMA occupies the matrix pipe for 8 passes, the vector
-        // ALU is free meanwhile)
+        // issue order: the splitting arithmetic of the next tile and its LDS writes between the
+        // MFMAs of this one (an MFMA occupies the matrix pipe for 8 passes, the vector ALU is free
+        // meanwhile; the nine 16-byte LDS writes, spread out, do not queue up at the tile's end)
         constexpr int NMF = MT == 1 ? 12 : 24;
 #pragma unroll
         for (int i = 0; i < NMF; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
             __builtin_amdgcn_sched_group_barrier(0x002, MT == 1 ? 12 : 6, 0);     // vector ALU
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                    // one LDS write
         }
         __syncthreads();
     };
