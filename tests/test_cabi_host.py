@@ -101,6 +101,37 @@ def test_bad_arguments_are_rejected_on_the_host(eg):
                                 null) == eg.ERR_UNSUPPORTED      # head dimension 128 > 64
 
 
+def test_refresh_eval_rejects_what_either_call_would(eg):
+    """egeria_refresh_eval validates the arguments of both halves on the host before anything is enqueued."""
+    L = eg.lib()
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)
+    d = eg.make_desc(eg.FC_RELU, dict(batch=4, c_in=8, c_out=8))
+    qw = eg.QWeights()
+    arr = (eg.QLinear * 1)()
+    arr[0].w_q, arr[0].scale = 0x2000, 0x3000
+    qw.n_linear, qw.linear = 1, arr
+    ptrs = (ctypes.c_void_p * 1)(0x4000)
+    wtab = (eg.Weight * 1)()
+    big = 1 << 30
+
+    def call(w=wtab, n_w=1, ws_w=fake, ws_w_bytes=big, desc=d, x=fake, a_t=ptrs, p_out=fake, ws=fake, ws_bytes=big):
+        return L.egeria_refresh_eval(w, n_w, ws_w, ws_w_bytes, ctypes.byref(desc), ctypes.byref(qw), x, eg.F32, a_t,
+                                     eg.F32, p_out, ws, ws_bytes, null)
+
+    assert call(x=null) == eg.ERR_INVALID_ARG                      # the evaluation's arguments
+    assert call(p_out=null) == eg.ERR_INVALID_ARG
+    assert call(ws_bytes=16) == eg.ERR_WORKSPACE_TOO_SMALL
+    assert call(a_t=(ctypes.c_void_p * 1)(0)) == eg.ERR_INVALID_ARG
+    assert call(n_w=-1) == eg.ERR_INVALID_ARG                      # the snapshot's arguments
+    assert call(ws_w=null) == eg.ERR_INVALID_ARG
+    assert call(ws_w_bytes=8) == eg.ERR_WORKSPACE_TOO_SMALL
+    wtab[0].out, wtab[0].in_, wtab[0].kh, wtab[0].kw = 8, 8, 0, 1  # a kernel of height 0
+    assert call() == eg.ERR_INVALID_ARG
+    too_big = eg.make_desc(eg.FC_RELU, dict(batch=200, c_in=8, c_out=8))
+    assert call(desc=too_big) == eg.ERR_UNSUPPORTED                # the metric takes at most 128 samples
+
+
 def test_profile_pause_is_harmless_when_nothing_is_armed(eg):
     L = eg.lib()
     assert L.egeria_profile_pause(1) == eg.OK and L.egeria_profile_pause(0) == eg.OK
