@@ -427,9 +427,15 @@ __device__ __forceinline__ uint32_t job_share_absmax(const WeightJob &jb, int lb
             a = a > c ? a : c;
             m = m > a ? m : a;
         }
-        for (; i < n4; i += 256) {
-            const uint32_t a = max4_bits(x4[i]);
-            m = m > a ? m : a;
+        if (i < n4) {                                                // at most three strides are left: one round trip
+            float4 t[3];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) t[k] = x4[i + 256 * k < n4 ? i + 256 * k : n4 - 1];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const uint32_t a = i + 256 * k < n4 ? max4_bits(t[k]) : 0u;
+                m = m > a ? m : a;
+            }
         }
         for (int64_t k = beg + (n4 << 2) + threadIdx.x; k < end; k += 256) {
             const uint32_t a = abs_bits(x[k]);
@@ -487,13 +493,25 @@ __device__ __forceinline__ void job_share_quantize(const WeightJob &jb, int lb, 
                 w[j] = quant1(v.x, inv) | (quant1(v.y, inv) << 8) | (quant1(v.z, inv) << 16) | (quant1(v.w, inv) << 24);
             }
         } else {
+            // sixteen gathered values, requested together: unconditional loads (a channel beyond c reads
+            // channel c - 1 and is dropped), since a load under a per-lane condition is awaited on its own
+            float v[16];
+            if (jb.bf16) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ch = c0 + e < jb.c ? c0 + e : jb.c - 1;
+                    v[e] = bf16_to_f32(((const uint16_t *)jb.x)[(oc * jb.c + ch) * jb.hw + pix]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int ch = c0 + e < jb.c ? c0 + e : jb.c - 1;
+                    v[e] = ((const float *)jb.x)[(oc * jb.c + ch) * jb.hw + pix];
+                }
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                if (c0 + e < jb.c) {
-                    const int64_t idx = (oc * jb.c + c0 + e) * jb.hw + pix;
-                    const float v = jb.bf16 ? bf16_to_f32(((const uint16_t *)jb.x)[idx]) : ((const float *)jb.x)[idx];
-                    w[e >> 2] |= quant1(v, inv) << ((e & 3) * 8);
-                }
+                if (c0 + e < jb.c) w[e >> 2] |= quant1(v[e], inv) << ((e & 3) * 8);
         }
         *(uint4 *)(jb.q + (u << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
