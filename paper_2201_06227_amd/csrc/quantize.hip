@@ -121,7 +121,30 @@ __device__ __forceinline__ void quantize_row_units(const void *__restrict__ x, i
     const int64_t units = rows * upr;
     const bool narrow = units < (1LL << 32);
     const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
-    for (int64_t u = first; u < units; u += stride) {
+    int64_t u = first;
+    if (!BF16 && cols == ldq && ((uintptr_t)x & 15) == 0 && ((uintptr_t)q & 15) == 0) {
+        // fp32 rows without padding are one contiguous run of units: four of a thread's units (sixteen
+        // 16-byte loads) in flight together when it has that many (a single workgroup quantising a
+        // whole small matrix would otherwise pay one memory round trip per unit)
+        const float4 *x4 = (const float4 *)x;
+        for (; u + 3 * stride < units; u += 4 * stride) {
+            float4 v[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[k][j] = x4[(u + k * stride) * 4 + j];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    w[j] = quant1(v[k][j].x, inv) | (quant1(v[k][j].y, inv) << 8) | (quant1(v[k][j].z, inv) << 16) |
+                           (quant1(v[k][j].w, inv) << 24);
+                *(uint4 *)(q + ((u + k * stride) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
+    for (; u < units; u += stride) {
         const int64_t row = div_u(u, upr, narrow);
         const int64_t c0 = (u - row * upr) << 4;
         const int64_t base = row * cols + c0;
