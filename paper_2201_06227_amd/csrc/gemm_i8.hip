@@ -801,9 +801,11 @@ __global__ __launch_bounds__(256) void conv3x3_c16_fused_kernel(const GemmArgs g
             if (has_res) t = t + (float)(int8_t)(rc >> (8 * e)) * rs;
             if (g.act == 1) t = t > 0.0f ? t : 0.0f;
             const bool ch_ok = ch0 + e < g.N;
-            const uint32_t ab = g.amax_pos ? (t > 0.0f ? __float_as_uint(t) : 0u) : abs_bits(t);
-            amax = (ch_ok && ab > amax) ? ab : amax;
-            codes |= (ch_ok ? quant1(t, q_inv) : 0u) << (8 * e);                  // pad columns of the int8 output are zero
+            if (g.absmax_out) {
+                const uint32_t ab = g.amax_pos ? (t > 0.0f ? __float_as_uint(t) : 0u) : abs_bits(t);
+                amax = (ch_ok && ab > amax) ? ab : amax;
+            }
+            if (g.q_out) codes |= (ch_ok ? quant1(t, q_inv) : 0u) << (8 * e);     // pad columns of the int8 output are zero
             v[e] = t;
         }
         if (g.y) {
