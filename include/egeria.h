@@ -16,16 +16,29 @@
  *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The
  *     descriptor structs themselves are HOST memory holding device pointers.
  *   - The caller owns every buffer.  The library never allocates or frees
- *     device memory and never synchronises: all work is enqueued on `stream`
- *     (a hipStream_t passed as void*; NULL is the default stream) and results
- *     land in device memory when the stream reaches them.
+ *     device memory and never synchronises: work is enqueued on `stream` (a
+ *     hipStream_t passed as void*; NULL is the default stream) and results
+ *     land in device memory when the stream reaches them.  One exception to
+ *     "on `stream`": for a stack of layers (n_layers > 1)
+ *     egeria_plasticity_eval and egeria_refresh_eval enqueue the score of
+ *     layer l on a side stream that the library creates once per device
+ *     (default priority, on the device that is current at the first such
+ *     call), ordered against `stream` with events in both directions; the
+ *     side stream has joined `stream` again when the call returns, so
+ *     whatever the caller enqueues on `stream` afterwards is ordered behind
+ *     the whole call, and the call can be captured into a HIP graph.  The
+ *     device of `stream` must be the current device.
  *   - Device pointers must be 16-byte aligned.
  *   - Argument errors are found on the host before anything is launched and
  *     are reported through the return code; nothing is thrown.
  *   - A NaN or infinity met by a quantiser sets a flag word inside the
  *     workspace; egeria_check reads it back (that call does synchronise).
- *   - Calls are re-entrant as long as they use distinct workspaces.  Two calls
- *     that share a workspace must be ordered on one stream.
+ *   - Calls are re-entrant as long as they use distinct workspaces (host
+ *     threads may call concurrently; the host-side enqueueing of stack
+ *     evaluations, which share the device's side stream and its events, is
+ *     serialised by a lock inside the library, and their scores then run one
+ *     call after the other on that stream).  Two calls that share a workspace
+ *     must be ordered on one stream.
  *
  * Quantisation rule (the paper names int8 post-training quantisation and
  * leaves the arithmetic to its framework; this library fixes it as):
@@ -212,7 +225,10 @@ egeria_status egeria_quantize_weights(const egeria_weight *w, int32_t n, void *w
                                       void *stream);
 size_t egeria_quantize_weights_workspace_bytes(int32_t n);
 
-/* x_i = q_i * scale. */
+/* Section 4.1: the value an int8 code of the reference model stands for,
+ * x_i = q_i * scale (one fp32 multiply).  q int8 [n], scale 1 fp32, x fp32 [n]
+ * out; n == 0 is valid.  This is what a skip connection of the convolution
+ * modules adds (the dequantised block input). */
 egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, float *x,
                                 void *stream);
 
@@ -237,7 +253,18 @@ size_t egeria_quantize_workspace_bytes(void);
  * (dynamic scale), the contraction is int8 x int8 -> int32 on the matrix
  * cores, and the epilogue is, in fp32 and in this order: s = s_x * s_w;
  * y = fma((float)acc, s, bias); [+ residual]; activation.  The residual of the
- * conv kinds is the dequantised block input. */
+ * conv kinds is the dequantised block input.
+ * Transformer kinds (Section 5: dynamic quantisation, only the four linear
+ * layers of a layer are int8): post-LN encoder layer, inference mode, no mask;
+ * attention, layer norm and the erf-form GELU are floating point and are
+ * evaluated so that every int8 code and scale of the following GEMM is the one
+ * an fp64 evaluation rounded once to fp32 gives.  Limits of these kinds: x must
+ * be EGERIA_F32 (a bf16 mini-batch is EGERIA_ERR_UNSUPPORTED), hidden / heads
+ * <= 64 (larger heads: EGERIA_ERR_UNSUPPORTED), batch * seq < 2^31, at most 51
+ * layers per stack; the score calls further need batch <= 128.
+ * Errors: EGERIA_ERR_INVALID_ARG for a null or misaligned pointer, a bad
+ * descriptor, n_linear / n_norm / taps->n that do not fit the module;
+ * EGERIA_ERR_UNSUPPORTED as listed; EGERIA_ERR_WORKSPACE_TOO_SMALL. */
 egeria_status egeria_ref_forward(const egeria_block_desc *desc, const egeria_qweights *qw,
                                  const void *x, egeria_dtype x_dt, float *a_ref,
                                  const egeria_taps *taps, void *ws, size_t ws_bytes, void *stream);
@@ -254,7 +281,10 @@ egeria_status egeria_plasticity(const void *a_train, egeria_dtype t_dt, const vo
 
 size_t egeria_plasticity_workspace_bytes(int32_t b, int64_t D);
 
-/* Reference forward of a module (or stack) followed by one score per layer:
+/* Sections 4.1-4.2, one plasticity evaluation: reference forward of a module
+ * (or stack; Section 4.1, as egeria_ref_forward without observation points)
+ * followed by one score per layer (Section 4.2, Eq. 1, as egeria_plasticity on
+ * that layer's A_R, which stays inside the workspace):
  * a_train is a HOST array of desc->n_layers device pointers (each [batch, D] of
  * type t_dt), p_out receives n_layers fp32 scores.  ws: at least
  * egeria_workspace_bytes(desc) (which includes room for A_R and the metric). */
@@ -282,7 +312,9 @@ egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_
  * egeria_plasticity_eval need for this module; 0 if desc is invalid. */
 size_t egeria_workspace_bytes(const egeria_block_desc *desc);
 
-/* Reads the workspace's flag word back (synchronises `stream`): returns
+/* Section 4.1 leaves open what happens "if int8 fails"; the one failure this
+ * library detects itself is a non-finite value at a quantiser (its scale would
+ * be meaningless).  Reads the workspace's flag word back (synchronises `stream`): returns
  * EGERIA_ERR_NONFINITE if a quantiser that used this workspace met a NaN or
  * an infinity since the last check, and clears the flag. */
 egeria_status egeria_check(void *ws, void *stream);
@@ -384,32 +416,6 @@ egeria_status egeria_cache_put(const egeria_cache_desc *desc, void *cache, size_
                                const int64_t *ids, int32_t n, const void *rows, void *stream);
 egeria_status egeria_cache_get(const egeria_cache_desc *desc, const void *cache, size_t cache_bytes,
                                const int64_t *ids, int64_t n, void *out, uint8_t *hit, void *stream);
-
-/* Instrumentation for benchmarks (not part of the method): time every launch
- * of one kernel class with a pair of HIP events recorded on the launch's own
- * stream, so that a caller can time that kernel inside a larger timed region.
- * egeria_profile_begin arms recording for up to max_launches launches (events
- * are host-side objects the library creates once and reuses).
- * egeria_profile_end waits for the recorded events, writes the durations in
- * milliseconds to the HOST array ms_out (at most `capacity` of them), stores
- * the number recorded in *n_out (HOST) and disarms.  Process wide, not
- * thread-safe; do not use while a stream is being captured. */
-typedef enum {
-    EGERIA_KERNEL_NONE = 0,
-    EGERIA_KERNEL_ABSMAX = 1,       /* absolute-maximum reduction            */
-    EGERIA_KERNEL_QUANTIZE = 2,     /* fp32/bf16 -> int8 map                 */
-    EGERIA_KERNEL_GEMM = 3,         /* int8 GEMM / implicit-GEMM convolution */
-    EGERIA_KERNEL_GRAM = 4,         /* split-K Gram partials of the metric   */
-    EGERIA_KERNEL_ATTENTION = 5,
-    EGERIA_KERNEL_LAYERNORM = 6,
-    EGERIA_KERNEL_CACHE_COPY = 7    /* row copies of the activation cache    */
-} egeria_kernel_class;
-
-egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches);
-/* Between begin and end: paused != 0 stops recording (launches go out without events, which cost
- * host time), paused == 0 resumes it.  Lets a caller sample some steps of a timed loop only. */
-egeria_status egeria_profile_pause(int32_t paused);
-egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus
 }

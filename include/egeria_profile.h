@@ -1,0 +1,44 @@
+/*
+ * libegeria: timing instrumentation for benchmarks.  Not part of the method and
+ * not needed by any caller of include/egeria.h; exported for bench.py, which
+ * times one kernel class inside a larger timed region.
+ */
+#ifndef EGERIA_PROFILE_H
+#define EGERIA_PROFILE_H
+
+#include "egeria.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Time every launch
+ * of one kernel class with a pair of HIP events recorded on the launch's own
+ * stream, so that a caller can time that kernel inside a larger timed region.
+ * egeria_profile_begin arms recording for up to max_launches launches (events
+ * are host-side objects the library creates once and reuses).
+ * egeria_profile_end waits for the recorded events, writes the durations in
+ * milliseconds to the HOST array ms_out (at most `capacity` of them), stores
+ * the number recorded in *n_out (HOST) and disarms.  Process wide, not
+ * thread-safe; do not use while a stream is being captured. */
+typedef enum {
+    EGERIA_KERNEL_NONE = 0,
+    EGERIA_KERNEL_ABSMAX = 1,       /* absolute-maximum reduction            */
+    EGERIA_KERNEL_QUANTIZE = 2,     /* fp32/bf16 -> int8 map                 */
+    EGERIA_KERNEL_GEMM = 3,         /* int8 GEMM / implicit-GEMM convolution */
+    EGERIA_KERNEL_GRAM = 4,         /* split-K Gram partials of the metric   */
+    EGERIA_KERNEL_ATTENTION = 5,
+    EGERIA_KERNEL_LAYERNORM = 6,
+    EGERIA_KERNEL_CACHE_COPY = 7    /* row copies of the activation cache    */
+} egeria_kernel_class;
+
+egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches);
+/* Between begin and end: paused != 0 stops recording (launches go out without events, which cost
+ * host time), paused == 0 resumes it.  Lets a caller sample some steps of a timed loop only. */
+egeria_status egeria_profile_pause(int32_t paused);
+egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGERIA_PROFILE_H */

@@ -32,16 +32,35 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = sources() + [os.path.join(CSRC, "common.hpp"),
-                        os.path.join(os.path.dirname(HERE), "include", "egeria.h")]
+                        os.path.join(os.path.dirname(HERE), "include", "egeria.h"),
+                        os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_library(force: bool = True) -> str:
-    """Compile every HIP source for gfx950 into paper_2201_06227_amd/libegeria.so."""
-    if not force and not is_stale():
-        return LIB
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + sources()
+def _run(cmd):
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + proc.stdout)
+
+
+def build_library(force: bool = True) -> str:
+    """Compile every HIP source for gfx950 and link paper_2201_06227_amd/libegeria.so.  The sources
+    are independent translation units (no device code calls across them), compiled side by side.
+    force=False recompiles only the sources that are newer than their object files."""
+    if not force and not is_stale():
+        return LIB
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    jobs = []
+    headers = [os.path.join(CSRC, "common.hpp"), os.path.join(os.path.dirname(HERE), "include", "egeria.h"),
+               os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h")]
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        fresh = os.path.exists(obj) and all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in [src] + headers)
+        jobs.append(([HIPCC] + compile_flags + ["-c", src, "-o", obj], obj, force or not fresh))
+    with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+        list(pool.map(lambda j: _run(j[0]) if j[2] else None, jobs))
+    _run([HIPCC, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB] + [j[1] for j in jobs])
     return LIB

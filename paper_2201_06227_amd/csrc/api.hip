@@ -2,12 +2,26 @@
 // planning and the per-module launch sequences of the reference forward.
 // Nothing here allocates device memory or synchronises, except egeria_check.
 #include "common.hpp"
+#include <mutex>
 #include <vector>
 
 using namespace egeria;
 
 namespace egeria {
 ProfileState g_profile;
+
+int compute_units()
+{
+    static int cu[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return 256;                        // no device (host-only sizing calls): the MI355X figure
+    if (cu[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        cu[dev] = v;
+    }
+    return cu[dev];
+}
 }
 
 namespace {
@@ -649,29 +663,35 @@ size_t egeria_workspace_bytes(const egeria_block_desc *desc)
     return p.ok ? p.total : 0;
 }
 
-// Side stream of egeria_plasticity_eval for layer stacks, with the events that
-// order it against the caller's stream.  Created once per device on first use
-// (default priority); calls that use it must not overlap in time.
+// Side stream of the stack evaluations (egeria_plasticity_eval / egeria_refresh_eval with
+// n_layers > 1), with the events that order it against the caller's stream.  One per device,
+// created on first use (default priority) on the device that is current then.  Every stack
+// evaluation of a device shares it: g_side_mutex is held while such a call enqueues its work, so
+// the record / wait pairs of two host threads never interleave (a wait refers to the event's last
+// record at the time of the wait call), and the scores of concurrent calls simply queue up one
+// call after the other on the side stream.
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t produced[2] = {nullptr, nullptr};
     hipEvent_t scored[2] = {nullptr, nullptr};
 };
+static std::mutex g_side_mutex;
 
+// call with g_side_mutex held
 static SideStream *side_stream()
 {
-    static SideStream per_device[16];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    static SideStream per_device[kMaxDevices];
+    const int dev = current_device();
+    if (dev < 0) return nullptr;
     SideStream &s = per_device[dev];
     if (!s.stream) {
-        hipStream_t st = nullptr;
-        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        SideStream t;
+        if (hipStreamCreateWithFlags(&t.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
         for (int i = 0; i < 2; ++i) {
-            if (hipEventCreateWithFlags(&s.produced[i], hipEventDisableTiming) != hipSuccess) return nullptr;
-            if (hipEventCreateWithFlags(&s.scored[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&t.produced[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&t.scored[i], hipEventDisableTiming) != hipSuccess) return nullptr;
         }
-        s.stream = st;
+        s = t;
     }
     return &s;
 }
@@ -703,6 +723,8 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     // by fp32 MFMA and HBM, the next layer starts with HBM-bound kernels).  The two
     // A_R buffers alternate: layer l + 2 may overwrite the buffer only after the
     // score of layer l has read it.  The side stream joins the main one at the end.
+    std::unique_lock<std::mutex> side_lock(g_side_mutex, std::defer_lock);
+    if (eval && p.n_layers > 1) side_lock.lock();
     SideStream *side = (eval && p.n_layers > 1) ? side_stream() : nullptr;
     if (eval && p.n_layers > 1 && !side) return EGERIA_ERR_HIP;
     for (int l = 0; l < p.n_layers; ++l) {

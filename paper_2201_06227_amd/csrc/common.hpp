@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include "../../include/egeria.h"
+#include "../../include/egeria_profile.h"
 
 namespace egeria {
 
@@ -31,6 +32,21 @@ constexpr int kAmaxWays = 64;
 constexpr int kAmaxStride = 64;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- per-device host state -------------------------------------------------
+// Function attributes, symbol addresses and streams belong to one device each:
+// whatever the library sets up lazily is kept per device, indexed by the device
+// that is current at the call.
+constexpr int kMaxDevices = 16;
+inline int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+// Compute units of the current device (256 on MI355X), queried once per device;
+// the tile and chunk choosers size their grids by it.
+int compute_units();
 inline size_t header_bytes(int slots)
 {
     return align_up(4 * (size_t)(kHeaderFixedWords + slots * (kAmaxWays * kAmaxStride + 1) + kAbsPartials), 256);

@@ -475,23 +475,25 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     const dim3 grid((unsigned)(tpx * 8)), block(256);
     constexpr size_t smem = (size_t)stages_for(BM, BN, BK) * (BM + BN) * BK;
     hipError_t e;
+    const int dev = current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
     if (g.conv3x3) {
-        static bool set = false;
-        if (!set) {
+        static bool set[kMaxDevices] = {};                   // the attribute belongs to one device's code object
+        if (!set[dev]) {
             e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, true, BK, ET>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
-            set = true;
+            set[dev] = true;
         }
         return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, true, BK, ET>, grid, block, smem, st, g,
                         (int)tiles, tpx);
     }
-    static bool set = false;
-    if (!set) {
+    static bool set[kMaxDevices] = {};
+    if (!set[dev]) {
         e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        set = true;
+        set[dev] = true;
     }
     return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>, grid, block, smem, st, g,
                     (int)tiles, tpx);
@@ -889,7 +891,7 @@ static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
 }
 
 // Tile choice.  A tile shape is priced by the work the chip does for it,
-// padding included: workgroups run in rounds of 256 CUs x (workgroups resident
+// padding included: workgroups run in rounds of (compute units) x (workgroups resident
 // per CU), a partly filled last round costs as much as a full one, and the
 // smaller shapes pay more LDS and L1 traffic per MFMA.  With fp32 outputs the
 // epilogue (convert, scale, store) costs as much as the K loop unless K is
@@ -927,7 +929,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
         if (sh.resident == 1 && g.kp < 2048) continue;
         if (sh.bm * sh.bn > 128 * 128 && g.kp < 512) continue;     // store bound: many small workgroups in flight
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
-        const int64_t slots = 256 * (int64_t)sh.resident;
+        const int64_t slots = compute_units() * (int64_t)sh.resident;
         const int64_t rounds = (tiles + slots - 1) / slots;
         double cost = (double)rounds * sh.resident * sh.bm * sh.bn * sh.penalty;
         // K of a few steps: the kernel is a stream of fp32 stores, and the more workgroups a CU holds the

@@ -64,7 +64,7 @@ static GramPlan plan_gram(int32_t b, int64_t D)
     // about one workgroup per CU: measured per score (partials + finaliser, us) for targets of 128 / 256 /
     // 512 / 1024 workgroups: b = 32, D = 98304: 19.6 / 17.6 / 20.6 / 24.6; b = 64, D = 200704: 57.7 / 43.5 /
     // 43.8 / 55.9 (more chunks mean more partials for the finaliser to add)
-    int64_t want = (256 + p.nmacro - 1) / p.nmacro;
+    int64_t want = (compute_units() + p.nmacro - 1) / p.nmacro;
     int64_t cap = D / ((p.mt == 1 ? 4 : 2) * (int64_t)b);  // bound the partials by a fraction of the input bytes
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
@@ -455,6 +455,8 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
                              int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st)
 {
     const GramPlan p = plan_gram(b, D);
+    const int dev = current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
     uint32_t *counter = (uint32_t *)ws_part;
     double *rowsum = (double *)((char *)ws_part + off_rowsum());
     float *part = (float *)((char *)ws_part + off_partials(b));
@@ -467,12 +469,12 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     do {                                                                                               \
         /* two stages of nine bf16 planes of 4 KiB, twelve when off-diagonal macro tiles exist */      \
         constexpr size_t smem = (size_t)2 * (OFF ? 12 : 9) * 4096;                                     \
-        static bool attr_set = false;                                                                  \
-        if (!attr_set) {                                                                               \
+        static bool attr_set[kMaxDevices] = {};                                                        \
+        if (!attr_set[dev]) {                                                                          \
             e = hipFuncSetAttribute((const void *)gram_partial_kernel<MTV, OFF, T, R, V>,              \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);            \
             if (e != hipSuccess) return e;                                                             \
-            attr_set = true;                                                                           \
+            attr_set[dev] = true;                                                                      \
         }                                                                                              \
         e = launch_k(EGERIA_KERNEL_GRAM, gram_partial_kernel<MTV, OFF, T, R, V>, grid, block, smem,    \
                      st, a_t, a_r, (int)b, D, p, part, counter);                                       \

@@ -122,10 +122,11 @@ __device__ __forceinline__ void quantize_row_units(const void *__restrict__ x, i
     const bool narrow = units < (1LL << 32);
     const bool vec_ok = BF16 ? ((cols & 7) == 0) : ((cols & 3) == 0);
     int64_t u = first;
-    if (!BF16 && cols == ldq && ((uintptr_t)x & 15) == 0 && ((uintptr_t)q & 15) == 0) {
-        // fp32 rows without padding are one contiguous run of units: four of a thread's units (sixteen
-        // 16-byte loads) in flight together when it has that many (a single workgroup quantising a
-        // whole small matrix would otherwise pay one memory round trip per unit)
+    if (!BF16 && cols == ldq && (cols & 15) == 0 && ((uintptr_t)x & 15) == 0 && ((uintptr_t)q & 15) == 0) {
+        // fp32 rows without padding are one contiguous run of whole units (cols a multiple of 16, so
+        // the last unit ends where the tensor ends): four of a thread's units (sixteen 16-byte loads)
+        // in flight together when it has that many (a single workgroup quantising a whole small
+        // matrix would otherwise pay one memory round trip per unit)
         const float4 *x4 = (const float4 *)x;
         for (; u + 3 * stride < units; u += 4 * stride) {
             float4 v[4][4];

@@ -95,3 +95,24 @@ def assert_conv_q(gpu_q, want_nchw, taps_per_row=1):
 def rel_to_absmax(a, b):
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+def assert_within_ulp(got, want, max_ulp=1, what=""):
+    """fp32 arrays equal up to `max_ulp` units in the last place; returns (and prints, when not zero)
+    the number of elements that differ at all.  For tensors that both sides evaluate in fp64 and round
+    once: the fp64 values may differ in their last bits (other summation order, another math library),
+    which moves a rounded fp32 value by one ulp in about one element in 10^8."""
+    got = np.ascontiguousarray(got, dtype=np.float32).reshape(-1)
+    want = np.ascontiguousarray(want, dtype=np.float32).reshape(-1)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.isfinite(got).all() and np.isfinite(want).all(), what
+    gi, wi = got.view(np.int32).astype(np.int64), want.view(np.int32).astype(np.int64)
+    # order-preserving map of the bit patterns (negative values mirrored)
+    gi = np.where(gi < 0, -(gi & 0x7fffffff), gi)
+    wi = np.where(wi < 0, -(wi & 0x7fffffff), wi)
+    d = np.abs(gi - wi)
+    ndiff = int((d != 0).sum())
+    assert d.max(initial=0) <= max_ulp, (what, int(d.max()), ndiff)
+    if ndiff:
+        print(f"{what}: {ndiff} of {d.size} elements differ by one ulp")
+    return ndiff

@@ -79,6 +79,48 @@ def test_oracle_f16_rounds_weights_and_layer_inputs(name, make):
         assert np.array_equal(fo.ref_forward(wl2, "f16")["l0.y"], fo.ref_forward(wl2, "f32")["l0.y"])
 
 
+@pytest.mark.parametrize("precision", ["f16", "f32"])
+@pytest.mark.parametrize("pad", [0, 1])
+def test_oracle_conv_against_brute_force(precision, pad):
+    """The contraction step of `conv` is a library routine; here it is checked against the plain
+    definition written out as loops (cross-correlation, stride 1, zero padding) on a tiny shape,
+    with exact rational sums so that the only rounding is the oracle's single one to float32."""
+    from fractions import Fraction
+    rng = np.random.default_rng(77 + pad)
+    k = 2 * pad + 1
+    B, C, H, W, OC = 2, 3, 4, 5, 2
+    x = rng.standard_normal((B, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((OC, C, k, k)).astype(np.float32)
+    bias = rng.standard_normal(OC).astype(np.float32)
+    y, xr, acc = fo.conv(x, w, bias, precision, pad, residual=None, relu=False)
+    wr = fo.r(w, precision)
+    assert np.array_equal(xr, fo.r(x, precision))
+    for b in range(B):
+        for oc in range(OC):
+            for oh in range(H):
+                for ow in range(W):
+                    s = Fraction(0)
+                    for c in range(C):
+                        for kh in range(k):
+                            for kw in range(k):
+                                ih, iw = oh + kh - pad, ow + kw - pad
+                                if 0 <= ih < H and 0 <= iw < W:
+                                    s += Fraction(float(xr[b, c, ih, iw])) * Fraction(float(wr[oc, c, kh, kw]))
+                    want = np.float32(float(s))          # exact sum, rounded once (double rounding via
+                    # fp64 cannot matter here: 27 products of 24-bit values stay far from fp32 ties)
+                    assert abs(float(acc[b, oc, oh, ow]) - float(want)) <= 2.0 ** -23 * abs(float(want)) + 1e-30
+                    assert y[b, oc, oh, ow] == np.float32(acc[b, oc, oh, ow] + bias[oc])
+    # a shifted one-hot kernel reproduces the shifted input (orientation: cross-correlation, not convolution)
+    if pad == 1:
+        w1 = np.zeros((1, 1, 3, 3), np.float32)
+        w1[0, 0, 0, 2] = 1.0                              # tap (kh, kw) = (0, 2): output(oh, ow) = x(oh - 1, ow + 1)
+        x1 = fo.r(rng.standard_normal((1, 1, 4, 4)).astype(np.float32), precision)
+        y1 = fo.conv(x1, w1, None, precision, 1, relu=False)[0]
+        want = np.zeros_like(x1)
+        want[0, 0, 1:, :-1] = x1[0, 0, :-1, 1:]
+        assert np.array_equal(y1, want)
+
+
 def test_oracle_skip_connection_adds_the_rounded_input():
     wl = si.make_basic_block(b=1, c=4, h=3, w=3, seed=34)
     wl.weights = [np.zeros_like(w) for w in wl.weights]
@@ -138,7 +180,8 @@ def _rows(a):
 
 FLOAT_CASES = SMALL + [("fc_cfg1", lambda: si.make_config(1)),
                        ("basic_cfg2", lambda: si.make_config(2)),
-                       ("bottleneck_mid", lambda: si.make_bottleneck(b=4, c_in=256, c_mid=64, h=14, w=14, seed=35))]
+                       ("bottleneck_mid", lambda: si.make_bottleneck(b=4, c_in=256, c_mid=64, h=14, w=14, seed=35)),
+                       ("bottleneck_cfg3", lambda: si.make_config(3))]
 
 
 @pytest.mark.gpu
@@ -158,7 +201,10 @@ def test_float_reference_matches_oracle(name, make, precision):
             tol = 2e-5 * np.abs(want_y).max()
         else:
             flips = (t["x"] != _rows(ot[f"l{i}.x"])).mean()
-            assert flips <= 2e-3                                                # rare float16 boundary cases only
+            # float16 boundary cases only: an input y flips when the fp32 sum's error (about 1e-6 max|y|
+            # after K = 1024 terms) exceeds its distance to a float16 boundary (spacing 2^-11 |y|), which
+            # happens for the small post-ReLU values: below 1 % of the inputs at K = 1024, 0.1 % at K <= 256
+            assert flips <= 2e-2
             tol = 4e-6 * np.abs(want_y).max() + 2 * 2.0 ** -10 * np.abs(ot[f"l{i}.x"]).max() * np.abs(wl.weights[i]).max()
         assert np.abs(t["y"] - want_y).max() <= tol, (i, name)
         assert np.abs(t["acc"] - _rows(ot[f"l{i}.acc"])).max() <= tol, (i, name)
@@ -167,19 +213,27 @@ def test_float_reference_matches_oracle(name, make, precision):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("precision", ["f16", "f32"])
-def test_float_reference_score(precision, orc):
-    """Plasticity against a float-precision reference (cfg 2): the fused call equals the metric on the
-    stored activation bit for bit, and agrees with the oracle chain + fp64 metric to 1e-3 (the score is
-    a difference of nearly equal Gram matrices, so fp32-rounding-level differences of A_R show)."""
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_float_reference_score(precision, cfg, orc):
+    """Plasticity against a float-precision reference (cfg 2 and cfg 3 at full size).
+    (i) The metric itself: the fused call equals the metric on the stored activation bit for bit, and
+        is within 1e-4 of the fp64 metric evaluated on that same stored activation.
+    (ii) End to end against the oracle chain: here the two A_R differ at fp32-rounding level (fp32 sums on
+        the matrix cores against fp64 sums rounded once: relative 1e-6 of max|y| per layer, see the
+        tolerances above), and P is the squared difference of two Gram matrices that agree to about
+        |A_T - A_R| / |A_R| = 1e-2 (the perturbation of the training weights): a relative change d of
+        A_R moves P by about 2 d / 1e-2, i.e. 2e-4 for d = 1e-6 - the bar for this leg is 1e-3."""
     from paper_2201_06227_amd import binding as eg
     import tests.gpu_common as gc
-    wl = si.make_config(2)
+    wl = si.make_config(cfg)
     a_ref, taps, ref, ws = _gpu_float_forward(wl, precision)
     a_t = si.train_forward(wl)
     p = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
     eg.plasticity_eval(ref, gc.to_dev(wl.x), [a_t[0].to(gc.DEV)], p, ws)
     sep = eg.plasticity(a_t[0].to(gc.DEV), torch.from_numpy(a_ref).to(gc.DEV).reshape(wl.batch, -1))
     assert p.item() == sep.item()
+    same = orc.sp_loss(a_t[0].numpy().reshape(wl.batch, -1), a_ref.reshape(wl.batch, -1))
+    assert abs(p.item() - same) <= 1e-4 * abs(same) + 1e-12 * 4.0 / wl.batch, (p.item(), same)
     want = orc.sp_loss(a_t[0].numpy(), _rows(fo.ref_forward(wl, precision)["a_ref"]).reshape(wl.batch, -1))
     assert p.item() == pytest.approx(want, rel=1e-3)
 

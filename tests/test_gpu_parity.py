@@ -40,7 +40,7 @@ def p_close(got, want, b):
 
 # --------------------------------------------------------------------------- quantise
 
-@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 1000, 4099, (1 << 20) + 3])
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 1000, 4099, 12305, 16380, 16383, 16384, (1 << 20) + 3])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_quantize_flat_bit_exact(eg, gc, orc, n, dtype):
     rng = np.random.default_rng(100 + n)
@@ -55,6 +55,32 @@ def test_quantize_flat_bit_exact(eg, gc, orc, n, dtype):
     assert (q.cpu().numpy() == want_q).all()
     xh = eg.dequantize(q, s).cpu().numpy()
     assert (xh == orc.dequantize(want_q, want_s)).all()
+
+
+@pytest.mark.parametrize("n", [15, 1000, 12289, 12305, 16380, 16383, 16385, 70001])
+def test_quantize_flat_stays_inside_its_buffers(eg, gc, orc, n):
+    """q is int8 [n] exactly: the bytes after it are not the library's to write, whatever the tail of
+    the tensor looks like (the last 16-code unit of a ragged tensor is written byte by byte)."""
+    import ctypes
+    rng = np.random.default_rng(4000 + n)
+    x = (rng.standard_normal(n) * 2).astype(np.float32)
+    pad = 4096
+    xbuf = torch.full((n + pad,), float("nan"), dtype=torch.float32, device=gc.DEV)   # what follows x must not matter
+    xbuf[:n] = gc.to_dev(x)
+    qbuf = torch.full((n + pad,), 0x55, dtype=torch.int8, device=gc.DEV)
+    scale = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+    ws = eg.workspace(eg.quantize_workspace_bytes())
+    rc = eg.lib().egeria_quantize(ctypes.c_void_p(xbuf.data_ptr()), eg.F32, n, None, ctypes.c_void_p(qbuf.data_ptr()),
+                                  ctypes.c_void_p(scale.data_ptr()), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+                                  eg._stream())
+    assert rc == eg.OK
+    torch.cuda.synchronize()
+    want_q, want_s = orc.quantize(x)
+    assert eg.check(ws) == eg.OK
+    assert scale.item() == want_s
+    got = qbuf.cpu().numpy()
+    assert (got[:n] == want_q).all()
+    assert (got[n:] == 0x55).all()
 
 
 def test_quantize_special_tensors(eg, gc, orc):
@@ -442,13 +468,19 @@ def test_plasticity_full_size_shapes(eg, gc, orc, b, D, dt):
 # fp32 tensor is compared for equality, as for the convolution modules.
 
 def _check_bert_layer_taps(gc, taps, ot, l):
+    """The contract of the Transformer modules: every int8 code, every scale and every int32 accumulator
+    equals the oracle's; so does every GEMM output that is a pure function of them (one fma).  The GELU
+    output (fp64 erf on both sides, different math libraries) is compared within one fp32 ulp."""
     for i in range(4):
         t, pre = taps[4 * l + i], f"L{l}.l{i}."
         xq = ot[pre + "xq"]
         assert t["x_scale"][0] == ot[pre + "sx"], pre
         gc.assert_int8_rows(t["x_q"], xq)
         assert (t["acc"] == ot[pre + "acc"]).all(), pre
-        assert (t["y"] == ot[pre + "y"]).all(), pre
+        if i == 2:
+            gc.assert_within_ulp(t["y"], ot[pre + "y"], 1, pre + "y (gelu)")
+        else:
+            assert (t["y"] == ot[pre + "y"]).all(), pre
 
 
 BERT_CASES = [dict(b=2, s=12, hidden=48, heads=4, ffn=96, n_layers=1),
@@ -465,12 +497,12 @@ def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
     ot = orc.ref_forward(wl)
     for l in range(kw["n_layers"]):
         _check_bert_layer_taps(gc, taps, ot, l)
-        assert (a_ref[l] == ot["a_ref"][l].reshape(kw["b"], -1)).all()
-    # an unobserved run never stores the first feed-forward layer's pre-activations (the
-    # GEMM runs as a maximum pass and a pass that writes the codes of gelu(y)): same bits
+        gc.assert_within_ulp(a_ref[l], ot["a_ref"][l].reshape(kw["b"], -1), 1, f"A_R layer {l}")
+    # an unobserved run takes other kernels in places (GELU inside a quantiser, attention on the
+    # fast path with certified codes): the same activations as the observed run, bit for bit
     plain, _, _ = gc.run_forward(wl, with_taps=False)
     for l in range(kw["n_layers"]):
-        assert (plain[l] == ot["a_ref"][l].reshape(kw["b"], -1)).all(), l
+        assert (plain[l] == a_ref[l]).all(), l
     a_t = si.train_forward(wl)
     ws = eg.workspace(eg.workspace_bytes(ref.desc))
     p = torch.zeros(kw["n_layers"], dtype=torch.float32, device=gc.DEV)
@@ -492,11 +524,11 @@ def test_bert_small_preactivations(eg, gc, orc):
     assert float(np.abs(ot["L0.l2.acc"]).max()) > 0 and float(ot["L0.l2.y"].max()) < 0.3
     for l in range(2):
         _check_bert_layer_taps(gc, taps, ot, l)
-        assert (a_ref[l] == ot["a_ref"][l].reshape(2, -1)).all()
-    # unobserved run: the exact maximum comes from a GEMM pass of its own
+        gc.assert_within_ulp(a_ref[l], ot["a_ref"][l].reshape(2, -1), 1, f"A_R layer {l}")
+    # unobserved run: the exact maximum comes from a pass of its own
     plain, _, _ = gc.run_forward(wl, with_taps=False)
     for l in range(2):
-        assert (plain[l] == ot["a_ref"][l].reshape(2, -1)).all(), l
+        assert (plain[l] == a_ref[l]).all(), l
 
 
 def test_bert_layer_full_size(eg, gc, orc):
@@ -505,9 +537,9 @@ def test_bert_layer_full_size(eg, gc, orc):
     a_ref, taps, ref = gc.run_forward(wl)
     ot = orc.ref_forward(wl)
     _check_bert_layer_taps(gc, taps, ot, 0)
-    assert (a_ref[0] == ot["a_ref"][0].reshape(32, -1)).all()
+    gc.assert_within_ulp(a_ref[0], ot["a_ref"][0].reshape(32, -1), 1, "A_R")
     plain, _, _ = gc.run_forward(wl, with_taps=False)
-    assert (plain[0] == ot["a_ref"][0].reshape(32, -1)).all()
+    assert (plain[0] == a_ref[0]).all()
     a_t = si.train_forward(wl)
     assert a_t[0].dtype == torch.bfloat16
     ws = eg.workspace(eg.workspace_bytes(ref.desc))
@@ -517,45 +549,83 @@ def test_bert_layer_full_size(eg, gc, orc):
     assert p_close(p.item(), want, 32), (p.item(), want)
 
 
-def test_bert_stack_full_size(eg, gc, orc):
-    """Config 5: 12 layers, batch 64 x seq 256.  The oracle chain is run for the
-    first two layers at full size (the full depth is covered bit-exactly by the
-    12-layer case at batch 8 x seq 64 above); all 12 layers are also checked
-    through properties that hold at any size."""
-    wl = si.make_config(5)
-    ref = gc.build_reference(wl)
-    x = gc.to_dev(wl.x)
-    n, b, D = 12, wl.batch, 256 * 768
-    a_ref = torch.empty((n, b, D), dtype=torch.float32, device=gc.DEV)
-    ws = eg.workspace(eg.workspace_bytes(ref.desc))
-    eg.ref_forward(ref, x, a_ref, ws)
-    torch.cuda.synchronize()
-    assert eg.check(ws) == eg.OK
-    # every token row of every layer is layer-normalised (gamma 1, beta 0)
-    rows = a_ref.reshape(n, -1, 768)
+class _Cfg5Chain:
+    """Config 5 at full size (12 layers, batch 64 x seq 256): the GPU runs once (an observed run that
+    keeps the int8 input and the scale of all 48 GEMMs, an unobserved run - the one the benchmark
+    times - and the fused forward + scores call); the oracle chain is advanced one layer per test."""
+
+    def __init__(self, eg, gc, orc):
+        import ctypes
+        self.wl = wl = si.make_config(5)
+        self.n, self.b, self.D = 12, wl.batch, 256 * 768
+        n, b, D = self.n, self.b, self.D
+        ref = gc.build_reference(wl)
+        x = gc.to_dev(wl.x)
+        ws = eg.workspace(eg.workspace_bytes(ref.desc))
+        # observation points: codes and scales only (accumulators and outputs follow from them)
+        shapes = gc.tap_shapes(wl)
+        arr = (eg.Tap * len(shapes))()
+        self.xq, self.sx = [], []
+        for i, sh in enumerate(shapes):
+            q = torch.zeros((sh["M"], sh["kp"]), dtype=torch.int8, device=gc.DEV)
+            sc = torch.zeros(1, dtype=torch.float32, device=gc.DEV)
+            arr[i].x_q, arr[i].x_scale, arr[i].acc, arr[i].y = q.data_ptr(), sc.data_ptr(), None, None
+            self.xq.append(q)
+            self.sx.append(sc)
+        taps = eg.Taps()
+        taps.n, taps.tap = len(shapes), arr
+        self.a_obs = torch.empty((n, b, D), dtype=torch.float32, device=gc.DEV)
+        eg.ref_forward(ref, x, self.a_obs, ws, taps)
+        torch.cuda.synchronize()
+        assert eg.check(ws) == eg.OK
+        self.a_ref = torch.empty((n, b, D), dtype=torch.float32, device=gc.DEV)
+        eg.ref_forward(ref, x, self.a_ref, ws)
+        torch.cuda.synchronize()
+        assert eg.check(ws) == eg.OK
+        self.a_t = si.train_forward(wl, device=gc.DEV)
+        self.p = torch.zeros(n, dtype=torch.float32, device=gc.DEV)
+        eg.plasticity_eval(ref, x, self.a_t, self.p, ws)
+        torch.cuda.synchronize()
+        self.qw = orc.quantize_weights(wl.weights)
+        self.cur = wl.x                     # input of the oracle's next layer
+        self.next_layer = 0
+        self.ulp_diffs = []
+
+
+@pytest.fixture(scope="module")
+def cfg5(eg, gc, orc):
+    return _Cfg5Chain(eg, gc, orc)
+
+
+@pytest.mark.parametrize("l", list(range(12)))
+def test_bert_stack_full_size(eg, gc, orc, cfg5, l):
+    """Config 5, layer l of 12 at batch 64 x seq 256, against the oracle chain run to that depth: the
+    int8 input and scale of each of the layer's four GEMMs bit for bit, A_R within one fp32 ulp (the
+    number of differing elements is printed), the unobserved run equal to the observed one, and the
+    layer's score from the fused call within tolerance of the fp64 metric on the oracle's activations."""
+    c = cfg5
+    assert c.next_layer == l, "the layers of the chain are tested in order"
+    d = c.wl.dims
+    taps = {}
+    out, _ = orc.bert_layer(c.cur, c.qw[4 * l:4 * l + 4], c.wl.biases[4 * l:4 * l + 4], d["heads"], d["ln_eps"], taps, "")
+    for i in range(4):
+        assert c.sx[4 * l + i].item() == taps[f"l{i}.sx"], (l, i)
+        gc.assert_int8_rows(c.xq[4 * l + i].cpu().numpy(), taps[f"l{i}.xq"])
+    got = c.a_obs[l].cpu().numpy()
+    ndiff = gc.assert_within_ulp(got, out.reshape(c.b, -1), 1, f"A_R layer {l}")
+    c.ulp_diffs.append(ndiff)
+    assert torch.equal(c.a_ref[l], c.a_obs[l])
+    # every token row is layer-normalised (gamma 1, beta 0)
+    rows = c.a_ref[l].reshape(-1, 768)
     assert rows.mean(-1).abs().max().item() < 1e-5
     assert (rows.var(-1, unbiased=False) - 1).abs().max().item() < 1e-4
-    # the first two layers against the oracle chain, bit for bit
-    import copy
-    wl2 = copy.copy(wl)
-    wl2.weights, wl2.biases = wl.weights[:8], wl.biases[:8]
-    wl2.dims = dict(wl.dims, n_layers=2)
-    ot = orc.ref_forward(wl2, keep_taps=False)
-    for l in range(2):
-        assert (a_ref[l].cpu().numpy() == ot["a_ref"][l].reshape(b, -1)).all()
-    # scores: fused call == separate metric call on the stored activations, bit for bit;
-    # every layer's score against the fp64 metric on the GPU chain's activation (identical
-    # to the oracle's for the layers compared above); layers 0-1 end to end
-    a_t = si.train_forward(wl, device=gc.DEV)
-    p = torch.zeros(n, dtype=torch.float32, device=gc.DEV)
-    eg.plasticity_eval(ref, x, a_t, p, ws)
-    torch.cuda.synchronize()
-    for l in range(n):
-        assert eg.plasticity(a_t[l], a_ref[l]).item() == p[l].item()
-        assert 0 < p[l].item() < 4.0 / b
-    for l in range(2):
-        want = orc.sp_loss(a_t[l].cpu().numpy(), ot["a_ref"][l])
-        assert p_close(p[l].item(), want, b), (l, p[l].item(), want)
+    want = orc.sp_loss(c.a_t[l].cpu().numpy(), out)
+    assert p_close(c.p[l].item(), want, c.b), (l, c.p[l].item(), want)
+    assert eg.plasticity(c.a_t[l], c.a_ref[l]).item() == c.p[l].item()
+    c.cur = out
+    c.next_layer = l + 1
+    if l == 11:
+        print("cfg5 A_R elements that differ from the oracle by one ulp, per layer:", c.ulp_diffs)
 
 
 PER_CHANNEL_CASES = [("fc", dict(b=5, k=100, n=7)), ("fc", dict(b=130, k=200, n=257)),
