@@ -281,6 +281,24 @@ egeria_status egeria_plasticity(const void *a_train, egeria_dtype t_dt, const vo
 
 size_t egeria_plasticity_workspace_bytes(int32_t b, int64_t D);
 
+/* egeria_plasticity for callers that cannot allocate device memory and so have
+ * no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (minus ws), same kernels
+ * and the same result bit for bit; the scratch memory (ticket counter, row
+ * shares, split-K partials) is a 16 MiB array inside the library's device
+ * image, one copy per GPU, held until the process ends.  The call allocates
+ * nothing and does not synchronise.
+ * Limits: as egeria_plasticity, and egeria_plasticity_workspace_bytes(b, D)
+ * must not exceed 16 MiB (EGERIA_ERR_UNSUPPORTED otherwise; every b <= 128 fits
+ * on a 256-CU device).  All calls on one GPU share that GPU's array, which
+ * keeps the previous call's contents (the kernels clear what must start at
+ * zero): calls on one GPU that overlap in time - two streams, two threads -
+ * race on it and give undefined scores; order them on one stream.  The device
+ * of `stream` must be the current device. */
+egeria_status egeria_plasticity_noalloc(const void *a_train, egeria_dtype t_dt, const void *a_ref,
+                                        egeria_dtype r_dt, int32_t b, int64_t D, float *p_out,
+                                        void *stream);
+
 /* Sections 4.1-4.2, one plasticity evaluation: reference forward of a module
  * (or stack; Section 4.1, as egeria_ref_forward without observation points)
  * followed by one score per layer (Section 4.2, Eq. 1, as egeria_plasticity on

@@ -96,7 +96,7 @@ EXPORTS = [
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
     "egeria_freeze_init", "egeria_freeze_observe",
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
-    "egeria_refresh_eval",
+    "egeria_refresh_eval", "egeria_plasticity_noalloc",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -138,6 +138,8 @@ def lib():
                                      _vp, ctypes.POINTER(Taps), _vp, _sz, _vp]
     L.egeria_plasticity.restype = ctypes.c_int
     L.egeria_plasticity.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int, _i32, _i64, _vp, _vp, _sz, _vp]
+    L.egeria_plasticity_noalloc.restype = ctypes.c_int
+    L.egeria_plasticity_noalloc.argtypes = [_vp, ctypes.c_int, _vp, ctypes.c_int, _i32, _i64, _vp, _vp]
     L.egeria_plasticity_workspace_bytes.restype = _sz
     L.egeria_plasticity_workspace_bytes.argtypes = [_i32, _i64]
     L.egeria_plasticity_eval.restype = ctypes.c_int
@@ -442,6 +444,19 @@ def plasticity(a_train: torch.Tensor, a_ref: torch.Tensor, p_out: Optional[torch
     rc = lib().egeria_plasticity(_ptr(a_train), _dt(a_train), _ptr(a_ref), _dt(a_ref), b, D, _ptr(p_out),
                                  _ptr(ws), ws.numel(), _stream())
     _check(rc, "egeria_plasticity")
+    return p_out
+
+
+def plasticity_noalloc(a_train: torch.Tensor, a_ref: torch.Tensor, p_out: torch.Tensor) -> torch.Tensor:
+    """egeria_plasticity_noalloc: the score into the caller's p_out; nothing is allocated here either."""
+    a_train, a_ref = _dev(a_train), _dev(a_ref)
+    b = a_train.shape[0]
+    D = a_train.numel() // b if b else 0
+    if a_ref.shape[0] != b or a_ref.numel() != a_train.numel():
+        raise ValueError("a_train and a_ref must both be [b, D]")
+    rc = lib().egeria_plasticity_noalloc(_ptr(a_train), _dt(a_train), _ptr(a_ref), _dt(a_ref), b, D, _ptr(p_out),
+                                         _stream())
+    _check(rc, "egeria_plasticity_noalloc")
     return p_out
 
 

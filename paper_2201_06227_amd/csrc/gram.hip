@@ -37,6 +37,7 @@
 //   workgroup to finish adds the b shares in index order and writes P.
 //   Results are bit-reproducible from call to call.
 #include "common.hpp"
+#include <mutex>
 
 namespace egeria {
 
@@ -504,3 +505,56 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
 }
 
 }  // namespace egeria
+
+// ---- the metric for callers that cannot allocate ------------------------------------------
+// egeria_plasticity takes its scratch memory (ticket counter, row shares, split-K partials) from a
+// workspace the caller allocated.  Code under HIP graph capture, tight serving loops and harnesses
+// that forbid allocation have nowhere to get one: egeria_plasticity_noalloc runs the same two
+// kernels on a scratch array that lives in the library's own device image.  Each GPU holds its own
+// copy of the array, at its own address, until the process ends; `scratch` below is only the
+// host-side handle of the symbol, and the device address is looked up once per device.
+namespace {
+constexpr size_t kScratchBytes = (size_t)16 << 20;      // >= plasticity_partial_bytes(b, D) for every b <= 128 on 256 CUs
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[egeria::kMaxDevices] = {};
+}  // namespace
+
+// (no `used` attribute: the compiler exports a file-scope static device array that host code names, and
+// the runtime finds it by that exported name; marked `used` it stays a local symbol of the code object)
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of this GPU's copy of the array (the current device's), looked up on first use.
+static hipError_t scratch_address(void **out)
+{
+    const int dev = egeria::current_device();
+    if (dev < 0) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" egeria_status egeria_plasticity_noalloc(const void *a_train, egeria_dtype t_dt, const void *a_ref,
+                                                   egeria_dtype r_dt, int32_t b, int64_t D, float *p_out, void *stream)
+{
+    using namespace egeria;
+    if (!a_train || !a_ref || !p_out || b < 1 || D < 1) return EGERIA_ERR_INVALID_ARG;
+    if (((uintptr_t)a_train & 15u) || ((uintptr_t)a_ref & 15u) || ((uintptr_t)p_out & 3u)) return EGERIA_ERR_INVALID_ARG;
+    if ((t_dt != EGERIA_F32 && t_dt != EGERIA_BF16) || (r_dt != EGERIA_F32 && r_dt != EGERIA_BF16))
+        return EGERIA_ERR_INVALID_ARG;
+    if (b > 128) return EGERIA_ERR_UNSUPPORTED;
+    if (plasticity_partial_bytes(b, D) > kScratchBytes) return EGERIA_ERR_UNSUPPORTED;     // beyond the array
+    void *ptr = nullptr;
+    if (scratch_address(&ptr) != hipSuccess) return EGERIA_ERR_HIP;
+    // the kernels take the array's device address as they take the caller's workspace in
+    // egeria_plasticity; what must start at zero (the finaliser's ticket) is cleared by the first kernel
+    if (launch_plasticity(a_train, t_dt, a_ref, r_dt, b, D, p_out, ptr, (hipStream_t)stream) != hipSuccess)
+        return EGERIA_ERR_HIP;
+    return EGERIA_OK;
+}
