@@ -57,6 +57,7 @@ struct Plan {
     int64_t D = 0;          // features per sample of the hooked activation
     size_t off_q[3] = {0, 0, 0};      // int8 activation buffers
     size_t off_f[5] = {0, 0, 0, 0, 0};  // fp32 intermediates
+    size_t off_rec = 0;               // per-workgroup records of the fast attention kernel (Transformer kinds)
     size_t off_aref[2] = {0, 0};      // A_R ping-pong (egeria_plasticity_eval)
     size_t off_part = 0;              // metric partials
     size_t fwd_bytes = 0;             // header + forward buffers
@@ -124,7 +125,8 @@ Plan make_plan(const egeria_block_desc *d)
     }
     default: {
         p.n_layers = d->n_layers;
-        p.slots = 5 * p.n_layers;      // four quantise points per layer + one exact-absmax word for the GELU
+        // four quantise points per layer + one exact-absmax word for the GELU + one for the attention context
+        p.slots = 6 * p.n_layers;
         p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
         take(header_bytes(p.slots));
         const int64_t kmax = pad16(d->hidden > d->ffn ? d->hidden : d->ffn);
@@ -134,6 +136,7 @@ Plan make_plan(const egeria_block_desc *d)
         p.off_f[2] = take((size_t)(p.M * d->hidden) * 4);       // attention / ffn projection
         p.off_f[3] = take((size_t)(p.M * d->hidden) * 4);       // post-attention layer norm
         p.off_f[4] = take((size_t)(p.M * d->ffn) * 4);          // ffn hidden
+        p.off_rec = take(attention_records_bytes(d->batch, d->seq, d->heads));
         break;
     }
     }
@@ -417,11 +420,18 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
                                     f.scale(s0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
     EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
-    EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
-
-    EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.amax(s0 + 1), f.n_amax(s0 + 1), f.stride_amax(s0 + 1), nullptr, xq, f.scale(s0 + 1), nullptr,
-                                ws_flag(f.ws), f.st));
-    EG_OK(f.copy_tap_q(s0 + 1, xq, (size_t)(M * hp), f.scale(s0 + 1)));
+    if (f.taps) {
+        // observed runs: the context itself in fp64, then the plain quantiser
+        EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
+        EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.amax(s0 + 1), f.n_amax(s0 + 1), f.stride_amax(s0 + 1),
+                                    nullptr, xq, f.scale(s0 + 1), nullptr, ws_flag(f.ws), f.st));
+        EG_OK(f.copy_tap_q(s0 + 1, xq, (size_t)(M * hp), f.scale(s0 + 1)));
+    } else {
+        // unobserved runs: fp32 matrix-core attention, codes and scale certified against the fp64 evaluation
+        EG_HIP(launch_attention_certified(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.ws + f.p.off_rec,
+                                          f.slot(5 * f.p.n_layers + l), xq, hp, f.scale(s0 + 1), ws_flag(f.ws),
+                                          ws_flag(f.ws) + kUnsureWord, f.st));
+    }
     EG_OK(run_gemm(f, s0 + 1, xq, hp, M, Hd, hp, false, 0, 0, 0, f.scale(s0 + 1), 0, nullptr, nullptr, 0, proj,
                    nullptr));
     EG_HIP(launch_layernorm(cur, proj, M, Hd, nm ? nm[0].gamma : nullptr, nm ? nm[0].beta : nullptr, d->ln_eps,

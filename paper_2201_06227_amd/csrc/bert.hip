@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int d = 16 * u + 4 * g + e;
-                qr[qb][4 * u + e] = (q < S && d < dh) ? (double)qv[4 * u + e] * scale : 0.0;
+                qr[qb][4 * u + e] = (q < S && d < dh) ? (double)qv[4 * u + e] : 0.0;
             }
     }
 
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int key = j0 + kb * 16 + 4 * r + g;
-                    if (key >= S) st[kb][qb][r] = -INFINITY;
+                    st[kb][qb][r] = key >= S ? -INFINITY : st[kb][qb][r] * scale;   // q.k first, then 1/sqrt(dh)
                     mx = fmax(mx, st[kb][qb][r]);
                 }
             mx = fmax(mx, __shfl_xor(mx, 16, kWave));
@@ -387,6 +387,584 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
         __shared__ uint32_t sm4[4];
         block_atomic_max(amax, absmax_out, sm4);
     }
+}
+
+// ---- the same attention on the fp32 matrix-core instructions, with certified int8 codes ----------
+// Unobserved runs do not need the context as the fp64 evaluation gives it: all that leaves this stage
+// is the int8 input of the next GEMM and its scale.  Four launches:
+//   1. attention_fast_kernel: the structure of the kernel above in fp32 (v_mfma_f32_16x16x4f32, hardware
+//      exp2), 2.2x faster.  It stores an approximate context and, per workgroup, a record: the largest
+//      |context| it stored and an error bound E for its values (below).
+//   2. attention_absmax_exact_kernel: the tensor's absolute maximum as the fp64 evaluation gives it.  Every
+//      value that can be the maximum (|x| + E >= largest |x| - largest E; as a rule one) is re-evaluated in fp64.
+//   3. quantize_attention_scan_kernel: the streaming map to codes.  code(x) = clamp(rne(x * inv)) is
+//      monotone in x, so an approximate value whose interval [x - E, x + E] maps to one code has that
+//      code; the others (a few in ten thousand) are put on a list.
+//   4. attention_fix_kernel: a wave per listed value re-evaluates it in fp64 and stores its code.
+// The bound: E = 2^-24 * max|v| of the head * (kErrBase + kErrPerScore * max|score| of the workgroup).  It is
+// an empirical bound with margin, not a proof: the measured error of kernel 1 against the fp64 kernel on
+// BERT-base-shaped inputs (64 x 12 heads x 256 x 64) has a maximum of 0.96 * 2^-24 * max|v| over 12.6 M
+// values (median 0.03, 99.99th percentile 0.5) with scores up to 2.5, where E is 6.5 of these units.
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr float kErrBase = 4.0f, kErrPerScore = 1.0f;
+struct AttnRecord {
+    uint32_t amax_bits;     // largest |approximate context| of the workgroup's 64 queries x head dims
+    float err;              // E for those values
+};
+
+__global__ __launch_bounds__(256) void attention_fast_kernel(const float *__restrict__ qkv, int B, int S, int Hd,
+                                                             int heads, int dh, float scale, float *__restrict__ ctx,
+                                                             AttnRecord *__restrict__ rec, int total, int per_xcd)
+{
+    __shared__ __attribute__((aligned(16))) float sKb[2][kKeyTile][kKVPad];
+    __shared__ __attribute__((aligned(16))) float sVb[2][kKeyTile][kKVPad];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    constexpr int QT = 64;
+    const int qtiles = (S + QT - 1) / QT;
+    const int vid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || vid >= total) return;
+    const int bh = vid / qtiles, qt = vid % qtiles;
+    const int bi = bh / heads, hd = bh % heads;
+    const int64_t tok0 = (int64_t)bi * S;
+    const int64_t ld = 3 * (int64_t)Hd;
+    const float *qbase = qkv + hd * dh, *kbase = qbase + Hd, *vbase = qbase + 2 * Hd;
+    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
+    // query rows as the B operand of S^T = K Q^T: lane (c, g) holds dims 16u + 4g + e of query c
+    float qr[16];
+    const int q = qt * QT + wave * 16 + c;
+    {
+        const float *qrow = qbase + (tok0 + (q < S ? q : S - 1)) * ld;
+        float qv[16];
+        if (vec4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int d0 = 16 * u + 4 * g;
+                const float4 v = *(const float4 *)(qrow + (d0 < dh ? d0 : 0));
+                qv[4 * u] = v.x; qv[4 * u + 1] = v.y; qv[4 * u + 2] = v.z; qv[4 * u + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int d = 16 * u + 4 * g + e;
+                    qv[4 * u + e] = qrow[d < dh ? d : 0];
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int d = 16 * u + 4 * g + e;
+                qr[4 * u + e] = (q < S && d < dh) ? qv[4 * u + e] : 0.0f;
+            }
+    }
+    v4f o[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[db][r] = 0.0f;
+    float mrun = -INFINITY, lrun = 0.0f;
+    float smax = 0.0f;                  // largest |score| met by this lane
+    uint32_t vmax = 0;                  // largest |v| staged by this thread (bit pattern)
+    float4 pk[2], pv[2];
+    auto fetch = [&](int j0) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + it * 256, kr = sl >> 4, d = (sl & 15) * 4;
+            const int64_t off = (tok0 + j0 + kr) * ld + d;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b4 = a;
+            if (j0 + kr < S) {
+                if (vec4 && d + 4 <= dh) {
+                    a = *(const float4 *)(kbase + off);
+                    b4 = *(const float4 *)(vbase + off);
+                } else {
+                    float ea[4] = {0.f, 0.f, 0.f, 0.f}, eb[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (d + e < dh) { ea[e] = kbase[off + e]; eb[e] = vbase[off + e]; }
+                    a = make_float4(ea[0], ea[1], ea[2], ea[3]);
+                    b4 = make_float4(eb[0], eb[1], eb[2], eb[3]);
+                }
+            }
+            pk[it] = a;
+            pv[it] = b4;
+        }
+    };
+    auto stash = [&](int stage) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + it * 256, kr = sl >> 4, d = (sl & 15) * 4;
+            *(float4 *)&sKb[stage][kr][d] = pk[it];
+            *(float4 *)&sVb[stage][kr][d] = pv[it];
+            uint32_t a0 = abs_bits(pv[it].x), a1 = abs_bits(pv[it].y), a2 = abs_bits(pv[it].z), a3 = abs_bits(pv[it].w);
+            a0 = a0 > a1 ? a0 : a1;
+            a2 = a2 > a3 ? a2 : a3;
+            a0 = a0 > a2 ? a0 : a2;
+            vmax = vmax > a0 ? vmax : a0;
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    int stage = 0;
+    constexpr float kLog2e = 1.44269504088896340736f;
+    for (int j0 = 0; j0 < S; j0 += kKeyTile, stage ^= 1) {
+        const bool more = j0 + kKeyTile < S;
+        if (more) fetch(j0 + kKeyTile);
+        float (*sK)[kKVPad] = sKb[stage];
+        float (*sV)[kKVPad] = sVb[stage];
+        v4f st[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) st[kb][r] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const float4 kv = *(const float4 *)&sK[kb * 16 + c][16 * u + 4 * g];
+                const float k4[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    st[kb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k4[e], qr[4 * u + e], st[kb], 0, 0, 0);
+            }
+        }
+        // register r of st[kb] is key j0 + 16 kb + 4 g + r for this lane's query
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int key = j0 + kb * 16 + 4 * g + r;
+                const float sc = st[kb][r] * scale;
+                smax = key < S ? fmaxf(smax, fabsf(sc)) : smax;
+                st[kb][r] = key < S ? sc : -INFINITY;
+                mx = fmaxf(mx, st[kb][r]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float mnew = fmaxf(mrun, mx);
+        const float corr = __builtin_amdgcn_exp2f((mrun - mnew) * kLog2e);
+        float ps = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                st[kb][r] = __builtin_amdgcn_exp2f((st[kb][r] - mnew) * kLog2e);
+                ps += st[kb][r];
+            }
+        ps += __shfl_xor(ps, 16, kWave);
+        ps += __shfl_xor(ps, 32, kWave);
+        lrun = lrun * corr + ps;
+        mrun = mnew;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[db][r] *= corr;
+        // O^T += V^T P^T: step (kb, r) contracts keys 16 kb + 4 g + r, g = 0..3
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int kr = kb * 16 + 4 * g + r;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+                    o[db] = __builtin_amdgcn_mfma_f32_16x16x4f32(sV[kr][db * 16 + c], st[kb][r], o[db], 0, 0, 0);
+            }
+        if (more) stash(stage ^ 1);
+        __syncthreads();
+    }
+
+    uint32_t amax = 0;
+    if (q < S) {
+        float *dst = ctx + (tok0 + q) * Hd + hd * dh;
+        const float inv = 1.0f / lrun;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int d = db * 16 + 4 * g;              // registers 0..3: four consecutive head dims
+            float v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                v[r] = o[db][r] * inv;
+                const uint32_t ab = abs_bits(v[r]);
+                amax = (d + r < dh && ab > amax) ? ab : amax;
+            }
+            if (vec4 && d + 4 <= dh) {
+                *(float4 *)(dst + d) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (d + r < dh) dst[d + r] = v[r];
+            }
+        }
+    }
+    // the workgroup's record: largest |context| stored, and the error bound of its values
+    __shared__ uint32_t red[3][4];
+    amax = wave_max_u32(amax);
+    vmax = wave_max_u32(vmax);
+    const uint32_t sbits = wave_max_u32(__float_as_uint(smax));       // non-negative floats order like integers
+    if (lane == 0) { red[0][wave] = amax; red[1][wave] = vmax; red[2][wave] = sbits; }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t a = 0, v = 0, sb = 0;
+        for (int w = 0; w < 4; ++w) {
+            a = a > red[0][w] ? a : red[0][w];
+            v = v > red[1][w] ? v : red[1][w];
+            sb = sb > red[2][w] ? sb : red[2][w];
+        }
+        AttnRecord r;
+        r.amax_bits = a;
+        r.err = 5.9604645e-8f * __uint_as_float(v) * (kErrBase + kErrPerScore * __uint_as_float(sb));
+        if (!(r.err <= 3.402823466e+38f)) r.amax_bits = 0x7f800000u;   // non-finite inputs: flagged downstream
+        rec[vid] = r;
+    }
+}
+
+// The context value of one (query token, head, dim) as the fp64 evaluation defines it:
+// scores in fp64 (products summed over the head dims in ascending
+// order, then the 1/sqrt(dh) factor), soft-max and the weighted sum of v in fp64, rounded once.  q, k and
+// v rows are read from the packed qkv tensor.  Every load is unconditional (indices clamped to valid
+// ones, the query zero beyond dh): a load under a condition is awaited on its own, and a key row would
+// cost sixteen memory round trips instead of one.
+// (kept compact and inlined once per kernel: called as a function it needs scratch memory for the
+// caller's registers and ran five times slower)
+__device__ __forceinline__ float context_exact(const float *__restrict__ qkv, int S, int Hd, int heads, int dh, double scale,
+                                            uint32_t el, double *red)
+{
+    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;           // whole 16-byte units, 16-byte aligned rows
+    const uint32_t mrow = el / (uint32_t)Hd, col = el - mrow * (uint32_t)Hd;
+    const uint32_t bi = mrow / (uint32_t)S, hd = col / (uint32_t)dh, dd = col - hd * (uint32_t)dh;
+    const int64_t ld = 3 * (int64_t)Hd;
+    const float *q = qkv + (int64_t)mrow * ld + hd * dh;
+    const float *kb = qkv + (int64_t)bi * S * ld + Hd + hd * dh, *vb = kb + Hd + dd;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int units = dh >> 2;
+    // the query row goes through LDS (64 floats behind the 12 doubles of red): every thread needs all of it
+    float *qs = (float *)(red + 12);
+    __syncthreads();                                          // an earlier call has finished with red and qs
+    if (tid < 64) qs[tid] = tid < dh ? q[tid] : 0.0f;
+    __syncthreads();
+    double m = -INFINITY, l = 0.0, o = 0.0;
+    for (int j0 = 0; j0 < S; j0 += 256) {
+        const int j = j0 + tid;
+        const int jj = j < S ? j : S - 1;
+        const float *kr = kb + (int64_t)jj * ld;
+        const float vj = vb[(int64_t)jj * ld];
+        // a product of two fp32 values is exact in fp64, so each fma below is the multiply and the
+        // add of the plain definition, in its order (dims ascending)
+        double acc = 0.0;
+        if (vec4) {
+            float4 kv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kv[u] = *(const float4 *)(kr + 4 * (u < units ? u : units - 1));
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (u < units) {
+                    const float4 qv = *(const float4 *)&qs[4 * u];
+                    acc = fma((double)qv.x, (double)kv[u].x, acc);
+                    acc = fma((double)qv.y, (double)kv[u].y, acc);
+                    acc = fma((double)qv.z, (double)kv[u].z, acc);
+                    acc = fma((double)qv.w, (double)kv[u].w, acc);
+                }
+            }
+        } else {
+            for (int d = 0; d < dh; ++d) acc = fma((double)qs[d], (double)kr[d], acc);   // odd head sizes: plain loop
+        }
+        const double sc = j < S ? acc * scale : -INFINITY;
+        double cm = sc;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) cm = fmax(cm, __shfl_xor(cm, off, kWave));
+        __syncthreads();                                      // red is free (an earlier block, an earlier call)
+        if (lane == 0) red[wave] = cm;
+        __syncthreads();
+        const double mnew = fmax(m, fmax(fmax(red[0], red[1]), fmax(red[2], red[3])));
+        const double p = exp(sc - mnew);                 // exp(-inf) = 0 for the keys beyond S
+        const double corr = j0 == 0 ? 0.0 : exp(m - mnew);
+        const double ps = wave_sum(p), po = wave_sum(p * (double)vj);
+        if (lane == 0) { red[4 + wave] = ps; red[8 + wave] = po; }
+        __syncthreads();
+        l = l * corr + ((red[4] + red[5]) + (red[6] + red[7]));
+        o = o * corr + ((red[8] + red[9]) + (red[10] + red[11]));
+        m = mnew;
+    }
+    return (float)(o / l);
+}
+
+// Workgroup-uniform walk over the values a predicate marks among 256 consecutive candidates: every thread
+// passes its own flag, and `visit(k)` runs, in all threads, for every marked k = 0..255 in ascending order.
+template <typename F>
+__device__ __forceinline__ void for_each_marked(bool mine, uint64_t *masks, F visit)
+{
+    const uint64_t b = __ballot(mine);
+    __syncthreads();                                          // masks is free
+    if ((threadIdx.x & 63) == 0) masks[threadIdx.x >> 6] = b;
+    __syncthreads();
+    for (int w = 0; w < 4; ++w) {
+        uint64_t mask = masks[w];
+        while (mask) {
+            const int src = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            visit(w * 64 + src);
+        }
+    }
+}
+
+// Exact absolute maximum of the context: one workgroup per record.  Each reduces all records to the largest
+// stored |x| (A) and the largest E (eight record loads of a thread in flight at a time); a value can be the
+// exact maximum only if |x| + E_record >= A - E_max.  A workgroup whose record cannot hold such a value is
+// done; the others (as a rule one) rescan the record's 64 x dh values and re-evaluate those that pass the
+// test.  The value that holds A passes, so the word `exact` ends up with the exact maximum (it starts at
+// zero: cleared by the chain's first kernel).
+__global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float *__restrict__ qkv,
+                                                                     const float *__restrict__ ctx,
+                                                                     const AttnRecord *__restrict__ rec, int nrec,
+                                                                     int S, int Hd, int heads, int dh, double scale,
+                                                                     uint32_t *__restrict__ exact,
+                                                                     uint32_t *__restrict__ list_count)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *list_count = 0u;      // the list the next kernel fills
+    __shared__ uint32_t sa[4];
+    __shared__ float se[4];
+    __shared__ __attribute__((aligned(16))) double red[12 + 32];
+    __shared__ uint64_t masks[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const AttnRecord mine = rec[blockIdx.x];
+    uint32_t a = 0;
+    float e = 0.0f;
+    const uint2 *rec2 = (const uint2 *)rec;
+    for (int i0 = 0; i0 < nrec; i0 += 256 * 8) {
+        uint2 r[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = i0 + tid + 256 * k;
+            r[k] = rec2[i < nrec ? i : nrec - 1];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            a = a > r[k].x ? a : r[k].x;
+            e = fmaxf(e, __uint_as_float(r[k].y));
+        }
+    }
+    a = wave_max_u32(a);
+    e = wave_max(e);
+    if (lane == 0) { sa[wave] = a; se[wave] = e; }
+    __syncthreads();
+    a = sa[0] > sa[1] ? sa[0] : sa[1];
+    a = a > sa[2] ? a : sa[2];
+    a = a > sa[3] ? a : sa[3];
+    e = fmaxf(fmaxf(se[0], se[1]), fmaxf(se[2], se[3]));
+    if (a >= 0x7f800000u) {                                   // NaN / Inf in the tensor: it is the "maximum"
+        if (blockIdx.x == 0 && tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, a);
+        return;
+    }
+    const float floor_v = __uint_as_float(a) - e;             // values below this cannot be the maximum
+    if (!(__uint_as_float(mine.amax_bits) + mine.err >= floor_v)) return;
+    const int qtiles = (S + 63) / 64;
+    const int bh = blockIdx.x / qtiles, qt = blockIdx.x % qtiles;
+    const int bi = bh / heads, hd = bh % heads;
+    const int64_t tok0 = (int64_t)bi * S;
+    const int nq = S - qt * 64 < 64 ? S - qt * 64 : 64;
+    const int n_el = nq * dh;
+    uint32_t best = 0;
+    // candidates are found 256 values at a time and re-evaluated one by one by the workgroup
+    for (int base = 0; base < n_el; base += 256) {
+        const int idx = base + tid;
+        bool cand = false;
+        if (idx < n_el) {
+            const int qq = qt * 64 + idx / dh, d = idx % dh;
+            cand = fabsf(ctx[(tok0 + qq) * Hd + hd * dh + d]) + mine.err >= floor_v;
+        }
+        for_each_marked(cand, masks, [&](int k) {
+            const int cidx = base + k;
+            const int qq = qt * 64 + cidx / dh, d = cidx % dh;
+            const float x = context_exact(qkv, S, Hd, heads, dh, scale, (uint32_t)((tok0 + qq) * Hd + hd * dh + d), red);
+            const uint32_t ab = abs_bits(x);
+            best = best > ab ? best : ab;
+        });
+    }
+    if (tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, best);
+}
+
+// The int8 codes of the context under the tensor's exact scale, as a streaming pass over the approximate
+// context: a thread maps 16 consecutive values of a token row (one 16-byte store; WIDE: head size and row
+// length are multiples of 16, so the sixteen share a head) or a single value.  A value whose interval
+// [x - E, x + E] maps to two codes is appended to a list in global memory (its index in the [tokens, Hd]
+// tensor) and gets a provisional code; attention_fix_kernel re-evaluates the listed values in fp64.  The list
+// holds kFixList entries, far above the one value in a few thousand that is uncertain; if it overflows
+// all the same, attention_fix_kernel finds the uncertain values by a scan of its own.
+constexpr uint32_t kFixList = 1u << 16;
+struct FixList {
+    uint32_t count;                 // uncertain values met (entries beyond kFixList are not stored)
+    uint32_t pad[3];
+    uint32_t entry[kFixList];
+};
+
+// true if the approximate value x with error bound err does not settle its code
+__device__ __forceinline__ bool code_uncertain(float x, float err, float inv)
+{
+    const float e2 = err * 1.001f + 1.0e-37f;                     // covers the rounding of x -+ err itself
+    return quant1(x - e2, inv) != quant1(x + e2, inv) || !(e2 <= 3.402823466e+38f);
+}
+
+template <bool WIDE>
+__global__ __launch_bounds__(256) void quantize_attention_scan_kernel(
+    const float *__restrict__ ctx, const AttnRecord *__restrict__ rec, int64_t M, int S, int Hd, int heads, int dh,
+    const uint32_t *__restrict__ exact, int8_t *__restrict__ xq, int64_t ldq, float *__restrict__ scale_out,
+    uint32_t *__restrict__ flag, FixList *__restrict__ fix)
+{
+    float sc_f;
+    bool bad;
+    const float inv = scale_from_bits(reduce_ways(exact), nullptr, &sc_f, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish(sc_f, bad, scale_out, nullptr, flag);
+    const uint32_t qtiles = (uint32_t)(S + 63) / 64u;
+    const uint32_t upr = (uint32_t)(WIDE ? ldq / 16 : ldq);      // units per int8 row (pad columns included when !WIDE)
+    const uint32_t units = (uint32_t)M * upr;                    // below 2^32 (checked by the launcher)
+    for (uint32_t u = blockIdx.x * 256u + threadIdx.x; u < units; u += gridDim.x * 256u) {
+        const uint32_t m = u / upr, cu = u - m * upr;
+        const uint32_t bi = m / (uint32_t)S, s_idx = m - bi * (uint32_t)S;
+        if (WIDE) {
+            const uint32_t col = cu * 16u, hd = col / (uint32_t)dh;
+            const float err = rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err;
+            const float4 *p = (const float4 *)(ctx + (int64_t)m * Hd + col);
+            float4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = p[j];
+            uint32_t w[4];
+            uint32_t unsure = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                w[j] = quant1(v[j].x, inv) | quant1(v[j].y, inv) << 8 | quant1(v[j].z, inv) << 16 | quant1(v[j].w, inv) << 24;
+                unsure |= (code_uncertain(v[j].x, err, inv) ? 1u : 0u) << (4 * j) | (code_uncertain(v[j].y, err, inv) ? 2u : 0u) << (4 * j) |
+                          (code_uncertain(v[j].z, err, inv) ? 4u : 0u) << (4 * j) | (code_uncertain(v[j].w, err, inv) ? 8u : 0u) << (4 * j);
+            }
+            *(uint4 *)(xq + (int64_t)m * ldq + col) = make_uint4(w[0], w[1], w[2], w[3]);
+            if (bad) unsure = 0;
+            while (unsure) {
+                const int e = __ffs((int)unsure) - 1;
+                unsure &= unsure - 1;
+                const uint32_t at = atomicAdd(&fix->count, 1u);
+                if (at < kFixList) fix->entry[at] = m * (uint32_t)Hd + col + (uint32_t)e;
+            }
+        } else {
+            uint32_t code = 0;
+            if (cu < (uint32_t)Hd) {
+                const float x = ctx[(int64_t)m * Hd + cu];
+                const uint32_t hd = cu / (uint32_t)dh;
+                const float err = rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err;
+                code = quant1(x, inv);
+                if (!bad && code_uncertain(x, err, inv)) {
+                    const uint32_t at = atomicAdd(&fix->count, 1u);
+                    if (at < kFixList) fix->entry[at] = m * (uint32_t)Hd + cu;
+                }
+            }
+            xq[(int64_t)m * ldq + cu] = (int8_t)code;            // pad columns: zero
+        }
+    }
+}
+
+// A workgroup per listed value: fp64 re-evaluation, then its code replaces the provisional one.  If the
+// list overflowed, the uncertain values are found again here instead: workgroups take 256 values of the
+// context at a time, apply the scan kernel's test and re-evaluate whatever fails it.
+__global__ __launch_bounds__(256, 4) void attention_fix_kernel(const float *__restrict__ qkv, const float *__restrict__ ctx,
+                                                            const AttnRecord *__restrict__ rec, int64_t M, int S, int Hd,
+                                                            int heads, int dh, double scale,
+                                                            const uint32_t *__restrict__ exact, int8_t *__restrict__ xq,
+                                                            int64_t ldq, const FixList *__restrict__ fix,
+                                                            uint32_t *__restrict__ unsure_total)
+{
+    __shared__ __attribute__((aligned(16))) double red[12 + 32];
+    float sc_f;
+    bool bad;
+    const float inv = scale_from_bits(reduce_ways(exact), nullptr, &sc_f, &bad);
+    const uint32_t count = fix->count;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && unsure_total && count) atomicAdd(unsure_total, count);
+    if (bad) return;
+    const int tid = threadIdx.x;
+    __shared__ uint32_t todo[256];
+    __shared__ uint32_t n_todo;
+    const bool listed = count <= kFixList;
+    const uint32_t total = (uint32_t)(M * Hd), qtiles = (uint32_t)(S + 63) / 64u;
+    // batches of up to 256 values to re-evaluate: the workgroup's share of the list, or (list overflowed)
+    // whatever fails the scan kernel's test among 256 consecutive values of the context
+    const uint32_t n_batches = listed ? (count + gridDim.x - 1) / gridDim.x : (total + 255u) / 256u;
+    for (uint32_t b = listed ? 0u : blockIdx.x; b < n_batches; b += listed ? 1u : gridDim.x) {
+        __syncthreads();                                          // todo is free
+        if (tid == 0) n_todo = 0;
+        __syncthreads();
+        if (listed) {
+            const uint32_t i = b * gridDim.x + blockIdx.x;        // one listed value per workgroup and batch
+            if (tid == 0 && i < count) { todo[0] = fix->entry[i]; n_todo = 1; }
+        } else {
+            const uint32_t el = b * 256u + (uint32_t)tid;
+            if (el < total) {
+                const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
+                const uint32_t bi = m / (uint32_t)S, s_idx = m - bi * (uint32_t)S, hd = col / (uint32_t)dh;
+                if (code_uncertain(ctx[el], rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err, inv))
+                    todo[atomicAdd(&n_todo, 1u)] = el;
+            }
+        }
+        __syncthreads();
+        const uint32_t n = n_todo;
+        for (uint32_t k = 0; k < n; ++k) {
+            const uint32_t el = todo[k];
+            const float x = context_exact(qkv, S, Hd, heads, dh, scale, el, red);
+            const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
+            if (tid == 0) xq[(int64_t)m * ldq + col] = (int8_t)quant1(x, inv);
+        }
+    }
+}
+
+static bool attn_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads)
+{
+    return align_up(sizeof(FixList), 256) + align_up((size_t)B * heads * ((S + 63) / 64) * sizeof(AttnRecord), 256);
+}
+
+hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
+                                      void *records, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
+                                      uint32_t *flag, uint32_t *unsure_total, hipStream_t st)
+{
+    const int dh = Hd / heads;
+    const int qtiles = (S + 63) / 64;
+    const int64_t grid = (int64_t)B * heads * qtiles;
+    const int64_t M = (int64_t)B * S;
+    if (grid <= 0) return hipSuccess;
+    // what the kernels assume: heads of at most 64 dims, 32-bit indices of the context's values, rows that
+    // 16-byte vector accesses may touch when the head size allows them
+    if (dh > kDh || grid > 0x7ffffff0LL || M * Hd >= (1LL << 32) || ldq < Hd) return hipErrorInvalidValue;
+    if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(xq) || !attn_aligned16(records)) return hipErrorInvalidValue;
+    FixList *fix = (FixList *)records;
+    AttnRecord *rec = (AttnRecord *)((char *)records + align_up(sizeof(FixList), 256));
+    const int per_xcd = (int)((grid + 7) / 8);
+    const double scale = 1.0 / sqrt((double)dh);
+    hipError_t e = launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
+                            qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, (float)scale, ctx, rec, (int)grid, per_xcd);
+    if (e != hipSuccess) return e;
+    const int nrec = (int)grid;
+    e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)nrec), dim3(256), 0, st, qkv,
+                 (const float *)ctx, (const AttnRecord *)rec, nrec, (int)S, (int)Hd, (int)heads, dh, scale, exact_slot,
+                 &fix->count);
+    if (e != hipSuccess) return e;
+    const bool wide = (dh & 15) == 0 && (Hd & 15) == 0 && ldq == Hd;
+    const int64_t units = M * (wide ? ldq / 16 : ldq);
+    if (units >= (1LL << 32)) return hipErrorInvalidValue;
+    int64_t blocks = (units + 255) / 256;
+    blocks = blocks > 8192 ? 8192 : (blocks < 1 ? 1 : blocks);
+    if (wide)
+        e = launch_k(EGERIA_KERNEL_QUANTIZE, quantize_attention_scan_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st,
+                     (const float *)ctx, (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh,
+                     (const uint32_t *)exact_slot, xq, ldq, scale_out, flag, fix);
+    else
+        e = launch_k(EGERIA_KERNEL_QUANTIZE, quantize_attention_scan_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st,
+                     (const float *)ctx, (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh,
+                     (const uint32_t *)exact_slot, xq, ldq, scale_out, flag, fix);
+    if (e != hipSuccess) return e;
+    return launch_k(EGERIA_KERNEL_QUANTIZE, attention_fix_kernel, dim3(2048), dim3(256), 0, st, qkv, (const float *)ctx,
+                    (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh, scale, (const uint32_t *)exact_slot, xq, ldq,
+                    (const FixList *)fix, unsure_total);
 }
 
 hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads,

@@ -24,6 +24,9 @@ constexpr int kWave = 64;
 constexpr uint32_t kFlagMagic = 0xE6E71A00u;
 constexpr uint32_t kFlagNonFinite = 1u;
 constexpr int kHeaderFixedWords = 16;
+// word 4 of the header: how many attention-context values the certified quantiser re-evaluated in fp64
+// during the last reference forward (cleared by the chain's first kernel; read by benchmarks and tests)
+constexpr int kUnsureWord = 4;
 constexpr int kAbsPartials = 512;
 // An atomically combined maximum is spread over kAmaxWays words, kAmaxStride
 // words apart (workgroup id modulo the ways picks the word): thousands of
@@ -274,6 +277,16 @@ hipError_t launch_layernorm(const float *x, const float *res, int64_t rows, int3
 // optional atomicMax of |ctx|.
 hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads,
                             float *ctx, uint32_t *absmax_out, hipStream_t st);
+
+// The same attention for unobserved runs: fp32 matrix-core arithmetic, then the int8 codes [B*S, ldq] and
+// the scale of the context as the fp64 evaluation defines them (values whose code the approximate result
+// does not settle are re-evaluated in fp64).  ctx receives the approximate context (scratch), records
+// attention_records_bytes(...) bytes of scratch, exact_slot an atomically combined maximum word (zero on
+// entry), unsure_total (nullable) is incremented by the number of re-evaluated values.
+size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads);
+hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
+                                      void *records, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
+                                      uint32_t *flag, uint32_t *unsure_total, hipStream_t st);
 
 // Training plasticity.  ws_part must hold plasticity_partial_bytes(b, D).
 size_t plasticity_partial_bytes(int32_t b, int64_t D);

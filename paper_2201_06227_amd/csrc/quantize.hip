@@ -21,9 +21,13 @@ template <bool BF16>
 __device__ __forceinline__ void absmax_share(const void *__restrict__ xv, int64_t n, uint32_t *__restrict__ partials,
                                              uint32_t *__restrict__ reset, int n_reset, int blk, int nblks)
 {
-    if (blk == 0)
+    if (blk == 0) {
         for (int t = threadIdx.x; t < n_reset * kAmaxWays; t += blockDim.x)
             reset[(size_t)(t / kAmaxWays) * kAmaxWays * kAmaxStride + (t % kAmaxWays) * kAmaxStride] = 0u;
+        // `reset` is the first atomic slot, kHeaderFixedWords words into the workspace: the header's
+        // counter of re-evaluated attention values starts every chain at zero as well
+        if (n_reset > 0 && threadIdx.x == 0) reset[kUnsureWord - kHeaderFixedWords] = 0u;
+    }
     const int64_t tid = (int64_t)blk * blockDim.x + threadIdx.x;
     const int64_t nthreads = (int64_t)nblks * blockDim.x;
     uint32_t m = 0;
