@@ -506,6 +506,65 @@ def reference_precisions(cfg, device, steps):
     return out
 
 
+def attention_error(cfg, device):
+    """Error of the fp32 matrix-core attention kernel against the fp64 one, layer by layer, on the qkv
+    tensors of the workload's own reference forward, set against the bound E the certified quantiser works
+    with: E = 2^-24 * (max|v| of the head * (4 + max|score| of the workgroup) + 16 |x|).  Prints a text table."""
+    import ctypes
+    import torch
+    import synth_inputs as si
+    from paper_2201_06227_amd import binding as eg
+    wl = si.make_config(cfg)
+    d = wl.dims
+    dev = torch.device(device)
+    W = [torch.from_numpy(w).to(dev) for w in wl.weights]
+    Bs = [None if b is None else torch.from_numpy(b).to(dev) for b in wl.biases]
+    ref = eg.make_reference(wl.kind, wl.dims, W, Bs)
+    n, b, S, H, heads = d["n_layers"], d["batch"], d["seq"], d["hidden"], d["heads"]
+    dh = H // heads
+    # observed run that keeps the output of every layer's QKV GEMM
+    arr = (eg.Tap * (4 * n))()
+    qkvs = []
+    for l in range(n):
+        y = torch.empty((b, S, 3 * H), dtype=torch.float32, device=dev)
+        arr[4 * l].y = y.data_ptr()
+        qkvs.append(y)
+    taps = eg.Taps()
+    taps.n, taps.tap = 4 * n, arr
+    a_ref = torch.empty((n, b, S * H), dtype=torch.float32, device=dev)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), dev)
+    eg.ref_forward(ref, torch.from_numpy(wl.x).to(dev), a_ref, ws, taps)
+    torch.cuda.synchronize()
+    print(f"# {WORKLOAD_NAMES[cfg]}: attention_fast_kernel against attention_kernel (fp64), per layer")
+    print("# err = |fast - fp64| per context value; E = the certified quantiser's bound for that value; unit = 2^-24 * max|v| of the head")
+    print("layer  absmax(ctx)  max|v|  max|score|  median err/unit  p99.99 err/unit  max err/unit  max err/E  values with err > E  uncertain codes (fraction)")
+    qt = (S + 63) // 64
+    for l in range(n):
+        c64, _ = eg.profile_attention(qkvs[l], heads, 0)
+        c32, rec = eg.profile_attention(qkvs[l], heads, 1)
+        torch.cuda.synchronize()
+        E = rec[:, 1].contiguous().view(torch.float32).view(b, heads, qt)                  # [b, h, qtile]
+        E_el = E.permute(0, 2, 1).repeat_interleave(64, dim=1)[:, :S, :, None].expand(b, S, heads, dh).reshape(b, S, H)
+        v = qkvs[l][:, :, 2 * H:].reshape(b, S, heads, dh)
+        vmax = v.abs().amax(dim=(1, 3))                                                        # [b, h]
+        unit = (vmax * 2.0 ** -24)[:, None, :, None].expand(b, S, heads, dh).reshape(b, S, H)
+        err = (c32.double() - c64.double()).abs().float()
+        r_unit = (err / unit).flatten()
+        smax_base = E_el                                        # the record's part of the bound
+        E_el = E_el + 16.0 * 2.0 ** -24 * c32.abs()            # ... plus the part that grows with the value
+        r_E = err / E_el
+        smax = ((E / (2.0 ** -24 * vmax[:, :, None])) - 4.0).max().item()
+        del smax_base
+        absmax = c64.abs().max().item()
+        inv = 127.0 / absmax
+        lo = torch.round((c32 - E_el * 1.001) * inv)
+        hi = torch.round((c32 + E_el * 1.001) * inv)
+        k = max(1, int(r_unit.numel() * 1e-4))
+        p9999 = torch.topk(r_unit, k).values[-1].item()
+        print(f"{l:5d}  {absmax:11.4f}  {v.abs().max().item():6.3f}  {smax:10.2f}  {r_unit.median().item():15.3f}  {p9999:15.3f}  "
+              f"{r_unit.max().item():12.3f}  {r_E.max().item():9.3f}  {int((r_E > 1).sum().item()):19d}  {(lo != hi).float().mean().item():.2e}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -518,7 +577,15 @@ def main():
                     help="after the run, launch a scaled copy of known size (64 MiB int8 -> 256 MiB fp32) three times: "
                          "the reference that bench_traffic.py scales the HBM counters of a rocprofv3 --pmc run by; "
                          "the static-scale, reference-precision and activation-cache legs are skipped")
+    ap.add_argument("--attention-error", action="store_true",
+                    help="instead of the benchmark: error of the fp32 attention kernel against the fp64 one on the "
+                         "workload's own layers, against the certified quantiser's bound (text table)")
     args = ap.parse_args()
+    if args.attention_error:
+        from paper_2201_06227_amd import binding as eg
+        eg.lib()
+        attention_error(args.workload, "cuda:0")
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU leg (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)

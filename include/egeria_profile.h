@@ -38,6 +38,15 @@ egeria_status egeria_profile_begin(int32_t kernel_class, int32_t max_launches);
 egeria_status egeria_profile_pause(int32_t paused);
 egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out);
 
+/* The attention of a Transformer layer on its own, for measuring the fast kernel's error against the fp64
+ * one (bench.py --attention-error).  qkv: fp32 [B, S, 3 * hidden] (q | k | v per token), ctx: fp32
+ * [B, S, hidden] out.  mode 0: the fp64 kernel of observed runs.  mode 1: the fp32 matrix-core kernel of
+ * unobserved runs; records then receives B * heads * ceil(S / 64) pairs {uint32 bit pattern of the largest
+ * |ctx| of a workgroup's 64 queries x head dims, fp32 error bound E of those values} (DEVICE, 16-byte
+ * aligned; ignored in mode 0).  Limits as for the Transformer kinds of egeria_ref_forward. */
+egeria_status egeria_profile_attention(const float *qkv, int32_t B, int32_t S, int32_t hidden, int32_t heads,
+                                       int32_t mode, float *ctx, void *records, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

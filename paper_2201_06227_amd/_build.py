@@ -33,7 +33,7 @@ def is_stale() -> bool:
     t = os.path.getmtime(LIB)
     deps = sources() + [os.path.join(CSRC, "common.hpp"),
                         os.path.join(os.path.dirname(HERE), "include", "egeria.h"),
-                        os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h")]
+                        os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h"), os.path.join(CSRC, "gelu_table.inc")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -55,7 +55,7 @@ def build_library(force: bool = True) -> str:
     compile_flags = [f for f in FLAGS if f != "-shared"]
     jobs = []
     headers = [os.path.join(CSRC, "common.hpp"), os.path.join(os.path.dirname(HERE), "include", "egeria.h"),
-               os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h")]
+               os.path.join(os.path.dirname(HERE), "include", "egeria_profile.h"), os.path.join(CSRC, "gelu_table.inc")]
     for src in sources():
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
         fresh = os.path.exists(obj) and all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in [src] + headers)

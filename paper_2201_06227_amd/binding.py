@@ -96,7 +96,7 @@ EXPORTS = [
     "egeria_profile_end", "egeria_quantize_weights", "egeria_quantize_weights_workspace_bytes",
     "egeria_freeze_init", "egeria_freeze_observe",
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
-    "egeria_refresh_eval", "egeria_plasticity_noalloc",
+    "egeria_refresh_eval", "egeria_plasticity_noalloc", "egeria_profile_attention",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -159,6 +159,8 @@ def lib():
     L.egeria_profile_pause.argtypes = [_i32]
     L.egeria_profile_end.restype = ctypes.c_int
     L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
+    L.egeria_profile_attention.restype = ctypes.c_int
+    L.egeria_profile_attention.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
     L.egeria_freeze_init.restype = ctypes.c_int
     L.egeria_freeze_init.argtypes = [ctypes.POINTER(FreezeState), _i32, _i32, ctypes.c_double, _i32]
     L.egeria_freeze_observe.restype = ctypes.c_int
@@ -518,6 +520,18 @@ class ActivationCache:
                                       _ptr(_dev(ids)) if n else None, n, _ptr(_dev(out)) if n else None,
                                       _ptr(hit) if n else None, _stream()), "egeria_cache_get")
         return hit
+
+
+def profile_attention(qkv: torch.Tensor, heads: int, mode: int):
+    """egeria_profile_attention: (ctx [B, S, hidden], records [n, 2] int32 view or None)."""
+    qkv = _dev(qkv)
+    B, S, h3 = qkv.shape
+    hidden = h3 // 3
+    ctx = torch.empty((B, S, hidden), dtype=torch.float32, device=qkv.device)
+    rec = torch.zeros((B * heads * ((S + 63) // 64), 2), dtype=torch.int32, device=qkv.device) if mode == 1 else None
+    _check(lib().egeria_profile_attention(_ptr(qkv), B, S, hidden, heads, mode, _ptr(ctx), _ptr(rec), _stream()),
+           "egeria_profile_attention")
+    return ctx, rec
 
 
 def profile_begin(kernel_class: int, max_launches: int) -> None:

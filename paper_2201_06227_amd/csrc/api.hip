@@ -944,6 +944,18 @@ egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out
     return EGERIA_OK;
 }
 
+egeria_status egeria_profile_attention(const float *qkv, int32_t B, int32_t S, int32_t hidden, int32_t heads,
+                                       int32_t mode, float *ctx, void *records, void *stream)
+{
+    if (!qkv || !ctx || B < 1 || S < 1 || hidden < 1 || heads < 1 || hidden % heads != 0) return EGERIA_ERR_INVALID_ARG;
+    if (!aligned16(qkv) || !aligned16(ctx) || (mode != 0 && mode != 1)) return EGERIA_ERR_INVALID_ARG;
+    if (mode == 1 && (!records || !aligned16(records))) return EGERIA_ERR_INVALID_ARG;
+    if (hidden / heads > 64) return EGERIA_ERR_UNSUPPORTED;
+    if (mode == 0) EG_HIP(launch_attention(qkv, B, S, hidden, heads, ctx, nullptr, (hipStream_t)stream));
+    else EG_HIP(launch_attention_fast(qkv, B, S, hidden, heads, ctx, records, (hipStream_t)stream));
+    return EGERIA_OK;
+}
+
 const char *egeria_status_string(egeria_status s)
 {
     switch (s) {

@@ -401,12 +401,17 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 //      monotone in x, so an approximate value whose interval [x - E, x + E] maps to one code has that
 //      code; the others (a few in ten thousand) are put on a list.
 //   4. attention_fix_kernel: a wave per listed value re-evaluates it in fp64 and stores its code.
-// The bound: E = 2^-24 * max|v| of the head * (kErrBase + kErrPerScore * max|score| of the workgroup).  It is
-// an empirical bound with margin, not a proof: the measured error of kernel 1 against the fp64 kernel on
-// BERT-base-shaped inputs (64 x 12 heads x 256 x 64) has a maximum of 0.96 * 2^-24 * max|v| over 12.6 M
-// values (median 0.03, 99.99th percentile 0.5) with scores up to 2.5, where E is 6.5 of these units.
+// The bound of a value x: E = 2^-24 * (max|v| of the head * (kErrBase + kErrPerScore * max|score| of the
+// workgroup) + 16 |x|).  It is an empirical bound with margin, not a proof: bench.py --attention-error
+// measures kernel 1 against the fp64 kernel on the twelve layers of the BERT-base-shaped stack (12.6 M
+// values each) and prints the largest error / E per layer.
 typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr float kErrBase = 4.0f, kErrPerScore = 1.0f;
+// ... plus a part that grows with the value itself (the drift of the matrix cores' accumulation is
+// proportional to the sums it carries): kErrRel * 2^-24 * |x|
+constexpr float kErrRel = 16.0f * 5.9604645e-8f;
+// error bound of one approximate context value x whose workgroup's record says err
+__device__ __forceinline__ float value_err(float err, float x) { return fmaf(kErrRel, fabsf(x), err); }
 struct AttnRecord {
     uint32_t amax_bits;     // largest |approximate context| of the workgroup's 64 queries x head dims
     float err;              // E for those values
@@ -520,15 +525,23 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) st[kb][r] = 0.0f;
+        // The matrix cores' accumulation is not round-to-nearest over a chain of instructions: measured against
+        // fp64, a sum carried through n dependent MFMAs drifts by about n/4 ulp of its size, always towards
+        // zero.  Chains are therefore kept short (four instructions from a zero accumulator) and their
+        // results are added on the vector ALU, which rounds to nearest: the error of the context dropped
+        // from 14 to 4 ulp of the tensor's maximum for 4 % more time.
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const float4 kv = *(const float4 *)&sK[kb * 16 + c][16 * u + 4 * g];
                 const float k4[4] = {kv.x, kv.y, kv.z, kv.w};
+                v4f part = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    st[kb] = __builtin_amdgcn_mfma_f32_16x16x4f32(k4[e], qr[4 * u + e], st[kb], 0, 0, 0);
+                    part = __builtin_amdgcn_mfma_f32_16x16x4f32(k4[e], qr[4 * u + e], part, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) st[kb][r] += part[r];
             }
         }
         // register r of st[kb] is key j0 + 16 kb + 4 g + r for this lane's query
@@ -559,11 +572,13 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
         ps += __shfl_xor(ps, 32, kWave);
         lrun = lrun * corr + ps;
         mrun = mnew;
+        // this tile's V^T P^T from a zero accumulator (step (kb, r) contracts keys 16 kb + 4 g + r, g = 0..3),
+        // then O^T = O^T * corr + tile on the vector ALU
+        v4f ot[4];
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) o[db][r] *= corr;
-        // O^T += V^T P^T: step (kb, r) contracts keys 16 kb + 4 g + r, g = 0..3
+            for (int r = 0; r < 4; ++r) ot[db][r] = 0.0f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -571,8 +586,12 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
                 const int kr = kb * 16 + 4 * g + r;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
-                    o[db] = __builtin_amdgcn_mfma_f32_16x16x4f32(sV[kr][db * 16 + c], st[kb][r], o[db], 0, 0, 0);
+                    ot[db] = __builtin_amdgcn_mfma_f32_16x16x4f32(sV[kr][db * 16 + c], st[kb][r], ot[db], 0, 0, 0);
             }
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[db][r] = fmaf(o[db][r], corr, ot[db][r]);
         if (more) stash(stage ^ 1);
         __syncthreads();
     }
@@ -759,8 +778,10 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
         if (blockIdx.x == 0 && tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, a);
         return;
     }
-    const float floor_v = __uint_as_float(a) - e;             // values below this cannot be the maximum
-    if (!(__uint_as_float(mine.amax_bits) + mine.err >= floor_v)) return;
+    const float A = __uint_as_float(a);
+    const float floor_v = A - value_err(e, A);                // values below this cannot be the maximum
+    const float mine_max = __uint_as_float(mine.amax_bits);
+    if (!(mine_max + value_err(mine.err, mine_max) >= floor_v)) return;
     const int qtiles = (S + 63) / 64;
     const int bh = blockIdx.x / qtiles, qt = blockIdx.x % qtiles;
     const int bi = bh / heads, hd = bh % heads;
@@ -774,7 +795,8 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
         bool cand = false;
         if (idx < n_el) {
             const int qq = qt * 64 + idx / dh, d = idx % dh;
-            cand = fabsf(ctx[(tok0 + qq) * Hd + hd * dh + d]) + mine.err >= floor_v;
+            const float x = fabsf(ctx[(tok0 + qq) * Hd + hd * dh + d]);
+            cand = x + value_err(mine.err, x) >= floor_v;
         }
         for_each_marked(cand, masks, [&](int k) {
             const int cidx = base + k;
@@ -804,7 +826,7 @@ struct FixList {
 // true if the approximate value x with error bound err does not settle its code
 __device__ __forceinline__ bool code_uncertain(float x, float err, float inv)
 {
-    const float e2 = err * 1.001f + 1.0e-37f;                     // covers the rounding of x -+ err itself
+    const float e2 = value_err(err, x) * 1.001f + 1.0e-37f;       // (the factor covers the rounding of x -+ e2 itself)
     return quant1(x - e2, inv) != quant1(x + e2, inv) || !(e2 <= 3.402823466e+38f);
 }
 
@@ -921,6 +943,22 @@ static bool attn_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(
 size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads)
 {
     return align_up(sizeof(FixList), 256) + align_up((size_t)B * heads * ((S + 63) / 64) * sizeof(AttnRecord), 256);
+}
+
+// Kernel 1 alone (benchmark instrumentation: its error against the fp64 kernel): approximate context and the
+// per-workgroup records {largest |x| as a bit pattern, error bound E}, B * heads * ceil(S / 64) of them.
+hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
+                                 void *records, hipStream_t st)
+{
+    const int dh = Hd / heads;
+    const int64_t grid = (int64_t)B * heads * ((S + 63) / 64);
+    if (grid <= 0) return hipSuccess;
+    if (dh > kDh || grid > 0x7ffffff0LL) return hipErrorInvalidValue;
+    if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(records)) return hipErrorInvalidValue;
+    const int per_xcd = (int)((grid + 7) / 8);
+    return launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, qkv,
+                    (int)B, (int)S, (int)Hd, (int)heads, dh, (float)(1.0 / sqrt((double)dh)), ctx, (AttnRecord *)records,
+                    (int)grid, per_xcd);
 }
 
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,

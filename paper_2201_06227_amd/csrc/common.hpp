@@ -284,6 +284,8 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
 // attention_records_bytes(...) bytes of scratch, exact_slot an atomically combined maximum word (zero on
 // entry), unsure_total (nullable) is incremented by the number of re-evaluated values.
 size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads);
+hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
+                                 void *records, hipStream_t st);
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
                                       void *records, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
                                       uint32_t *flag, uint32_t *unsure_total, hipStream_t st);

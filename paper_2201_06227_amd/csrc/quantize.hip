@@ -666,9 +666,9 @@ hipError_t launch_quantize_weights(const WeightBatch &b, int total_blocks, bool 
 // ---- fused GELU + quantise ---------------------------------------------------------------
 // The GELU output of a Transformer layer's first feed-forward GEMM is consumed
 // only by the next quantiser, and its codes must equal those of the fp64
-// evaluation rounded to fp32.  GELU is evaluated in fp32 first; a lane falls
-// back to the fp64 form only when its value times inv lies closer to a rounding
-// boundary than the fp32 evaluation's error bound (a few elements per 100 000).
+// evaluation rounded to fp32.  GELU is evaluated in fp32 first (cubic pieces from a
+// table); a lane falls back to the fp64 form only when the error bound of that
+// evaluation leaves two candidate codes (a few elements per 100 000).
 __device__ __forceinline__ float gelu_exact(float v)
 {
     const double d = (double)v;
@@ -701,31 +701,21 @@ hipError_t launch_gelu_absmax_exact(const float *v, int64_t n, const uint32_t *v
                     exact_absmax);
 }
 
-// fp32 GELU through the rational-times-Gaussian form of the complementary error
-// function (Abramowitz & Stegun 7.1.26: erfc(x) = (a1 t + ... + a5 t^5) exp(-x^2),
-// t = 1 / (1 + p x), |error| <= 1.5e-7 for x >= 0).  For v < 0 the factor
-// 1 + erf(v / sqrt 2) = erfc(|v| / sqrt 2) is used as it comes, without
-// cancellation.  With the hardware reciprocal and exponential (1 ulp each) and
-// fp32 Horner steps the absolute error of the factor stays below 6e-7, that of
-// gelu below 1e-6 * max(1, |v|): the bound the quantiser below relies on.
-__device__ __forceinline__ float gelu_fast(float v)
+// fp32 GELU from a table of cubic pieces (gelu_table.inc: 256 pieces of width 1/16 on [-8, 8), generated
+// with the measured error of the fp32 evaluation; beyond 8 gelu(v) rounds to v, below -8 it lies within
+// 5e-15 of the table's first value).  |approximation - gelu| <= kGeluErrAbs + kGeluErrRel * |gelu|.
+#include "gelu_table.inc"
+
+__device__ __forceinline__ float gelu_table(float v, const float4 *__restrict__ tab)
 {
-    const float ax = fabsf(v) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    p = p * t;
-    const float e = __builtin_amdgcn_exp2f(ax * ax * -1.44269504088896340736f);
-    const float c = p * e;                         // erfc(|v| / sqrt 2)
-    const float w = v < 0.0f ? c : 2.0f - c;       // 1 + erf(v / sqrt 2)
-    return 0.5f * v * w;
+    const float vc = fminf(fmaxf(v, -8.0f), 7.999999f);
+    const int i = (int)fmaf(vc, 16.0f, 128.0f);                  // piece, 0..255
+    const float t = vc - fmaf((float)i, 0.0625f, -8.0f);
+    const float4 c = tab[i];
+    const float g = fmaf(fmaf(fmaf(c.w, t, c.z), t, c.y), t, c.x);
+    return v >= 8.0f ? v : g;
 }
 
-// Code of gelu(v) from the fp32 evaluation; *unsure is set when the value
-// times inv lies within the evaluation's error bound of a rounding boundary
-// (a few elements per 100 000): the caller then takes the fp64 form.
 __device__ __forceinline__ uint32_t code_of(float t)
 {
     float r = rintf(t);
@@ -733,14 +723,18 @@ __device__ __forceinline__ uint32_t code_of(float t)
     return (uint32_t)((int)r) & 0xffu;
 }
 
-__device__ __forceinline__ uint32_t quant_gelu_fast(float v, float inv, bool *unsure)
+// Code of gelu(v) from the table.  The code clamp(rne(fp32(g * inv))) is monotone in g, so when both ends of
+// the interval that the error bound leaves for g * inv round to the same integer, that integer is the code
+// of the exact value; *unsure is set otherwise (a few values per 100 000) and the caller takes the fp64 form.
+// err_abs_inv = kGeluErrAbs * inv.  (The relative part also covers the rounding of the two products.)
+__device__ __forceinline__ uint32_t quant_gelu_fast(float v, float inv, float err_abs_inv, const float4 *__restrict__ tab,
+                                                    bool *unsure)
 {
-    const float t = gelu_fast(v) * inv;
-    // |fp32 gelu - exact| <= 1e-6 * max(1, |v|); times inv, plus the product's own rounding
-    const float bound = inv * 1.0e-6f * fmaxf(1.0f, fabsf(v)) + 2.0e-5f;
-    const float frac = t - floorf(t);
-    *unsure = !(fabsf(frac - 0.5f) > bound);
-    return code_of(t);
+    const float t = gelu_table(v, tab) * inv;
+    const float e = fmaf(kGeluErrRel + 3.0e-7f, fabsf(t), err_abs_inv);
+    const float lo = rintf(t - e), hi = rintf(t + e);
+    *unsure = !(lo == hi);
+    return (uint32_t)((int)fminf(fmaxf(hi, -127.0f), 127.0f)) & 0xffu;
 }
 
 __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
@@ -758,6 +752,10 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
     float inv = (float)(127.0 / (double)absmax);
     if (!(inv <= 3.402823466e+38f) || !(scale > 0.0f)) { scale = 1.0f; inv = 0.0f; }
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(scale, bad, scale_out, nullptr, flag);
+    __shared__ float4 tab[256];                    // the table, once per workgroup (256 threads)
+    tab[threadIdx.x] = kGeluTable[threadIdx.x];
+    __syncthreads();
+    const float err_abs_inv = kGeluErrAbs * inv;
     const int64_t upr = ldq >> 4;
     const int64_t units = rows * upr;
     const bool narrow = units < (1LL << 32);
@@ -777,8 +775,9 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 bool u0, u1, u2, u3;
-                w[j] = quant_gelu_fast(x[j].x, inv, &u0) | (quant_gelu_fast(x[j].y, inv, &u1) << 8) |
-                       (quant_gelu_fast(x[j].z, inv, &u2) << 16) | (quant_gelu_fast(x[j].w, inv, &u3) << 24);
+                w[j] = quant_gelu_fast(x[j].x, inv, err_abs_inv, tab, &u0) | (quant_gelu_fast(x[j].y, inv, err_abs_inv, tab, &u1) << 8) |
+                       (quant_gelu_fast(x[j].z, inv, err_abs_inv, tab, &u2) << 16) |
+                       (quant_gelu_fast(x[j].w, inv, err_abs_inv, tab, &u3) << 24);
                 redo |= ((u0 ? 1u : 0u) | (u1 ? 2u : 0u) | (u2 ? 4u : 0u) | (u3 ? 8u : 0u)) << (4 * j);
             }
         } else {

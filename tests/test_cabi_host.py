@@ -157,3 +157,18 @@ def test_missing_library_fails_loudly(eg, monkeypatch, tmp_path):
     monkeypatch.setattr(_build, "LIB", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError):
         eg.lib()
+
+
+def test_gelu_table_is_what_its_generator_writes():
+    """The table of cubic GELU pieces compiled into the fused quantiser is the committed generator's output,
+    and its measured error against the fp64 function stays far inside the bound the kernel certifies with
+    (values outside the bound's interval would only cost a fall-back to fp64, never a wrong code, as long as
+    the bound holds - which is what the generator measures on 64 points per piece)."""
+    import importlib.util
+    path = os.path.join(ROOT, "paper_2201_06227_amd", "csrc", "gen_gelu_table.py")
+    spec = importlib.util.spec_from_file_location("gen_gelu_table", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    text, worst_abs, worst_rel = mod.table_text()
+    assert text == open(os.path.join(ROOT, "paper_2201_06227_amd", "csrc", "gelu_table.inc")).read()
+    assert worst_abs < 5e-8 and worst_rel < 2e-7
