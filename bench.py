@@ -418,11 +418,9 @@ def freeze_decision_timing(eg, with_oracle):
     out = {"evaluations": n, "library_ns_per_evaluation": round(lib_ns, 1),
            "note": "through the ctypes binding; the C call itself is a few tens of ns"}
     if with_oracle:
-        from oracle.freeze_oracle import FreezeOracle
-        o = FreezeOracle(1 << 20, 10, 0.0, True)
+        from oracle import freeze_oracle
         t0 = time.perf_counter()
-        for p in series[:4000]:
-            o.checkPlasticity(p, 0.1)
+        freeze_oracle.decide(series[:4000], [0.1] * 4000, 1 << 20, 10, 0.0, True)
         out["oracle_ns_per_evaluation"] = round((time.perf_counter() - t0) / 4000 * 1e9, 1)
     return out
 
