@@ -78,8 +78,11 @@ typedef enum { EGERIA_F32 = 0, EGERIA_BF16 = 1 } egeria_dtype;
  * precisions weights and every layer's input are rounded to nearest even to
  * that precision, products are summed in fp32 on the matrix cores, the epilogue
  * is y = act(sum + bias [+ block input as cast]) in fp32; there are no scales.
- * FC and convolution modules only (BERT kinds: EGERIA_ERR_UNSUPPORTED), no
- * static activation scales, no per-channel scales. */
+ * In a Transformer encoder layer the four linear layers (the ones the int8
+ * reference quantises, Section 5) run at that precision; attention, GELU (erf
+ * form, on the fp32 output of the first feed-forward layer) and the layer
+ * norms take and give fp32 and are evaluated in fp64.  No static activation
+ * scales, no per-channel scales. */
 typedef enum { EGERIA_REF_INT8 = 0, EGERIA_REF_F16 = 1, EGERIA_REF_F32 = 2 } egeria_ref_precision;
 
 /* Kinds of layer module the reference forward knows. */

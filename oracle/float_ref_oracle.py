@@ -17,14 +17,23 @@ i.e. weights and every layer's input live in the reference precision, sums are
 kept in (at least) float32, and the skip connection adds the block's input as
 the reference model holds it.  Convolutions use the library's float64
 convolution as the contraction step.  Module kinds: FC + ReLU, basic block,
-bottleneck (the paper's Table 2 is measured on a ResNet); the Transformer kinds
-are not covered.
+bottleneck (the paper's Table 2 is measured on a ResNet) and the Transformer
+encoder layer / stack.  In an encoder layer only the four linear layers run in
+the reference precision, exactly the four the int8 reference quantises
+(Section 5): the attention between them, the GELU and the two layer norms take
+and give float32 and are evaluated in float64, rounded once:
+
+    gelu(v) = v/2 * (1 + erf(v / sqrt 2))      on the float32 output of the
+                                               first feed-forward layer
 """
 from __future__ import annotations
 
 import numpy as np
 import torch
 import torch.nn.functional as F
+from scipy.special import erf
+
+from . import oracle as _int8_oracle       # its float32 attention and layer norm (no int8 arithmetic)
 
 PRECISIONS = ("f16", "f32")
 
@@ -61,10 +70,39 @@ def conv(x, w, bias, precision, pad, residual=None, relu=True):
     return _finish(acc, bias, residual, relu, 1), xr, acc.astype(np.float32)
 
 
+def gelu(v):
+    """erf-form GELU of float32 values, evaluated in float64 and rounded once."""
+    v64 = np.asarray(v, np.float32).astype(np.float64)
+    return (0.5 * v64 * (1.0 + erf(v64 / np.sqrt(2.0)))).astype(np.float32)
+
+
+def bert_layer(x, W, B, heads, precision, ln_eps, taps, tag):
+    """Post-LN encoder layer, inference mode: x [b, s, hidden] -> [b, s, hidden]."""
+    b, s, hd = x.shape
+
+    def lin(i, v):
+        y, xr, acc = linear(v.reshape(b * s, -1), W[i], B[i], precision, relu=False)
+        taps[f"{tag}l{i}.x"], taps[f"{tag}l{i}.acc"] = xr, acc
+        return y
+
+    qkv = lin(0, x)
+    taps[tag + "l0.y"] = qkv
+    ctx = _int8_oracle.attention(qkv.reshape(b, s, 3 * hd), heads)
+    o = lin(1, ctx)
+    taps[tag + "l1.y"] = o
+    y1 = _int8_oracle.layernorm(x, o.reshape(b, s, hd), eps=ln_eps)
+    f = gelu(lin(2, y1))
+    taps[tag + "l2.y"] = f
+    z = lin(3, f)
+    taps[tag + "l3.y"] = z
+    return _int8_oracle.layernorm(y1, z.reshape(b, s, hd), eps=ln_eps)
+
+
 def ref_forward(wl, precision):
-    """Taps of the float-precision reference forward of a synthetic workload
-    (kinds 0-2): per layer the rounded input `l<i>.x`, the float32 sum `l<i>.acc`
-    and the output `l<i>.y`; `a_ref` is the module's activation."""
+    """Taps of the float-precision reference forward of a synthetic workload:
+    per layer the rounded input `l<i>.x`, the float32 sum `l<i>.acc` and the
+    output `l<i>.y` (prefixed `L<layer>.` for the Transformer kinds); `a_ref` is
+    the module's activation (a list, one per layer, for the Transformer kinds)."""
     assert precision in PRECISIONS
     k, W, B = wl.kind, wl.weights, wl.biases
     t = {}
@@ -85,6 +123,14 @@ def ref_forward(wl, precision):
         h2 = keep(1, conv(h1, W[1], B[1], precision, 1))
         y = keep(2, conv(h2, W[2], B[2], precision, 0, res))
     else:
-        raise ValueError("float reference precisions cover the FC and convolution kinds")
+        d = wl.dims
+        n_layers = d["n_layers"] if k == 4 else 1
+        cur, outs = np.asarray(wl.x, np.float32), []
+        for l in range(n_layers):
+            cur = bert_layer(cur, W[4 * l:4 * l + 4], B[4 * l:4 * l + 4], d["heads"], precision, d["ln_eps"], t,
+                             f"L{l}.")
+            outs.append(cur)
+        t["a_ref"] = outs
+        return t
     t["a_ref"] = y
     return t

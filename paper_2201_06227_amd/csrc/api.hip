@@ -129,8 +129,7 @@ Plan make_plan(const egeria_block_desc *d)
         p.slots = 6 * p.n_layers;
         p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
         take(header_bytes(p.slots));
-        const int64_t kmax = pad16(d->hidden > d->ffn ? d->hidden : d->ffn);
-        p.off_q[0] = take((size_t)(p.M * kmax));
+        p.off_q[0] = take((size_t)(p.M * op_bytes(d, d->hidden > d->ffn ? d->hidden : d->ffn)));
         p.off_f[0] = take((size_t)(p.M * 3 * d->hidden) * 4);   // qkv
         p.off_f[1] = take((size_t)(p.M * d->hidden) * 4);       // ctx
         p.off_f[2] = take((size_t)(p.M * d->hidden) * 4);       // attention / ffn projection
@@ -458,6 +457,43 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     return EGERIA_OK;
 }
 
+// One encoder layer at float16 / float32 reference precision (Section 6.4): the four linear layers
+// take their input cast to the reference precision and give fp32; attention (fp64 evaluation), GELU
+// (erf form, fp64 evaluation) and the layer norms are the fp32 operators of the int8 path's
+// observed runs.  Observation points as in forward_float; y of the first feed-forward layer is the
+// GELU's output.
+egeria_status forward_float_bert_layer(const Fwd &f, int l, const float *cur, float *out)
+{
+    const egeria_block_desc *d = f.d;
+    const int64_t M = f.p.M;
+    const int32_t Hd = d->hidden, F = d->ffn;
+    const int et = d->ref_precision, es = et == EGERIA_REF_F16 ? 2 : 4;
+    const int32_t hb = (int32_t)op_bytes(d, Hd), fb = (int32_t)op_bytes(d, F);
+    const int s0 = 4 * l;
+    const egeria_norm *nm = f.qw->norm ? &f.qw->norm[2 * l] : nullptr;
+    float *qkv = f.fbuf(0), *ctx = f.fbuf(1), *proj = f.fbuf(2), *y1 = f.fbuf(3), *ff = f.fbuf(4);
+    float *one = f.scale(0);
+    int8_t *xq = f.qbuf(0);
+    auto linear = [&](int li, const float *src, int32_t k, int32_t kb, int32_t n, float *y, bool tap_y) -> egeria_status {
+        EG_HIP(launch_cast_chlast(src, EGERIA_F32, M, k, 1, kb / es, et, xq, one, f.st));
+        const egeria_tap *t = f.tap(li);
+        if (t && t->x_q) EG_HIP(hipMemcpyAsync(t->x_q, xq, (size_t)(M * kb), hipMemcpyDeviceToDevice, f.st));
+        return run_gemm(f, li, xq, kb, M, n, kb, false, 0, 0, 0, one, 0, nullptr, nullptr, 0, y, nullptr, false, tap_y);
+    };
+    EG_OK(linear(s0, cur, Hd, hb, 3 * Hd, qkv, true));
+    EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, nullptr, f.st));
+    EG_OK(linear(s0 + 1, ctx, Hd, hb, Hd, proj, true));
+    EG_HIP(launch_layernorm(cur, proj, M, Hd, nm ? nm[0].gamma : nullptr, nm ? nm[0].beta : nullptr, d->ln_eps, y1,
+                            nullptr, f.st));
+    EG_OK(linear(s0 + 2, y1, Hd, hb, F, ff, false));
+    EG_HIP(launch_gelu_exact(ff, M * (int64_t)F, ff, f.st));
+    EG_OK(f.copy_tap_y(s0 + 2, ff, (size_t)M * F * 4));
+    EG_OK(linear(s0 + 3, ff, F, fb, Hd, proj, true));
+    EG_HIP(launch_layernorm(y1, proj, M, Hd, nm ? nm[1].gamma : nullptr, nm ? nm[1].beta : nullptr, d->ln_eps, out,
+                            nullptr, f.st));
+    return EGERIA_OK;
+}
+
 egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights *qw, const void *x,
                            egeria_dtype x_dt, const egeria_taps *taps, void *ws, size_t ws_bytes, Plan &p)
 {
@@ -466,8 +502,7 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
     p = make_plan(desc);
     if (!p.ok) return EGERIA_ERR_INVALID_ARG;
     if (x_dt != EGERIA_F32 && x_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
-    if (desc->ref_precision != EGERIA_REF_INT8 && (desc->kind >= EGERIA_BERT_LAYER || qw->act_scale))
-        return EGERIA_ERR_UNSUPPORTED;
+    if (desc->ref_precision != EGERIA_REF_INT8 && qw->act_scale) return EGERIA_ERR_UNSUPPORTED;
     if (desc->kind >= EGERIA_BERT_LAYER) {
         if (x_dt != EGERIA_F32) return EGERIA_ERR_UNSUPPORTED;
         if (desc->hidden / desc->heads > 64) return EGERIA_ERR_UNSUPPORTED;
@@ -726,7 +761,8 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
             EG_HIP(launch_plasticity(a_train[0], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out, f.ws + p.off_part, st));
         return EGERIA_OK;
     }
-    EG_OK(f.input_absmax(x, x_dt, p.M * desc->hidden));
+    const bool float_ref = desc->ref_precision != EGERIA_REF_INT8;
+    if (!float_ref) EG_OK(f.input_absmax(x, x_dt, p.M * desc->hidden));
     const float *cur = (const float *)x;
     // The score of layer l only needs that layer's output, so it runs on a side
     // stream while the main stream goes on with layer l + 1 (the score is bound
@@ -740,7 +776,8 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     for (int l = 0; l < p.n_layers; ++l) {
         float *out = a_ref ? a_ref + (size_t)l * aref_elems : (float *)(f.ws + p.off_aref[l & 1]);
         if (side && l >= 2) EG_HIP(hipStreamWaitEvent(st, side->scored[l & 1], 0));
-        EG_OK(forward_bert_layer(f, l, cur, out, l + 1 == p.n_layers));
+        if (float_ref) EG_OK(forward_float_bert_layer(f, l, cur, out));
+        else EG_OK(forward_bert_layer(f, l, cur, out, l + 1 == p.n_layers));
         if (eval) {
             hipStream_t ms = side ? side->stream : st;
             if (side) {

@@ -812,7 +812,7 @@ hipError_t launch_quantize_gelu_rows(const float *v, int64_t rows, int64_t cols,
                     rows, cols, ldq, vmax, exact_absmax, q, scale_out, flag);
 }
 
-__global__ __launch_bounds__(256) void gelu_exact_kernel(const float *__restrict__ v, int64_t n, float *__restrict__ y)
+__global__ __launch_bounds__(256) void gelu_exact_kernel(const float *v, int64_t n, float *y)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
         y[i] = gelu_exact(v[i]);
