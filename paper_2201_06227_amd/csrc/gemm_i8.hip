@@ -5,8 +5,9 @@
 //   acc[m, n] = sum_k a[m, k] * w[n, k]          (both operands K-contiguous)
 //   y[m, n]   = act( fma((float)acc, sx*sw, bias[n]) [+ residual] )
 //
-// One workgroup of 4 waves owns a BM x BN tile of the output (256x256 down to
-// 128x32, chosen so that the grid still fills the chip).  Per K step of 64 or
+// One workgroup of 4 (or, for the two largest tiles of big linear layers, 8)
+// waves owns a BM x BN tile of the output (256x256 down to 128x32, chosen so
+// that the grid still fills the chip).  Per K step of 64 or
 // 128 bytes the tile's A and W rows go from global memory straight into a ring
 // of LDS stages (buffer loads with the LDS modifier; 16-byte units, rotated by
 // an exclusive-or of the row so that the 128-bit operand reads of a wave fall
@@ -28,7 +29,13 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // K bytes per step, BK: 128 (one 128-byte cache line of every row per request)
 // or 64.  With 64-byte steps each line is fetched half now and half one step
-// later; the stage is half as large, so more workgroups or stages fit a CU.
+// later; the stage is half as large, so more workgroups or stages fit a CU -
+// but a request for half a line costs the L2 -> LDS path as much as one for a
+// whole line (measured: 29 against 62 bytes per clock and compute unit), so the
+// 64-byte shapes are bound by that path as soon as the matrix cores are fed
+// well.  The eight-wave shapes take whole lines, two stages of them, and a
+// tile large enough that one workgroup per compute unit keeps two waves on
+// every SIMD.
 // LDS stages of a tile shape: one being read, the others being filled.
 constexpr int stages_for(int bm, int bn, int bk)
 {
@@ -116,7 +123,7 @@ constexpr int resident_target(int bm, int bn)
 }
 
 template <int BM, int BN, int WM, int WN, bool CONV, int BK, int ET>
-__global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(const GemmArgs g, int tiles,
+__global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8_kernel(const GemmArgs g, int tiles,
                                                                                int tiles_per_xcd)
 {
     typedef typename AccOf<ET>::type acc_t;
@@ -127,11 +134,12 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     constexpr int kRowsPerChunk = 64 / UPR;      // rows one load instruction of a wave covers
     constexpr int SWR = 16 / UPR;                // rows that share a rotation of the K units
     constexpr int NSUB = BK / 32;                // 32-byte sub-steps (one MFMA deep) per step
-    static_assert(WM * WN == 4, "four waves per workgroup");
+    constexpr int NW = WM * WN, NT = 64 * NW;          // waves and threads per workgroup
+    static_assert(NW == 4 || NW == 8, "four or eight waves per workgroup");
     static_assert(BM % kRowsPerChunk == 0 && BN % kRowsPerChunk == 0, "tiles are made of whole chunks");
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_CH = BM / kRowsPerChunk, B_CH = BN / kRowsPerChunk; // 1-KiB chunks per K step
-    constexpr int A_IT = (A_CH + 3) / 4, B_IT = (B_CH + 3) / 4;         // chunks per wave
+    constexpr int A_IT = (A_CH + NW - 1) / NW, B_IT = (B_CH + NW - 1) / NW;         // chunks per wave
     constexpr int STAGE = (BM + BN) * kBK;
     constexpr int NST = stages_for(BM, BN, BK);
     constexpr int NLD = A_IT + B_IT;                                    // loads per wave and K step
@@ -179,7 +187,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte *)lds;      // LDS address of the stage array
     const int rloc = lane / UPR;                                 // row within the chunk
     // K unit this lane fetches: slot ^ ((row / SWR) % UPR) with row = chunk * (64 / UPR) + rloc and
-    // chunk = wave + 4 * it; the chunk's share of that is (chunk * 4) % UPR = (wave % 2) * 4 % UPR
+    // chunk = wave + NW * it; the chunk's share of that is (chunk * 4) % UPR = (wave % 2) * 4 % UPR
     const int unit = (lane % UPR) ^ (((wave_u & 1) * 4 + rloc / SWR) % UPR);
     static_assert(A_CH % 2 == 0 && B_CH % 2 == 0, "a wave's chunks must keep their parity");
     uint32_t a_base[A_IT];               // byte offset of the row (linear) or of the centre pixel (conv)
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     int a_oh[A_IT], a_ow[A_IT];
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-        const int r = ((wave_u + it * 4) % A_CH) * kRowsPerChunk + rloc;
+        const int r = ((wave_u + it * NW) % A_CH) * kRowsPerChunk + rloc;
         const int64_t m = m0 + r;
         a_ok[it] = m < g.M;
         a_base[it] = a_ok[it] ? (uint32_t)(m * (CONV ? (int64_t)g.cp : g.lda)) : 0u;
@@ -202,7 +210,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     bool b_ok[B_IT];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
-        const int r = ((wave_u + it * 4) % B_CH) * kRowsPerChunk + rloc;
+        const int r = ((wave_u + it * NW) % B_CH) * kRowsPerChunk + rloc;
         b_ok[it] = n0 + r < g.N;
         b_base[it] = b_ok[it] ? (uint32_t)(n0 + r) * (uint32_t)g.kp : 0u;
     }
@@ -235,14 +243,14 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         const uint32_t sA = lds0 + stage * STAGE, sB = sA + BM * kBK;
         if (idx < A_IT) {
             const int it = idx;
-            const int chunk = (wave_u + it * 4) % A_CH;
+            const int chunk = (wave_u + it * NW) % A_CH;
             bool ok = a_ok[it] && sa.k_ok;
             if (CONV)
                 ok = ok && (unsigned)(a_oh[it] + sa.dh) < (unsigned)g.H && (unsigned)(a_ow[it] + sa.dw) < (unsigned)g.W;
             load_to_lds_b128(rsrc_a, sA + chunk * 1024, ok ? a_base[it] + (uint32_t)sa.delta : kOob);
         } else {
             const int it = idx - A_IT;
-            const int chunk = (wave_u + it * 4) % B_CH;
+            const int chunk = (wave_u + it * NW) % B_CH;
             load_to_lds_b128(rsrc_w, sB + chunk * 1024, (b_ok[it] && sa.k_ok) ? b_base[it] + (uint32_t)sa.k0 : kOob);
         }
     };
@@ -352,12 +360,12 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
     constexpr bool RES_LDS = ET == 0;
     static_assert(!RES_LDS || (size_t)NST * STAGE >= (size_t)BM * BN, "the residual tile must fit the stage memory");
     if (RES_LDS && g.res_q) {
-        constexpr int RU = BN / 16, RIT = (BM * RU + 255) / 256;     // 16-byte units per row, units per thread
+        constexpr int RU = BN / 16, RIT = (BM * RU + NT - 1) / NT;     // 16-byte units per row, units per thread
         v4i rv[RIT];
         __syncthreads();                                              // every wave has read its last operands
 #pragma unroll
         for (int it = 0; it < RIT; ++it) {
-            const int u = tid + it * 256, rr = u / RU, cu = u % RU;
+            const int u = tid + it * NT, rr = u / RU, cu = u % RU;
             const int64_t m = m0 + rr;
             const int64_t col = n0 + cu * 16;
             rv[it] = v4i{0, 0, 0, 0};
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         }
 #pragma unroll
         for (int it = 0; it < RIT; ++it) {
-            const int u = tid + it * 256;
+            const int u = tid + it * NT;
             if (u < BM * RU) *(v4i *)&lds[(u / RU) * BN + (u % RU) * 16] = rv[it];
         }
         __syncthreads();
@@ -460,8 +468,26 @@ __global__ __launch_bounds__(256, resident_target(BM, BN)) void gemm_i8_kernel(c
         else emit(F{}, F{}, F{}, F{}, F{});
     }
     if (g.absmax_out) {
-        __shared__ uint32_t sm4[4];
-        block_atomic_max((uint32_t)amax, g.absmax_out, sm4);
+        __shared__ uint32_t smw[NW];
+        if constexpr (NW == 4) {
+            block_atomic_max((uint32_t)amax, g.absmax_out, smw);
+        } else {
+            uint32_t v = (uint32_t)amax;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+                v = o > v ? o : v;
+            }
+            if (lane == 0) smw[wave] = v;
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t a = 0;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) a = smw[w] > a ? smw[w] : a;
+                uint32_t *way = g.absmax_out + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride;
+                if (a > __hip_atomic_load(way, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(way, a);
+            }
+        }
     }
 }
 
@@ -472,7 +498,7 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     if (tiles <= 0) return hipSuccess;
     if (tiles > 0x3fffffffLL) return hipErrorInvalidValue;
     const int tpx = (int)((tiles + 7) / 8);
-    const dim3 grid((unsigned)(tpx * 8)), block(256);
+    const dim3 grid((unsigned)(tpx * 8)), block(64 * WM * WN);
     constexpr size_t smem = (size_t)stages_for(BM, BN, BK) * (BM + BN) * BK;
     hipError_t e;
     const int dev = current_device();
@@ -864,14 +890,14 @@ hipError_t launch_conv3x3_c16_fused(const GemmArgs &g, const ConvFuse &z, hipStr
 // and the relative cost of a unit of tile area (smaller tiles move more LDS
 // and L1 bytes per MFMA).
 struct TileShape {
-    int bm, bn, bk, resident;
+    int bm, bn, bk, resident, waves;
     double penalty;
 };
-constexpr int kNumShapes = 9;
+constexpr int kNumShapes = 11;
 static const TileShape kShapes[kNumShapes] = {
-    {256, 256, 64, 1, 1.00},  {256, 192, 128, 1, 1.03}, {256, 128, 64, 2, 1.06}, {128, 192, 64, 2, 1.10},
-    {128, 128, 64, 3, 1.20},  {128, 128, 128, 2, 1.22}, {128, 64, 64, 4, 1.40},  {128, 64, 128, 3, 1.38},
-    {256, 128, 128, 1, 1.05},
+    {256, 256, 64, 1, 4, 1.00},  {256, 192, 128, 1, 4, 1.03}, {256, 128, 64, 2, 4, 1.06}, {128, 192, 64, 2, 4, 1.10},
+    {128, 128, 64, 3, 4, 1.20},  {128, 128, 128, 2, 4, 1.22}, {128, 64, 64, 4, 4, 1.40},  {128, 64, 128, 3, 4, 1.38},
+    {256, 128, 128, 1, 4, 1.05}, {256, 256, 128, 1, 8, 1.00}, {256, 192, 128, 1, 8, 1.02},
 };
 
 static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
@@ -886,6 +912,8 @@ static hipError_t launch_shape(int i, const GemmArgs &g, hipStream_t st)
     case 6: return launch_variant<128, 64, 2, 2, 64>(g, st);
     case 7: return launch_variant<128, 64, 2, 2, 128>(g, st);
     case 8: return launch_variant<256, 128, 2, 2, 128>(g, st);
+    case 9: return launch_variant<256, 256, 2, 4, 128>(g, st);
+    case 10: return launch_variant<256, 192, 4, 2, 128>(g, st);
     default: return hipErrorInvalidValue;
     }
 }
@@ -926,9 +954,17 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     double best_cost = 0.0;
     for (int i = 0; i < kNumShapes; ++i) {
         const TileShape &sh = kShapes[i];
-        if (sh.resident == 1 && g.kp < 2048) continue;
-        if (sh.bm * sh.bn > 128 * 128 && g.kp < 512) continue;     // store bound: many small workgroups in flight
         const int64_t tiles = ((g.M + sh.bm - 1) / sh.bm) * (int64_t)((g.N + sh.bn - 1) / sh.bn);
+        if (sh.waves == 8) {
+            // eight waves on one large tile with whole-line K steps: linear layers with a long K that fill every
+            // compute unit.  (With K = 768 they win by 5-10 % when timed alone, where the fp32 output stays in the
+            // last-level cache, and lose as much inside an encoder layer, where it goes to HBM and the shapes
+            // with two workgroups per compute unit hide more of the store behind the other workgroup's K loop.)
+            if (g.conv3x3 || g.kp < 2048 || tiles < compute_units()) continue;
+        } else if (sh.resident == 1 && g.kp < 2048) {
+            continue;
+        }
+        if (sh.bm * sh.bn > 128 * 128 && g.kp < 512) continue;     // store bound: many small workgroups in flight
         const int64_t slots = compute_units() * (int64_t)sh.resident;
         const int64_t rounds = (tiles + slots - 1) / slots;
         double cost = (double)rounds * sh.resident * sh.bm * sh.bn * sh.penalty;
