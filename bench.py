@@ -474,25 +474,27 @@ def activation_cache_timing(eg, device, with_oracle):
 
 def reference_precisions(cfg, device, steps):
     """The workload's evaluation with the reference model at float16 and float32 (Section 6.4,
-    Table 2 of the paper compares the three precisions): reference forward + score per call; the
-    cast of the snapshot (done once per reference refresh) is outside the loop."""
+    Table 2 of the paper compares the three precisions) and with affine uint8 activation codes
+    (Section 5: the framework's default activation code): reference forward + score per call; the
+    cast or quantisation of the snapshot (done once per reference refresh) is outside the loop."""
     import torch
     import synth_inputs as si
     from paper_2201_06227_amd import binding as eg
     wl = si.make_config(cfg)
-    if wl.kind not in (si.KIND_FC_RELU, si.KIND_BASIC_BLOCK, si.KIND_BOTTLENECK):
-        return None
     dev = torch.device(device)
     W = [torch.from_numpy(w).to(dev) for w in wl.weights]
     B = [None if b is None else torch.from_numpy(b).to(dev) for b in wl.biases]
     x = torch.from_numpy(wl.x).to(dev)
     a_t = [t.contiguous() for t in si.train_forward(wl, device=device)]
     out = {}
-    for name, prec in (("float16", eg.REF_F16), ("float32", eg.REF_F32)):
-        ref = eg.make_float_reference(wl.kind, wl.dims, W, B, prec)
+    for name, prec in (("float16", eg.REF_F16), ("float32", eg.REF_F32), ("int8_affine_activations", None)):
+        if prec is None:
+            ref = eg.make_reference(wl.kind, wl.dims, W, B, act_scheme=eg.ACT_AFFINE)
+        else:
+            ref = eg.make_float_reference(wl.kind, wl.dims, W, B, prec)
         ws = eg.workspace(eg.workspace_bytes(ref.desc), device)
-        p = torch.zeros(1, dtype=torch.float32, device=device)
-        for _ in range(5):
+        p = torch.zeros(len(a_t), dtype=torch.float32, device=device)
+        for _ in range(2):
             eg.plasticity_eval(ref, x, a_t, p, ws)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -500,7 +502,8 @@ def reference_precisions(cfg, device, steps):
             eg.plasticity_eval(ref, x, a_t, p, ws)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
-        out[name] = {"evals_per_s": round(1.0 / dt, 2), "ms_per_step": round(dt * 1e3, 4), "plasticity": float(p.item())}
+        out[name] = {"evals_per_s": round(len(a_t) / dt, 2), "ms_per_step": round(dt * 1e3, 4),
+                     "plasticity": [float(v) for v in p.cpu()]}
     return out
 
 
@@ -726,7 +729,8 @@ def main():
         # measured on cfg 2 when the headline workload is a Transformer one
         side_cfg = args.workload if args.workload <= 3 else 2
         result["static_scale_mode"] = dict(static_mode(side_cfg, device, 100) or {}, workload=WORKLOAD_NAMES[side_cfg])
-        result["reference_precisions"] = dict(reference_precisions(side_cfg, device, 100) or {}, workload=WORKLOAD_NAMES[side_cfg])
+        result["reference_precisions"] = dict(reference_precisions(args.workload, device, 100 if args.workload <= 3 else 5),
+                                              workload=WORKLOAD_NAMES[args.workload])
         result["activation_cache"] = activation_cache_timing(eg, device, not args.no_cpu)
     result["freeze_decision"] = freeze_decision_timing(eg, not args.no_cpu)
     if not args.no_cpu:

@@ -85,6 +85,26 @@ typedef enum { EGERIA_F32 = 0, EGERIA_BF16 = 1 } egeria_dtype;
  * scales, no per-channel scales. */
 typedef enum { EGERIA_REF_INT8 = 0, EGERIA_REF_F16 = 1, EGERIA_REF_F32 = 2 } egeria_ref_precision;
 
+/* Code of the activations of the int8 reference model.  Symmetric: codes in
+ * [-127, 127], zero point 0, scale = absmax / 127 (the default, and what every
+ * description above and below assumes).  Affine: the framework's default
+ * activation code (Section 5 delegates the int8 arithmetic to the framework's
+ * quantisation): uint8 codes with a zero point, from the extrema of the tensor,
+ * every operation an IEEE fp32 one:
+ *   hi = max(max x, 0), lo = min(min x, 0)
+ *   scale = max((hi - lo) / 255, 2^-23);  zp = clamp(0 - rne(lo / scale), 0, 255)
+ *   q = clamp(rne(x * (1 / scale)) + zp, 0, 255);  the value of a code is (q - zp) * scale.
+ * Weights stay symmetric int8.  A layer multiplies the centred codes,
+ * acc = sum_k (q_k - zp) * w_k (int32, exact; a padded 3x3 window pads the real
+ * value zero, i.e. the centred code 0), and the epilogue is the symmetric one
+ * with this acc and this scale.  In memory and at the observation points a
+ * code is stored as the int8 value q - 128.  Affine codes need
+ * egeria_qlinear.colsum; they exclude static activation scales and the float
+ * reference precisions, and every quantise point costs two launches of its own
+ * (no fused quantisers; the Transformer kinds take the fp64 attention of the
+ * observed runs). */
+typedef enum { EGERIA_ACT_SYMMETRIC = 0, EGERIA_ACT_AFFINE = 1 } egeria_act_scheme;
+
 /* Kinds of layer module the reference forward knows. */
 typedef enum {
     EGERIA_FC_RELU = 0,      /* y = ReLU(x W^T + bias)                                   */
@@ -111,6 +131,7 @@ typedef struct {
     int32_t n_layers;
     float ln_eps;
     int32_t ref_precision;          /* egeria_ref_precision; 0 = int8 */
+    int32_t act_scheme;             /* egeria_act_scheme; 0 = symmetric */
 } egeria_block_desc;
 
 /* HOST struct.  One quantised linear / convolution layer of the reference model.
@@ -125,6 +146,8 @@ typedef struct {
     const float *scale;             /* 1 fp32, or fp32 [out] when per_channel */
     const float *bias;
     int32_t per_channel;            /* 0: one scale for the tensor; 1: one per output channel */
+    const int32_t *colsum;          /* affine activation codes only: what egeria_quantize_weights writes to
+                                       egeria_weight.colsum for this tensor; else unused, may be NULL */
 } egeria_qlinear;
 
 /* HOST struct.  Affine parameters of one layer norm (each fp32 [hidden] or NULL
@@ -161,12 +184,14 @@ typedef struct {
  * output after the epilogue [M, out].  Any pointer may be NULL.  At a float
  * reference precision x_q receives the cast operand rows (float16 / float32,
  * each row padded to 16 bytes), acc the bit patterns of the fp32 sums, x_scale
- * is not written. */
+ * is not written.  With affine activation codes x_q receives q - 128, x_zp
+ * (1 int32, else not written) the zero point, acc the sums of the centred codes. */
 typedef struct {
     int8_t *x_q;
     float *x_scale;
     int32_t *acc;
     float *y;
+    int32_t *x_zp;
 } egeria_tap;
 
 typedef struct {
@@ -214,6 +239,12 @@ typedef struct {
     int32_t precision;              /* egeria_ref_precision.  Float precisions: w_q receives float16 / float32
                                        values [out, kh, kw, cp], cp = `in` padded with zeros to a whole number of
                                        16-byte units (8 / 4 values); scale is not written and may be NULL */
+    int32_t *colsum;                /* out, or NULL: sums of the int8 codes the affine activation codes need
+                                       (egeria_act_scheme), int32 [classes, out]: for kh = kw = 1 one class, the
+                                       sum over `in`; for a 3x3 kernel 16 classes, class c the sum over `in` and over
+                                       the window positions that lie inside the image for an output pixel with
+                                       (c & 1) first row, (c & 2) last row, (c & 4) first column, (c & 8) last column.
+                                       int8 precision only */
 } egeria_weight;
 
 /* Section 4.1, reference-model generation: quantises all n weight tensors of
@@ -236,6 +267,15 @@ egeria_status egeria_dequantize(const int8_t *q, const float *scale, int64_t n, 
                                 void *stream);
 
 size_t egeria_quantize_workspace_bytes(void);
+
+/* Affine uint8 codes of n contiguous values (egeria_act_scheme): q uint8
+ * [egeria_padded(n)] (the bytes past n are written as zero), scale_out 1 fp32,
+ * zp_out 1 int32.  ws at least
+ * egeria_quantize_affine_workspace_bytes() bytes; n == 0 is valid (scale 2^-23,
+ * zero point 0). */
+egeria_status egeria_quantize_affine(const void *x, egeria_dtype dt, int64_t n, uint8_t *q, float *scale_out,
+                                     int32_t *zp_out, void *ws, size_t ws_bytes, void *stream);
+size_t egeria_quantize_affine_workspace_bytes(void);
 
 /* Section 4.1 / 4.2: forward of the int8 reference model of one layer module on
  * the mini-batch x, producing the hooked activation A_R.

@@ -18,6 +18,7 @@ from . import _build
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_NONFINITE, ERR_HIP = range(6)
 F32, BF16 = 0, 1
 REF_INT8, REF_F16, REF_F32 = 0, 1, 2
+ACT_SYMMETRIC, ACT_AFFINE = 0, 1
 FC_RELU, BASIC_BLOCK, BOTTLENECK, BERT_LAYER, BERT_STACK = range(5)
 
 _vp = ctypes.c_void_p
@@ -30,11 +31,11 @@ class BlockDesc(ctypes.Structure):
     _fields_ = [("kind", _i32), ("batch", _i32), ("c_in", _i32), ("c_mid", _i32), ("c_out", _i32),
                 ("height", _i32), ("width", _i32), ("has_residual", _i32), ("seq", _i32),
                 ("hidden", _i32), ("heads", _i32), ("ffn", _i32), ("n_layers", _i32),
-                ("ln_eps", ctypes.c_float), ("ref_precision", _i32)]
+                ("ln_eps", ctypes.c_float), ("ref_precision", _i32), ("act_scheme", _i32)]
 
 
 class QLinear(ctypes.Structure):
-    _fields_ = [("w_q", _vp), ("scale", _vp), ("bias", _vp), ("per_channel", _i32)]
+    _fields_ = [("w_q", _vp), ("scale", _vp), ("bias", _vp), ("per_channel", _i32), ("colsum", _vp)]
 
 
 class Norm(ctypes.Structure):
@@ -47,7 +48,7 @@ class QWeights(ctypes.Structure):
 
 
 class Tap(ctypes.Structure):
-    _fields_ = [("x_q", _vp), ("x_scale", _vp), ("acc", _vp), ("y", _vp)]
+    _fields_ = [("x_q", _vp), ("x_scale", _vp), ("acc", _vp), ("y", _vp), ("x_zp", _vp)]
 
 
 class Taps(ctypes.Structure):
@@ -56,7 +57,7 @@ class Taps(ctypes.Structure):
 
 class Weight(ctypes.Structure):
     _fields_ = [("w", _vp), ("dtype", _i32), ("out", _i32), ("in_", _i32), ("kh", _i32), ("kw", _i32),
-                ("w_q", _vp), ("scale", _vp), ("per_channel", _i32), ("precision", _i32)]
+                ("w_q", _vp), ("scale", _vp), ("per_channel", _i32), ("precision", _i32), ("colsum", _vp)]
 
 
 FREEZE_MAX_W = 256
@@ -97,6 +98,7 @@ EXPORTS = [
     "egeria_freeze_init", "egeria_freeze_observe",
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
     "egeria_refresh_eval", "egeria_plasticity_noalloc", "egeria_profile_attention",
+    "egeria_quantize_affine", "egeria_quantize_affine_workspace_bytes",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -133,6 +135,10 @@ def lib():
     L.egeria_dequantize.argtypes = [_vp, _vp, _i64, _vp, _vp]
     L.egeria_quantize_workspace_bytes.restype = _sz
     L.egeria_quantize_workspace_bytes.argtypes = []
+    L.egeria_quantize_affine.restype = ctypes.c_int
+    L.egeria_quantize_affine.argtypes = [_vp, ctypes.c_int, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.egeria_quantize_affine_workspace_bytes.restype = _sz
+    L.egeria_quantize_affine_workspace_bytes.argtypes = []
     L.egeria_ref_forward.restype = ctypes.c_int
     L.egeria_ref_forward.argtypes = [ctypes.POINTER(BlockDesc), ctypes.POINTER(QWeights), _vp, ctypes.c_int,
                                      _vp, ctypes.POINTER(Taps), _vp, _sz, _vp]
@@ -265,11 +271,30 @@ def quantize_nchw(x: torch.Tensor, fixed_scale: Optional[torch.Tensor] = None, w
     return q, scale
 
 
+def quantize_affine(x: torch.Tensor):
+    """egeria_quantize_affine: uint8 codes (same shape as x), 1-element fp32 scale, 1-element int32 zero point."""
+    x = _dev(x)
+    n = x.numel()
+    q = torch.empty(padded(n), dtype=torch.uint8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    zp = torch.empty(1, dtype=torch.int32, device=x.device)
+    ws = workspace(int(lib().egeria_quantize_affine_workspace_bytes()), x.device)
+    rc = lib().egeria_quantize_affine(_ptr(x), _dt(x), n, _ptr(q), _ptr(scale), _ptr(zp), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "egeria_quantize_affine")
+    return q[:n].reshape(x.shape), scale, zp
+
+
+def colsum_like(w: torch.Tensor) -> torch.Tensor:
+    """Buffer for egeria_weight.colsum of a weight tensor: int32 [classes, out]."""
+    return torch.empty((16 if w.dim() == 4 and w.shape[2] == 3 else 1, w.shape[0]), dtype=torch.int32, device=w.device)
+
+
 def weight_table(weights: Sequence[torch.Tensor], w_q: Sequence[torch.Tensor], scales: Sequence[torch.Tensor],
-                 per_channel: bool = False):
+                 per_channel: bool = False, colsums: Optional[Sequence[torch.Tensor]] = None):
     """HOST array of egeria_weight descriptors for egeria_quantize_weights."""
     tab = (Weight * len(weights))()
-    for t, w, q, s in zip(tab, weights, w_q, scales):
+    for i, (t, w, q, s) in enumerate(zip(tab, weights, w_q, scales)):
+        t.colsum = None if colsums is None else colsums[i].data_ptr()
         t.per_channel = 1 if per_channel else 0
         _dev(w)
         if w.dim() == 4:
@@ -285,10 +310,12 @@ def quantize_weights_workspace_bytes(n: int) -> int:
     return int(lib().egeria_quantize_weights_workspace_bytes(int(n)))
 
 
-def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor] = None, per_channel: bool = False):
+def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor] = None, per_channel: bool = False,
+                     colsums: Optional[Sequence[torch.Tensor]] = None):
     """egeria_quantize_weights: every tensor of a snapshot in one call.  Returns
     the int8 tensors ([out, padded(in)] or [out, kh, kw, padded(in)]) and scales
-    (1 value per tensor, or [out] values with per_channel)."""
+    (1 value per tensor, or [out] values with per_channel); colsums (see colsum_like)
+    receive the sums of the codes that affine activation codes need."""
     dev = weights[0].device if weights else "cuda"
     w_q, scales = [], []
     for w in weights:
@@ -297,7 +324,7 @@ def quantize_weights(weights: Sequence[torch.Tensor], ws: Optional[torch.Tensor]
         w_q.append(torch.empty(shape, dtype=torch.int8, device=dev))
         scales.append(torch.empty(w.shape[0] if per_channel else 1, dtype=torch.float32, device=dev))
     ws = workspace(quantize_weights_workspace_bytes(len(weights)), dev) if ws is None else ws
-    tab = weight_table(weights, w_q, scales, per_channel)
+    tab = weight_table(weights, w_q, scales, per_channel, colsums)
     rc = lib().egeria_quantize_weights(tab, len(weights), _ptr(ws), ws.numel(), _stream())
     _check(rc, "egeria_quantize_weights")
     return w_q, scales
@@ -321,6 +348,7 @@ def make_desc(kind: int, dims: dict) -> BlockDesc:
     d.n_layers = int(dims.get("n_layers", 1))
     d.ln_eps = float(dims.get("ln_eps", 0.0))
     d.ref_precision = int(dims.get("ref_precision", REF_INT8))
+    d.act_scheme = int(dims.get("act_scheme", ACT_SYMMETRIC))
     return d
 
 
@@ -338,13 +366,16 @@ class ReferenceModel:
 
 def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
                    biases: Sequence[Optional[torch.Tensor]],
-                   act_scales: Optional[torch.Tensor] = None, per_channel: bool = False) -> ReferenceModel:
+                   act_scales: Optional[torch.Tensor] = None, per_channel: bool = False,
+                   act_scheme: int = ACT_SYMMETRIC) -> ReferenceModel:
     """Reference-model generation: quantise every weight tensor of the snapshot
     with the library (egeria_quantize_rows for [out, in], egeria_quantize_nchw for
-    [out, in, kh, kw]) and marshal the result."""
+    [out, in, kh, kw]) and marshal the result.  act_scheme = ACT_AFFINE: affine uint8
+    activation codes (the weight-code sums they need are made along with the codes)."""
     w_q, scales = [], []
-    if per_channel:
-        w_q, scales = quantize_weights(list(weights), per_channel=True)
+    colsums = [colsum_like(w) for w in weights] if act_scheme == ACT_AFFINE else None
+    if per_channel or colsums is not None:
+        w_q, scales = quantize_weights(list(weights), per_channel=per_channel, colsums=colsums)
     else:
         ws = workspace(quantize_workspace_bytes(), weights[0].device)
         for w in weights:
@@ -357,13 +388,15 @@ def make_reference(kind: int, dims: dict, weights: Sequence[torch.Tensor],
         arr[i].w_q = w_q[i].data_ptr()
         arr[i].scale = scales[i].data_ptr()
         arr[i].bias = 0 if biases[i] is None else biases[i].data_ptr()
+        arr[i].colsum = None if colsums is None else colsums[i].data_ptr()
     qw = QWeights()
     qw.n_linear = len(weights)
     qw.linear = arr
     qw.n_norm = 0
     qw.norm = None
     qw.act_scale = None if act_scales is None else _dev(act_scales).data_ptr()   # fp32 [n_linear], static scales
-    return ReferenceModel(make_desc(kind, dims), qw, w_q, scales, list(biases), (arr, act_scales))
+    return ReferenceModel(make_desc(kind, dict(dims, act_scheme=act_scheme)), qw, w_q, scales, list(biases),
+                          (arr, act_scales, colsums))
 
 
 def op_row_bytes(c: int, precision: int) -> int:
@@ -412,8 +445,10 @@ def make_taps(ref: ReferenceModel, shapes: Sequence[dict], device="cuda"):
         sc = torch.zeros(1, dtype=torch.float32, device=device)
         acc = torch.zeros((s["M"], s["N"]), dtype=torch.int32, device=device)
         y = torch.zeros((s["M"], s["N"]), dtype=torch.float32, device=device)
+        zp = torch.zeros(1, dtype=torch.int32, device=device)
         arr[i].x_q, arr[i].x_scale, arr[i].acc, arr[i].y = xq.data_ptr(), sc.data_ptr(), acc.data_ptr(), y.data_ptr()
-        bufs.append(dict(x_q=xq, x_scale=sc, acc=acc, y=y))
+        arr[i].x_zp = zp.data_ptr()
+        bufs.append(dict(x_q=xq, x_scale=sc, acc=acc, y=y, x_zp=zp))
     taps = Taps()
     taps.n = len(shapes)
     taps.tap = arr

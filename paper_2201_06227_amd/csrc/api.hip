@@ -58,6 +58,7 @@ struct Plan {
     size_t off_q[3] = {0, 0, 0};      // int8 activation buffers
     size_t off_f[5] = {0, 0, 0, 0, 0};  // fp32 intermediates
     size_t off_rec = 0;               // per-workgroup records of the fast attention kernel (Transformer kinds)
+    size_t off_aff = 0;               // affine activation codes: partial extrema, then one zero point per quantise point
     size_t off_aref[2] = {0, 0};      // A_R ping-pong (egeria_plasticity_eval)
     size_t off_part = 0;              // metric partials
     size_t fwd_bytes = 0;             // header + forward buffers
@@ -74,6 +75,7 @@ bool valid_desc(const egeria_block_desc *d)
 {
     if (!d || d->batch < 1) return false;
     if (d->ref_precision < EGERIA_REF_INT8 || d->ref_precision > EGERIA_REF_F32) return false;
+    if (d->act_scheme != EGERIA_ACT_SYMMETRIC && d->act_scheme != EGERIA_ACT_AFFINE) return false;
     switch (d->kind) {
     case EGERIA_FC_RELU:
         return d->c_in >= 1 && d->c_out >= 1;
@@ -139,6 +141,7 @@ Plan make_plan(const egeria_block_desc *d)
         break;
     }
     }
+    if (d->act_scheme == EGERIA_ACT_AFFINE) p.off_aff = take(affine_partial_bytes() + 4 * (size_t)p.slots);
     p.fwd_bytes = off;
     const size_t aref = (size_t)b * (size_t)p.D * 4;
     p.off_aref[0] = take(aref);
@@ -187,6 +190,23 @@ struct Fwd {
         return EGERIA_OK;
     }
 
+    // affine activation codes: scratch of the extrema pass, zero point of quantise point i
+    uint32_t *aff_partials() const { return (uint32_t *)(ws + p.off_aff); }
+    int32_t *zp(int i) const { return (int32_t *)(ws + p.off_aff + affine_partial_bytes()) + i; }
+    // quantise point `slot`: [n, c, hw] channel planes (hw = 1: matrix rows) -> stored codes in qbuf(qi)
+    egeria_status quantize_affine(const void *src, egeria_dtype dt, int64_t n, int64_t c, int64_t hw, int qi, int slot) const
+    {
+        const int64_t total = n * c * hw;
+        EG_HIP(launch_minmax(src, dt, total, aff_partials(), st));
+        EG_HIP(launch_quantize_affine(src, dt, n, c, hw, pad16(c), aff_partials(), minmax_blocks(total), 128, qbuf(qi),
+                                      scale(slot), zp(slot), ws_flag(ws), st));
+        const egeria_tap *t = tap(slot);
+        if (t && t->x_q) EG_HIP(hipMemcpyAsync(t->x_q, qbuf(qi), (size_t)(n * hw * pad16(c)), hipMemcpyDeviceToDevice, st));
+        if (t && t->x_scale) EG_HIP(hipMemcpyAsync(t->x_scale, scale(slot), 4, hipMemcpyDeviceToDevice, st));
+        if (t && t->x_zp) EG_HIP(hipMemcpyAsync(t->x_zp, zp(slot), 4, hipMemcpyDeviceToDevice, st));
+        return EGERIA_OK;
+    }
+
     egeria_status copy_tap_q(int i, const int8_t *src, size_t bytes, const float *sc) const
     {
         const egeria_tap *t = tap(i);
@@ -214,7 +234,8 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
                        bool conv, int32_t H, int32_t W, int32_t cp, const float *sx, int act,
                        const int8_t *res_q, const float *res_scale, int64_t res_ld, float *y,
                        uint32_t *absmax_out, bool amax_pos = false, bool tap_y = true, int8_t *q_out = nullptr,
-                       int64_t q_ld = 0, const float *q_scale = nullptr)
+                       int64_t q_ld = 0, const float *q_scale = nullptr, const int32_t *zp_in = nullptr,
+                       const int32_t *zp_res = nullptr)
 {
     const egeria_qlinear &L = f.qw->linear[li];
     GemmArgs g{};
@@ -233,6 +254,7 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     g.absmax_out = absmax_out;
     g.amax_pos = amax_pos ? 1 : 0;
     g.q_out = q_out; g.q_ld = q_ld; g.q_scale = q_scale;
+    g.zp_in = zp_in; g.colsum = L.colsum; g.zp_res = zp_res;
     EG_HIP(launch_gemm_i8(g, f.st));
     return (tap_y && y) ? f.copy_tap_y(li, y, (size_t)M * N * 4) : EGERIA_OK;
 }
@@ -457,6 +479,69 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     return EGERIA_OK;
 }
 
+// The FC and convolution modules with affine uint8 activation codes (Section 5: the framework's
+// default activation code).  Every quantise point is an extrema pass and a code pass of its own; the
+// contraction and the epilogue are the symmetric path's, with the zero points handed to the epilogue.
+egeria_status forward_affine(Fwd &f, const void *x, egeria_dtype dt, float *a_ref)
+{
+    const egeria_block_desc *d = f.d;
+    auto gemm = [&](int li, int qi, int64_t lda, int64_t M, int32_t N, int32_t kp, bool conv, int32_t cp, int slot,
+                    const int8_t *res, int64_t res_ld, float *y) {
+        return run_gemm(f, li, f.qbuf(qi), lda, M, N, kp, conv, d->height, d->width, cp, f.scale(slot), 1, res,
+                        res ? f.scale(0) : nullptr, res_ld, y, nullptr, false, true, nullptr, 0, nullptr, f.zp(slot),
+                        res ? f.zp(0) : nullptr);
+    };
+    if (d->kind == EGERIA_FC_RELU) {
+        const int32_t kp = (int32_t)pad16(d->c_in);
+        EG_OK(f.quantize_affine(x, dt, d->batch, d->c_in, 1, 0, 0));
+        return gemm(0, 0, kp, d->batch, d->c_out, kp, false, 0, 0, nullptr, 0, a_ref);
+    }
+    const int64_t M = f.p.M, hw = (int64_t)d->height * d->width;
+    const int32_t cin_p = (int32_t)pad16(d->c_in), cmid_p = (int32_t)pad16(d->c_mid);
+    EG_OK(f.quantize_affine(x, dt, d->batch, d->c_in, hw, 0, 0));
+    const int8_t *res = d->has_residual ? f.qbuf(0) : nullptr;
+    if (d->kind == EGERIA_BASIC_BLOCK) {
+        EG_OK(gemm(0, 0, 0, M, d->c_mid, 9 * cin_p, true, cin_p, 0, nullptr, 0, f.fbuf(0)));
+        EG_OK(f.quantize_affine(f.fbuf(0), EGERIA_F32, M, d->c_mid, 1, 1, 1));
+        return gemm(1, 1, 0, M, d->c_out, 9 * cmid_p, true, cmid_p, 1, res, cin_p, a_ref);
+    }
+    EG_OK(gemm(0, 0, cin_p, M, d->c_mid, cin_p, false, 0, 0, nullptr, 0, f.fbuf(0)));
+    EG_OK(f.quantize_affine(f.fbuf(0), EGERIA_F32, M, d->c_mid, 1, 1, 1));
+    EG_OK(gemm(1, 1, 0, M, d->c_mid, 9 * cmid_p, true, cmid_p, 1, nullptr, 0, f.fbuf(1)));
+    EG_OK(f.quantize_affine(f.fbuf(1), EGERIA_F32, M, d->c_mid, 1, 2, 2));
+    return gemm(2, 2, cmid_p, M, d->c_out, cmid_p, false, 0, 2, res, cin_p, a_ref);
+}
+
+// One encoder layer with affine uint8 activation codes: the four linear layers as above, attention in its
+// fp64 evaluation, GELU (erf form, fp64 evaluation) on the fp32 output of the first feed-forward layer.
+egeria_status forward_affine_bert_layer(const Fwd &f, int l, const float *cur, float *out)
+{
+    const egeria_block_desc *d = f.d;
+    const int64_t M = f.p.M;
+    const int32_t Hd = d->hidden, F = d->ffn;
+    const int32_t hp = (int32_t)pad16(Hd), fp = (int32_t)pad16(F);
+    const int s0 = 4 * l;
+    const egeria_norm *nm = f.qw->norm ? &f.qw->norm[2 * l] : nullptr;
+    float *qkv = f.fbuf(0), *ctx = f.fbuf(1), *proj = f.fbuf(2), *y1 = f.fbuf(3), *ff = f.fbuf(4);
+    auto linear = [&](int li, const float *src, int32_t k, int32_t kp, int32_t n, float *y, bool tap_y) -> egeria_status {
+        EG_OK(f.quantize_affine(src, EGERIA_F32, M, k, 1, 0, li));
+        return run_gemm(f, li, f.qbuf(0), kp, M, n, kp, false, 0, 0, 0, f.scale(li), 0, nullptr, nullptr, 0, y, nullptr, false,
+                        tap_y, nullptr, 0, nullptr, f.zp(li), nullptr);
+    };
+    EG_OK(linear(s0, cur, Hd, hp, 3 * Hd, qkv, true));
+    EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, nullptr, f.st));
+    EG_OK(linear(s0 + 1, ctx, Hd, hp, Hd, proj, true));
+    EG_HIP(launch_layernorm(cur, proj, M, Hd, nm ? nm[0].gamma : nullptr, nm ? nm[0].beta : nullptr, d->ln_eps, y1,
+                            nullptr, f.st));
+    EG_OK(linear(s0 + 2, y1, Hd, hp, F, ff, false));
+    EG_HIP(launch_gelu_exact(ff, M * (int64_t)F, ff, f.st));
+    EG_OK(f.copy_tap_y(s0 + 2, ff, (size_t)M * F * 4));
+    EG_OK(linear(s0 + 3, ff, F, fp, Hd, proj, true));
+    EG_HIP(launch_layernorm(y1, proj, M, Hd, nm ? nm[1].gamma : nullptr, nm ? nm[1].beta : nullptr, d->ln_eps, out,
+                            nullptr, f.st));
+    return EGERIA_OK;
+}
+
 // One encoder layer at float16 / float32 reference precision (Section 6.4): the four linear layers
 // take their input cast to the reference precision and give fp32; attention (fp64 evaluation), GELU
 // (erf form, fp64 evaluation) and the layer norms are the fp32 operators of the int8 path's
@@ -503,6 +588,8 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
     if (!p.ok) return EGERIA_ERR_INVALID_ARG;
     if (x_dt != EGERIA_F32 && x_dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
     if (desc->ref_precision != EGERIA_REF_INT8 && qw->act_scale) return EGERIA_ERR_UNSUPPORTED;
+    if (desc->act_scheme == EGERIA_ACT_AFFINE && (qw->act_scale || desc->ref_precision != EGERIA_REF_INT8))
+        return EGERIA_ERR_UNSUPPORTED;
     if (desc->kind >= EGERIA_BERT_LAYER) {
         if (x_dt != EGERIA_F32) return EGERIA_ERR_UNSUPPORTED;
         if (desc->hidden / desc->heads > 64) return EGERIA_ERR_UNSUPPORTED;
@@ -516,6 +603,8 @@ egeria_status check_common(const egeria_block_desc *desc, const egeria_qweights 
         if (!L.w_q || !aligned16(L.w_q)) return EGERIA_ERR_INVALID_ARG;
         if (desc->ref_precision == EGERIA_REF_INT8 && !L.scale) return EGERIA_ERR_INVALID_ARG;
         if (desc->ref_precision != EGERIA_REF_INT8 && L.per_channel) return EGERIA_ERR_INVALID_ARG;
+        if (desc->act_scheme == EGERIA_ACT_AFFINE && (!L.colsum || (reinterpret_cast<uintptr_t>(L.colsum) & 3u)))
+            return EGERIA_ERR_INVALID_ARG;
     }
     if (taps && (taps->n != p.n_linear || !taps->tap)) return EGERIA_ERR_INVALID_ARG;
     if (p.M > 0x7fffffffLL || p.slots > 256) return EGERIA_ERR_UNSUPPORTED;
@@ -600,6 +689,24 @@ egeria_status egeria_quantize_nchw(const void *x, egeria_dtype dt, int64_t n, in
     return EGERIA_OK;
 }
 
+size_t egeria_quantize_affine_workspace_bytes(void) { return 256 + affine_partial_bytes(); }
+
+egeria_status egeria_quantize_affine(const void *x, egeria_dtype dt, int64_t n, uint8_t *q, float *scale_out,
+                                     int32_t *zp_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0 || !scale_out || !zp_out || !ws) return EGERIA_ERR_INVALID_ARG;
+    if (n > 0 && (!x || !q)) return EGERIA_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(q) || !aligned16(ws)) return EGERIA_ERR_INVALID_ARG;
+    if (dt != EGERIA_F32 && dt != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
+    if (ws_bytes < egeria_quantize_affine_workspace_bytes()) return EGERIA_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t *partials = (uint32_t *)((char *)ws + 256);
+    EG_HIP(launch_minmax(x, dt, n, partials, st));
+    EG_HIP(launch_quantize_affine(x, dt, 1, n, 1, pad16(n), partials, minmax_blocks(n), 0, q, scale_out, zp_out, ws_flag(ws),
+                                  st));
+    return EGERIA_OK;
+}
+
 size_t egeria_quantize_weights_workspace_bytes(int32_t n)
 {
     if (n < 0) return 0;
@@ -623,6 +730,10 @@ static egeria_status quantize_weights_impl(const egeria_weight *w, int32_t n, vo
         if (t.dtype != EGERIA_F32 && t.dtype != EGERIA_BF16) return EGERIA_ERR_INVALID_ARG;
         if (t.precision < EGERIA_REF_INT8 || t.precision > EGERIA_REF_F32) return EGERIA_ERR_INVALID_ARG;
         if (t.precision != EGERIA_REF_INT8 && t.per_channel) return EGERIA_ERR_INVALID_ARG;
+        if (t.colsum) {
+            if (t.precision != EGERIA_REF_INT8 || (reinterpret_cast<uintptr_t>(t.colsum) & 3u)) return EGERIA_ERR_INVALID_ARG;
+            if (!((t.kh == 1 && t.kw == 1) || (t.kh == 3 && t.kw == 3))) return EGERIA_ERR_UNSUPPORTED;
+        }
         const int64_t total = (int64_t)t.out * t.in * t.kh * t.kw;
         if (total > 0 && (!t.w || !t.w_q)) return EGERIA_ERR_INVALID_ARG;
         if (!aligned16(t.w) || !aligned16(t.w_q)) return EGERIA_ERR_INVALID_ARG;
@@ -685,6 +796,11 @@ static egeria_status quantize_weights_impl(const egeria_weight *w, int32_t n, vo
                 if (take_q) *xq_carried = true;
             }
         }
+    }
+    // sums of the codes just written, for modules with affine activation codes
+    for (int i = 0; i < n; ++i) {
+        const egeria_weight &t = w[i];
+        if (t.colsum) EG_HIP(launch_colsum(t.w_q, t.out, t.kh * t.kw, (int32_t)pad16(t.in), t.colsum, st));
     }
     return EGERIA_OK;
 }
@@ -755,6 +871,7 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     if (desc->kind < EGERIA_BERT_LAYER) {
         float *out = a_ref ? a_ref : (float *)(f.ws + p.off_aref[0]);
         if (desc->ref_precision != EGERIA_REF_INT8) EG_OK(forward_float(f, x, x_dt, out));
+        else if (desc->act_scheme == EGERIA_ACT_AFFINE) EG_OK(forward_affine(f, x, x_dt, out));
         else if (desc->kind == EGERIA_FC_RELU) EG_OK(forward_fc(f, x, x_dt, out));
         else EG_OK(forward_conv_block(f, x, x_dt, out));
         if (eval)
@@ -762,7 +879,8 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
         return EGERIA_OK;
     }
     const bool float_ref = desc->ref_precision != EGERIA_REF_INT8;
-    if (!float_ref) EG_OK(f.input_absmax(x, x_dt, p.M * desc->hidden));
+    const bool affine = desc->act_scheme == EGERIA_ACT_AFFINE;
+    if (!float_ref && !affine) EG_OK(f.input_absmax(x, x_dt, p.M * desc->hidden));
     const float *cur = (const float *)x;
     // The score of layer l only needs that layer's output, so it runs on a side
     // stream while the main stream goes on with layer l + 1 (the score is bound
@@ -777,6 +895,7 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
         float *out = a_ref ? a_ref + (size_t)l * aref_elems : (float *)(f.ws + p.off_aref[l & 1]);
         if (side && l >= 2) EG_HIP(hipStreamWaitEvent(st, side->scored[l & 1], 0));
         if (float_ref) EG_OK(forward_float_bert_layer(f, l, cur, out));
+        else if (affine) EG_OK(forward_affine_bert_layer(f, l, cur, out));
         else EG_OK(forward_bert_layer(f, l, cur, out, l + 1 == p.n_layers));
         if (eval) {
             hipStream_t ms = side ? side->stream : st;
@@ -847,7 +966,7 @@ egeria_status egeria_plasticity_eval(const egeria_block_desc *desc, const egeria
 // the one-launch quantiser).
 static int64_t input_max_elems(const egeria_block_desc *d, const egeria_qweights *qw, const Plan &p)
 {
-    if (qw->act_scale || d->ref_precision != EGERIA_REF_INT8) return 0;
+    if (qw->act_scale || d->ref_precision != EGERIA_REF_INT8 || d->act_scheme != EGERIA_ACT_SYMMETRIC) return 0;
     if (d->kind == EGERIA_FC_RELU) return fc_input_is_small(d) ? 0 : (int64_t)d->batch * d->c_in;
     if (d->kind == EGERIA_BASIC_BLOCK || d->kind == EGERIA_BOTTLENECK) return p.M * d->c_in;
     return p.M * d->hidden;
@@ -874,7 +993,8 @@ egeria_status egeria_refresh_eval(const egeria_weight *w, int32_t n_w, void *ws_
     job.n_reset = p.slots;
     job.bf16 = x_dt == EGERIA_BF16 ? 1 : 0;
     job.nblk = job.n > 0 ? absmax_blocks(job.n, x_dt) : 0;
-    if (desc->kind == EGERIA_FC_RELU && !qw->act_scale && desc->ref_precision == EGERIA_REF_INT8 && fc_input_is_small(desc)) {
+    if (desc->kind == EGERIA_FC_RELU && !qw->act_scale && desc->ref_precision == EGERIA_REF_INT8 &&
+        desc->act_scheme == EGERIA_ACT_SYMMETRIC && fc_input_is_small(desc)) {
         // the whole quantisation of a small FC input is one workgroup's work
         job.n = (int64_t)desc->batch * desc->c_in;
         job.nblk = 1;

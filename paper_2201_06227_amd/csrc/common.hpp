@@ -204,6 +204,22 @@ hipError_t launch_dequantize(const int8_t *q, const float *scale, int64_t n, flo
 hipError_t launch_cast_chlast(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw, int64_t cpe, int et,
                               void *out, float *one, hipStream_t st);
 
+// Affine uint8 activation codes (stored as q - 128): the extrema of n values as per-workgroup partial
+// results (affine_partial_bytes() bytes of scratch hold them), then the codes of [n, c, hw] channel planes
+// (hw = 1: matrix rows) as [n, hw, cp] bytes with zero pad channels; every workgroup reduces the nb =
+// minmax_blocks(...) partial results to the scale and the zero point, which workgroup 0 stores.
+// store_offset: 128 for the GEMM operand form, 0 for plain uint8 codes.
+int minmax_blocks(int64_t n);
+size_t affine_partial_bytes();
+hipError_t launch_minmax(const void *x, egeria_dtype dt, int64_t n, uint32_t *partials, hipStream_t st);
+hipError_t launch_quantize_affine(const void *x, egeria_dtype dt, int64_t n, int64_t c, int64_t hw, int64_t cp,
+                                  const uint32_t *partials, int nb, int store_offset, void *q, float *scale_out,
+                                  int32_t *zp_out, uint32_t *flag, hipStream_t st);
+// Sums of the int8 weight codes [out, taps, cp] per output channel: int32 [out] for taps = 1, and for a 3x3
+// kernel (taps = 9) int32 [16, out], class c leaving out the window positions outside the image for a pixel
+// in the first row (c & 1), last row (c & 2), first column (c & 4), last column (c & 8).
+hipError_t launch_colsum(const int8_t *w_q, int32_t out, int32_t taps, int32_t cp, int32_t *colsum, hipStream_t st);
+
 // int8 GEMM / implicit-GEMM convolution with fused dequantising epilogue.
 struct GemmArgs {
     const int8_t *a;        // activations: [M, lda] (linear, 1x1 conv) or [B, H, W, cp] (3x3 conv)
@@ -239,6 +255,12 @@ struct GemmArgs {
     // res_ld in elements, res_scale unused; acc_out receives the fp32 sums' bit patterns; no q_out,
     // no absmax_out)
     int32_t et;
+    // affine activation codes (int8 operands only): a holds q - 128; *zp_in is the zero point of a, colsum
+    // the weight-code sums of launch_colsum; the accumulator becomes acc + (128 - zp) * colsum[class][n].
+    // *zp_res: zero point of the residual codes (res_q holds q - 128 as well).  NULL: symmetric codes.
+    const int32_t *zp_in;
+    const int32_t *colsum;
+    const int32_t *zp_res;
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 

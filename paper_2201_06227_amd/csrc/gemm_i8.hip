@@ -164,6 +164,9 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
     const float rs = g.res_q ? (ET == 0 ? *g.res_scale : 1.0f) : 0.0f;
     float q_inv = 0.0f;                          // multiplier of the optional int8 output
     if (g.q_out) q_inv = (float)(1.0 / (double)*g.q_scale);
+    // affine activation codes: stored codes are q - 128, so 128 - zero point goes back in
+    const int zmul = (ET == 0 && g.zp_in) ? 128 - *g.zp_in : 0;
+    const int rmul = (ET == 0 && g.zp_res) ? 128 - *g.zp_res : 0;
 
     // Operands go from global memory straight into LDS (buffer loads with the
     // LDS modifier): one such instruction of a wave fills 1 KiB, lane l writing
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
     // when only positive values are wanted) order like signed integers.
     const bool pos = g.amax_pos != 0;
     int32_t amax = 0;
-    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (g.y || g.q_out) && !g.acc_out;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (g.y || g.q_out) && !g.acc_out && !g.zp_in && !g.zp_res;
     const uint32_t qoff = g.q_out ? (uint32_t)(lrow * g.q_ld + lcol) : 0u;
     const uint32_t yoff = (uint32_t)(lrow * g.ldy + lcol);
     const uint32_t roff = g.res_q ? (uint32_t)(lrow * g.res_ld + lcol) : 0u;
@@ -434,11 +437,25 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
                         if (g.q_out && !col_ok && col0 + lcol < g.q_ld && rr < rows_left) qb[(size_t)rr * g.q_ld + qoff] = 0;
                         continue;
                     }
-                    const auto a = acc[i][j][r];
+                    auto a = acc[i][j][r];
+                    if constexpr (EDGE && ET == 0) {
+                        if (g.zp_in) {
+                            // the sum of the centred codes: the weight codes of this output channel, over the
+                            // window positions inside the image for this pixel, times 128 - zero point
+                            int cls = 0;
+                            if (CONV) {
+                                const uint32_t m = (uint32_t)(row0 + lrow + rr);
+                                const uint32_t mrow = m / (uint32_t)g.W;
+                                const int ow = (int)(m - mrow * (uint32_t)g.W), oh = (int)(mrow % (uint32_t)g.H);
+                                cls = (oh == 0 ? 1 : 0) | (oh == g.H - 1 ? 2 : 0) | (ow == 0 ? 4 : 0) | (ow == g.W - 1 ? 8 : 0);
+                            }
+                            a += zmul * g.colsum[(size_t)cls * g.N + col0 + lcol];
+                        }
+                    }
                     float v = fmaf((float)a, sj, bj);
                     if (EDGE ? g.res_q != nullptr : RES) {
                         if constexpr (RES_LDS)
-                            v = v + (float)(int8_t)lds[((wm_u * TM + i) * 32 + lrow + rr) * BN + (wn_u * TN + j) * 32 + lcol] * rs;
+                            v = v + (float)((int)(int8_t)lds[((wm_u * TM + i) * 32 + lrow + rr) * BN + (wn_u * TN + j) * 32 + lcol] + rmul) * rs;
                         else if constexpr (!EDGE && RES)
                             v = v + rpre[r] * rs;
                         else
@@ -943,7 +960,7 @@ hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
     if (g.et == 1) return launch_float<1>(g, st);
     if (g.et == 2) return launch_float<2>(g, st);
     if (g.et != 0) return hipErrorInvalidValue;
-    if (g.conv3x3 && g.cp == 16 && g.N <= 32) {
+    if (g.conv3x3 && g.cp == 16 && g.N <= 32 && !g.zp_in) {   // (symmetric codes only)
         const int64_t blocks = (g.M + 127) / 128;
         if (blocks <= 0) return hipSuccess;
         if (g.M >= (1LL << 31)) return hipErrorInvalidValue;            // 32-bit pixel arithmetic in the kernel
