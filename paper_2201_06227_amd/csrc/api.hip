@@ -160,7 +160,6 @@ struct Fwd {
     Plan p;
     hipStream_t st;
 
-    uint32_t *clear_word = nullptr; // a word the module's last GEMM clears (ticket of a one-launch score)
     int n_in = 1;           // per-workgroup maxima the input's absmax kernel wrote
     bool input_max_done = false;    // an earlier launch has already taken the input's maxima
     bool input_codes_done = false;  // ... and its int8 codes and scale as well
@@ -256,7 +255,6 @@ egeria_status run_gemm(const Fwd &f, int li, const int8_t *a, int64_t lda, int64
     g.amax_pos = amax_pos ? 1 : 0;
     g.q_out = q_out; g.q_ld = q_ld; g.q_scale = q_scale;
     g.zp_in = zp_in; g.colsum = L.colsum; g.zp_res = zp_res;
-    g.clear_word = f.clear_word;
     EG_HIP(launch_gemm_i8(g, f.st));
     return (tap_y && y) ? f.copy_tap_y(li, y, (size_t)M * N * 4) : EGERIA_OK;
 }
@@ -872,16 +870,12 @@ static egeria_status forward_impl(const egeria_block_desc *desc, const egeria_qw
     const size_t aref_elems = (size_t)desc->batch * (size_t)p.D;
     if (desc->kind < EGERIA_BERT_LAYER) {
         float *out = a_ref ? a_ref : (float *)(f.ws + p.off_aref[0]);
-        // a small FC module: its GEMM clears the ticket that lets the score's partial-product launch finalise itself
-        const bool one_launch = eval && desc->kind == EGERIA_FC_RELU && plasticity_fits_one_launch(desc->batch, p.D);
-        if (one_launch) f.clear_word = plasticity_ticket_word(f.ws + p.off_part);
         if (desc->ref_precision != EGERIA_REF_INT8) EG_OK(forward_float(f, x, x_dt, out));
         else if (desc->act_scheme == EGERIA_ACT_AFFINE) EG_OK(forward_affine(f, x, x_dt, out));
         else if (desc->kind == EGERIA_FC_RELU) EG_OK(forward_fc(f, x, x_dt, out));
         else EG_OK(forward_conv_block(f, x, x_dt, out));
         if (eval)
-            EG_HIP(launch_plasticity(a_train[0], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out, f.ws + p.off_part, st,
-                                     one_launch));
+            EG_HIP(launch_plasticity(a_train[0], t_dt, out, EGERIA_F32, desc->batch, p.D, p_out, f.ws + p.off_part, st));
         return EGERIA_OK;
     }
     const bool float_ref = desc->ref_precision != EGERIA_REF_INT8;

@@ -261,7 +261,6 @@ struct GemmArgs {
     const int32_t *zp_in;
     const int32_t *colsum;
     const int32_t *zp_res;
-    uint32_t *clear_word;   // optional: workgroup 0 stores 0 here (the ticket of a later kernel of the stream)
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
 
@@ -315,13 +314,8 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
 
 // Training plasticity.  ws_part must hold plasticity_partial_bytes(b, D).
 size_t plasticity_partial_bytes(int32_t b, int64_t D);
-// ticket_is_clear: an earlier kernel on the stream has zeroed *plasticity_ticket_word(ws_part); small problems
-// (plasticity_fits_one_launch) then take one launch instead of two, with the same result bit for bit.
-bool plasticity_fits_one_launch(int32_t b, int64_t D);
-uint32_t *plasticity_ticket_word(void *ws_part);
 hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r, egeria_dtype r_dt,
-                             int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st,
-                             bool ticket_is_clear = false);
+                             int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st);
 
 // ---- device helpers ------------------------------------------------------------
 #ifdef __HIPCC__

@@ -151,7 +151,6 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
     if (local >= tiles_per_xcd || tile >= tiles) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (g.clear_word && blockIdx.x == 0 && tid == 0) *g.clear_word = 0u;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave / WN, wn = wave % WN;
     const int tiles_n = (g.N + BN - 1) / BN;

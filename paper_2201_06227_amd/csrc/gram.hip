@@ -149,19 +149,12 @@ __device__ __forceinline__ Split8 split8(const float (&x)[8])
     return o;
 }
 
-template <int NOTHING>
-__device__ __forceinline__ void finalize_in_last_workgroup(const float *__restrict__ part, int nsplit, int nmacro, int b,
-                                                           double *__restrict__ rowsum, uint32_t *__restrict__ counter,
-                                                           float *__restrict__ p_out);
-
 template <int MT, bool OFFD, int TDT, int RDT, bool FAST>
 __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restrict__ at,
                                                            const void *__restrict__ ar, int b,
                                                            int64_t D, GramPlan p,
                                                            float *__restrict__ part,
-                                                           uint32_t *__restrict__ counter,
-                                                           double *__restrict__ rowsum,
-                                                           float *__restrict__ p_fused)
+                                                           uint32_t *__restrict__ counter)
 {
     constexpr int ROWS = MT * 32;                 // rows per side of the macro tile
     constexpr int KT = MT == 1 ? 64 : 32;         // features per K tile
@@ -371,28 +364,20 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const void *__restric
             }
         }
     }
-    if (p_fused) finalize_in_last_workgroup<0>(part, p.nsplit, p.nmacro, b, rowsum, counter, p_fused);
 }
 
-// The share of row i in the score (b <= 128), computed by one workgroup: the 256 threads form G = 256 / W
-// groups of W >= b lanes (W = 32, 64 or 128); group g adds chunks g, g + G, ... of row i of M, M^T and B
-// in fp64, lane j taking column j (coalesced 4 W-byte reads), and the G sums are added in group order.
-// COHERENT: the partial results were written by other workgroups of the same launch (loads that bypass
-// the compute unit's cache).  Every thread gets the share.
-struct FinalizeShared {
-    double sm[3][256];
-    double wsum[4];
-};
-template <bool COHERENT>
-__device__ __forceinline__ float part_load(const float *p)
+// One workgroup per row i (b <= 128).  The 256 threads form G = 256 / W groups of
+// W >= b lanes (W = 32, 64 or 128); group g adds chunks g, g + G, ... of row i
+// of M, M^T and B in fp64, lane j taking column j (coalesced 4 W-byte reads),
+// and the G sums are added in group order.
+__global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restrict__ part, int nsplit, int b,
+                                                          double *__restrict__ rowsum,
+                                                          uint32_t *__restrict__ counter,
+                                                          float *__restrict__ p_out)
 {
-    if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return *p;
-}
-template <bool COHERENT>
-__device__ __forceinline__ double row_share(const float *__restrict__ part, int nsplit, int b, int i, FinalizeShared &fs)
-{
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    __shared__ double sm[3][256];
+    __shared__ double wsum[4];
+    const int i = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int W = b <= 32 ? 32 : (b <= 64 ? 64 : 128), G = 256 / W;
     const int j = t & (W - 1), grp = t / W;
     const size_t nelem = (size_t)b * b, cstride = 3 * nelem;
@@ -406,9 +391,9 @@ __device__ __forceinline__ double row_share(const float *__restrict__ part, int 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const float *pc = p + (size_t)(c + u * G) * cstride;
-                vm[u] = part_load<COHERENT>(pc);
-                vt[u] = part_load<COHERENT>(pc + nelem);
-                vb[u] = part_load<COHERENT>(pc + 2 * nelem);
+                vm[u] = pc[0];
+                vt[u] = pc[nelem];
+                vb[u] = pc[2 * nelem];
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -419,23 +404,22 @@ __device__ __forceinline__ double row_share(const float *__restrict__ part, int 
         }
         for (; c < nsplit; c += G) {
             const float *pc = p + (size_t)c * cstride;
-            am += (double)part_load<COHERENT>(pc);
-            at += (double)part_load<COHERENT>(pc + nelem);
-            ab += (double)part_load<COHERENT>(pc + 2 * nelem);
+            am += (double)pc[0];
+            at += (double)pc[nelem];
+            ab += (double)pc[2 * nelem];
         }
     }
-    __syncthreads();                               // the shared sums of the row before are no longer read
-    fs.sm[0][t] = am;
-    fs.sm[1][t] = at;
-    fs.sm[2][t] = ab;
+    sm[0][t] = am;
+    sm[1][t] = at;
+    sm[2][t] = ab;
     __syncthreads();
     double gt = 0.0, gr = 0.0;
     if (t < W && t < b) {
         double m = 0.0, mt = 0.0, bb = 0.0;
         for (int g = 0; g < G; ++g) {
-            m += fs.sm[0][g * W + t];
-            mt += fs.sm[1][g * W + t];
-            bb += fs.sm[2][g * W + t];
+            m += sm[0][g * W + t];
+            mt += sm[1][g * W + t];
+            bb += sm[2][g * W + t];
         }
         gr = bb;                                   // row i of R R^T
         gt = bb + 0.5 * (m + mt);                  // row i of T T^T
@@ -444,35 +428,15 @@ __device__ __forceinline__ double row_share(const float *__restrict__ part, int 
     auto row_sum = [&](double v) {
         v = wave_sum(v);
         __syncthreads();
-        if (lane == 0) fs.wsum[wave] = v;
+        if (lane == 0) wsum[wave] = v;
         __syncthreads();
-        return fs.wsum[0] + fs.wsum[1];
+        return wsum[0] + wsum[1];
     };
     double nt = sqrt(row_sum(gt * gt)), nr = sqrt(row_sum(gr * gr));
     nt = nt < 1e-12 ? 1e-12 : nt;
     nr = nr < 1e-12 ? 1e-12 : nr;
     const double d = (t < W && t < b) ? gt / nt - gr / nr : 0.0;
-    return row_sum(d * d);
-}
-
-// the score from the b row shares: lane l of one wave takes rows l and l + 64
-__device__ __forceinline__ void score_from_shares(const double *shares, int b, int lane, float *p_out)
-{
-    const double v0 = lane < b ? __hip_atomic_load(&shares[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-    const double v1 = lane + 64 < b ? __hip_atomic_load(&shares[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-    const double tot = wave_sum(v0 + v1);
-    if (lane == 0) *p_out = (float)(tot / ((double)b * (double)b));
-}
-
-// One workgroup per row; the last one to arrive adds the shares.
-__global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restrict__ part, int nsplit, int b,
-                                                          double *__restrict__ rowsum,
-                                                          uint32_t *__restrict__ counter,
-                                                          float *__restrict__ p_out)
-{
-    __shared__ FinalizeShared fs;
-    const int i = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const double share = row_share<false>(part, nsplit, b, i, fs);
+    const double share = row_sum(d * d);
     __shared__ uint32_t ticket_s;
     if (t == 0) {
         rowsum[i] = share;
@@ -482,56 +446,16 @@ __global__ __launch_bounds__(256) void sp_finalize_kernel(const float *__restric
     __syncthreads();
     if (ticket_s != (uint32_t)(b - 1) || wave != 0) return;
     __threadfence();                                       // see every other workgroup's share
-    score_from_shares(rowsum, b, lane, p_out);
+    const double v0 = lane < b ? __hip_atomic_load(&rowsum[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    const double v1 = lane + 64 < b ? __hip_atomic_load(&rowsum[lane + 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    const double tot = wave_sum(v0 + v1);
+    if (lane == 0) *p_out = (float)(tot / ((double)b * (double)b));
 }
-
-// Small problems (a few workgroups of partial results): the last workgroup of the partial-product launch to
-// arrive does the finaliser's work itself, row by row, in the same order of additions - one launch instead of
-// two.  The ticket word counter[1] must be zero on entry (the caller has an earlier kernel of the stream clear
-// it); the last workgroup leaves it zero again.
-template <int NOTHING>
-__device__ __forceinline__ void finalize_in_last_workgroup(const float *__restrict__ part, int nsplit, int nmacro, int b,
-                                                           double *__restrict__ rowsum, uint32_t *__restrict__ counter,
-                                                           float *__restrict__ p_out)
-{
-    __shared__ FinalizeShared fs;
-    __shared__ uint32_t ticket_s;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    __syncthreads();                                       // this workgroup's partial results are all issued
-    if (t == 0) {
-        __threadfence();
-        ticket_s = atomicAdd(counter + 1, 1u);
-    }
-    __syncthreads();
-    if (ticket_s != (uint32_t)(nsplit * nmacro - 1)) return;
-    __threadfence();
-    for (int i = 0; i < b; ++i) {
-        const double share = row_share<true>(part, nsplit, b, i, fs);
-        if (t == 0) rowsum[i] = share;
-    }
-    __syncthreads();
-    if (t == 0) {
-        __threadfence();
-        counter[1] = 0u;
-    }
-    __syncthreads();
-    if (wave == 0) score_from_shares(rowsum, b, lane, p_out);
-}
-
-bool plasticity_fits_one_launch(int32_t b, int64_t D)
-{
-    const GramPlan p = plan_gram(b, D);
-    return p.nsplit * p.nmacro <= 16;
-}
-
-uint32_t *plasticity_ticket_word(void *ws_part) { return (uint32_t *)ws_part + 1; }
 
 hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r, egeria_dtype r_dt,
-                             int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st, bool ticket_is_clear)
+                             int32_t b, int64_t D, float *p_out, void *ws_part, hipStream_t st)
 {
     const GramPlan p = plan_gram(b, D);
-    const bool one_launch = ticket_is_clear && p.nsplit * p.nmacro <= 16;
-    float *p_fused = one_launch ? p_out : nullptr;
     const int dev = current_device();
     if (dev < 0) return hipErrorInvalidDevice;
     uint32_t *counter = (uint32_t *)ws_part;
@@ -554,7 +478,7 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
             attr_set[dev] = true;                                                                      \
         }                                                                                              \
         e = launch_k(EGERIA_KERNEL_GRAM, gram_partial_kernel<MTV, OFF, T, R, V>, grid, block, smem,    \
-                     st, a_t, a_r, (int)b, D, p, part, counter, rowsum, p_fused);                      \
+                     st, a_t, a_r, (int)b, D, p, part, counter);                                       \
     } while (0)
 #define EGERIA_GRAM_DT(MTV, OFF)                                                                       \
     do {                                                                                               \
@@ -575,7 +499,7 @@ hipError_t launch_plasticity(const void *a_t, egeria_dtype t_dt, const void *a_r
     else EGERIA_GRAM_DT(2, true);
 #undef EGERIA_GRAM_DT
 #undef EGERIA_GRAM
-    if (e != hipSuccess || one_launch) return e;
+    if (e != hipSuccess) return e;
     return launch_k(EGERIA_KERNEL_NONE, sp_finalize_kernel, dim3((unsigned)b), dim3(256), 0, st, (const float *)part,
                     p.nsplit, (int)b, rowsum, counter, p_out);
 }
