@@ -192,6 +192,30 @@ def test_fc_module_bit_exact(eg, gc, orc, kw):
     assert (a_ref[0] == ot["a_ref"]).all()
 
 
+@pytest.mark.parametrize("kw", [dict(b=1, k=16, n=8), dict(b=5, k=100, n=7), dict(b=32, k=512, n=512),
+                                dict(b=64, k=96, n=700), dict(b=128, k=64, n=1024)],
+                         ids=lambda k: "b{b}_k{k}_n{n}".format(**k))
+def test_fc_score_equals_the_metric_on_its_activation(eg, gc, orc, kw):
+    """The fused evaluation of an FC module gives the score the metric gives on the stored activation, bit for
+    bit, call after call on a workspace that starts with stale bytes, and within 1e-4 of the oracle."""
+    wl = si.make_fc(seed=300 + kw["n"], **kw)
+    ref = gc.build_reference(wl)
+    x = gc.to_dev(wl.x)
+    a_t = si.train_forward(wl)[0].to(gc.DEV)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    ws.fill_(0xA5)
+    a_ref = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    eg.ref_forward(ref, x, a_ref, ws)
+    sep = eg.plasticity(a_t, a_ref.reshape(wl.batch, -1))
+    want = orc.sp_loss(a_t.float().cpu().numpy(), orc.ref_forward(wl)["a_ref"])
+    for rep in range(3):
+        p = torch.full((1,), -1.0, dtype=torch.float32, device=gc.DEV)
+        eg.plasticity_eval(ref, x, [a_t], p, ws)
+        torch.cuda.synchronize()
+        assert p.item() == sep.item(), (rep, p.item(), sep.item())
+    assert abs(p.item() - want) <= 1e-4 * abs(want) + 1e-12 * 4.0 / wl.batch
+
+
 BASIC_CASES = [dict(b=1, c=1, h=1, w=1), dict(b=3, c=8, h=7, w=6), dict(b=2, c=20, h=9, w=11),
                dict(b=5, c=16, h=32, w=32), dict(b=2, c=64, h=13, w=13)]
 
