@@ -47,6 +47,25 @@ egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out
 egeria_status egeria_profile_attention(const float *qkv, int32_t B, int32_t S, int32_t hidden, int32_t heads,
                                        int32_t mode, float *ctx, void *records, void *stream);
 
+/* What the device delivers to kernels shaped like this library's: one small complete kernel per kind, run
+ * twice (the second run is timed with events on `stream`).  ms_out: duration of that run; work_out: what it
+ * did - operations (matrix instructions: 2 per multiply-add) or bytes (LDS, L2 -> LDS, copy: read + written).
+ * iters: length of the inner loop (ignored by the copy); scratch: DEVICE, at least 256 MiB. */
+typedef enum {
+    EGERIA_MICRO_MFMA_I8 = 0,        /* v_mfma_i32_32x32x32_i8, two workgroups of four waves per compute unit */
+    EGERIA_MICRO_MFMA_BF16 = 1,      /* v_mfma_f32_32x32x16_bf16 */
+    EGERIA_MICRO_MFMA_F32_32 = 2,    /* v_mfma_f32_32x32x2_f32 */
+    EGERIA_MICRO_MFMA_F32_16 = 3,    /* v_mfma_f32_16x16x4_f32 */
+    EGERIA_MICRO_MFMA_F64 = 4,       /* v_mfma_f64_16x16x4_f64 */
+    EGERIA_MICRO_LDS_READ = 5,       /* ds_read_b128 without bank conflicts */
+    EGERIA_MICRO_LDS_WRITE = 6,      /* ds_write_b128 without bank conflicts */
+    EGERIA_MICRO_L2_TO_LDS_LINE = 7, /* buffer loads with the LDS modifier, whole 128-byte lines of L2-resident rows */
+    EGERIA_MICRO_L2_TO_LDS_HALF = 8, /* ... half lines (64 bytes per row and request) */
+    EGERIA_MICRO_HBM_COPY = 9        /* 128 MiB copied with 16-byte accesses */
+} egeria_micro_kind;
+egeria_status egeria_microbench(int32_t kind, int32_t iters, void *scratch, size_t scratch_bytes, float *ms_out,
+                                double *work_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libegeria.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm_i8.hip", "gram.hip", "bert.hip", "freeze.hip", "cache.hip", "cast.hip", "affine.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm_i8.hip", "gram.hip", "bert.hip", "freeze.hip", "cache.hip", "cast.hip", "affine.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

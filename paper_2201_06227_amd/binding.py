@@ -98,7 +98,7 @@ EXPORTS = [
     "egeria_freeze_init", "egeria_freeze_observe",
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
     "egeria_refresh_eval", "egeria_plasticity_noalloc", "egeria_profile_attention",
-    "egeria_quantize_affine", "egeria_quantize_affine_workspace_bytes",
+    "egeria_quantize_affine", "egeria_quantize_affine_workspace_bytes", "egeria_microbench",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -167,6 +167,9 @@ def lib():
     L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
     L.egeria_profile_attention.restype = ctypes.c_int
     L.egeria_profile_attention.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+    L.egeria_microbench.restype = ctypes.c_int
+    L.egeria_microbench.argtypes = [_i32, _i32, _vp, _sz, ctypes.POINTER(ctypes.c_float),
+                                    ctypes.POINTER(ctypes.c_double), _vp]
     L.egeria_freeze_init.restype = ctypes.c_int
     L.egeria_freeze_init.argtypes = [ctypes.POINTER(FreezeState), _i32, _i32, ctypes.c_double, _i32]
     L.egeria_freeze_observe.restype = ctypes.c_int
@@ -509,6 +512,19 @@ def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torc
                                       _dt(a_train[0]), _ptr(p_out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "egeria_plasticity_eval")
     return p_out
+
+
+MICRO_KINDS = ["mfma_i32_32x32x32_i8", "mfma_f32_32x32x16_bf16", "mfma_f32_32x32x2_f32", "mfma_f32_16x16x4_f32",
+               "mfma_f64_16x16x4_f64", "lds_read_b128", "lds_write_b128", "l2_to_lds_whole_lines", "l2_to_lds_half_lines",
+               "hbm_copy"]
+
+
+def microbench(kind: int, iters: int, scratch: torch.Tensor):
+    """egeria_microbench: (milliseconds, work done) of one micro-measurement."""
+    ms, work = ctypes.c_float(0), ctypes.c_double(0)
+    _check(lib().egeria_microbench(int(kind), int(iters), _ptr(scratch), scratch.numel(), ctypes.byref(ms),
+                                   ctypes.byref(work), _stream()), "egeria_microbench")
+    return ms.value, work.value
 
 
 def check(ws: torch.Tensor) -> int:
