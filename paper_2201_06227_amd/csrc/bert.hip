@@ -402,14 +402,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 //      code; the others (a few in ten thousand) are put on a list.
 //   4. attention_fix_kernel: a wave per listed value re-evaluates it in fp64 and stores its code.
 // The bound of a value x: E = 2^-24 * (max|v| of the head * (kErrBase + kErrPerScore * max|score| of the
-// workgroup) + 16 |x|).  It is an empirical bound with margin, not a proof: bench.py --attention-error
+// workgroup) + kErrRel |x|).  It is an empirical bound with margin, not a proof: bench.py --attention-error
 // measures kernel 1 against the fp64 kernel on the twelve layers of the BERT-base-shaped stack (12.6 M
 // values each) and prints the largest error / E per layer.
 typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr float kErrBase = 4.0f, kErrPerScore = 1.0f;
+constexpr float kErrBase = 2.0f, kErrPerScore = 0.5f;
 // ... plus a part that grows with the value itself (the drift of the matrix cores' accumulation is
 // proportional to the sums it carries): kErrRel * 2^-24 * |x|
-constexpr float kErrRel = 16.0f * 5.9604645e-8f;
+constexpr float kErrRel = 10.0f * 5.9604645e-8f;
 // error bound of one approximate context value x whose workgroup's record says err
 __device__ __forceinline__ float value_err(float err, float x) { return fmaf(kErrRel, fabsf(x), err); }
 struct AttnRecord {
