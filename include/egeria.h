@@ -303,7 +303,7 @@ size_t egeria_quantize_affine_workspace_bytes(void);
  * evaluated so that every int8 code and scale of the following GEMM is the one
  * an fp64 evaluation rounded once to fp32 gives.  Limits of these kinds: x must
  * be EGERIA_F32 (a bf16 mini-batch is EGERIA_ERR_UNSUPPORTED), hidden / heads
- * <= 64 (larger heads: EGERIA_ERR_UNSUPPORTED), batch * seq < 2^31, at most 42
+ * <= 64 (larger heads: EGERIA_ERR_UNSUPPORTED), batch * seq < 2^31, at most 36
  * layers per stack; the score calls further need batch <= 128.
  * Errors: EGERIA_ERR_INVALID_ARG for a null or misaligned pointer, a bad
  * descriptor, n_linear / n_norm / taps->n that do not fit the module;

@@ -128,7 +128,8 @@ Plan make_plan(const egeria_block_desc *d)
     default: {
         p.n_layers = d->n_layers;
         // four quantise points per layer + one exact-absmax word for the GELU + one for the attention context
-        p.slots = 6 * p.n_layers;
+        // + one for the largest error bound of the fast attention kernel's records
+        p.slots = 7 * p.n_layers;
         p.n_linear = 4 * p.n_layers; p.M = b * d->seq; p.D = (int64_t)d->seq * d->hidden;
         take(header_bytes(p.slots));
         p.off_q[0] = take((size_t)(p.M * op_bytes(d, d->hidden > d->ffn ? d->hidden : d->ffn)));
@@ -450,7 +451,8 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
     } else {
         // unobserved runs: fp32 matrix-core attention, codes and scale certified against the fp64 evaluation
         EG_HIP(launch_attention_certified(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.ws + f.p.off_rec,
-                                          f.slot(5 * f.p.n_layers + l), xq, hp, f.scale(s0 + 1), ws_flag(f.ws),
+                                          f.slot(s0 + 1), f.slot(6 * f.p.n_layers + l), f.slot(5 * f.p.n_layers + l), xq, hp,
+                                          f.scale(s0 + 1), ws_flag(f.ws),
                                           ws_flag(f.ws) + kUnsureWord, f.st));
     }
     EG_OK(run_gemm(f, s0 + 1, xq, hp, M, Hd, hp, false, 0, 0, 0, f.scale(s0 + 1), 0, nullptr, nullptr, 0, proj,

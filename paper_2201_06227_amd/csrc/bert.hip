@@ -419,7 +419,9 @@ struct AttnRecord {
 
 __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__restrict__ qkv, int B, int S, int Hd,
                                                              int heads, int dh, float scale, float *__restrict__ ctx,
-                                                             AttnRecord *__restrict__ rec, int total, int per_xcd)
+                                                             AttnRecord *__restrict__ rec, int total, int per_xcd,
+                                                             uint32_t *__restrict__ amax_slot,
+                                                             uint32_t *__restrict__ err_slot)
 {
     __shared__ __attribute__((aligned(16))) float sKb[2][kKeyTile][kKVPad];
     __shared__ __attribute__((aligned(16))) float sVb[2][kKeyTile][kKVPad];
@@ -638,6 +640,15 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
         r.err = 5.9604645e-8f * __uint_as_float(v) * (kErrBase + kErrPerScore * __uint_as_float(sb));
         if (!(r.err <= 3.402823466e+38f)) r.amax_bits = 0x7f800000u;   // non-finite inputs: flagged downstream
         rec[vid] = r;
+        // the largest of both over all workgroups, for the kernel that settles the exact maximum (atomically
+        // combined words spread over ways; both are non-negative floats, whose bit patterns order like them)
+        if (amax_slot) {
+            uint32_t *wa = amax_slot + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride;
+            uint32_t *we = err_slot + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride;
+            const uint32_t eb = __float_as_uint(r.err);
+            if (r.amax_bits > __hip_atomic_load(wa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(wa, r.amax_bits);
+            if (eb > __hip_atomic_load(we, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(we, eb);
+        }
     }
 }
 
@@ -730,50 +741,28 @@ __device__ __forceinline__ void for_each_marked(bool mine, uint64_t *masks, F vi
     }
 }
 
-// Exact absolute maximum of the context: one workgroup per record.  Each reduces all records to the largest
-// stored |x| (A) and the largest E (eight record loads of a thread in flight at a time); a value can be the
-// exact maximum only if |x| + E_record >= A - E_max.  A workgroup whose record cannot hold such a value is
+// Exact absolute maximum of the context: one workgroup per record.  The largest stored |x| (A) and the largest E
+// over all records come from two atomically combined words the first kernel filled; a value can be the exact
+// maximum only if |x| + E_record >= A - E_max.  A workgroup whose record cannot hold such a value is
 // done; the others (as a rule one) rescan the record's 64 x dh values and re-evaluate those that pass the
 // test.  The value that holds A passes, so the word `exact` ends up with the exact maximum (it starts at
 // zero: cleared by the chain's first kernel).
 __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float *__restrict__ qkv,
                                                                      const float *__restrict__ ctx,
-                                                                     const AttnRecord *__restrict__ rec, int nrec,
+                                                                     const AttnRecord *__restrict__ rec,
+                                                                     const uint32_t *__restrict__ amax_slot,
+                                                                     const uint32_t *__restrict__ err_slot,
                                                                      int S, int Hd, int heads, int dh, double scale,
                                                                      uint32_t *__restrict__ exact,
                                                                      uint32_t *__restrict__ list_count)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) *list_count = 0u;      // the list the next kernel fills
-    __shared__ uint32_t sa[4];
-    __shared__ float se[4];
     __shared__ __attribute__((aligned(16))) double red[12 + 32];
     __shared__ uint64_t masks[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const AttnRecord mine = rec[blockIdx.x];
-    uint32_t a = 0;
-    float e = 0.0f;
-    const uint2 *rec2 = (const uint2 *)rec;
-    for (int i0 = 0; i0 < nrec; i0 += 256 * 8) {
-        uint2 r[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int i = i0 + tid + 256 * k;
-            r[k] = rec2[i < nrec ? i : nrec - 1];
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            a = a > r[k].x ? a : r[k].x;
-            e = fmaxf(e, __uint_as_float(r[k].y));
-        }
-    }
-    a = wave_max_u32(a);
-    e = wave_max(e);
-    if (lane == 0) { sa[wave] = a; se[wave] = e; }
-    __syncthreads();
-    a = sa[0] > sa[1] ? sa[0] : sa[1];
-    a = a > sa[2] ? a : sa[2];
-    a = a > sa[3] ? a : sa[3];
-    e = fmaxf(fmaxf(se[0], se[1]), fmaxf(se[2], se[3]));
+    const uint32_t a = reduce_ways(amax_slot);
+    const float e = __uint_as_float(reduce_ways(err_slot));
     if (a >= 0x7f800000u) {                                   // NaN / Inf in the tensor: it is the "maximum"
         if (blockIdx.x == 0 && tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, a);
         return;
@@ -824,10 +813,14 @@ struct FixList {
 };
 
 // true if the approximate value x with error bound err does not settle its code
+// (The exact value y lies in [x - e, x + e]; its code is clamp(rne(fl(y * inv))) with fl(y * inv) within
+// e * inv + 2^-23 |t| of t = fl(x * inv).  The two codes can differ only if that interval reaches the rounding
+// boundary next to t, i.e. |t - rne(t)| + e * inv + 2^-23 |t| >= 1/2; the margins below are a little wider.)
 __device__ __forceinline__ bool code_uncertain(float x, float err, float inv)
 {
-    const float e2 = value_err(err, x) * 1.001f + 1.0e-37f;       // (the factor covers the rounding of x -+ e2 itself)
-    return quant1(x - e2, inv) != quant1(x + e2, inv) || !(e2 <= 3.402823466e+38f);
+    const float t = x * inv;
+    const float reach = fmaf(value_err(err, x) * 1.001f, inv, 2.4e-7f * fabsf(t)) + 1.0e-30f;
+    return !(fabsf(t - rintf(t)) + reach < 0.5f);                  // also true for a non-finite bound
 }
 
 template <bool WIDE>
@@ -958,11 +951,11 @@ hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t
     const int per_xcd = (int)((grid + 7) / 8);
     return launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, qkv,
                     (int)B, (int)S, (int)Hd, (int)heads, dh, (float)(1.0 / sqrt((double)dh)), ctx, (AttnRecord *)records,
-                    (int)grid, per_xcd);
+                    (int)grid, per_xcd, (uint32_t *)nullptr, (uint32_t *)nullptr);
 }
 
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
-                                      void *records, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
+                                      void *records, uint32_t *amax_slot, uint32_t *err_slot, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
                                       uint32_t *flag, uint32_t *unsure_total, hipStream_t st)
 {
     const int dh = Hd / heads;
@@ -979,12 +972,13 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
     const int per_xcd = (int)((grid + 7) / 8);
     const double scale = 1.0 / sqrt((double)dh);
     hipError_t e = launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
-                            qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, (float)scale, ctx, rec, (int)grid, per_xcd);
+                            qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, (float)scale, ctx, rec, (int)grid, per_xcd,
+                            amax_slot, err_slot);
     if (e != hipSuccess) return e;
     const int nrec = (int)grid;
     e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)nrec), dim3(256), 0, st, qkv,
-                 (const float *)ctx, (const AttnRecord *)rec, nrec, (int)S, (int)Hd, (int)heads, dh, scale, exact_slot,
-                 &fix->count);
+                 (const float *)ctx, (const AttnRecord *)rec, (const uint32_t *)amax_slot, (const uint32_t *)err_slot, (int)S,
+                 (int)Hd, (int)heads, dh, scale, exact_slot, &fix->count);
     if (e != hipSuccess) return e;
     const bool wide = (dh & 15) == 0 && (Hd & 15) == 0 && ldq == Hd;
     const int64_t units = M * (wide ? ldq / 16 : ldq);

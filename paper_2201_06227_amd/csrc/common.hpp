@@ -303,13 +303,14 @@ hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, 
 // The same attention for unobserved runs: fp32 matrix-core arithmetic, then the int8 codes [B*S, ldq] and
 // the scale of the context as the fp64 evaluation defines them (values whose code the approximate result
 // does not settle are re-evaluated in fp64).  ctx receives the approximate context (scratch), records
-// attention_records_bytes(...) bytes of scratch, exact_slot an atomically combined maximum word (zero on
-// entry), unsure_total (nullable) is incremented by the number of re-evaluated values.
+// attention_records_bytes(...) bytes of scratch, amax_slot, err_slot and exact_slot atomically combined maximum
+// words (zero on entry), unsure_total (nullable) is incremented by the number of re-evaluated values.
 size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads);
 hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
                                  void *records, hipStream_t st);
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
-                                      void *records, uint32_t *exact_slot, int8_t *xq, int64_t ldq, float *scale_out,
+                                      void *records, uint32_t *amax_slot, uint32_t *err_slot, uint32_t *exact_slot,
+                                      int8_t *xq, int64_t ldq, float *scale_out,
                                       uint32_t *flag, uint32_t *unsure_total, hipStream_t st);
 
 // Training plasticity.  ws_part must hold plasticity_partial_bytes(b, D).
