@@ -722,6 +722,75 @@ __device__ __forceinline__ float context_exact(const float *__restrict__ qkv, in
     return (float)(o / l);
 }
 
+// The same value computed by one wave on its own (no workgroup barriers, so the four waves of a workgroup
+// work on four values at once): lane l takes keys l, l + 64, ... with an online soft-max over the passes.
+__device__ __forceinline__ float context_exact_wave(const float *__restrict__ qkv, int S, int Hd, int heads, int dh,
+                                                 double scale, uint32_t el)
+{
+    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
+    const uint32_t mrow = el / (uint32_t)Hd, col = el - mrow * (uint32_t)Hd;
+    const uint32_t bi = mrow / (uint32_t)S, hd = col / (uint32_t)dh, dd = col - hd * (uint32_t)dh;
+    const int64_t ld = 3 * (int64_t)Hd;
+    const float *q = qkv + (int64_t)mrow * ld + hd * dh;
+    const float *kb = qkv + (int64_t)bi * S * ld + Hd + hd * dh, *vb = kb + Hd + dd;
+    const int lane = threadIdx.x & 63;
+    const int units = dh >> 2;
+    double m = -INFINITY, l = 0.0, o = 0.0;
+    if (vec4) {
+        float4 qv[16];                                           // the whole query row in every lane (one line, broadcast)
+#pragma unroll
+        for (int u = 0; u < 16; ++u) qv[u] = *(const float4 *)(q + 4 * (u < units ? u : units - 1));
+        for (int j0 = 0; j0 < S; j0 += 64) {
+            const int j = j0 + lane;
+            const int jj = j < S ? j : S - 1;
+            const float *kr = kb + (int64_t)jj * ld;
+            float4 kv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kv[u] = *(const float4 *)(kr + 4 * (u < units ? u : units - 1));
+            const float vj = vb[(int64_t)jj * ld];
+            double acc = 0.0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (u < units) {
+                    acc = fma((double)qv[u].x, (double)kv[u].x, acc);
+                    acc = fma((double)qv[u].y, (double)kv[u].y, acc);
+                    acc = fma((double)qv[u].z, (double)kv[u].z, acc);
+                    acc = fma((double)qv[u].w, (double)kv[u].w, acc);
+                }
+            }
+            const double sc = j0 + lane < S ? acc * scale : -INFINITY;
+            double cm = sc;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) cm = fmax(cm, __shfl_xor(cm, off, kWave));
+            const double mnew = fmax(m, cm);
+            const double p = exp(sc - mnew);                     // exp(-inf) = 0 for the keys beyond S
+            const double corr = j0 == 0 ? 0.0 : exp(m - mnew);
+            l = l * corr + wave_sum(p);
+            o = o * corr + wave_sum(p * (double)vj);
+            m = mnew;
+        }
+    } else {
+        for (int j0 = 0; j0 < S; j0 += 64) {
+            const int j = j0 + lane;
+            const int jj = j < S ? j : S - 1;
+            const float *kr = kb + (int64_t)jj * ld;
+            double acc = 0.0;
+            for (int d = 0; d < dh; ++d) acc = fma((double)q[d], (double)kr[d], acc);
+            const double sc = j < S ? acc * scale : -INFINITY;
+            double cm = sc;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) cm = fmax(cm, __shfl_xor(cm, off, kWave));
+            const double mnew = fmax(m, cm);
+            const double p = exp(sc - mnew);
+            const double corr = j0 == 0 ? 0.0 : exp(m - mnew);
+            l = l * corr + wave_sum(p);
+            o = o * corr + wave_sum(p * (double)vb[(int64_t)jj * ld]);
+            m = mnew;
+        }
+    }
+    return (float)(o / l);
+}
+
 // Workgroup-uniform walk over the values a predicate marks among 256 consecutive candidates: every thread
 // passes its own flag, and `visit(k)` runs, in all threads, for every marked k = 0..255 in ascending order.
 template <typename F>
@@ -778,15 +847,19 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
     const int nq = S - qt * 64 < 64 ? S - qt * 64 : 64;
     const int n_el = nq * dh;
     uint32_t best = 0;
-    // candidates are found 256 values at a time and re-evaluated one by one by the workgroup
-    for (int base = 0; base < n_el; base += 256) {
-        const int idx = base + tid;
-        bool cand = false;
-        if (idx < n_el) {
-            const int qq = qt * 64 + idx / dh, d = idx % dh;
-            const float x = fabsf(ctx[(tok0 + qq) * Hd + hd * dh + d]);
-            cand = x + value_err(mine.err, x) >= floor_v;
-        }
+    // the block's values, sixteen per thread requested together (indices clamped, the surplus masked below);
+    // candidates are then taken 256 values at a time and re-evaluated one by one by the workgroup
+    float xs[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int idx = k * 256 + tid < n_el ? k * 256 + tid : 0;
+        xs[k] = fabsf(ctx[(tok0 + qt * 64 + idx / dh) * Hd + hd * dh + idx % dh]);
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int base = k * 256;
+        if (base >= n_el) break;
+        const bool cand = base + tid < n_el && xs[k] + value_err(mine.err, xs[k]) >= floor_v;
         for_each_marked(cand, masks, [&](int k) {
             const int cidx = base + k;
             const int qq = qt * 64 + cidx / dh, d = cidx % dh;
@@ -879,39 +952,39 @@ __global__ __launch_bounds__(256) void quantize_attention_scan_kernel(
     }
 }
 
-// A workgroup per listed value: fp64 re-evaluation, then its code replaces the provisional one.  If the
+// A wave per listed value: fp64 re-evaluation, then its code replaces the provisional one.  If the
 // list overflowed, the uncertain values are found again here instead: workgroups take 256 values of the
-// context at a time, apply the scan kernel's test and re-evaluate whatever fails it.
-__global__ __launch_bounds__(256, 4) void attention_fix_kernel(const float *__restrict__ qkv, const float *__restrict__ ctx,
+// context at a time, apply the scan kernel's test and their waves re-evaluate whatever fails it.
+__global__ __launch_bounds__(256, 2) void attention_fix_kernel(const float *__restrict__ qkv, const float *__restrict__ ctx,
                                                             const AttnRecord *__restrict__ rec, int64_t M, int S, int Hd,
                                                             int heads, int dh, double scale,
                                                             const uint32_t *__restrict__ exact, int8_t *__restrict__ xq,
                                                             int64_t ldq, const FixList *__restrict__ fix,
                                                             uint32_t *__restrict__ unsure_total)
 {
-    __shared__ __attribute__((aligned(16))) double red[12 + 32];
     float sc_f;
     bool bad;
     const float inv = scale_from_bits(reduce_ways(exact), nullptr, &sc_f, &bad);
     const uint32_t count = fix->count;
     if (blockIdx.x == 0 && threadIdx.x == 0 && unsure_total && count) atomicAdd(unsure_total, count);
     if (bad) return;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ uint32_t todo[256];
     __shared__ uint32_t n_todo;
     const bool listed = count <= kFixList;
     const uint32_t total = (uint32_t)(M * Hd), qtiles = (uint32_t)(S + 63) / 64u;
-    // batches of up to 256 values to re-evaluate: the workgroup's share of the list, or (list overflowed)
-    // whatever fails the scan kernel's test among 256 consecutive values of the context
-    const uint32_t n_batches = listed ? (count + gridDim.x - 1) / gridDim.x : (total + 255u) / 256u;
+    // batches: four listed values per workgroup (one per wave), or (list overflowed) whatever fails the scan
+    // kernel's test among 256 consecutive values of the context
+    const uint32_t n_batches = listed ? (count + 4u * gridDim.x - 1u) / (4u * gridDim.x) : (total + 255u) / 256u;
     for (uint32_t b = listed ? 0u : blockIdx.x; b < n_batches; b += listed ? 1u : gridDim.x) {
-        __syncthreads();                                          // todo is free
-        if (tid == 0) n_todo = 0;
-        __syncthreads();
+        uint32_t n, first = 0;
         if (listed) {
-            const uint32_t i = b * gridDim.x + blockIdx.x;        // one listed value per workgroup and batch
-            if (tid == 0 && i < count) { todo[0] = fix->entry[i]; n_todo = 1; }
+            first = (b * gridDim.x + blockIdx.x) * 4u;
+            n = first >= count ? 0u : (count - first < 4u ? count - first : 4u);
         } else {
+            __syncthreads();                                      // todo is free
+            if (tid == 0) n_todo = 0;
+            __syncthreads();
             const uint32_t el = b * 256u + (uint32_t)tid;
             if (el < total) {
                 const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
@@ -919,14 +992,14 @@ __global__ __launch_bounds__(256, 4) void attention_fix_kernel(const float *__re
                 if (code_uncertain(ctx[el], rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err, inv))
                     todo[atomicAdd(&n_todo, 1u)] = el;
             }
+            __syncthreads();
+            n = n_todo;
         }
-        __syncthreads();
-        const uint32_t n = n_todo;
-        for (uint32_t k = 0; k < n; ++k) {
-            const uint32_t el = todo[k];
-            const float x = context_exact(qkv, S, Hd, heads, dh, scale, el, red);
+        for (uint32_t k = (uint32_t)wave; k < n; k += 4u) {
+            const uint32_t el = (uint32_t)__builtin_amdgcn_readfirstlane((int)(listed ? fix->entry[first + k] : todo[k]));
+            const float x = context_exact_wave(qkv, S, Hd, heads, dh, scale, el);
             const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
-            if (tid == 0) xq[(int64_t)m * ldq + col] = (int8_t)quant1(x, inv);
+            if (lane == 0) xq[(int64_t)m * ldq + col] = (int8_t)quant1(x, inv);
         }
     }
 }
@@ -994,7 +1067,7 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
                      (const float *)ctx, (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh,
                      (const uint32_t *)exact_slot, xq, ldq, scale_out, flag, fix);
     if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_QUANTIZE, attention_fix_kernel, dim3(2048), dim3(256), 0, st, qkv, (const float *)ctx,
+    return launch_k(EGERIA_KERNEL_QUANTIZE, attention_fix_kernel, dim3(1024), dim3(256), 0, st, qkv, (const float *)ctx,
                     (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh, scale, (const uint32_t *)exact_slot, xq, ldq,
                     (const FixList *)fix, unsure_total);
 }
