@@ -47,6 +47,13 @@ egeria_status egeria_profile_end(float *ms_out, int32_t capacity, int32_t *n_out
 egeria_status egeria_profile_attention(const float *qkv, int32_t B, int32_t S, int32_t hidden, int32_t heads,
                                        int32_t mode, float *ctx, void *records, void *stream);
 
+/* Unobserved runs of the Transformer kinds evaluate attention with the certified fp32 kernels when the two
+ * products take at least this many flops (4 * batch * heads * seq^2 * head size; default 5e9), with the fp64
+ * kernel below it: the results are the same, the certified path has four launches of fixed cost.  Sets the
+ * threshold (a negative value leaves it unchanged) and returns the previous one; process-wide, for tests that
+ * exercise the certified kernels on small shapes. */
+double egeria_profile_attention_threshold(double min_flops);
+
 /* What the device delivers to kernels shaped like this library's: one small complete kernel per kind, run
  * twice (the second run is timed with events on `stream`).  ms_out: duration of that run; work_out: what it
  * did - operations (matrix instructions: 2 per multiply-add) or bytes (LDS, L2 -> LDS, copy: read + written).

@@ -99,6 +99,7 @@ EXPORTS = [
     "egeria_cache_bytes", "egeria_cache_init", "egeria_cache_put", "egeria_cache_get", "egeria_profile_pause",
     "egeria_refresh_eval", "egeria_plasticity_noalloc", "egeria_profile_attention",
     "egeria_quantize_affine", "egeria_quantize_affine_workspace_bytes", "egeria_microbench",
+    "egeria_profile_attention_threshold",
 ]
 
 (KERNEL_NONE, KERNEL_ABSMAX, KERNEL_QUANTIZE, KERNEL_GEMM, KERNEL_GRAM, KERNEL_ATTENTION, KERNEL_LAYERNORM,
@@ -167,6 +168,8 @@ def lib():
     L.egeria_profile_end.argtypes = [ctypes.POINTER(ctypes.c_float), _i32, ctypes.POINTER(_i32)]
     L.egeria_profile_attention.restype = ctypes.c_int
     L.egeria_profile_attention.argtypes = [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]
+    L.egeria_profile_attention_threshold.restype = ctypes.c_double
+    L.egeria_profile_attention_threshold.argtypes = [ctypes.c_double]
     L.egeria_microbench.restype = ctypes.c_int
     L.egeria_microbench.argtypes = [_i32, _i32, _vp, _sz, ctypes.POINTER(ctypes.c_float),
                                     ctypes.POINTER(ctypes.c_double), _vp]
@@ -517,6 +520,11 @@ def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torc
 MICRO_KINDS = ["mfma_i32_32x32x32_i8", "mfma_f32_32x32x16_bf16", "mfma_f32_32x32x2_f32", "mfma_f32_16x16x4_f32",
                "mfma_f64_16x16x4_f64", "lds_read_b128", "lds_write_b128", "l2_to_lds_whole_lines", "l2_to_lds_half_lines",
                "hbm_copy"]
+
+
+def attention_threshold(min_flops: float = -1.0) -> float:
+    """egeria_profile_attention_threshold: sets (if >= 0) and returns the previous threshold."""
+    return float(lib().egeria_profile_attention_threshold(float(min_flops)))
 
 
 def microbench(kind: int, iters: int, scratch: torch.Tensor):

@@ -425,6 +425,10 @@ egeria_status forward_float(Fwd &f, const void *x, egeria_dtype dt, float *a_ref
     return run_gemm(f, 2, f.qbuf(2), cmid_b, M, d->c_out, cmid_b, false, 0, 0, 0, one, 1, res, one, res_ld, a_ref, nullptr);
 }
 
+// Attention sizes (flops of the two products) from which unobserved runs take the certified fp32 kernels;
+// egeria_profile_attention_threshold lets tests run them on small shapes too.
+double g_attention_min_flops = 5.0e9;
+
 // One encoder layer: `cur` -> `out`.  slot 4l must already hold absmax(cur).
 egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *out, bool last)
 {
@@ -442,8 +446,11 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
                                     f.scale(s0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
     EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
-    if (f.taps) {
-        // observed runs: the context itself in fp64, then the plain quantiser
+    // The certified fp32 attention is four launches with about 70 us of fixed cost between them; it pays when the
+    // fp64 kernel would take longer than that (cfg 4, one layer of 32 x 128 tokens: fp64 46 us; cfg 5: 315 us).
+    const double attention_flops = 4.0 * d->batch * d->heads * (double)d->seq * d->seq * (Hd / d->heads);
+    if (f.taps || attention_flops < g_attention_min_flops) {
+        // observed runs (and small ones): the context itself in fp64, then the plain quantiser
         EG_HIP(launch_attention(qkv, d->batch, d->seq, Hd, d->heads, ctx, f.slot(s0 + 1), f.st));
         EG_HIP(launch_quantize_rows(ctx, EGERIA_F32, M, Hd, hp, f.amax(s0 + 1), f.n_amax(s0 + 1), f.stride_amax(s0 + 1),
                                     nullptr, xq, f.scale(s0 + 1), nullptr, ws_flag(f.ws), f.st));
@@ -1113,6 +1120,13 @@ egeria_status egeria_profile_attention(const float *qkv, int32_t B, int32_t S, i
     if (mode == 0) EG_HIP(launch_attention(qkv, B, S, hidden, heads, ctx, nullptr, (hipStream_t)stream));
     else EG_HIP(launch_attention_fast(qkv, B, S, hidden, heads, ctx, records, (hipStream_t)stream));
     return EGERIA_OK;
+}
+
+double egeria_profile_attention_threshold(double min_flops)
+{
+    const double old = g_attention_min_flops;
+    if (min_flops >= 0.0) g_attention_min_flops = min_flops;
+    return old;
 }
 
 const char *egeria_status_string(egeria_status s)

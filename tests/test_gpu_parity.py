@@ -31,6 +31,16 @@ def gc():
     return gpu_common
 
 
+@pytest.fixture(autouse=True)
+def certified_attention_at_every_size(eg):
+    """Unobserved Transformer runs take the certified fp32 attention kernels only above a size threshold (below
+    it the fp64 kernel is faster); the tests of this module exercise those kernels on small and ragged shapes
+    too.  test_attention_paths_agree covers the default choice."""
+    old = eg.attention_threshold(0.0)
+    yield
+    eg.attention_threshold(old)
+
+
 P_RTOL = 1e-4
 
 
@@ -534,6 +544,26 @@ def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
     for l in range(kw["n_layers"]):
         want = orc.sp_loss(a_t[l].numpy(), ot["a_ref"][l])
         assert p_close(p[l].item(), want, kw["b"]), (l, p[l].item(), want)
+
+
+def test_attention_paths_agree(eg, gc):
+    """The two evaluations of attention in unobserved runs (fp64 kernel below the size threshold, certified fp32
+    kernels above it) and the observed run give the same A_R bit for bit."""
+    wl = si.make_bert(b=3, s=77, hidden=200, heads=5, ffn=328, n_layers=2, seed=61, train_act_dtype="f32")
+    ref = gc.build_reference(wl)
+    x = gc.to_dev(wl.x)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    outs = []
+    for thr in (0.0, 5.0e9):
+        eg.attention_threshold(thr)
+        a = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+        eg.ref_forward(ref, x, a, ws)
+        torch.cuda.synchronize()
+        assert eg.check(ws) == eg.OK
+        outs.append(a)
+    observed, _, _ = gc.run_forward(wl)
+    assert torch.equal(outs[0], outs[1])
+    assert np.array_equal(outs[0].cpu().numpy().reshape(observed.shape), observed)
 
 
 def test_bert_small_preactivations(eg, gc, orc):
