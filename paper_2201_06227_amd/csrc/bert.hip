@@ -2,6 +2,7 @@
 // under dynamic quantisation (Section 5 of the paper) only the linear layers
 // are int8; self-attention and layer norm read and write fp32 tensors.
 #include "common.hpp"
+#include <type_traits>
 
 namespace egeria {
 
@@ -391,16 +392,16 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 
 // ---- the same attention on the fp32 matrix-core instructions, with certified int8 codes ----------
 // Unobserved runs do not need the context as the fp64 evaluation gives it: all that leaves this stage
-// is the int8 input of the next GEMM and its scale.  Four launches:
+// is the int8 input of the next GEMM and its scale.  Three launches:
 //   1. attention_fast_kernel: the structure of the kernel above in fp32 (v_mfma_f32_16x16x4f32, hardware
 //      exp2), 2.2x faster.  It stores an approximate context and, per workgroup, a record: the largest
 //      |context| it stored and an error bound E for its values (below).
 //   2. attention_absmax_exact_kernel: the tensor's absolute maximum as the fp64 evaluation gives it.  Every
 //      value that can be the maximum (|x| + E >= largest |x| - largest E; as a rule one) is re-evaluated in fp64.
-//   3. quantize_attention_scan_kernel: the streaming map to codes.  code(x) = clamp(rne(x * inv)) is
+//   3. quantize_attention_certify_kernel: the streaming map to codes.  code(x) = clamp(rne(x * inv)) is
 //      monotone in x, so an approximate value whose interval [x - E, x + E] maps to one code has that
-//      code; the others (a few in ten thousand) are put on a list.
-//   4. attention_fix_kernel: a wave per listed value re-evaluates it in fp64 and stores its code.
+//      code; the others (a few in ten thousand) are re-evaluated in fp64, a wave per value, by the
+//      workgroup that met them.
 // The bound of a value x: E = 2^-24 * (max|v| of the head * (kErrBase + kErrPerScore * max|score| of the
 // workgroup) + kErrRel |x|).  It is an empirical bound with margin, not a proof: bench.py --attention-error
 // measures kernel 1 against the fp64 kernel on the twelve layers of the BERT-base-shaped stack (12.6 M
@@ -722,75 +723,6 @@ __device__ __forceinline__ float context_exact(const float *__restrict__ qkv, in
     return (float)(o / l);
 }
 
-// The same value computed by one wave on its own (no workgroup barriers, so the four waves of a workgroup
-// work on four values at once): lane l takes keys l, l + 64, ... with an online soft-max over the passes.
-__device__ __forceinline__ float context_exact_wave(const float *__restrict__ qkv, int S, int Hd, int heads, int dh,
-                                                 double scale, uint32_t el)
-{
-    const bool vec4 = (dh & 3) == 0 && (Hd & 3) == 0;
-    const uint32_t mrow = el / (uint32_t)Hd, col = el - mrow * (uint32_t)Hd;
-    const uint32_t bi = mrow / (uint32_t)S, hd = col / (uint32_t)dh, dd = col - hd * (uint32_t)dh;
-    const int64_t ld = 3 * (int64_t)Hd;
-    const float *q = qkv + (int64_t)mrow * ld + hd * dh;
-    const float *kb = qkv + (int64_t)bi * S * ld + Hd + hd * dh, *vb = kb + Hd + dd;
-    const int lane = threadIdx.x & 63;
-    const int units = dh >> 2;
-    double m = -INFINITY, l = 0.0, o = 0.0;
-    if (vec4) {
-        float4 qv[16];                                           // the whole query row in every lane (one line, broadcast)
-#pragma unroll
-        for (int u = 0; u < 16; ++u) qv[u] = *(const float4 *)(q + 4 * (u < units ? u : units - 1));
-        for (int j0 = 0; j0 < S; j0 += 64) {
-            const int j = j0 + lane;
-            const int jj = j < S ? j : S - 1;
-            const float *kr = kb + (int64_t)jj * ld;
-            float4 kv[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) kv[u] = *(const float4 *)(kr + 4 * (u < units ? u : units - 1));
-            const float vj = vb[(int64_t)jj * ld];
-            double acc = 0.0;
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                if (u < units) {
-                    acc = fma((double)qv[u].x, (double)kv[u].x, acc);
-                    acc = fma((double)qv[u].y, (double)kv[u].y, acc);
-                    acc = fma((double)qv[u].z, (double)kv[u].z, acc);
-                    acc = fma((double)qv[u].w, (double)kv[u].w, acc);
-                }
-            }
-            const double sc = j0 + lane < S ? acc * scale : -INFINITY;
-            double cm = sc;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) cm = fmax(cm, __shfl_xor(cm, off, kWave));
-            const double mnew = fmax(m, cm);
-            const double p = exp(sc - mnew);                     // exp(-inf) = 0 for the keys beyond S
-            const double corr = j0 == 0 ? 0.0 : exp(m - mnew);
-            l = l * corr + wave_sum(p);
-            o = o * corr + wave_sum(p * (double)vj);
-            m = mnew;
-        }
-    } else {
-        for (int j0 = 0; j0 < S; j0 += 64) {
-            const int j = j0 + lane;
-            const int jj = j < S ? j : S - 1;
-            const float *kr = kb + (int64_t)jj * ld;
-            double acc = 0.0;
-            for (int d = 0; d < dh; ++d) acc = fma((double)q[d], (double)kr[d], acc);
-            const double sc = j < S ? acc * scale : -INFINITY;
-            double cm = sc;
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) cm = fmax(cm, __shfl_xor(cm, off, kWave));
-            const double mnew = fmax(m, cm);
-            const double p = exp(sc - mnew);
-            const double corr = j0 == 0 ? 0.0 : exp(m - mnew);
-            l = l * corr + wave_sum(p);
-            o = o * corr + wave_sum(p * (double)vb[(int64_t)jj * ld]);
-            m = mnew;
-        }
-    }
-    return (float)(o / l);
-}
-
 // Workgroup-uniform walk over the values a predicate marks among 256 consecutive candidates: every thread
 // passes its own flag, and `visit(k)` runs, in all threads, for every marked k = 0..255 in ascending order.
 template <typename F>
@@ -822,10 +754,8 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
                                                                      const uint32_t *__restrict__ amax_slot,
                                                                      const uint32_t *__restrict__ err_slot,
                                                                      int S, int Hd, int heads, int dh, double scale,
-                                                                     uint32_t *__restrict__ exact,
-                                                                     uint32_t *__restrict__ list_count)
+                                                                     uint32_t *__restrict__ exact)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *list_count = 0u;      // the list the next kernel fills
     __shared__ __attribute__((aligned(16))) double red[12 + 32];
     __shared__ uint64_t masks[4];
     const int tid = threadIdx.x;
@@ -871,19 +801,22 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
     if (tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, best);
 }
 
-// The int8 codes of the context under the tensor's exact scale, as a streaming pass over the approximate
-// context: a thread maps 16 consecutive values of a token row (one 16-byte store; WIDE: head size and row
-// length are multiples of 16, so the sixteen share a head) or a single value.  A value whose interval
-// [x - E, x + E] maps to two codes is appended to a list in global memory (its index in the [tokens, Hd]
-// tensor) and gets a provisional code; attention_fix_kernel re-evaluates the listed values in fp64.  The list
-// holds kFixList entries, far above the one value in a few thousand that is uncertain; if it overflows
-// all the same, attention_fix_kernel finds the uncertain values by a scan of its own.
-constexpr uint32_t kFixList = 1u << 16;
-struct FixList {
-    uint32_t count;                 // uncertain values met (entries beyond kFixList are not stored)
-    uint32_t pad[3];
-    uint32_t entry[kFixList];
-};
+// The int8 codes of the context under the tensor's exact scale: one workgroup per (batch element, head).
+// It streams over the head's slice of the approximate context, 256 units a pass: a thread maps 16
+// consecutive values of a token row (one 16-byte store; WIDE: head size and row length are multiples of
+// 16) or a single value.  A value whose interval [x - E, x + E] maps to two codes gets a provisional code
+// and goes on the workgroup's list in LDS (token * dh + dim within the head; the list has room for every
+// value of a pass).  After each pass the workgroup re-evaluates the listed values in fp64 and overwrites
+// their codes.  A re-evaluation needs all keys of its head (S x dh floats): read from global memory per
+// value, that traffic (and the sixteen-byte pieces of 256 different rows each load instruction asks
+// for) bounds the whole step.  KLDS (S <= 256, head size a multiple of 4): the workgroup copies the
+// head's keys into LDS once, with coalesced loads, and each of its waves re-evaluates one listed value
+// at a time from there: lane l holds keys l, l + 64, ..., a row of LDS each (rows padded by 16 bytes,
+// so the lanes' 16-byte reads do not collide), the query row is broadcast from LDS, and only the value
+// column (one float per key) comes from global memory.  Otherwise the workgroup-wide evaluation above
+// is used, one value after the other.
+constexpr int kKeysLds = 256;            // keys a workgroup can hold
+constexpr int kKeyRow = kDh + 4;         // floats per key row in LDS (one 16-byte pad)
 
 // true if the approximate value x with error bound err does not settle its code
 // (The exact value y lies in [x - e, x + e]; its code is clamp(rne(fl(y * inv))) with fl(y * inv) within
@@ -896,119 +829,208 @@ __device__ __forceinline__ bool code_uncertain(float x, float err, float inv)
     return !(fabsf(t - rintf(t)) + reach < 0.5f);                  // also true for a non-finite bound
 }
 
-template <bool WIDE>
-__global__ __launch_bounds__(256) void quantize_attention_scan_kernel(
-    const float *__restrict__ ctx, const AttnRecord *__restrict__ rec, int64_t M, int S, int Hd, int heads, int dh,
-    const uint32_t *__restrict__ exact, int8_t *__restrict__ xq, int64_t ldq, float *__restrict__ scale_out,
-    uint32_t *__restrict__ flag, FixList *__restrict__ fix)
+template <bool WIDE, bool KLDS>
+__global__ __launch_bounds__(256, KLDS ? 2 : 3) void quantize_attention_certify_kernel(
+    const float *__restrict__ qkv, const float *__restrict__ ctx, const AttnRecord *__restrict__ rec, int S, int Hd,
+    int heads, int dh, double scale, const uint32_t *__restrict__ exact, int8_t *xq, int64_t ldq,
+    float *__restrict__ scale_out, uint32_t *__restrict__ flag, uint32_t *__restrict__ unsure_total)
 {
+    constexpr int PER = WIDE ? 16 : 1;                            // values of a unit
+    constexpr int NPRE = WIDE && KLDS ? 4 : 1;                    // passes whose loads are requested together
+    constexpr uint32_t kList = 4096;                              // list entries served per round
+    using Entry = std::conditional_t<KLDS, uint16_t, uint32_t>;   // KLDS: S * dh <= 256 * 64
+    __shared__ Entry todo[kList];
+    __shared__ uint32_t n_todo, more;
+    __shared__ __attribute__((aligned(16))) double red[KLDS ? 2 : 12 + 32];
+    __shared__ __attribute__((aligned(16))) float ks[KLDS ? kKeysLds * kKeyRow : 4];
+    __shared__ __attribute__((aligned(16))) float qs[KLDS ? 4 * kDh : 4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t bh = blockIdx.x, bi = bh / (uint32_t)heads, hd = bh - bi * (uint32_t)heads;
+    const uint32_t qtiles = (uint32_t)(S + 63) / 64u;
+    const uint32_t tok0 = bi * (uint32_t)S;
+    const int64_t ld = 3 * (int64_t)Hd;
+    const float *qb = qkv + (int64_t)tok0 * ld + hd * dh, *kb = qb + Hd, *vb = kb + Hd;
+    // units per token: 16-value groups of the head, or single columns (the last head also clears the pad
+    // columns [Hd, ldq) of its tokens)
+    const uint32_t upt = WIDE ? (uint32_t)dh / 16u : (uint32_t)dh + (hd + 1u == (uint32_t)heads ? (uint32_t)(ldq - Hd) : 0u);
+    const uint32_t units = (uint32_t)S * upt;
+    // a group of passes: unit `first + 256 i + tid` is this thread's in pass i (clamped to a valid one for
+    // the loads; the surplus is masked where it is used)
+    float4 v[NPRE][WIDE ? 4 : 1];
+    auto request = [&](uint32_t first) {
+#pragma unroll
+        for (int i = 0; i < NPRE; ++i) {
+            const uint32_t u = first + 256u * i + (uint32_t)tid, uc = u < units ? u : units - 1u;
+            const uint32_t t = uc / upt, part = uc - t * upt;
+            if (WIDE) {
+                const float4 *p = (const float4 *)(ctx + (int64_t)(tok0 + t) * Hd + hd * (uint32_t)dh + part * 16u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[i][j] = p[j];
+            } else {
+                const uint32_t col = hd * (uint32_t)dh + part;
+                v[i][0].x = ctx[(int64_t)(tok0 + t) * Hd + (col < (uint32_t)Hd ? col : (uint32_t)Hd - 1u)];
+            }
+        }
+    };
+    request(0);
+    if (KLDS) {
+        // the head's keys, eight 16-byte pieces per thread in flight (the first barrier below orders them
+        // before any read)
+        const int cpr = dh >> 2, total = S * cpr;
+        for (int c0 = 0; c0 < total; c0 += 256 * 8) {
+            float4 t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = c0 + i * 256 + tid;
+                const int cc = c < total ? c : total - 1;
+                t[i] = *(const float4 *)(kb + (int64_t)(cc / cpr) * ld + 4 * (cc % cpr));
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = c0 + i * 256 + tid;
+                if (c < total) *(float4 *)&ks[(c / cpr) * kKeyRow + 4 * (c % cpr)] = t[i];
+            }
+        }
+    }
     float sc_f;
     bool bad;
     const float inv = scale_from_bits(reduce_ways(exact), nullptr, &sc_f, &bad);
     if (blockIdx.x == 0 && threadIdx.x == 0) publish(sc_f, bad, scale_out, nullptr, flag);
-    const uint32_t qtiles = (uint32_t)(S + 63) / 64u;
-    const uint32_t upr = (uint32_t)(WIDE ? ldq / 16 : ldq);      // units per int8 row (pad columns included when !WIDE)
-    const uint32_t units = (uint32_t)M * upr;                    // below 2^32 (checked by the launcher)
-    for (uint32_t u = blockIdx.x * 256u + threadIdx.x; u < units; u += gridDim.x * 256u) {
-        const uint32_t m = u / upr, cu = u - m * upr;
-        const uint32_t bi = m / (uint32_t)S, s_idx = m - bi * (uint32_t)S;
-        if (WIDE) {
-            const uint32_t col = cu * 16u, hd = col / (uint32_t)dh;
-            const float err = rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err;
-            const float4 *p = (const float4 *)(ctx + (int64_t)m * Hd + col);
-            float4 v[4];
+    uint32_t met = 0;
+    // the loop bounds are the same in every thread of the workgroup (barriers inside)
+    for (uint32_t first = 0; first < units; first += 256u * NPRE) {
+        if (first) request(first);
+        // provisional codes; pend[i]: which of the unit's values do not settle their code
+        uint32_t pend[NPRE], at[NPRE];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = p[j];
-            uint32_t w[4];
-            uint32_t unsure = 0;
+        for (int i = 0; i < NPRE; ++i) {
+            const uint32_t u = first + 256u * i + (uint32_t)tid;
+            pend[i] = 0;
+            at[i] = 0;
+            if (u < units) {
+                const uint32_t t = u / upt, part = u - t * upt;
+                const uint32_t m = tok0 + t;
+                const float err = rec[bh * qtiles + t / 64u].err;
+                if (WIDE) {
+                    const uint32_t col = hd * (uint32_t)dh + part * 16u;
+                    uint32_t w[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                w[j] = quant1(v[j].x, inv) | quant1(v[j].y, inv) << 8 | quant1(v[j].z, inv) << 16 | quant1(v[j].w, inv) << 24;
-                unsure |= (code_uncertain(v[j].x, err, inv) ? 1u : 0u) << (4 * j) | (code_uncertain(v[j].y, err, inv) ? 2u : 0u) << (4 * j) |
-                          (code_uncertain(v[j].z, err, inv) ? 4u : 0u) << (4 * j) | (code_uncertain(v[j].w, err, inv) ? 8u : 0u) << (4 * j);
+                    for (int j = 0; j < 4; ++j) {
+                        const float4 x = v[i][j];
+                        w[j] = quant1(x.x, inv) | quant1(x.y, inv) << 8 | quant1(x.z, inv) << 16 | quant1(x.w, inv) << 24;
+                        pend[i] |= (code_uncertain(x.x, err, inv) ? 1u : 0u) << (4 * j) | (code_uncertain(x.y, err, inv) ? 2u : 0u) << (4 * j) |
+                                   (code_uncertain(x.z, err, inv) ? 4u : 0u) << (4 * j) | (code_uncertain(x.w, err, inv) ? 8u : 0u) << (4 * j);
+                    }
+                    *(uint4 *)(xq + (int64_t)m * ldq + col) = make_uint4(w[0], w[1], w[2], w[3]);
+                    at[i] = t * (uint32_t)dh + part * 16u;
+                } else {
+                    const uint32_t col = hd * (uint32_t)dh + part;
+                    uint32_t code = 0;
+                    if (col < (uint32_t)Hd) {
+                        code = quant1(v[i][0].x, inv);
+                        pend[i] = code_uncertain(v[i][0].x, err, inv) ? 1u : 0u;
+                    }
+                    xq[(int64_t)m * ldq + col] = (int8_t)code;   // pad columns: zero
+                    at[i] = t * (uint32_t)dh + part;
+                }
+                if (bad) pend[i] = 0;
             }
-            *(uint4 *)(xq + (int64_t)m * ldq + col) = make_uint4(w[0], w[1], w[2], w[3]);
-            if (bad) unsure = 0;
-            while (unsure) {
-                const int e = __ffs((int)unsure) - 1;
-                unsure &= unsure - 1;
-                const uint32_t at = atomicAdd(&fix->count, 1u);
-                if (at < kFixList) fix->entry[at] = m * (uint32_t)Hd + col + (uint32_t)e;
-            }
-        } else {
-            uint32_t code = 0;
-            if (cu < (uint32_t)Hd) {
-                const float x = ctx[(int64_t)m * Hd + cu];
-                const uint32_t hd = cu / (uint32_t)dh;
-                const float err = rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err;
-                code = quant1(x, inv);
-                if (!bad && code_uncertain(x, err, inv)) {
-                    const uint32_t at = atomicAdd(&fix->count, 1u);
-                    if (at < kFixList) fix->entry[at] = m * (uint32_t)Hd + cu;
+        }
+        // rounds: the pending values go on the list (as many as it holds), the workgroup serves the list
+        bool again;
+        do {
+            __syncthreads();                                      // the list of the round before has been served
+            if (tid == 0) { n_todo = 0; more = 0; }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NPRE; ++i) {
+                while (pend[i]) {
+                    const uint32_t slot = atomicAdd(&n_todo, 1u);
+                    if (slot >= kList) { more = 1; break; }
+                    const int e = __ffs((int)pend[i]) - 1;
+                    pend[i] &= pend[i] - 1;
+                    todo[slot] = (Entry)(at[i] + (uint32_t)e);
                 }
             }
-            xq[(int64_t)m * ldq + cu] = (int8_t)code;            // pad columns: zero
-        }
-    }
-}
-
-// A wave per listed value: fp64 re-evaluation, then its code replaces the provisional one.  If the
-// list overflowed, the uncertain values are found again here instead: workgroups take 256 values of the
-// context at a time, apply the scan kernel's test and their waves re-evaluate whatever fails it.
-__global__ __launch_bounds__(256, 2) void attention_fix_kernel(const float *__restrict__ qkv, const float *__restrict__ ctx,
-                                                            const AttnRecord *__restrict__ rec, int64_t M, int S, int Hd,
-                                                            int heads, int dh, double scale,
-                                                            const uint32_t *__restrict__ exact, int8_t *__restrict__ xq,
-                                                            int64_t ldq, const FixList *__restrict__ fix,
-                                                            uint32_t *__restrict__ unsure_total)
-{
-    float sc_f;
-    bool bad;
-    const float inv = scale_from_bits(reduce_ways(exact), nullptr, &sc_f, &bad);
-    const uint32_t count = fix->count;
-    if (blockIdx.x == 0 && threadIdx.x == 0 && unsure_total && count) atomicAdd(unsure_total, count);
-    if (bad) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ uint32_t todo[256];
-    __shared__ uint32_t n_todo;
-    const bool listed = count <= kFixList;
-    const uint32_t total = (uint32_t)(M * Hd), qtiles = (uint32_t)(S + 63) / 64u;
-    // batches: four listed values per workgroup (one per wave), or (list overflowed) whatever fails the scan
-    // kernel's test among 256 consecutive values of the context
-    const uint32_t n_batches = listed ? (count + 4u * gridDim.x - 1u) / (4u * gridDim.x) : (total + 255u) / 256u;
-    for (uint32_t b = listed ? 0u : blockIdx.x; b < n_batches; b += listed ? 1u : gridDim.x) {
-        uint32_t n, first = 0;
-        if (listed) {
-            first = (b * gridDim.x + blockIdx.x) * 4u;
-            n = first >= count ? 0u : (count - first < 4u ? count - first : 4u);
-        } else {
-            __syncthreads();                                      // todo is free
-            if (tid == 0) n_todo = 0;
-            __syncthreads();
-            const uint32_t el = b * 256u + (uint32_t)tid;
-            if (el < total) {
-                const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
-                const uint32_t bi = m / (uint32_t)S, s_idx = m - bi * (uint32_t)S, hd = col / (uint32_t)dh;
-                if (code_uncertain(ctx[el], rec[(bi * (uint32_t)heads + hd) * qtiles + s_idx / 64u].err, inv))
-                    todo[atomicAdd(&n_todo, 1u)] = el;
+            __syncthreads();                                      // list complete, provisional codes stored
+            const uint32_t n = n_todo < kList ? n_todo : kList;
+            again = more != 0;
+            met += n;
+            if (KLDS) {
+                const int cpr = dh >> 2, nk = (S + 63) >> 6;      // 16-byte pieces per row, keys per lane
+                for (uint32_t k0 = 0; k0 < n; k0 += 4u) {         // a value per wave
+                    const uint32_t k = k0 + (uint32_t)wave;
+                    const bool active = k < n;
+                    const uint32_t e = todo[active ? k : k0];
+                    const uint32_t t = e / (uint32_t)dh, d = e - t * (uint32_t)dh;
+                    float vj[4];
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        const int j = lane + 64 * kk;
+                        vj[kk] = vb[(int64_t)(j < S ? j : S - 1) * ld + d];
+                    }
+                    qs[wave * kDh + lane] = lane < dh ? qb[(int64_t)t * ld + lane] : 0.0f;
+                    __syncthreads();
+                    if (active) {
+                        // a product of two fp32 values is exact in fp64, so each fma is the multiply and the
+                        // add of the plain definition, dims in ascending order
+                        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                        for (int u4 = 0; u4 < kDh / 4; ++u4) {
+                            if (u4 < cpr) {
+                                const float4 qv = *(const float4 *)&qs[wave * kDh + 4 * u4];
+#pragma unroll
+                                for (int kk = 0; kk < 4; ++kk) {
+                                    if (kk < nk) {
+                                        const int j = lane + 64 * kk;
+                                        const float4 kv = *(const float4 *)&ks[(j < S ? j : S - 1) * kKeyRow + 4 * u4];
+                                        acc[kk] = fma((double)qv.x, (double)kv.x, acc[kk]);
+                                        acc[kk] = fma((double)qv.y, (double)kv.y, acc[kk]);
+                                        acc[kk] = fma((double)qv.z, (double)kv.z, acc[kk]);
+                                        acc[kk] = fma((double)qv.w, (double)kv.w, acc[kk]);
+                                    }
+                                }
+                            }
+                        }
+                        double sc[4], mx = -INFINITY;
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) {
+                            sc[kk] = lane + 64 * kk < S ? acc[kk] * scale : -INFINITY;
+                            mx = fmax(mx, sc[kk]);
+                        }
+#pragma unroll
+                        for (int off = 32; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, kWave));
+                        double l = 0.0, o = 0.0;
+#pragma unroll
+                        for (int kk = 0; kk < 4; ++kk) {
+                            const double pr = exp(sc[kk] - mx);      // exp(-inf) = 0 for the keys beyond S
+                            l += pr;
+                            o += pr * (double)vj[kk];
+                        }
+                        l = wave_sum(l);
+                        o = wave_sum(o);
+                        if (lane == 0) xq[(int64_t)(tok0 + t) * ldq + hd * dh + d] = (int8_t)quant1((float)(o / l), inv);
+                    }
+                    __syncthreads();                              // qs is free
+                }
+            } else {
+                for (uint32_t k = 0; k < n; ++k) {
+                    const uint32_t e = (uint32_t)__builtin_amdgcn_readfirstlane((int)todo[k]);
+                    const uint32_t t = e / (uint32_t)dh, d = e - t * (uint32_t)dh;
+                    const float x = context_exact(qkv, S, Hd, heads, dh, scale, (tok0 + t) * (uint32_t)Hd + hd * (uint32_t)dh + d, red);
+                    if (tid == 0) xq[(int64_t)(tok0 + t) * ldq + hd * dh + d] = (int8_t)quant1(x, inv);
+                }
             }
-            __syncthreads();
-            n = n_todo;
-        }
-        for (uint32_t k = (uint32_t)wave; k < n; k += 4u) {
-            const uint32_t el = (uint32_t)__builtin_amdgcn_readfirstlane((int)(listed ? fix->entry[first + k] : todo[k]));
-            const float x = context_exact_wave(qkv, S, Hd, heads, dh, scale, el);
-            const uint32_t m = el / (uint32_t)Hd, col = el - m * (uint32_t)Hd;
-            if (lane == 0) xq[(int64_t)m * ldq + col] = (int8_t)quant1(x, inv);
-        }
+        } while (again);
     }
+    if (tid == 0 && unsure_total && met) atomicAdd(unsure_total, met);
 }
 
 static bool attn_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads)
 {
-    return align_up(sizeof(FixList), 256) + align_up((size_t)B * heads * ((S + 63) / 64) * sizeof(AttnRecord), 256);
+    return align_up((size_t)B * heads * ((S + 63) / 64) * sizeof(AttnRecord), 256);
 }
 
 // Kernel 1 alone (benchmark instrumentation: its error against the fp64 kernel): approximate context and the
@@ -1040,8 +1062,7 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
     // 16-byte vector accesses may touch when the head size allows them
     if (dh > kDh || grid > 0x7ffffff0LL || M * Hd >= (1LL << 32) || ldq < Hd) return hipErrorInvalidValue;
     if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(xq) || !attn_aligned16(records)) return hipErrorInvalidValue;
-    FixList *fix = (FixList *)records;
-    AttnRecord *rec = (AttnRecord *)((char *)records + align_up(sizeof(FixList), 256));
+    AttnRecord *rec = (AttnRecord *)records;
     const int per_xcd = (int)((grid + 7) / 8);
     const double scale = 1.0 / sqrt((double)dh);
     hipError_t e = launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
@@ -1051,25 +1072,19 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
     const int nrec = (int)grid;
     e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)nrec), dim3(256), 0, st, qkv,
                  (const float *)ctx, (const AttnRecord *)rec, (const uint32_t *)amax_slot, (const uint32_t *)err_slot, (int)S,
-                 (int)Hd, (int)heads, dh, scale, exact_slot, &fix->count);
+                 (int)Hd, (int)heads, dh, scale, exact_slot);
     if (e != hipSuccess) return e;
     const bool wide = (dh & 15) == 0 && (Hd & 15) == 0 && ldq == Hd;
-    const int64_t units = M * (wide ? ldq / 16 : ldq);
-    if (units >= (1LL << 32)) return hipErrorInvalidValue;
-    int64_t blocks = (units + 255) / 256;
-    blocks = blocks > 8192 ? 8192 : (blocks < 1 ? 1 : blocks);
-    if (wide)
-        e = launch_k(EGERIA_KERNEL_QUANTIZE, quantize_attention_scan_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st,
-                     (const float *)ctx, (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh,
-                     (const uint32_t *)exact_slot, xq, ldq, scale_out, flag, fix);
-    else
-        e = launch_k(EGERIA_KERNEL_QUANTIZE, quantize_attention_scan_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st,
-                     (const float *)ctx, (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh,
-                     (const uint32_t *)exact_slot, xq, ldq, scale_out, flag, fix);
-    if (e != hipSuccess) return e;
-    return launch_k(EGERIA_KERNEL_QUANTIZE, attention_fix_kernel, dim3(1024), dim3(256), 0, st, qkv, (const float *)ctx,
-                    (const AttnRecord *)rec, M, (int)S, (int)Hd, (int)heads, dh, scale, (const uint32_t *)exact_slot, xq, ldq,
-                    (const FixList *)fix, unsure_total);
+    if ((int64_t)S * (dh + (ldq - Hd)) >= (1LL << 31)) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((int64_t)B * heads);
+    const bool klds = S <= kKeysLds && (dh & 3) == 0 && (Hd & 3) == 0;
+    auto go = [&](auto kernel) {
+        return launch_k(EGERIA_KERNEL_QUANTIZE, kernel, dim3(blocks), dim3(256), 0, st, qkv, (const float *)ctx,
+                        (const AttnRecord *)rec, (int)S, (int)Hd, (int)heads, dh, scale, (const uint32_t *)exact_slot, xq,
+                        ldq, scale_out, flag, unsure_total);
+    };
+    if (wide) return klds ? go(quantize_attention_certify_kernel<true, true>) : go(quantize_attention_certify_kernel<true, false>);
+    return klds ? go(quantize_attention_certify_kernel<false, true>) : go(quantize_attention_certify_kernel<false, false>);
 }
 
 hipError_t launch_attention(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads,

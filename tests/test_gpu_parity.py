@@ -546,10 +546,19 @@ def test_bert_modules_bit_exact_and_scored(eg, gc, orc, kw):
         assert p_close(p[l].item(), want, kw["b"]), (l, p[l].item(), want)
 
 
-def test_attention_paths_agree(eg, gc):
+# shapes that reach each variant of the certification kernel: keys held in LDS or read from global memory
+# (more than 256 keys, or a head size that is no multiple of 4), 16 values or one value per thread
+ATTENTION_SHAPES = [dict(b=3, s=77, hidden=200, heads=5, ffn=328, n_layers=2),      # keys in LDS, single values
+                    dict(b=2, s=200, hidden=128, heads=2, ffn=64, n_layers=2),      # keys in LDS, 16 per thread
+                    dict(b=1, s=300, hidden=96, heads=3, ffn=64, n_layers=2),       # keys from global memory, 16 per thread
+                    dict(b=2, s=70, hidden=66, heads=3, ffn=40, n_layers=2)]        # head size 22: plain loop
+
+
+@pytest.mark.parametrize("kw", ATTENTION_SHAPES, ids=lambda k: "b{b}_s{s}_h{hidden}_heads{heads}".format(**k))
+def test_attention_paths_agree(eg, gc, kw):
     """The two evaluations of attention in unobserved runs (fp64 kernel below the size threshold, certified fp32
     kernels above it) and the observed run give the same A_R bit for bit."""
-    wl = si.make_bert(b=3, s=77, hidden=200, heads=5, ffn=328, n_layers=2, seed=61, train_act_dtype="f32")
+    wl = si.make_bert(seed=61 + kw["s"], train_act_dtype="f32", **kw)
     ref = gc.build_reference(wl)
     x = gc.to_dev(wl.x)
     ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
