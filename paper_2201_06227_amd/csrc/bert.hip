@@ -742,63 +742,70 @@ __device__ __forceinline__ void for_each_marked(bool mine, uint64_t *masks, F vi
     }
 }
 
-// Exact absolute maximum of the context: one workgroup per record.  The largest stored |x| (A) and the largest E
-// over all records come from two atomically combined words the first kernel filled; a value can be the exact
-// maximum only if |x| + E_record >= A - E_max.  A workgroup whose record cannot hold such a value is
-// done; the others (as a rule one) rescan the record's 64 x dh values and re-evaluate those that pass the
-// test.  The value that holds A passes, so the word `exact` ends up with the exact maximum (it starts at
-// zero: cleared by the chain's first kernel).
+// Exact absolute maximum of the context.  The largest stored |x| (A) and the largest E over all records come
+// from two atomically combined words the first kernel filled; a value can be the exact maximum only if
+// |x| + E_record >= A - E_max.  A thread tests one record (a workgroup per 256 records: one memory round
+// trip for the whole grid, where a workgroup per record took six waves of workgroups); for the records that
+// pass (as a rule one in the whole tensor) the workgroup rescans the record's 64 x dh values and
+// re-evaluates those that pass the test.  The value that holds A passes, so the word `exact` ends up with
+// the exact maximum (it starts at zero: cleared by the chain's first kernel).
 __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float *__restrict__ qkv,
                                                                      const float *__restrict__ ctx,
-                                                                     const AttnRecord *__restrict__ rec,
+                                                                     const AttnRecord *__restrict__ rec, int nrec,
                                                                      const uint32_t *__restrict__ amax_slot,
                                                                      const uint32_t *__restrict__ err_slot,
                                                                      int S, int Hd, int heads, int dh, double scale,
                                                                      uint32_t *__restrict__ exact)
 {
     __shared__ __attribute__((aligned(16))) double red[12 + 32];
-    __shared__ uint64_t masks[4];
+    __shared__ uint64_t masks_rec[4], masks[4];
     const int tid = threadIdx.x;
-    const AttnRecord mine = rec[blockIdx.x];
+    const int rid = blockIdx.x * 256 + tid;
+    const AttnRecord mine = rec[rid < nrec ? rid : nrec - 1];
     const uint32_t a = reduce_ways(amax_slot);
     const float e = __uint_as_float(reduce_ways(err_slot));
     if (a >= 0x7f800000u) {                                   // NaN / Inf in the tensor: it is the "maximum"
-        if (blockIdx.x == 0 && tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, a);
+        if (blockIdx.x == 0 && tid == 0) atomicMax(exact, a);
         return;
     }
     const float A = __uint_as_float(a);
     const float floor_v = A - value_err(e, A);                // values below this cannot be the maximum
     const float mine_max = __uint_as_float(mine.amax_bits);
-    if (!(mine_max + value_err(mine.err, mine_max) >= floor_v)) return;
+    const bool holds = rid < nrec && mine_max + value_err(mine.err, mine_max) >= floor_v;
     const int qtiles = (S + 63) / 64;
-    const int bh = blockIdx.x / qtiles, qt = blockIdx.x % qtiles;
-    const int bi = bh / heads, hd = bh % heads;
-    const int64_t tok0 = (int64_t)bi * S;
-    const int nq = S - qt * 64 < 64 ? S - qt * 64 : 64;
-    const int n_el = nq * dh;
     uint32_t best = 0;
-    // the block's values, sixteen per thread requested together (indices clamped, the surplus masked below);
-    // candidates are then taken 256 values at a time and re-evaluated one by one by the workgroup
-    float xs[16];
+    for_each_marked(holds, masks_rec, [&](int kr) {
+        const int r = blockIdx.x * 256 + kr;
+        const float r_err = rec[r].err;
+        const int bh = r / qtiles, qt = r % qtiles;
+        const int bi = bh / heads, hd = bh % heads;
+        const int64_t tok0 = (int64_t)bi * S;
+        const int nq = S - qt * 64 < 64 ? S - qt * 64 : 64;
+        const int n_el = nq * dh;
+        // the record's values, sixteen per thread requested together (indices clamped, the surplus masked
+        // below); candidates are then taken 256 values at a time and re-evaluated one by one by the workgroup
+        float xs[16];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const int idx = k * 256 + tid < n_el ? k * 256 + tid : 0;
-        xs[k] = fabsf(ctx[(tok0 + qt * 64 + idx / dh) * Hd + hd * dh + idx % dh]);
-    }
+        for (int k = 0; k < 16; ++k) {
+            const int idx = k * 256 + tid < n_el ? k * 256 + tid : 0;
+            xs[k] = fabsf(ctx[(tok0 + qt * 64 + idx / dh) * Hd + hd * dh + idx % dh]);
+        }
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const int base = k * 256;
-        if (base >= n_el) break;
-        const bool cand = base + tid < n_el && xs[k] + value_err(mine.err, xs[k]) >= floor_v;
-        for_each_marked(cand, masks, [&](int k) {
-            const int cidx = base + k;
-            const int qq = qt * 64 + cidx / dh, d = cidx % dh;
-            const float x = context_exact(qkv, S, Hd, heads, dh, scale, (uint32_t)((tok0 + qq) * Hd + hd * dh + d), red);
-            const uint32_t ab = abs_bits(x);
-            best = best > ab ? best : ab;
-        });
-    }
-    if (tid == 0) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, best);
+        for (int k = 0; k < 16; ++k) {
+            const int base = k * 256;
+            if (base < n_el) {
+                const bool cand = base + tid < n_el && xs[k] + value_err(r_err, xs[k]) >= floor_v;
+                for_each_marked(cand, masks, [&](int kv) {
+                    const int cidx = base + kv;
+                    const int qq = qt * 64 + cidx / dh, d = cidx % dh;
+                    const float x = context_exact(qkv, S, Hd, heads, dh, scale, (uint32_t)((tok0 + qq) * Hd + hd * dh + d), red);
+                    const uint32_t ab = abs_bits(x);
+                    best = best > ab ? best : ab;
+                });
+            }
+        }
+    });
+    if (tid == 0 && best) atomicMax(exact + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, best);
 }
 
 // The int8 codes of the context under the tensor's exact scale: one workgroup per (batch element, head).
@@ -1070,8 +1077,8 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
                             amax_slot, err_slot);
     if (e != hipSuccess) return e;
     const int nrec = (int)grid;
-    e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)nrec), dim3(256), 0, st, qkv,
-                 (const float *)ctx, (const AttnRecord *)rec, (const uint32_t *)amax_slot, (const uint32_t *)err_slot, (int)S,
+    e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, st, qkv,
+                 (const float *)ctx, (const AttnRecord *)rec, nrec, (const uint32_t *)amax_slot, (const uint32_t *)err_slot, (int)S,
                  (int)Hd, (int)heads, dh, scale, exact_slot);
     if (e != hipSuccess) return e;
     const bool wide = (dh & 15) == 0 && (Hd & 15) == 0 && ldq == Hd;
