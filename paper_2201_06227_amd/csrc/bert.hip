@@ -653,6 +653,300 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
     }
 }
 
+// ---- kernel 1 on the bf16 matrix cores, every product an exact fp32 product -----------------------
+// The fp32 matrix instruction runs at 1/16 of the bf16 one.  An fp32 value is the sum of three bf16
+// values (8 + 8 + 8 significant bits: the value truncated, the remainder truncated, what is left; both
+// subtractions are exact), so a product x * y is nine bf16 x bf16 products, each exact in fp32; the six
+// largest are issued (v_mfma_f32_32x32x16_bf16, fp32 accumulation), the three dropped ones sum to less
+// than 2^-22 of the product: six bf16 instructions for what sixteen times as many fp32 ones did.  Within a
+// chain the small partial products come first, so that the sums carried through most of the chain are
+// small against the result (the matrix cores' accumulation drifts with the sums it carries).
+// Geometry: a workgroup is four waves x 32 queries of one head; a tile is 32 keys.  S^T = K Q^T and
+// O^T = V^T P^T as above, so a lane owns a query column: lane l holds query l % 32 and, of a 32-row
+// block, rows 8 (i / 4) + 4 (l / 32) + i % 4 in accumulator register i.  Operands: lane l supplies row
+// l % 32 and the 8 values of unit l / 32 of a 16-deep slab.  For the second product the lane's own
+// registers 8 s .. 8 s + 7 are its unit of slab s (which keys share a unit is free as long as the V
+// operand uses the same assignment), so P never leaves the registers; V is written to LDS transposed,
+// as bf16 planes [head dim][unit][slot] in that assignment.  K planes are [key][unit] with the units
+// xor-rotated by the row; V rows are padded to 80 bytes: all 16-byte operand reads are conflict free.
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+constexpr int kSplitQ = 128;             // queries per workgroup
+constexpr int kSplitKeys = 32;           // keys per tile
+constexpr int kSplitKRow = 128;          // bytes per key row of a K plane (8 units)
+constexpr int kSplitVRow = 80;           // bytes per head-dim row of a V plane (4 units + pad)
+constexpr int kSplitKPlane = kSplitKeys * kSplitKRow, kSplitVPlane = kDh * kSplitVRow;
+constexpr int kSplitStage = 3 * (kSplitKPlane + kSplitVPlane);
+
+struct Split3 {
+    v4u h, m, l;
+};
+// two floats -> the bf16 truncation of each, x0 in the low half
+__device__ __forceinline__ uint32_t pack_top16(float x1, float x0)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(x1), __float_as_uint(x0), 0x07060302u);
+}
+__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t &h, uint32_t &m, uint32_t &l)
+{
+    const float r0 = x0 - __uint_as_float(__float_as_uint(x0) & 0xffff0000u);
+    const float r1 = x1 - __uint_as_float(__float_as_uint(x1) & 0xffff0000u);
+    const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
+    const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+    h = pack_top16(x1, x0);
+    m = pack_top16(r1, r0);
+    l = pack_top16(l1, l0);
+}
+__device__ __forceinline__ Split3 split_eight(const float (&x)[8])
+{
+    Split3 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        uint32_t wh, wm, wl;
+        split_pair(x[2 * e], x[2 * e + 1], wh, wm, wl);
+        o.h[e] = wh;
+        o.m[e] = wm;
+        o.l[e] = wl;
+    }
+    return o;
+}
+
+__global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__restrict__ qkv, int B, int S, int Hd,
+                                                                 int heads, int dh, float scale, float *__restrict__ ctx,
+                                                                 AttnRecord *__restrict__ rec, int total, int per_xcd,
+                                                                 uint32_t *__restrict__ amax_slot,
+                                                                 uint32_t *__restrict__ err_slot)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kSplitStage];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int qblocks = (S + kSplitQ - 1) / kSplitQ, qtiles = (S + 63) / 64;
+    const int vid = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || vid >= total) return;
+    const int bh = vid / qblocks, qb = vid % qblocks;
+    const int bi = bh / heads, hd = bh % heads;
+    const int64_t tok0 = (int64_t)bi * S;
+    const int64_t ld = 3 * (int64_t)Hd;
+    const float *qbase = qkv + hd * dh, *kbase = qbase + Hd, *vbase = qbase + 2 * Hd;
+
+    // the wave's queries as the B operand of S^T = K Q^T: lane (r, h) holds dims 16 sl + 8 h .. + 7 of query r
+    const int q = qb * kSplitQ + wave * 32 + r;
+    Split3 qs[4];
+    {
+        const float *qrow = qbase + (tok0 + (q < S ? q : S - 1)) * ld;
+        float4 raw[8];
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            const int d0 = 16 * sl + 8 * h;
+            const int dc = d0 < dh ? d0 : 0;                     // head dims come in whole units of 8
+            raw[2 * sl] = *(const float4 *)(qrow + dc);
+            raw[2 * sl + 1] = *(const float4 *)(qrow + dc + 4);
+        }
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            const bool ok = q < S && 16 * sl + 8 * h < dh;
+            const float4 a = raw[2 * sl], b4 = raw[2 * sl + 1];
+            const float x[8] = {ok ? a.x : 0.f, ok ? a.y : 0.f, ok ? a.z : 0.f, ok ? a.w : 0.f,
+                                ok ? b4.x : 0.f, ok ? b4.y : 0.f, ok ? b4.z : 0.f, ok ? b4.w : 0.f};
+            qs[sl] = split_eight(x);
+        }
+    }
+
+    // staging.  K: thread t takes unit t % 8 (8 head dims) of key t / 8.  V: lane l of wave w takes head dims
+    // 4 (4 w + l % 4) .. + 3 of keys 2 (l / 4) and 2 (l / 4) + 1 (two keys that are neighbours in a unit: one
+    // 4-byte LDS word per head dim and plane; a wave's words fall into 64 different banks).
+    const int skr = tid >> 3, sku = tid & 7;
+    const int svd = 4 * (4 * wave + (lane & 3)), svk = 2 * (lane >> 2);
+    const uint32_t koff = (uint32_t)(skr * kSplitKRow + ((sku ^ ((skr >> 1) & 7)) * 16));
+    // key k of a tile: slab k / 16, unit 2 (k / 16) + (k / 4) % 2, slot 4 ((k / 8) % 2) + k % 4
+    const uint32_t voff = (uint32_t)(svd * kSplitVRow + (2 * (svk >> 4) + ((svk >> 2) & 1)) * 16 + (4 * ((svk >> 3) & 1) + (svk & 3)) * 2);
+    uint32_t vmax = 0;                  // largest |v| staged by this thread (bit pattern)
+    float4 pk[2], pv[2];
+    auto fetch = [&](int j0) {
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool kok = j0 + skr < S && 8 * sku < dh;
+        const float *kp = kbase + (tok0 + (kok ? j0 + skr : 0)) * ld + (kok ? 8 * sku : 0);
+        pk[0] = *(const float4 *)kp;
+        pk[1] = *(const float4 *)(kp + 4);
+        if (!kok) { pk[0] = z; pk[1] = z; }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const bool vok = j0 + svk + e < S && svd < dh;
+            pv[e] = *(const float4 *)(vbase + (tok0 + (vok ? j0 + svk + e : 0)) * ld + (vok ? svd : 0));
+            if (!vok) pv[e] = z;
+        }
+    };
+    auto stash = [&](int stage) {
+        uint8_t *kst = lds + stage * kSplitStage, *vst = kst + 3 * kSplitKPlane;
+        const float x[8] = {pk[0].x, pk[0].y, pk[0].z, pk[0].w, pk[1].x, pk[1].y, pk[1].z, pk[1].w};
+        const Split3 sp = split_eight(x);
+        *(v4u *)(kst + koff) = sp.h;
+        *(v4u *)(kst + kSplitKPlane + koff) = sp.m;
+        *(v4u *)(kst + 2 * kSplitKPlane + koff) = sp.l;
+        const float v0[4] = {pv[0].x, pv[0].y, pv[0].z, pv[0].w}, v1[4] = {pv[1].x, pv[1].y, pv[1].z, pv[1].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t wh, wm, wl;
+            split_pair(v0[e], v1[e], wh, wm, wl);
+            uint8_t *dst = vst + voff + e * kSplitVRow;
+            *(uint32_t *)dst = wh;
+            *(uint32_t *)(dst + kSplitVPlane) = wm;
+            *(uint32_t *)(dst + 2 * kSplitVPlane) = wl;
+            const uint32_t a0 = abs_bits(v0[e]), a1 = abs_bits(v1[e]);
+            vmax = vmax > a0 ? vmax : a0;
+            vmax = vmax > a1 ? vmax : a1;
+        }
+    };
+
+    v16f o[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+    float mrun = -INFINITY, lrun = 0.0f;
+    float smax = 0.0f;                  // largest |score| met by this lane
+    // (plane of the A operand, plane of the B operand), 0 = high part: smallest products first
+    constexpr int ia[6] = {2, 0, 1, 1, 0, 0}, ib[6] = {0, 2, 1, 0, 1, 0};
+    const uint32_t ka_off = (uint32_t)(r * kSplitKRow), ka_sw = (uint32_t)((r >> 1) & 7);
+    constexpr float kLog2e = 1.44269504088896340736f;
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    int stage = 0;
+    for (int j0 = 0; j0 < S; j0 += kSplitKeys, stage ^= 1) {
+        const bool more = j0 + kSplitKeys < S;
+        if (more) fetch(j0 + kSplitKeys);
+        const uint8_t *kst = lds + stage * kSplitStage, *vst = kst + 3 * kSplitKPlane;
+        // scores of 32 keys x 32 queries
+        v16f sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
+        {
+            v4u ka[3][4];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl)
+                    ka[pl][sl] = *(const v4u *)(kst + pl * kSplitKPlane + ka_off + ((((uint32_t)(2 * sl + h)) ^ ka_sw) * 16));
+#pragma unroll
+            for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl) {
+                    const v4u bq = ib[pr] == 0 ? qs[sl].h : (ib[pr] == 1 ? qs[sl].m : qs[sl].l);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ka[ia[pr]][sl]),
+                                                                   __builtin_bit_cast(v8bf, bq), sacc, 0, 0, 0);
+                }
+        }
+        // register i is key j0 + 8 (i / 4) + 4 h + i % 4 for this lane's query
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int key = j0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            const float sc = sacc[i] * scale;
+            smax = key < S ? fmaxf(smax, fabsf(sc)) : smax;
+            sacc[i] = key < S ? sc : -INFINITY;
+            mx = fmaxf(mx, sacc[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float mnew = fmaxf(mrun, mx);
+        const float corr = __builtin_amdgcn_exp2f((mrun - mnew) * kLog2e);
+        float ps = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sacc[i] = __builtin_amdgcn_exp2f((sacc[i] - mnew) * kLog2e);
+            ps += sacc[i];
+        }
+        ps += __shfl_xor(ps, 32, kWave);
+        lrun = lrun * corr + ps;
+        mrun = mnew;
+        // the lane's unit of slab s of P^T: its registers 8 s .. 8 s + 7
+        Split3 pp[2];
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            const float x[8] = {sacc[8 * sl], sacc[8 * sl + 1], sacc[8 * sl + 2], sacc[8 * sl + 3],
+                                sacc[8 * sl + 4], sacc[8 * sl + 5], sacc[8 * sl + 6], sacc[8 * sl + 7]};
+            pp[sl] = split_eight(x);
+        }
+        // this tile's V^T P^T from a zero accumulator, then O^T = O^T * corr + tile on the vector ALU
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+            v4u va[3][2];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+                for (int sl = 0; sl < 2; ++sl)
+                    va[pl][sl] = *(const v4u *)(vst + pl * kSplitVPlane + (32 * db + r) * kSplitVRow + (2 * sl + h) * 16);
+            v16f ot;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ot[i] = 0.0f;
+#pragma unroll
+            for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
+                for (int sl = 0; sl < 2; ++sl) {
+                    const v4u bp = ib[pr] == 0 ? pp[sl].h : (ib[pr] == 1 ? pp[sl].m : pp[sl].l);
+                    ot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, va[ia[pr]][sl]),
+                                                                 __builtin_bit_cast(v8bf, bp), ot, 0, 0, 0);
+                }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][i] = fmaf(o[db][i], corr, ot[i]);
+        }
+        if (more) stash(stage ^ 1);
+        __syncthreads();
+    }
+
+    // register i of block db is head dim 32 db + 8 (i / 4) + 4 h + i % 4 of this lane's query
+    uint32_t amax = 0;
+    if (q < S) {
+        float *dst = ctx + (tok0 + q) * Hd + hd * dh;
+        const float inv = 1.0f / lrun;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int d = 32 * db + 8 * g + 4 * h;
+                if (d < dh) {                                    // head dims come in whole units of 8
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = o[db][4 * g + e] * inv;
+                        const uint32_t ab = abs_bits(v[e]);
+                        amax = ab > amax ? ab : amax;
+                    }
+                    *(float4 *)(dst + d) = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
+    }
+    // records: one per 64 queries (a pair of waves): largest |context| stored, and the error bound of its values
+    __shared__ uint32_t red[3][4];
+    amax = wave_max_u32(amax);
+    vmax = wave_max_u32(vmax);
+    const uint32_t sbits = wave_max_u32(__float_as_uint(smax));       // non-negative floats order like integers
+    if (lane == 0) { red[0][wave] = amax; red[1][wave] = vmax; red[2][wave] = sbits; }
+    __syncthreads();
+    if (tid < 2) {
+        const int qt = qb * (kSplitQ / 64) + tid;
+        if (qt < qtiles) {
+            uint32_t v = 0;
+            for (int w = 0; w < 4; ++w) v = v > red[1][w] ? v : red[1][w];
+            const uint32_t a = red[0][2 * tid] > red[0][2 * tid + 1] ? red[0][2 * tid] : red[0][2 * tid + 1];
+            const uint32_t sb = red[2][2 * tid] > red[2][2 * tid + 1] ? red[2][2 * tid] : red[2][2 * tid + 1];
+            AttnRecord rc;
+            rc.amax_bits = a;
+            rc.err = 5.9604645e-8f * __uint_as_float(v) * (kErrBase + kErrPerScore * __uint_as_float(sb));
+            if (!(rc.err <= 3.402823466e+38f)) rc.amax_bits = 0x7f800000u;   // non-finite inputs: flagged downstream
+            rec[bh * qtiles + qt] = rc;
+            if (amax_slot) {
+                uint32_t *wa = amax_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride;
+                uint32_t *we = err_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride;
+                const uint32_t eb = __float_as_uint(rc.err);
+                if (rc.amax_bits > __hip_atomic_load(wa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(wa, rc.amax_bits);
+                if (eb > __hip_atomic_load(we, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(we, eb);
+            }
+        }
+    }
+}
+
 // The context value of one (query token, head, dim) as the fp64 evaluation defines it:
 // scores in fp64 (products summed over the head dims in ascending
 // order, then the 1/sqrt(dh) factor), soft-max and the weighted sum of v in fp64, rounded once.  q, k and
@@ -1040,8 +1334,27 @@ size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads)
     return align_up((size_t)B * heads * ((S + 63) / 64) * sizeof(AttnRecord), 256);
 }
 
+// Kernel 1: the bf16-split form when head dims come in whole units of 8 floats at 16-byte aligned addresses,
+// else the fp32 form.  Both fill the same records (one per 64 queries of a head).
+static hipError_t launch_attention_approx(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
+                                          AttnRecord *rec, uint32_t *amax_slot, uint32_t *err_slot, hipStream_t st)
+{
+    const int dh = Hd / heads;
+    const float scale = (float)(1.0 / sqrt((double)dh));
+    if ((dh & 7) == 0 && (Hd & 3) == 0) {
+        const int64_t grid = (int64_t)B * heads * ((S + kSplitQ - 1) / kSplitQ);
+        const int per_xcd = (int)((grid + 7) / 8);
+        return launch_k(EGERIA_KERNEL_ATTENTION, attention_split_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
+                        qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, scale, ctx, rec, (int)grid, per_xcd, amax_slot, err_slot);
+    }
+    const int64_t grid = (int64_t)B * heads * ((S + 63) / 64);
+    const int per_xcd = (int)((grid + 7) / 8);
+    return launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, qkv,
+                    (int)B, (int)S, (int)Hd, (int)heads, dh, scale, ctx, rec, (int)grid, per_xcd, amax_slot, err_slot);
+}
+
 // Kernel 1 alone (benchmark instrumentation: its error against the fp64 kernel): approximate context and the
-// per-workgroup records {largest |x| as a bit pattern, error bound E}, B * heads * ceil(S / 64) of them.
+// records {largest |x| as a bit pattern, error bound E}, B * heads * ceil(S / 64) of them.
 hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
                                  void *records, hipStream_t st)
 {
@@ -1050,10 +1363,7 @@ hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t
     if (grid <= 0) return hipSuccess;
     if (dh > kDh || grid > 0x7ffffff0LL) return hipErrorInvalidValue;
     if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(records)) return hipErrorInvalidValue;
-    const int per_xcd = (int)((grid + 7) / 8);
-    return launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, qkv,
-                    (int)B, (int)S, (int)Hd, (int)heads, dh, (float)(1.0 / sqrt((double)dh)), ctx, (AttnRecord *)records,
-                    (int)grid, per_xcd, (uint32_t *)nullptr, (uint32_t *)nullptr);
+    return launch_attention_approx(qkv, B, S, Hd, heads, ctx, (AttnRecord *)records, nullptr, nullptr, st);
 }
 
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
@@ -1070,11 +1380,8 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
     if (dh > kDh || grid > 0x7ffffff0LL || M * Hd >= (1LL << 32) || ldq < Hd) return hipErrorInvalidValue;
     if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(xq) || !attn_aligned16(records)) return hipErrorInvalidValue;
     AttnRecord *rec = (AttnRecord *)records;
-    const int per_xcd = (int)((grid + 7) / 8);
     const double scale = 1.0 / sqrt((double)dh);
-    hipError_t e = launch_k(EGERIA_KERNEL_ATTENTION, attention_fast_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
-                            qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, (float)scale, ctx, rec, (int)grid, per_xcd,
-                            amax_slot, err_slot);
+    hipError_t e = launch_attention_approx(qkv, B, S, Hd, heads, ctx, rec, amax_slot, err_slot, st);
     if (e != hipSuccess) return e;
     const int nrec = (int)grid;
     e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, st, qkv,
