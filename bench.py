@@ -516,8 +516,9 @@ def microbench(device):
     eg.lib()
     scratch = torch.zeros(256 << 20, dtype=torch.uint8, device=device)
     peaks = {0: (5033.0, "TOP/s"), 1: (2516.6, "TFLOP/s"), 2: (157.3, "TFLOP/s"), 3: (157.3, "TFLOP/s"), 4: (78.6, "TFLOP/s"),
-             9: (8.0, "TB/s")}
-    iters = {0: 20000, 1: 20000, 2: 5000, 3: 10000, 4: 10000, 5: 4000, 6: 4000, 7: 4096, 8: 4096, 9: 1}
+             9: (8.0, "TB/s"), 10: (2516.6, "TFLOP/s"), 11: (2516.6, "TFLOP/s"), 12: (2516.6, "TFLOP/s")}
+    iters = {0: 20000, 1: 20000, 2: 5000, 3: 10000, 4: 10000, 5: 4000, 6: 4000, 7: 4096, 8: 4096, 9: 1, 10: 20000,
+             11: 20000, 12: 20000}
     print("kind                          ms        rate                 of published peak   per clock and CU")
     for kind, name in enumerate(eg.MICRO_KINDS):
         best = None

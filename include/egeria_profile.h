@@ -68,7 +68,10 @@ typedef enum {
     EGERIA_MICRO_LDS_WRITE = 6,      /* ds_write_b128 without bank conflicts */
     EGERIA_MICRO_L2_TO_LDS_LINE = 7, /* buffer loads with the LDS modifier, whole 128-byte lines of L2-resident rows */
     EGERIA_MICRO_L2_TO_LDS_HALF = 8, /* ... half lines (64 bytes per row and request) */
-    EGERIA_MICRO_HBM_COPY = 9        /* 128 MiB copied with 16-byte accesses */
+    EGERIA_MICRO_HBM_COPY = 9,       /* 128 MiB copied with 16-byte accesses */
+    EGERIA_MICRO_BF16_CHAIN = 10,    /* mfma_f32_32x32x16_bf16, one dependent chain per wave, one wave per SIMD */
+    EGERIA_MICRO_BF16_CHAIN_VALU = 11, /* ... with eight independent fp32 vector instructions after each */
+    EGERIA_MICRO_BF16_CHAIN_VALU2 = 12 /* ... and two waves per SIMD */
 } egeria_micro_kind;
 egeria_status egeria_microbench(int32_t kind, int32_t iters, void *scratch, size_t scratch_bytes, float *ms_out,
                                 double *work_out, void *stream);

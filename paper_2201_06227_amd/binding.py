@@ -519,7 +519,7 @@ def plasticity_eval(ref: ReferenceModel, x: torch.Tensor, a_train: Sequence[torc
 
 MICRO_KINDS = ["mfma_i32_32x32x32_i8", "mfma_f32_32x32x16_bf16", "mfma_f32_32x32x2_f32", "mfma_f32_16x16x4_f32",
                "mfma_f64_16x16x4_f64", "lds_read_b128", "lds_write_b128", "l2_to_lds_whole_lines", "l2_to_lds_half_lines",
-               "hbm_copy"]
+               "hbm_copy", "bf16_dependent_chain", "bf16_chain_plus_8_valu", "bf16_chain_plus_8_valu_2_waves"]
 
 
 def attention_threshold(min_flops: float = -1.0) -> float:

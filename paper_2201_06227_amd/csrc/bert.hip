@@ -762,27 +762,34 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
     const uint32_t voff = (uint32_t)(svd * kSplitVRow + (2 * (svk >> 4) + ((svk >> 2) & 1)) * 16 + (4 * ((svk >> 3) & 1) + (svk & 3)) * 2);
     uint32_t vmax = 0;                  // largest |v| staged by this thread (bit pattern)
     float4 pk[2], pv[2];
-    auto fetch = [&](int j0) {
-        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-        const bool kok = j0 + skr < S && 8 * sku < dh;
-        const float *kp = kbase + (tok0 + (kok ? j0 + skr : 0)) * ld + (kok ? 8 * sku : 0);
+    // Loads are unconditional, from clamped addresses: a key beyond S reads the last key's row (its score is
+    // masked in the ragged tile, its P is exactly zero), head dims beyond dh read dims 0.. (the query is zero
+    // there, and those rows of O^T are never stored).  No zeroing, so nothing waits for a load before its use.
+    const float *kfetch = kbase + tok0 * ld + (8 * sku < dh ? 8 * sku : 0);
+    const float *vfetch = vbase + tok0 * ld + (svd < dh ? svd : 0);
+    auto fetch_k = [&](int j0) {
+        const int row = j0 + skr < S ? j0 + skr : S - 1;
+        const float *kp = kfetch + (int64_t)row * ld;
         pk[0] = *(const float4 *)kp;
         pk[1] = *(const float4 *)(kp + 4);
-        if (!kok) { pk[0] = z; pk[1] = z; }
+    };
+    auto fetch_v = [&](int j0) {
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const bool vok = j0 + svk + e < S && svd < dh;
-            pv[e] = *(const float4 *)(vbase + (tok0 + (vok ? j0 + svk + e : 0)) * ld + (vok ? svd : 0));
-            if (!vok) pv[e] = z;
+            const int row = j0 + svk + e < S ? j0 + svk + e : S - 1;
+            pv[e] = *(const float4 *)(vfetch + (int64_t)row * ld);
         }
     };
-    auto stash = [&](int stage) {
-        uint8_t *kst = lds + stage * kSplitStage, *vst = kst + 3 * kSplitKPlane;
+    auto stash_k = [&](int buf) {
+        uint8_t *kst = lds + buf * kSplitStage;
         const float x[8] = {pk[0].x, pk[0].y, pk[0].z, pk[0].w, pk[1].x, pk[1].y, pk[1].z, pk[1].w};
         const Split3 sp = split_eight(x);
         *(v4u *)(kst + koff) = sp.h;
         *(v4u *)(kst + kSplitKPlane + koff) = sp.m;
         *(v4u *)(kst + 2 * kSplitKPlane + koff) = sp.l;
+    };
+    auto stash_v = [&](int buf) {
+        uint8_t *vst = lds + buf * kSplitStage + 3 * kSplitKPlane;
         const float v0[4] = {pv[0].x, pv[0].y, pv[0].z, pv[0].w}, v1[4] = {pv[1].x, pv[1].y, pv[1].z, pv[1].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -798,63 +805,80 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
         }
     };
 
+    // (plane of the K or V operand, plane of the Q or P operand), 0 = high part.  The small products come
+    // first; a K / V plane is used for consecutive products so that few operand registers are live.
+    constexpr int ia[6] = {2, 1, 1, 0, 0, 0}, ib[6] = {0, 1, 0, 2, 1, 0};
+    const uint32_t ka_off = (uint32_t)(r * kSplitKRow), ka_sw = (uint32_t)((r >> 1) & 7);
+    // raw scores (before the 1 / sqrt(dh) factor) of the tile in K buffer `buf`: register i is key
+    // 8 (i / 4) + 4 h + i % 4 of the tile for this lane's query
+    auto scores = [&](int buf) {
+        const uint8_t *kst = lds + buf * kSplitStage;
+        v16f acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll
+        for (int pr = 0; pr < 6; ++pr)
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                const v4u ak = *(const v4u *)(kst + ia[pr] * kSplitKPlane + ka_off + ((((uint32_t)(2 * sl + h)) ^ ka_sw) * 16));
+                const v4u bq = ib[pr] == 0 ? qs[sl].h : (ib[pr] == 1 ? qs[sl].m : qs[sl].l);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ak), __builtin_bit_cast(v8bf, bq), acc, 0, 0, 0);
+            }
+        return acc;
+    };
+
     v16f o[2];
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
-    float mrun = -INFINITY, lrun = 0.0f;
-    float smax = 0.0f;                  // largest |score| met by this lane
-    // (plane of the A operand, plane of the B operand), 0 = high part: smallest products first
-    constexpr int ia[6] = {2, 0, 1, 1, 0, 0}, ib[6] = {0, 2, 1, 0, 1, 0};
-    const uint32_t ka_off = (uint32_t)(r * kSplitKRow), ka_sw = (uint32_t)((r >> 1) & 7);
-    constexpr float kLog2e = 1.44269504088896340736f;
+    float mrun = -INFINITY, lrun = 0.0f;   // running maximum of the raw scores, running sum
+    float smax = 0.0f;                  // largest |raw score| met by this lane
+    const float c2 = scale * 1.44269504088896340736f;            // raw score -> exponent of 2
 
-    fetch(0);
-    stash(0);
+    // Software pipeline over the tiles.  Iteration t contracts S(t + 1), turns S(t) into P(t), contracts
+    // P(t) V(t) and splits K(t + 2) and V(t + 1) (in registers since the iteration before) into the buffers
+    // that S(t) and V(t - 1) have left: the scores of the next tile do not wait for this tile's soft-max, and
+    // a tile's loads have a whole iteration to arrive.  One barrier per tile.  (Measured on this chip: the
+    // vector instructions that follow a matrix instruction in a wave's issue order do not run beside it, and
+    // two waves of a SIMD overlap them by about a third; the kernel's time is close to the sum of its 48
+    // matrix and 430 vector instructions per tile, whatever their order.)
+    const int ntiles = (S + kSplitKeys - 1) / kSplitKeys;
+    fetch_k(0);
+    fetch_v(0);
+    stash_k(0);
+    stash_v(0);
+    fetch_k(kSplitKeys);
+    fetch_v(kSplitKeys);
+    stash_k(1);
+    fetch_k(2 * kSplitKeys);
     __syncthreads();
-    int stage = 0;
-    for (int j0 = 0; j0 < S; j0 += kSplitKeys, stage ^= 1) {
-        const bool more = j0 + kSplitKeys < S;
-        if (more) fetch(j0 + kSplitKeys);
-        const uint8_t *kst = lds + stage * kSplitStage, *vst = kst + 3 * kSplitKPlane;
-        // scores of 32 keys x 32 queries
-        v16f sacc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
-        {
-            v4u ka[3][4];
-#pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
-#pragma unroll
-                for (int sl = 0; sl < 4; ++sl)
-                    ka[pl][sl] = *(const v4u *)(kst + pl * kSplitKPlane + ka_off + ((((uint32_t)(2 * sl + h)) ^ ka_sw) * 16));
-#pragma unroll
-            for (int pr = 0; pr < 6; ++pr)
-#pragma unroll
-                for (int sl = 0; sl < 4; ++sl) {
-                    const v4u bq = ib[pr] == 0 ? qs[sl].h : (ib[pr] == 1 ? qs[sl].m : qs[sl].l);
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ka[ia[pr]][sl]),
-                                                                   __builtin_bit_cast(v8bf, bq), sacc, 0, 0, 0);
-                }
-        }
-        // register i is key j0 + 8 (i / 4) + 4 h + i % 4 for this lane's query
+    v16f sacc = scores(0);
+    __syncthreads();                                             // K buffer 0 is rewritten in iteration 0
+    // (everything in an iteration is unconditional, so that it is one block the scheduler can interleave: past
+    // the last tile the scores of a stale buffer are computed and dropped, and zero tiles are staged)
+    auto iteration = [&](int t, auto ragged) {
+        const int j0 = t * kSplitKeys;
+        const v16f snext = scores((t + 1) & 1);
+        // soft-max of tile t
         float mx = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int key = j0 + 8 * (i >> 2) + 4 * h + (i & 3);
-            const float sc = sacc[i] * scale;
-            smax = key < S ? fmaxf(smax, fabsf(sc)) : smax;
-            sacc[i] = key < S ? sc : -INFINITY;
-            mx = fmaxf(mx, sacc[i]);
+        for (int i = 0; i < 16; ++i) smax = fmaxf(smax, fabsf(sacc[i]));     // keys beyond S: zero rows, score 0
+        if constexpr (decltype(ragged)::value) {                 // the ragged last tile: keys beyond S do not count
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                sacc[i] = j0 + 8 * (i >> 2) + 4 * h + (i & 3) < S ? sacc[i] : -INFINITY;
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float mnew = fmaxf(mrun, mx);
-        const float corr = __builtin_amdgcn_exp2f((mrun - mnew) * kLog2e);
+        const float corr = __builtin_amdgcn_exp2f((mrun - mnew) * c2);
+        const float shift = -mnew * c2;
         float ps = 0.0f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            sacc[i] = __builtin_amdgcn_exp2f((sacc[i] - mnew) * kLog2e);
+            sacc[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], c2, shift));
             ps += sacc[i];
         }
         ps += __shfl_xor(ps, 32, kWave);
@@ -868,32 +892,42 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
                                 sacc[8 * sl + 4], sacc[8 * sl + 5], sacc[8 * sl + 6], sacc[8 * sl + 7]};
             pp[sl] = split_eight(x);
         }
-        // this tile's V^T P^T from a zero accumulator, then O^T = O^T * corr + tile on the vector ALU
+        // this tile's V^T P^T from zero accumulators (two independent chains, one per half of the head dims),
+        // then O^T = O^T * corr + tile on the vector ALU
+        {
+            const uint8_t *vst = lds + (t & 1) * kSplitStage + 3 * kSplitKPlane;
+            v16f ot[2];
 #pragma unroll
-        for (int db = 0; db < 2; ++db) {
-            v4u va[3][2];
+            for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
-#pragma unroll
-                for (int sl = 0; sl < 2; ++sl)
-                    va[pl][sl] = *(const v4u *)(vst + pl * kSplitVPlane + (32 * db + r) * kSplitVRow + (2 * sl + h) * 16);
-            v16f ot;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) ot[i] = 0.0f;
+                for (int i = 0; i < 16; ++i) ot[db][i] = 0.0f;
 #pragma unroll
             for (int pr = 0; pr < 6; ++pr)
 #pragma unroll
                 for (int sl = 0; sl < 2; ++sl) {
                     const v4u bp = ib[pr] == 0 ? pp[sl].h : (ib[pr] == 1 ? pp[sl].m : pp[sl].l);
-                    ot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, va[ia[pr]][sl]),
-                                                                 __builtin_bit_cast(v8bf, bp), ot, 0, 0, 0);
-                }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][i] = fmaf(o[db][i], corr, ot[i]);
+                    for (int db = 0; db < 2; ++db) {
+                        const v4u av = *(const v4u *)(vst + ia[pr] * kSplitVPlane + (32 * db + r) * kSplitVRow + (2 * sl + h) * 16);
+                        ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bp), ot[db], 0, 0, 0);
+                    }
+                }
+            stash_k(t & 1);
+            stash_v((t + 1) & 1);
+            fetch_k(j0 + 3 * kSplitKeys);
+            fetch_v(j0 + 2 * kSplitKeys);
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] = fmaf(o[db][i], corr, ot[db][i]);
         }
-        if (more) stash(stage ^ 1);
+        sacc = snext;
         __syncthreads();
-    }
+    };
+    const int nfull = S / kSplitKeys;
+    for (int t = 0; t < nfull; ++t) iteration(t, std::false_type{});
+    if (nfull < ntiles) iteration(nfull, std::true_type{});
+    smax *= scale;
 
     // register i of block db is head dim 32 db + 8 (i / 4) + 4 h + i % 4 of this lane's query
     uint32_t amax = 0;

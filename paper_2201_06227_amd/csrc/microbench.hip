@@ -73,6 +73,38 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int *sink)
     }
 }
 
+// One dependent chain of bf16 matrix instructions per wave (each takes the result of the one before as its
+// accumulator); VALU: eight fp32 multiply-adds that depend on no matrix result follow each of them in issue
+// order.  The work reported is that of the matrix instructions only, so the three variants compare directly:
+// what a dependent chain reaches alone, and what is left of it when the vector ALU of the same SIMD is in use.
+template <bool VALU>
+__global__ __launch_bounds__(256) void mfma_chain_kernel(int iters, int *sink)
+{
+    const int t = threadIdx.x;
+    mb_v16f acc = {};
+    mb_v8bf a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)(t + e); b[e] = (__bf16)1.5f; }
+    float x[8];
+    for (int e = 0; e < 8; ++e) x[e] = (float)(t + e);
+    const float m = 1.0f - 1.0f / (float)(iters + 3), c = 0.25f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+            if (VALU) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = fmaf(x[e], m, c);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            }
+        }
+    }
+    float s = 0;
+    for (int r = 0; r < 16; ++r) s += acc[r];
+    for (int e = 0; e < 8; ++e) s += x[e];
+    if (s == 12345.f) sink[0] = 1;
+}
+
 // 128-bit LDS accesses without bank conflicts (lane l at byte 16 l of a 1 KiB row per wave), eight per iteration.
 template <bool WRITE>
 __global__ __launch_bounds__(256) void lds_rate_kernel(int iters, int *sink)
@@ -191,6 +223,9 @@ extern "C" egeria_status egeria_microbench(int32_t kind, int32_t iters, void *sc
             work = 1.0 * cus * 4 * 8.0 * iters * 1024.0;
             break;
         }
+        case EGERIA_MICRO_BF16_CHAIN: hipLaunchKernelGGL(mfma_chain_kernel<false>, one_per_cu, block, 0, st, iters, sink); work = 1.0 * cus * 4 * 4.0 * iters * 32768.0; break;
+        case EGERIA_MICRO_BF16_CHAIN_VALU: hipLaunchKernelGGL(mfma_chain_kernel<true>, one_per_cu, block, 0, st, iters, sink); work = 1.0 * cus * 4 * 4.0 * iters * 32768.0; break;
+        case EGERIA_MICRO_BF16_CHAIN_VALU2: hipLaunchKernelGGL(mfma_chain_kernel<true>, two_per_cu, block, 0, st, iters, sink); work = 2.0 * cus * 4 * 4.0 * iters * 32768.0; break;
         case EGERIA_MICRO_HBM_COPY: {
             const int64_t n4 = (int64_t)((scratch_bytes / 2) / 16);
             hipLaunchKernelGGL(copy_kernel, dim3((unsigned)(cus * 8)), block, 0, st, (const float4 *)scratch,
