@@ -118,7 +118,8 @@ def hbm_class_bytes(wl, cls, eg):
 
 
 KERNEL_SOURCES = {"gram_partial_kernel": "gram.hip", "gemm_i8_kernel": "gemm_i8.hip", "conv3x3_c16_fused_kernel": "gemm_i8.hip",
-                  "attention_fast_kernel": "bert.hip", "layernorm_vec_kernel": "bert.hip"}
+                  "attention_fast_kernel": "bert.hip", "attention_split_kernel": "bert.hip", "attention_kernel": "bert.hip",
+                  "layernorm_vec_kernel": "bert.hip"}
 
 
 def source_digest(kernel):
@@ -169,7 +170,17 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None, force_mfma=False):
     small_conv = wl.kind == si.KIND_BASIC_BLOCK and wl.dims["c_in"] <= 16 and wl.dims["c_out"] <= 32
     names = {eg.KERNEL_GRAM: "gram_partial_kernel",
              eg.KERNEL_GEMM: "conv3x3_c16_fused_kernel" if small_conv else "gemm_i8_kernel",
-             eg.KERNEL_ATTENTION: "attention_fast_kernel", eg.KERNEL_LAYERNORM: "layernorm_vec_kernel"}
+             eg.KERNEL_ATTENTION: "attention_split_kernel", eg.KERNEL_LAYERNORM: "layernorm_vec_kernel"}
+    att_peak = PEAK_GRAM_TFLOPS
+    if cls == eg.KERNEL_ATTENTION:
+        # which kernel an unobserved run takes (the library's rule): below 5 GFLOP the fp64 kernel; above it the
+        # approximate kernel with certified codes, on the bf16 matrix cores when head dims come in units of 8
+        d = wl.dims
+        dh = d["hidden"] // d["heads"]
+        if 4.0 * d["batch"] * d["heads"] * d["seq"] ** 2 * dh < 5.0e9:
+            names[cls], att_peak = "attention_kernel", PEAK_F64_MFMA_TFLOPS
+        elif dh % 8 or d["hidden"] % 4:
+            names[cls], att_peak = "attention_fast_kernel", PEAK_F32_MFMA_TFLOPS
     if not work or not durations_ms:
         return None
     per_step = len(work)
@@ -183,9 +194,9 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None, force_mfma=False):
     if cls == eg.KERNEL_GEMM:
         peak_c, unit_c, scale = PEAK_I8_TOPS, "TOP/s", 1e12
     elif cls == eg.KERNEL_ATTENTION:
-        # unobserved runs: fp32 products and sums on the fp32 matrix-core instructions (the values that
-        # decide an int8 code are re-evaluated in fp64 by the kernels that follow)
-        peak_c, unit_c, scale = PEAK_F32_MFMA_TFLOPS, "TFLOP/s", 1e12
+        # unobserved runs of the large shapes: exact fp32 products as six bf16 partial products each, fp32 sums
+        # (the values that decide an int8 code are re-evaluated in fp64 by the kernels that follow)
+        peak_c, unit_c, scale = att_peak, "TFLOP/s", 1e12
     elif cls == eg.KERNEL_LAYERNORM:
         peak_c, unit_c, scale = PEAK_F64_VALU_TFLOPS, "TFLOP/s", 1e12
     else:
@@ -533,7 +544,7 @@ def microbench(device):
 
 
 def attention_error(cfg, device):
-    """Error of the fp32 matrix-core attention kernel against the fp64 one, layer by layer, on the qkv
+    """Error of the approximate matrix-core attention kernel against the fp64 one, layer by layer, on the qkv
     tensors of the workload's own reference forward, set against the bound E the certified quantiser works
     with: E = 2^-24 * (max|v| of the head * (2 + max|score| of the workgroup / 2) + 10 |x|).  Prints a text table."""
     import ctypes
@@ -561,7 +572,7 @@ def attention_error(cfg, device):
     ws = eg.workspace(eg.workspace_bytes(ref.desc), dev)
     eg.ref_forward(ref, torch.from_numpy(wl.x).to(dev), a_ref, ws, taps)
     torch.cuda.synchronize()
-    print(f"# {WORKLOAD_NAMES[cfg]}: attention_fast_kernel against attention_kernel (fp64), per layer")
+    print(f"# {WORKLOAD_NAMES[cfg]}: the approximate attention kernel (attention_split_kernel when head dims come in units of 8, else attention_fast_kernel) against attention_kernel (fp64), per layer")
     print("# err = |fast - fp64| per context value; E = the certified quantiser's bound for that value; unit = 2^-24 * max|v| of the head")
     print("layer  absmax(ctx)  max|v|  max|score|  median err/unit  p99.99 err/unit  max err/unit  max err/E  values with err > E  uncertain codes (fraction)")
     qt = (S + 63) // 64
