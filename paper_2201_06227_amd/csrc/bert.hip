@@ -410,7 +410,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr float kErrBase = 2.0f, kErrPerScore = 0.5f;
 // ... plus a part that grows with the value itself (the drift of the matrix cores' accumulation is
 // proportional to the sums it carries): kErrRel * 2^-24 * |x|
-constexpr float kErrRel = 10.0f * 5.9604645e-8f;
+constexpr float kErrRel = 12.0f * 5.9604645e-8f;
 // error bound of one approximate context value x whose workgroup's record says err
 __device__ __forceinline__ float value_err(float err, float x) { return fmaf(kErrRel, fabsf(x), err); }
 struct AttnRecord {
