@@ -1000,24 +1000,37 @@ __device__ __forceinline__ float context_exact(const float *__restrict__ qkv, in
     const float *kb = qkv + (int64_t)bi * S * ld + Hd + hd * dh, *vb = kb + Hd + dd;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int units = dh >> 2;
-    // the query row goes through LDS (64 floats behind the 12 doubles of red): every thread needs all of it
+    // the query row goes through LDS (64 floats behind the 12 doubles of red): every thread needs all of it.
+    // Its load and the first block's key and value loads are requested together, before the barriers: the
+    // evaluation is a chain of memory round trips, and this takes one out of it.
     float *qs = (float *)(red + 12);
+    float4 kv[16];
+    float vj = 0.0f;
+    auto request = [&](int j0) {
+        const int j = j0 + tid;
+        const int jj = j < S ? j : S - 1;
+        const float *kr = kb + (int64_t)jj * ld;
+        vj = vb[(int64_t)jj * ld];
+        if (vec4) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) kv[u] = *(const float4 *)(kr + 4 * (u < units ? u : units - 1));
+        }
+    };
+    const float qreg = (tid < 64 && tid < dh) ? q[tid] : 0.0f;
+    request(0);
     __syncthreads();                                          // an earlier call has finished with red and qs
-    if (tid < 64) qs[tid] = tid < dh ? q[tid] : 0.0f;
+    if (tid < 64) qs[tid] = qreg;
     __syncthreads();
     double m = -INFINITY, l = 0.0, o = 0.0;
     for (int j0 = 0; j0 < S; j0 += 256) {
         const int j = j0 + tid;
         const int jj = j < S ? j : S - 1;
         const float *kr = kb + (int64_t)jj * ld;
-        const float vj = vb[(int64_t)jj * ld];
+        if (j0) request(j0);
         // a product of two fp32 values is exact in fp64, so each fma below is the multiply and the
         // add of the plain definition, in its order (dims ascending)
         double acc = 0.0;
         if (vec4) {
-            float4 kv[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) kv[u] = *(const float4 *)(kr + 4 * (u < units ? u : units - 1));
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 if (u < units) {
@@ -1087,6 +1100,7 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
 {
     __shared__ __attribute__((aligned(16))) double red[12 + 32];
     __shared__ uint64_t masks_rec[4], masks[4];
+    __shared__ float err_s;
     const int tid = threadIdx.x;
     const int rid = blockIdx.x * 256 + tid;
     const AttnRecord mine = rec[rid < nrec ? rid : nrec - 1];
@@ -1104,7 +1118,10 @@ __global__ __launch_bounds__(256) void attention_absmax_exact_kernel(const float
     uint32_t best = 0;
     for_each_marked(holds, masks_rec, [&](int kr) {
         const int r = blockIdx.x * 256 + kr;
-        const float r_err = rec[r].err;
+        __syncthreads();                                      // err_s is free
+        if (tid == kr) err_s = mine.err;                      // the record is in that thread's registers
+        __syncthreads();
+        const float r_err = err_s;
         const int bh = r / qtiles, qt = r % qtiles;
         const int bi = bh / heads, hd = bh % heads;
         const int64_t tok0 = (int64_t)bi * S;
