@@ -39,6 +39,19 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_GRAM_TFLOPS = PEAK_BF16_MFMA_TFLOPS / 6.0
 
 
+def layernorm_in_gemm(wl):
+    """The library's rule for taking the layer norm after the attention-output layer into that layer's launch
+    (unobserved runs): at least three quarters of the compute units' worth of 64-row workgroups, rows of at
+    most 768 floats in whole 16-byte units, K of at most 1024 bytes."""
+    d = wl.dims
+    if "seq" not in d:
+        return False
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    M, h = d["batch"] * d["seq"], d["hidden"]
+    return (M + 63) // 64 >= cus * 3 // 4 and h <= 768 and h % 4 == 0 and (h + 15) // 16 * 16 <= 1024
+
+
 def algorithmic_work(wl, cls, eg):
     """Per step, for one kernel class: list of (ops, bytes) per launch, the
     method's own arithmetic and the bytes it must move once (inputs read once,
@@ -69,7 +82,10 @@ def algorithmic_work(wl, cls, eg):
                       (M, d["c_out"], d["c_mid"], d["c_mid"], 1)]
         else:
             M, h, f = b * d["seq"], d["hidden"], d["ffn"]
-            shapes = [(M, 3 * h, h, h, 0), (M, h, h, h, 0), (M, f, h, h, 0), (M, h, f, f, 0)] * d["n_layers"]
+            shapes = [(M, 3 * h, h, h, 0), (M, h, h, h, 0), (M, f, h, h, 0), (M, h, f, f, 0)]
+            if layernorm_in_gemm(wl):
+                del shapes[1]            # that launch is counted with the layer norms, whose work it also does
+            shapes = shapes * d["n_layers"]
         narrow = wl.kind == si.KIND_BASIC_BLOCK and d["c_in"] <= 16
         for (M, N, K, kin, res) in shapes:
             if narrow:
@@ -84,8 +100,15 @@ def algorithmic_work(wl, cls, eg):
             out.append((4.0 * M * S * h, 4.0 * M * 3 * h + 4.0 * M * h))
     elif cls == eg.KERNEL_LAYERNORM and "seq" in d:
         M, h = b * d["seq"], d["hidden"]
-        for _ in range(2 * d["n_layers"]):
-            out.append((0.0, 12.0 * M * h))                                # x and the residual read, y written
+        for _ in range(d["n_layers"]):
+            if layernorm_in_gemm(wl):
+                # the attention-output layer and its layer norm in one launch: int8 rows and weights, the
+                # residual read, y written (the 2 M h h integer operations are not priced: the launch is bound by
+                # these bytes)
+                out.append((0.0, 1.0 * M * h + 1.0 * h * h + 8.0 * M * h))
+            else:
+                out.append((0.0, 12.0 * M * h))                            # x and the residual read, y written
+            out.append((0.0, 12.0 * M * h))
     return out
 
 
@@ -181,6 +204,7 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None, force_mfma=False):
             names[cls], att_peak = "attention_kernel", PEAK_F64_MFMA_TFLOPS
         elif dh % 8 or d["hidden"] % 4:
             names[cls], att_peak = "attention_fast_kernel", PEAK_F32_MFMA_TFLOPS
+    fused_ln = cls == eg.KERNEL_LAYERNORM and layernorm_in_gemm(wl)
     if not work or not durations_ms:
         return None
     per_step = len(work)
@@ -215,6 +239,9 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None, force_mfma=False):
         "intensity_op_per_byte": round(intensity, 2), "ridge_op_per_byte": round(ridge, 2),
         "steps_timed": n_steps,
     }
+    if fused_ln:
+        out["kernel"] = "layernorm_vec_kernel, and gemm_i8_kernel<64, 768, ...> with the layer norm in its epilogue"
+        out["traffic"] = None            # two kernels in one class: no single figure per launch
     if force_mfma:
         out["hbm_view"] = {"achieved": round(byts / total_s / 1e9, 3), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": round(byts / total_s / 1e9 / PEAK_HBM_GBS, 4),
@@ -222,7 +249,8 @@ def roofline_for(wl, cls, durations_ms, eg, steps, cfg=None, force_mfma=False):
                                    "written once); below the ridge the class is bound by this roof, not by the matrix cores"}
     # launches of different shapes inside a step (the four GEMMs of a Transformer layer, the three
     # convolutions of a bottleneck): average duration and rates per position in the step's period
-    period = 4 if (cls == eg.KERNEL_GEMM and per_step % 4 == 0 and per_step >= 4 and "seq" in wl.dims) else \
+    period = per_step // wl.dims["n_layers"] if (cls == eg.KERNEL_GEMM and "seq" in wl.dims and wl.dims.get("n_layers", 0) > 0
+                                                 and per_step % wl.dims["n_layers"] == 0) else \
         (per_step if per_step <= 4 else 0)
     if period > 1:
         shapes = []

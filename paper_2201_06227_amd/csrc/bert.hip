@@ -87,45 +87,12 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *__restr
             if (!gamma) gmv[i] = one4;
             if (!beta) btv[i] = zero4;
         }
-        double v[NV][4];
-        double s = 0.0;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            v[i][0] = (double)xv[i].x + (double)rv[i].x;
-            v[i][1] = (double)xv[i].y + (double)rv[i].y;
-            v[i][2] = (double)xv[i].z + (double)rv[i].z;
-            v[i][3] = (double)xv[i].w + (double)rv[i].w;
-            s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
-        }
-        const double mean = wave_sum(s) / (double)H;
-        double q = 0.0;
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-            if (lane + 64 * i < nv) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[i][e] -= mean;
-                    q += v[i][e] * v[i][e];
-                }
-            }
-        const double var = wave_sum(q) / (double)H;
-        const double rstd = 1.0 / sqrt(var + eps);
+        float4 o[NV];
+        ln_row_vec<NV>(xv, rv, gmv, btv, lane, nv, H, eps, o, amax);
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int c = lane + 64 * i;
-            if (c < nv) {
-                const float4 gm = gmv[i], bt = btv[i];
-                float4 o;
-                o.x = (float)(v[i][0] * rstd * (double)gm.x + (double)bt.x);
-                o.y = (float)(v[i][1] * rstd * (double)gm.y + (double)bt.y);
-                o.z = (float)(v[i][2] * rstd * (double)gm.z + (double)bt.z);
-                o.w = (float)(v[i][3] * rstd * (double)gm.w + (double)bt.w);
-                reinterpret_cast<float4 *>(y + row * H)[c] = o;
-                const uint32_t a0 = abs_bits(o.x), a1 = abs_bits(o.y), a2 = abs_bits(o.z), a3 = abs_bits(o.w);
-                const uint32_t m01 = a0 > a1 ? a0 : a1, m23 = a2 > a3 ? a2 : a3;
-                const uint32_t m = m01 > m23 ? m01 : m23;
-                amax = amax > m ? amax : m;
-            }
+            if (c < nv) reinterpret_cast<float4 *>(y + row * H)[c] = o[i];
         }
     }
     if (absmax_out) {

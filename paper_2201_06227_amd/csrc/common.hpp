@@ -261,8 +261,20 @@ struct GemmArgs {
     const int32_t *zp_in;
     const int32_t *colsum;
     const int32_t *zp_res;
+    // optional: the layer norm that follows a linear layer, in the same launch (int8 operands, N <= 768 a
+    // multiple of 4, no activation, residual codes, observation or int8 output): ln_out [M, N] receives
+    // LN(y + ln_res) with y the layer's fp32 output (never stored; g.y is ignored), ln_res fp32 [M, N],
+    // ln_gamma / ln_beta fp32 [N] or null; absmax_out then tracks |ln_out|.  Same arithmetic, in the same
+    // order, as launch_layernorm on the stored y.
+    float *ln_out;
+    const float *ln_res;
+    const float *ln_gamma;
+    const float *ln_beta;
+    double ln_eps;
 };
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st);
+// true if launch_gemm_i8 can take the layer norm of an [M, N] output into the GEMM's launch
+bool gemm_layernorm_fusable(int32_t N, const void *ln_out, const void *ln_res, const void *gamma, const void *beta);
 
 // The narrow 3x3 convolution (at most 16 input channels, at most 32 outputs) with the quantiser of
 // its operands folded in: the workgroup derives the scale of the quantise point itself, maps the
@@ -341,6 +353,56 @@ __device__ __forceinline__ double wave_sum(double v)
 // |v| as a bit pattern whose unsigned order is the order of |v|; NaN and Inf
 // compare above every finite value.
 __device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+// Layer norm of one row held by a wave, evaluated in fp64 and rounded once: lane l holds the 16-byte units
+// l, l + 64, ... of the row (x and residual already zeroed where absent or beyond the row's nv units, gamma
+// one and beta zero where absent).  Returns the outputs of the lane's units and raises amax to the largest
+// |output| bit pattern.  Every kernel that normalises a row goes through this one function, so they agree
+// bit for bit.
+template <int NV>
+__device__ __forceinline__ void ln_row_vec(const float4 (&xv)[NV], const float4 (&rv)[NV], const float4 (&gmv)[NV],
+                                           const float4 (&btv)[NV], int lane, int nv, int H, double eps,
+                                           float4 (&o)[NV], uint32_t &amax)
+{
+    double v[NV][4];
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        v[i][0] = (double)xv[i].x + (double)rv[i].x;
+        v[i][1] = (double)xv[i].y + (double)rv[i].y;
+        v[i][2] = (double)xv[i].z + (double)rv[i].z;
+        v[i][3] = (double)xv[i].w + (double)rv[i].w;
+        s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+    const double mean = wave_sum(s) / (double)H;
+    double q = 0.0;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+        if (lane + 64 * i < nv) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[i][e] -= mean;
+                q += v[i][e] * v[i][e];
+            }
+        }
+    const double var = wave_sum(q) / (double)H;
+    const double rstd = 1.0 / sqrt(var + eps);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        o[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (lane + 64 * i < nv) {
+            const float4 gm = gmv[i], bt = btv[i];
+            o[i].x = (float)(v[i][0] * rstd * (double)gm.x + (double)bt.x);
+            o[i].y = (float)(v[i][1] * rstd * (double)gm.y + (double)bt.y);
+            o[i].z = (float)(v[i][2] * rstd * (double)gm.z + (double)bt.z);
+            o[i].w = (float)(v[i][3] * rstd * (double)gm.w + (double)bt.w);
+            const uint32_t a0 = abs_bits(o[i].x), a1 = abs_bits(o[i].y), a2 = abs_bits(o[i].z), a3 = abs_bits(o[i].w);
+            const uint32_t m01 = a0 > a1 ? a0 : a1, m23 = a2 > a3 ? a2 : a3;
+            const uint32_t m = m01 > m23 ? m01 : m23;
+            amax = amax > m ? amax : m;
+        }
+    }
+}
 // Workgroup-wide maximum of a bit pattern, then at most one atomicMax per
 // workgroup, and none when the slot already holds a value at least as large.
 __device__ __forceinline__ void block_atomic_max(uint32_t v, uint32_t *slot, uint32_t *sm4)

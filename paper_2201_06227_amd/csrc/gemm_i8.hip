@@ -41,6 +41,7 @@ constexpr int stages_for(int bm, int bn, int bk)
 {
     const int stage = (bm + bn) * bk;
     if (bk == 64) {
+        if (bm == 64 && bn == 768) return 3;           // the row-owning tile: three stages fill the 160 KB exactly
         if (bm * bn < 256 * 192) return 3;
         const int fit = 150 * 1024 / stage;
         return fit > 6 ? 6 : fit;
@@ -122,7 +123,7 @@ constexpr int resident_target(int bm, int bn)
     return bm * bn > 256 * 128 ? 1 : (bm * bn > 128 * 128 ? 2 : 3);
 }
 
-template <int BM, int BN, int WM, int WN, bool CONV, int BK, int ET>
+template <int BM, int BN, int WM, int WN, bool CONV, int BK, int ET, bool LNF = false>
 __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8_kernel(const GemmArgs g, int tiles,
                                                                                int tiles_per_xcd)
 {
@@ -226,8 +227,14 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
         int k0, dh, dw, delta;
         bool k_ok;
     };
+    // The row-owning tile: every workgroup streams the whole weight matrix, so all of them would ask the L2 for
+    // the same rows at the same time; each starts at a K step of its own instead (integer sums do not depend
+    // on the order).  Steps past the end of K stay past the end.
+    const int nk_all = (g.kp + kBK - 1) / kBK;
+    const int k_rot = LNF ? tile % nk_all : 0;
     auto step_addr = [&](int kt) {
         StepAddr sa;
+        if (LNF && kt < nk_all) kt = kt + k_rot < nk_all ? kt + k_rot : kt + k_rot - nk_all;
         sa.k0 = kt * kBK + unit * 16;
         sa.k_ok = sa.k0 < g.kp;
         sa.dh = 0;
@@ -475,6 +482,78 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
     };
     using T = std::true_type;
     using F = std::false_type;
+    if constexpr (LNF) {
+        // The layer norm of the rows in the same launch: the workgroup owns whole rows (one tile across N).
+        // A 32-row block of the fp32 output goes to LDS (the stage memory is free now), then each wave
+        // normalises rows of it exactly as layernorm_vec_kernel does with a stored tensor: lane l holds the
+        // 16-byte units l, l + 64, ... of the row, and the arithmetic is the shared ln_row_vec.  The residual
+        // rows are requested before the barrier, gamma and beta once.
+        static_assert(WM == 1 && ET == 0 && !CONV, "whole rows of a linear layer with int8 operands");
+        constexpr int YS = BN + 8;                      // floats per row of the block in LDS (pad: the two rows a
+                                                        // store instruction writes fall into different banks)
+        constexpr int NV = BN / 256, RPW = 32 / NW;     // 16-byte units per lane and row; rows per wave and block
+        static_assert(BN % 256 == 0 && 32 % NW == 0, "rows of 256 NV floats, a wave takes whole rows");
+        static_assert((size_t)NST * STAGE >= (size_t)32 * YS * 4, "a 32-row block must fit the stage memory");
+        float *yt = (float *)lds;
+        const int H = g.N, nv = H >> 2;
+        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), one4 = make_float4(1.f, 1.f, 1.f, 1.f);
+        float4 gmv[NV], btv[NV];
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = lane + 64 * u, cc = c < nv ? c : nv - 1;
+            gmv[u] = g.ln_gamma ? reinterpret_cast<const float4 *>(g.ln_gamma)[cc] : one4;
+            btv[u] = g.ln_beta ? reinterpret_cast<const float4 *>(g.ln_beta)[cc] : zero4;
+        }
+        uint32_t amax_u = 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            __syncthreads();                            // the stage memory (or the block before) has been read
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = (wn_u * TN + j) * 32 + lcol;
+                const bool col_ok = col < g.N;
+                const float bj = (g.bias && col_ok) ? g.bias[col] : 0.0f;
+                const float sj = g.sw_per_n ? (col_ok ? sxv * g.sw[col] : 0.0f) : s;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    yt[(lrow + 8 * (r >> 2) + (r & 3)) * YS + col] = fmaf((float)acc[i][j][r], sj, bj);
+            }
+            float4 rv[RPW][NV];
+#pragma unroll
+            for (int k = 0; k < RPW; ++k) {
+                const int64_t row = m0 + i * 32 + wave_u + NW * k;
+                const float4 *rr = reinterpret_cast<const float4 *>(g.ln_res + (row < g.M ? row : g.M - 1) * H);
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    const int c = lane + 64 * u;
+                    rv[k][u] = rr[c < nv ? c : nv - 1];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < RPW; ++k) {
+                const int lr = wave_u + NW * k;
+                const int64_t row = m0 + i * 32 + lr;
+                if (row < g.M) {
+                    float4 xv[NV], o[NV];
+#pragma unroll
+                    for (int u = 0; u < NV; ++u) {
+                        const int c = lane + 64 * u;
+                        const bool in = c < nv;
+                        xv[u] = in ? *reinterpret_cast<const float4 *>(&yt[lr * YS + 4 * c]) : zero4;
+                        if (!in) rv[k][u] = zero4;
+                    }
+                    ln_row_vec<NV>(xv, rv[k], gmv, btv, lane, nv, H, g.ln_eps, o, amax_u);
+#pragma unroll
+                    for (int u = 0; u < NV; ++u) {
+                        const int c = lane + 64 * u;
+                        if (c < nv) reinterpret_cast<float4 *>(g.ln_out + row * H)[c] = o[u];
+                    }
+                }
+            }
+        }
+        amax = (int32_t)amax_u;
+    } else
     if (!interior || (g.q_out && (g.res_q || g.act != 1))) emit(T{}, F{}, F{}, F{}, F{});
     else if (g.q_out) emit(F{}, F{}, T{}, F{}, T{});
     else if (g.res_q) {
@@ -508,7 +587,7 @@ __global__ __launch_bounds__(64 * WM * WN, resident_target(BM, BN)) void gemm_i8
     }
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int ET = 0>
+template <int BM, int BN, int WM, int WN, int BK, int ET = 0, bool LNF = false>
 static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
 {
     const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
@@ -533,13 +612,14 @@ static hipError_t launch_variant(const GemmArgs &g, hipStream_t st)
     }
     static bool set[kMaxDevices] = {};
     if (!set[dev]) {
-        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>,
+        e = hipFuncSetAttribute((const void *)gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET, LNF>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         set[dev] = true;
     }
-    return launch_k(EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET>, grid, block, smem, st, g,
-                    (int)tiles, tpx);
+    // (instrumentation: the launch that also normalises its rows is timed with the layer norms, whose bytes bound it)
+    return launch_k(LNF ? EGERIA_KERNEL_LAYERNORM : EGERIA_KERNEL_GEMM, gemm_i8_kernel<BM, BN, WM, WN, false, BK, ET, LNF>,
+                    grid, block, smem, st, g, (int)tiles, tpx);
 }
 
 // ---- 3x3 convolution with at most 16 input channels and at most 32 outputs ----------------
@@ -955,8 +1035,20 @@ static hipError_t launch_float(const GemmArgs &g, hipStream_t st)
     return launch_variant<128, 64, 2, 2, 64, ET>(g, st);
 }
 
+bool gemm_layernorm_fusable(int32_t N, const void *ln_out, const void *ln_res, const void *gamma, const void *beta)
+{
+    auto ok16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    return N >= 4 && N <= 768 && (N & 3) == 0 && ln_out && ln_res && ok16(ln_out) && ok16(ln_res) && ok16(gamma) && ok16(beta);
+}
+
 hipError_t launch_gemm_i8(const GemmArgs &g, hipStream_t st)
 {
+    if (g.ln_out) {
+        // a linear layer and the layer norm of its rows in one launch: 64 whole rows per workgroup
+        if (g.et != 0 || g.conv3x3 || g.act || g.res_q || g.q_out || g.acc_out || g.zp_in || g.zp_res) return hipErrorInvalidValue;
+        if (!gemm_layernorm_fusable(g.N, g.ln_out, g.ln_res, g.ln_gamma, g.ln_beta)) return hipErrorInvalidValue;
+        return launch_variant<64, 768, 1, 8, 64, 0, true>(g, st);
+    }
     if (g.et == 1) return launch_float<1>(g, st);
     if (g.et == 2) return launch_float<2>(g, st);
     if (g.et != 0) return hipErrorInvalidValue;

@@ -521,7 +521,10 @@ BERT_CASES = [dict(b=2, s=12, hidden=48, heads=4, ffn=96, n_layers=1),
               dict(b=3, s=40, hidden=128, heads=2, ffn=200, n_layers=1),
               dict(b=2, s=130, hidden=192, heads=3, ffn=320, n_layers=3),
               dict(b=1, s=1, hidden=64, heads=1, ffn=16, n_layers=2),
-              dict(b=8, s=64, hidden=768, heads=12, ffn=3072, n_layers=12)]
+              dict(b=8, s=64, hidden=768, heads=12, ffn=3072, n_layers=12),
+              # enough rows (12288) for the attention-output layer and its layer norm to share a launch, with
+              # rows shorter than that kernel's tile
+              dict(b=48, s=256, hidden=64, heads=1, ffn=16, n_layers=2)]
 
 
 @pytest.mark.parametrize("kw", BERT_CASES, ids=lambda k: "b{b}_s{s}_h{hidden}_L{n_layers}".format(**k))
