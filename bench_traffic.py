@@ -42,9 +42,11 @@ def per_kernel(path, counter):
             if r["Counter_Name"] != counter or "egeria::" not in r["Kernel_Name"]:
                 continue
             name = r["Kernel_Name"].split("egeria::")[1].split("<")[0].split("(")[0]
-            # the GEMM kernel's last template argument is the operand type: only the int8 launches
-            # belong to the workload's step (bench.py also times float16 / float32 reference legs)
-            if name == "gemm_i8_kernel" and not re.search(r"gemm_i8_kernel<[^>]*, 0>", r["Kernel_Name"]):
+            # the GEMM kernel's last two template arguments are the operand type and whether the launch also
+            # normalises its rows: only the plain int8 launches belong to the GEMM class of the workload's step
+            # (bench.py also times float16 / float32 reference legs, and prices the normalising launch with
+            # the layer norms)
+            if name == "gemm_i8_kernel" and not re.search(r"gemm_i8_kernel<[^>]*, 0, false>", r["Kernel_Name"]):
                 continue
             out.setdefault(name, []).append(float(r["Counter_Value"]))
     return out
