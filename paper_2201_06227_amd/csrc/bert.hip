@@ -357,12 +357,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
     }
 }
 
-// ---- the same attention on the fp32 matrix-core instructions, with certified int8 codes ----------
+// ---- the same attention in fp32 arithmetic on the matrix cores, with certified int8 codes ----------
 // Unobserved runs do not need the context as the fp64 evaluation gives it: all that leaves this stage
 // is the int8 input of the next GEMM and its scale.  Three launches:
-//   1. attention_fast_kernel: the structure of the kernel above in fp32 (v_mfma_f32_16x16x4f32, hardware
-//      exp2), 2.2x faster.  It stores an approximate context and, per workgroup, a record: the largest
-//      |context| it stored and an error bound E for its values (below).
+//   1. an approximate attention with fp32 products and sums: attention_split_kernel (further down: every
+//      fp32 product as six bf16 partial products on the bf16 matrix cores; head dims in whole units of 8)
+//      or attention_fast_kernel (here: the structure of the kernel above on v_mfma_f32_16x16x4f32, hardware
+//      exp2; any head size).  It stores an approximate context and, per 64 queries of a head, a record: the
+//      largest |context| it stored and an error bound E for its values (below).
 //   2. attention_absmax_exact_kernel: the tensor's absolute maximum as the fp64 evaluation gives it.  Every
 //      value that can be the maximum (|x| + E >= largest |x| - largest E; as a rule one) is re-evaluated in fp64.
 //   3. quantize_attention_certify_kernel: the streaming map to codes.  code(x) = clamp(rne(x * inv)) is
