@@ -578,6 +578,22 @@ def test_attention_paths_agree(eg, gc, kw):
     assert np.array_equal(outs[0].cpu().numpy().reshape(observed.shape), observed)
 
 
+@pytest.mark.parametrize("column", ["query", "value"])
+def test_attention_reports_non_finite_values(eg, gc, column):
+    """An infinite bias in the QKV layer puts non-finite values into the attention (finite inputs and weights
+    do not reach that state): the approximate attention kernels must carry them into the status word, through
+    the value maximum of their records (value column) or through the stored context (query column)."""
+    wl = si.make_bert(b=2, s=70, hidden=64, heads=2, ffn=32, n_layers=1, seed=404, train_act_dtype="f32")
+    wl.biases[0] = wl.biases[0].copy()
+    wl.biases[0][(0 if column == "query" else 2 * 64) + 5] = np.inf
+    ref = gc.build_reference(wl)
+    ws = eg.workspace(eg.workspace_bytes(ref.desc), gc.DEV)
+    a = torch.empty(gc.a_ref_numel(wl), dtype=torch.float32, device=gc.DEV)
+    eg.ref_forward(ref, gc.to_dev(wl.x), a, ws)
+    torch.cuda.synchronize()
+    assert eg.check(ws) == eg.ERR_NONFINITE
+
+
 def test_bert_small_preactivations(eg, gc, orc):
     """The fused GELU quantiser takes absmax = gelu(max v) as a shortcut when
     max v >= 0.5; with tiny feed-forward weights it must fall back to the exact
