@@ -824,11 +824,11 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
     __syncthreads();
     v16f sacc = scores(0);
     __syncthreads();                                             // K buffer 0 is rewritten in iteration 0
-    // (everything in an iteration is unconditional, so that it is one block the scheduler can interleave: past
-    // the last tile the scores of a stale buffer are computed and dropped, and zero tiles are staged)
+    // (the loads are unconditional; scores and staging of tiles past the end are skipped under uniform branches)
     auto iteration = [&](int t, auto ragged) {
         const int j0 = t * kSplitKeys;
-        const v16f snext = scores((t + 1) & 1);
+        v16f snext = sacc;
+        if (t + 1 < ntiles) snext = scores((t + 1) & 1);
         // soft-max of tile t
         float mx = -INFINITY;
 #pragma unroll
@@ -881,8 +881,8 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
                         ot[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, av), __builtin_bit_cast(v8bf, bp), ot[db], 0, 0, 0);
                     }
                 }
-            stash_k(t & 1);
-            stash_v((t + 1) & 1);
+            if (t + 2 < ntiles) stash_k(t & 1);
+            if (t + 1 < ntiles) stash_v((t + 1) & 1);
             fetch_k(j0 + 3 * kSplitKeys);
             fetch_v(j0 + 2 * kSplitKeys);
 #pragma unroll
