@@ -2,6 +2,7 @@
 // reference model is an int8 post-training-quantised snapshot).  Two coalesced
 // HBM passes per tensor: an absolute-maximum reduction, then the map to codes.
 #include "common.hpp"
+#include <type_traits>
 
 namespace egeria {
 
@@ -706,6 +707,8 @@ hipError_t launch_gelu_absmax_exact(const float *v, int64_t n, const uint32_t *v
 // 5e-15 of the table's first value).  |approximation - gelu| <= kGeluErrAbs + kGeluErrRel * |gelu|.
 #include "gelu_table.inc"
 
+// BIG: values of 8 and more may occur (the caller knows the tensor's maximum); otherwise the test is left out.
+template <bool BIG>
 __device__ __forceinline__ float gelu_table(float v, const float4 *__restrict__ tab)
 {
     const float vc = fminf(fmaxf(v, -8.0f), 7.999999f);
@@ -713,7 +716,7 @@ __device__ __forceinline__ float gelu_table(float v, const float4 *__restrict__ 
     const float t = vc - fmaf((float)i, 0.0625f, -8.0f);
     const float4 c = tab[i];
     const float g = fmaf(fmaf(fmaf(c.w, t, c.z), t, c.y), t, c.x);
-    return v >= 8.0f ? v : g;
+    return (BIG && v >= 8.0f) ? v : g;
 }
 
 __device__ __forceinline__ uint32_t code_of(float t)
@@ -727,14 +730,18 @@ __device__ __forceinline__ uint32_t code_of(float t)
 // the interval that the error bound leaves for g * inv round to the same integer, that integer is the code
 // of the exact value; *unsure is set otherwise (a few values per 100 000) and the caller takes the fp64 form.
 // err_abs_inv = kGeluErrAbs * inv.  (The relative part also covers the rounding of the two products.)
+// (The interval [t - e, t + e] rounds to one integer if |t - rne(t)| + e < 1/2.  No clamp: the scale is the
+// tensor's exact maximum of |gelu| over 127, so |t| stays below 127.5 by the table's error bound; with a
+// non-finite maximum inv is 0 and every code is 0.)
+template <bool BIG>
 __device__ __forceinline__ uint32_t quant_gelu_fast(float v, float inv, float err_abs_inv, const float4 *__restrict__ tab,
                                                     bool *unsure)
 {
-    const float t = gelu_table(v, tab) * inv;
+    const float t = gelu_table<BIG>(v, tab) * inv;
     const float e = fmaf(kGeluErrRel + 3.0e-7f, fabsf(t), err_abs_inv);
-    const float lo = rintf(t - e), hi = rintf(t + e);
-    *unsure = !(lo == hi);
-    return (uint32_t)((int)fminf(fmaxf(hi, -127.0f), 127.0f)) & 0xffu;
+    const float rt = rintf(t);
+    *unsure = !(fabsf(t - rt) + e < 0.5f);
+    return (uint32_t)((int)rt) & 0xffu;
 }
 
 __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
@@ -760,44 +767,57 @@ __global__ __launch_bounds__(256) void quantize_gelu_rows_kernel(
     const int64_t units = rows * upr;
     const bool narrow = units < (1LL << 32);
     const bool vec_ok = (cols & 3) == 0;
-    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < units;
-         u += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = div_u(u, upr, narrow);
-        const int64_t c0 = (u - row * upr) << 4;
-        const int64_t base = row * cols + c0;
-        uint32_t w[4] = {0, 0, 0, 0};
-        uint32_t redo = 0;                         // elements that need the fp64 form
-        if (vec_ok && c0 + 16 <= cols) {
-            const float4 *p = (const float4 *)(v + base);
-            float4 x[4];
+    // a thread's units are `stride` apart: row and unit within the row advance by stride / upr and stride % upr
+    // (one division at the start instead of one per unit)
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t step_rows = div_u(stride, upr, narrow), step_units = stride - step_rows * upr;
+    auto run = [&](auto big_c) {
+        constexpr bool BIG = decltype(big_c)::value;
+        int64_t row = div_u(first, upr, narrow), cu = first - row * upr;
+        for (int64_t u = first; u < units; u += stride) {
+            const int64_t c0 = cu << 4;
+            const int64_t base = row * cols + c0;
+            uint32_t w[4] = {0, 0, 0, 0};
+            uint32_t redo = 0;                         // elements that need the fp64 form
+            if (vec_ok && c0 + 16 <= cols) {
+                const float4 *p = (const float4 *)(v + base);
+                float4 x[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) x[j] = p[j];
+                for (int j = 0; j < 4; ++j) x[j] = p[j];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bool u0, u1, u2, u3;
-                w[j] = quant_gelu_fast(x[j].x, inv, err_abs_inv, tab, &u0) | (quant_gelu_fast(x[j].y, inv, err_abs_inv, tab, &u1) << 8) |
-                       (quant_gelu_fast(x[j].z, inv, err_abs_inv, tab, &u2) << 16) |
-                       (quant_gelu_fast(x[j].w, inv, err_abs_inv, tab, &u3) << 24);
-                redo |= ((u0 ? 1u : 0u) | (u1 ? 2u : 0u) | (u2 ? 4u : 0u) | (u3 ? 8u : 0u)) << (4 * j);
+                for (int j = 0; j < 4; ++j) {
+                    bool u0, u1, u2, u3;
+                    w[j] = quant_gelu_fast<BIG>(x[j].x, inv, err_abs_inv, tab, &u0) |
+                           (quant_gelu_fast<BIG>(x[j].y, inv, err_abs_inv, tab, &u1) << 8) |
+                           (quant_gelu_fast<BIG>(x[j].z, inv, err_abs_inv, tab, &u2) << 16) |
+                           (quant_gelu_fast<BIG>(x[j].w, inv, err_abs_inv, tab, &u3) << 24);
+                    redo |= ((u0 ? 1u : 0u) | (u1 ? 2u : 0u) | (u2 ? 4u : 0u) | (u3 ? 8u : 0u)) << (4 * j);
+                }
+            } else {
+                redo = 0xffffu;                        // ragged tail of a row: every element through the loop below
             }
-        } else {
-            redo = 0xffffu;                        // ragged tail of a row: every element through the loop below
-        }
-        // one copy of the fp64 code, rolled: the values are re-read (they are in cache)
+            // one copy of the fp64 code, rolled: the values are re-read (they are in cache)
 #pragma unroll 1
-        while (redo) {
-            const int e = __ffs((int)redo) - 1;
-            redo &= redo - 1;
-            if (c0 + e >= cols) continue;
-            const uint32_t code = code_of(gelu_exact(v[base + e]) * inv);
-            const uint32_t sh = (e & 3) * 8, keep = ~(0xffu << sh);
-            if ((e >> 2) == 0) w[0] = (w[0] & keep) | (code << sh);
-            if ((e >> 2) == 1) w[1] = (w[1] & keep) | (code << sh);
-            if ((e >> 2) == 2) w[2] = (w[2] & keep) | (code << sh);
-            if ((e >> 2) == 3) w[3] = (w[3] & keep) | (code << sh);
+            while (redo) {
+                const int e = __ffs((int)redo) - 1;
+                redo &= redo - 1;
+                if (c0 + e >= cols) continue;
+                const uint32_t code = code_of(gelu_exact(v[base + e]) * inv);
+                const uint32_t sh = (e & 3) * 8, keep = ~(0xffu << sh);
+                if ((e >> 2) == 0) w[0] = (w[0] & keep) | (code << sh);
+                if ((e >> 2) == 1) w[1] = (w[1] & keep) | (code << sh);
+                if ((e >> 2) == 2) w[2] = (w[2] & keep) | (code << sh);
+                if ((e >> 2) == 3) w[3] = (w[3] & keep) | (code << sh);
+            }
+            *(uint4 *)(q + row * ldq + c0) = make_uint4(w[0], w[1], w[2], w[3]);
+            row += step_rows;
+            cu += step_units;
+            if (cu >= upr) { cu -= upr; ++row; }
         }
-        *(uint4 *)(q + row * ldq + c0) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
+    };
+    // values of 8 and more (where gelu(v) rounds to v and the table ends) only if the tensor's maximum says so
+    if (vm >= 8.0f || bad) run(std::true_type{}); else run(std::false_type{});
 }
 
 hipError_t launch_quantize_gelu_rows(const float *v, int64_t rows, int64_t cols, int64_t ldq,
