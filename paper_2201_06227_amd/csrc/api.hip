@@ -478,8 +478,9 @@ egeria_status forward_bert_layer(const Fwd &f, int l, const float *cur, float *o
                                     f.scale(s0), nullptr, ws_flag(f.ws), f.st));
     EG_OK(f.copy_tap_q(s0, xq, (size_t)(M * hp), f.scale(s0)));
     EG_OK(run_gemm(f, s0, xq, hp, M, 3 * Hd, hp, false, 0, 0, 0, f.scale(s0), 0, nullptr, nullptr, 0, qkv, nullptr));
-    // The certified fp32 attention is four launches with about 70 us of fixed cost between them; it pays when the
-    // fp64 kernel would take longer than that (cfg 4, one layer of 32 x 128 tokens: fp64 46 us; cfg 5: 315 us).
+    // The certified approximate attention is two or three launches with some tens of microseconds of fixed cost; it
+    // pays when the fp64 kernel would take longer than that (one layer of 32 x 128 tokens: fp64 46 us; the 12-layer
+    // stack of 64 x 256 tokens: 315 us).
     const double attention_flops = 4.0 * d->batch * d->heads * (double)d->seq * d->seq * (Hd / d->heads);
     if (f.taps || attention_flops < g_attention_min_flops) {
         // observed runs (and small ones): the context itself in fp64, then the plain quantiser

@@ -359,7 +359,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const float *__restrict_
 
 // ---- the same attention in fp32 arithmetic on the matrix cores, with certified int8 codes ----------
 // Unobserved runs do not need the context as the fp64 evaluation gives it: all that leaves this stage
-// is the int8 input of the next GEMM and its scale.  Three launches:
+// is the int8 input of the next GEMM and its scale.  Three launches (two with the bf16-split kernel, whose
+// workgroups settle the exact maximum themselves as they finish):
 //   1. an approximate attention with fp32 products and sums: attention_split_kernel (further down: every
 //      fp32 product as six bf16 partial products on the bf16 matrix cores; head dims in whole units of 8)
 //      or attention_fast_kernel (here: the structure of the kernel above on v_mfma_f32_16x16x4f32, hardware
@@ -641,6 +642,11 @@ __global__ __launch_bounds__(256) void attention_fast_kernel(const float *__rest
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+// (defined further down; the kernel below ends with the exact evaluation of its candidates for the maximum)
+__device__ __forceinline__ float context_exact(const float *__restrict__ qkv, int S, int Hd, int heads, int dh, double scale,
+                                               uint32_t el, double *red);
+template <typename F>
+__device__ __forceinline__ void for_each_marked(bool mine, uint64_t *masks, F visit);
 constexpr int kSplitQ = 128;             // queries per workgroup
 constexpr int kSplitKeys = 32;           // keys per tile
 constexpr int kSplitKRow = 128;          // bytes per key row of a K plane (8 units)
@@ -683,8 +689,8 @@ __device__ __forceinline__ Split3 split_eight(const float (&x)[8])
 __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__restrict__ qkv, int B, int S, int Hd,
                                                                  int heads, int dh, float scale, float *__restrict__ ctx,
                                                                  AttnRecord *__restrict__ rec, int total, int per_xcd,
-                                                                 uint32_t *__restrict__ amax_slot,
-                                                                 uint32_t *__restrict__ err_slot)
+                                                                 uint32_t *__restrict__ bound_slot,
+                                                                 uint32_t *__restrict__ exact_slot)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kSplitStage];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -922,13 +928,18 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
     }
     // records: one per 64 queries (a pair of waves): largest |context| stored, and the error bound of its values
     __shared__ uint32_t red[3][4];
+    __shared__ float rec_err[2], rec_low[2];
+    __shared__ uint32_t non_finite;
     amax = wave_max_u32(amax);
     vmax = wave_max_u32(vmax);
     const uint32_t sbits = wave_max_u32(__float_as_uint(smax));       // non-negative floats order like integers
     if (lane == 0) { red[0][wave] = amax; red[1][wave] = vmax; red[2][wave] = sbits; }
+    if (tid == 0) non_finite = 0;
     __syncthreads();
     if (tid < 2) {
         const int qt = qb * (kSplitQ / 64) + tid;
+        rec_err[tid] = 0.0f;
+        rec_low[tid] = 0.0f;
         if (qt < qtiles) {
             uint32_t v = 0;
             for (int w = 0; w < 4; ++w) v = v > red[1][w] ? v : red[1][w];
@@ -939,15 +950,64 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
             rc.err = 5.9604645e-8f * __uint_as_float(v) * (kErrBase + kErrPerScore * __uint_as_float(sb));
             if (!(rc.err <= 3.402823466e+38f)) rc.amax_bits = 0x7f800000u;   // non-finite inputs: flagged downstream
             rec[bh * qtiles + qt] = rc;
-            if (amax_slot) {
-                uint32_t *wa = amax_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride;
-                uint32_t *we = err_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride;
-                const uint32_t eb = __float_as_uint(rc.err);
-                if (rc.amax_bits > __hip_atomic_load(wa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(wa, rc.amax_bits);
-                if (eb > __hip_atomic_load(we, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(we, eb);
+            if (bound_slot) {
+                // The exact maximum of the tensor is found here too.  Every workgroup raises a shared word to a
+                // lower bound of its own exact maximum (largest stored |x| minus its error bound); a value can be
+                // the tensor's exact maximum only if |x| + E reaches the largest lower bound, whichever
+                // workgroups have reported so far: the workgroup that holds the maximum always sees a bound that
+                // its maximum passes.  Non-finite values: they are the "maximum".
+                uint32_t *wb = bound_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride;
+                if (rc.amax_bits >= 0x7f800000u) {
+                    atomicMax(exact_slot + ((blockIdx.x + tid) & (kAmaxWays - 1)) * kAmaxStride, rc.amax_bits);
+                    non_finite = 1;
+                } else {
+                    const float af = __uint_as_float(a);
+                    const float low = fmaxf(af - value_err(rc.err, af) * 1.001f, 0.0f);
+                    rec_err[tid] = rc.err;
+                    rec_low[tid] = low;
+                    const uint32_t lb = __float_as_uint(low);
+                    if (lb > __hip_atomic_load(wb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(wb, lb);
+                }
             }
         }
     }
+    if (!bound_slot) return;                                     // the kernel alone (error measurement)
+    __syncthreads();
+    if (non_finite) return;
+    // the largest lower bound reported so far (a stale value only admits more candidates)
+    uint32_t gb = __hip_atomic_load(bound_slot + lane * kAmaxStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    gb = wave_max_u32(gb);
+    const float e_r = rec_err[wave >> 1];
+    const float floor_v = fmaxf(__uint_as_float(gb), rec_low[wave >> 1]);
+    uint32_t cand = 0;                                           // bit 16 db + i: that register is a candidate
+    if (q < S) {
+        const float inv = 1.0f / lrun;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int d = 32 * db + 8 * (i >> 2) + 4 * h + (i & 3);
+                const float x = fabsf(o[db][i] * inv);
+                if (d < dh && x + value_err(e_r, x) * 1.001f >= floor_v) cand |= 1u << (16 * db + i);
+            }
+    }
+    if (!__syncthreads_or(cand != 0)) return;                    // as a rule: nothing to do
+    __shared__ uint64_t masks[4];
+    double *redd = (double *)lds;                                // the stage memory is free now
+    const double scale_d = 1.0 / sqrt((double)dh);
+    uint32_t best = 0;
+    for (int sl = 0; sl < 32; ++sl) {
+        if (!__syncthreads_or((cand >> sl) & 1u)) continue;
+        for_each_marked(((cand >> sl) & 1u) != 0, masks, [&](int k) {
+            const int wk = k >> 6, rk = k & 31, hk = (k >> 5) & 1;
+            const int qk = qb * kSplitQ + wk * 32 + rk;
+            const int dk = 32 * (sl >> 4) + 8 * ((sl & 15) >> 2) + 4 * hk + (sl & 3);
+            const float x = context_exact(qkv, S, Hd, heads, dh, scale_d, (uint32_t)((tok0 + qk) * Hd + hd * dh + dk), redd);
+            const uint32_t ab = abs_bits(x);
+            best = best > ab ? best : ab;
+        });
+    }
+    if (tid == 0 && best) atomicMax(exact_slot + (blockIdx.x & (kAmaxWays - 1)) * kAmaxStride, best);
 }
 
 // The context value of one (query token, head, dim) as the fp64 evaluation defines it:
@@ -1357,7 +1417,8 @@ size_t attention_records_bytes(int32_t B, int32_t S, int32_t heads)
 // Kernel 1: the bf16-split form when head dims come in whole units of 8 floats at 16-byte aligned addresses,
 // else the fp32 form.  Both fill the same records (one per 64 queries of a head).
 static hipError_t launch_attention_approx(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
-                                          AttnRecord *rec, uint32_t *amax_slot, uint32_t *err_slot, hipStream_t st)
+                                          AttnRecord *rec, uint32_t *amax_slot, uint32_t *err_slot, uint32_t *exact_slot,
+                                          hipStream_t st)
 {
     const int dh = Hd / heads;
     const float scale = (float)(1.0 / sqrt((double)dh));
@@ -1365,7 +1426,7 @@ static hipError_t launch_attention_approx(const float *qkv, int32_t B, int32_t S
         const int64_t grid = (int64_t)B * heads * ((S + kSplitQ - 1) / kSplitQ);
         const int per_xcd = (int)((grid + 7) / 8);
         return launch_k(EGERIA_KERNEL_ATTENTION, attention_split_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st,
-                        qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, scale, ctx, rec, (int)grid, per_xcd, amax_slot, err_slot);
+                        qkv, (int)B, (int)S, (int)Hd, (int)heads, dh, scale, ctx, rec, (int)grid, per_xcd, amax_slot, exact_slot);
     }
     const int64_t grid = (int64_t)B * heads * ((S + 63) / 64);
     const int per_xcd = (int)((grid + 7) / 8);
@@ -1383,7 +1444,7 @@ hipError_t launch_attention_fast(const float *qkv, int32_t B, int32_t S, int32_t
     if (grid <= 0) return hipSuccess;
     if (dh > kDh || grid > 0x7ffffff0LL) return hipErrorInvalidValue;
     if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(records)) return hipErrorInvalidValue;
-    return launch_attention_approx(qkv, B, S, Hd, heads, ctx, (AttnRecord *)records, nullptr, nullptr, st);
+    return launch_attention_approx(qkv, B, S, Hd, heads, ctx, (AttnRecord *)records, nullptr, nullptr, nullptr, st);
 }
 
 hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, int32_t Hd, int32_t heads, float *ctx,
@@ -1401,10 +1462,11 @@ hipError_t launch_attention_certified(const float *qkv, int32_t B, int32_t S, in
     if (!attn_aligned16(qkv) || !attn_aligned16(ctx) || !attn_aligned16(xq) || !attn_aligned16(records)) return hipErrorInvalidValue;
     AttnRecord *rec = (AttnRecord *)records;
     const double scale = 1.0 / sqrt((double)dh);
-    hipError_t e = launch_attention_approx(qkv, B, S, Hd, heads, ctx, rec, amax_slot, err_slot, st);
+    hipError_t e = launch_attention_approx(qkv, B, S, Hd, heads, ctx, rec, amax_slot, err_slot, exact_slot, st);
     if (e != hipSuccess) return e;
     const int nrec = (int)grid;
-    e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, st, qkv,
+    // (the bf16-split kernel settles the exact maximum itself; the fp32 kernel leaves it to a launch of its own)
+    if (!((dh & 7) == 0 && (Hd & 3) == 0)) e = launch_k(EGERIA_KERNEL_NONE, attention_absmax_exact_kernel, dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, st, qkv,
                  (const float *)ctx, (const AttnRecord *)rec, nrec, (const uint32_t *)amax_slot, (const uint32_t *)err_slot, (int)S,
                  (int)Hd, (int)heads, dh, scale, exact_slot);
     if (e != hipSuccess) return e;
