@@ -962,7 +962,8 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
                     non_finite = 1;
                 } else {
                     const float af = __uint_as_float(a);
-                    const float low = fmaxf(af - value_err(rc.err, af) * 1.001f, 0.0f);
+                    // (the factor and the 2^-23 |x| term cover the rounding of this fp32 arithmetic itself)
+                    const float low = fmaxf(af - fmaf(af, 1.2e-7f, value_err(rc.err, af) * 1.001f), 0.0f);
                     rec_err[tid] = rc.err;
                     rec_low[tid] = low;
                     const uint32_t lb = __float_as_uint(low);
@@ -988,7 +989,7 @@ __global__ __launch_bounds__(256, 2) void attention_split_kernel(const float *__
             for (int i = 0; i < 16; ++i) {
                 const int d = 32 * db + 8 * (i >> 2) + 4 * h + (i & 3);
                 const float x = fabsf(o[db][i] * inv);
-                if (d < dh && x + value_err(e_r, x) * 1.001f >= floor_v) cand |= 1u << (16 * db + i);
+                if (d < dh && x + fmaf(x, 1.2e-7f, value_err(e_r, x) * 1.001f) >= floor_v) cand |= 1u << (16 * db + i);
             }
     }
     if (!__syncthreads_or(cand != 0)) return;                    // as a rule: nothing to do
